@@ -1,0 +1,126 @@
+"""Seeded synthetic inputs and parameter sets shared by the tests, the benchmark and the smoke check.
+
+This module holds configuration data and random input generators only: none of the
+scheme's arithmetic lives here.  Both the CPU oracle and the HIP library are fed
+from these generators so that they see identical inputs.
+
+Parameter sets follow the rule "the c largest primes congruent to 1 mod 2N below
+2^b, in descending order" (checked against an independent primality routine in
+the tests).  Moduli are written as 2^b - delta.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Params:
+    name: str
+    logN: int
+    q: tuple  # ciphertext primes q_0 .. q_{L-1}
+    p: tuple  # special primes p_0 .. p_{K-1}
+    dnum: int
+
+    @property
+    def N(self) -> int:
+        return 1 << self.logN
+
+    @property
+    def L(self) -> int:
+        return len(self.q)
+
+    @property
+    def K(self) -> int:
+        return len(self.p)
+
+    @property
+    def alpha(self) -> int:
+        return -(-self.L // self.dnum)
+
+    @property
+    def moduli(self) -> List[int]:
+        return list(self.q) + list(self.p)
+
+
+_C1_Q = tuple(2**40 - d for d in (147455, 237567, 368639))
+_C1_P = (2**50 - 16383,)
+
+_N16_Q = tuple(
+    2**50 - d
+    for d in (
+        3014655, 4718591, 19529727, 20447231, 21102591, 22675455, 22806527, 23199743,
+        23461887, 23855103, 27131903, 28966911, 36438015, 36831231, 40894463, 42336255,
+        44826623, 45088767, 47579135, 54263807, 55312383, 60817407, 62128127, 63176703,
+    )
+)
+_N16_P = tuple(2**60 - d for d in (262143, 8126463, 9830399, 10878975))
+
+# Tiny configuration, as stated: N=2^12, three ~40-bit primes, one ~50-bit special prime, dnum=1.
+C1 = Params("C1", 12, _C1_Q, _C1_P, 1)
+# Same primes with one prime per digit (special modulus larger than every digit), used wherever
+# a decrypted result has to be meaningful.
+C1B = Params("C1B", 12, _C1_Q, _C1_P, 3)
+# N=2^16, 24 ~50-bit primes, 4 ~60-bit special primes, dnum=6: the throughput configuration.
+N16 = Params("N16", 16, _N16_Q, _N16_P, 6)
+
+
+def active_mod_idx(params: Params, level: int) -> List[int]:
+    """Modulus indices of the level + K limbs a key switch works on."""
+    return list(range(level)) + [params.L + k for k in range(params.K)]
+
+
+def rng(seed: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def uniform_limbs(seed: int, params: Params, mod_idx) -> np.ndarray:
+    """[len(mod_idx)][N] uint64, limb b uniform in [0, modulus[mod_idx[b]])."""
+    g = rng(seed)
+    mods = params.moduli
+    out = np.empty((len(mod_idx), params.N), dtype=np.uint64)
+    for b, mi in enumerate(mod_idx):
+        out[b] = g.integers(0, mods[mi], size=params.N, dtype=np.uint64)
+    return out
+
+
+def uniform_ct(seed: int, params: Params, level: int, comps: int = 2) -> np.ndarray:
+    """[comps][level][N] uniform residues: a ciphertext-shaped buffer with no decryption meaning."""
+    mi = list(range(level)) * comps
+    return uniform_limbs(seed, params, mi).reshape(comps, level, params.N)
+
+
+def uniform_evk(seed: int, params: Params) -> np.ndarray:
+    """[dnum][2][L+K][N] uniform residues: a key-shaped buffer for throughput runs."""
+    mi = list(range(params.L + params.K)) * (2 * params.dnum)
+    return uniform_limbs(seed, params, mi).reshape(params.dnum, 2, params.L + params.K, params.N)
+
+
+def slots_uniform(seed: int, n: int, lo: float = -1.0, hi: float = 1.0) -> np.ndarray:
+    """n real slot values uniform in [lo, hi]."""
+    return rng(seed).uniform(lo, hi, size=n)
+
+
+def small_coeffs(seed: int, N: int, bound: int) -> np.ndarray:
+    """int64[N] uniform in [-bound, bound]: an already-encoded plaintext polynomial."""
+    return rng(seed).integers(-bound, bound + 1, size=N, dtype=np.int64)
+
+
+def embeddings(seed: int, samples: int, dim: int = 768) -> np.ndarray:
+    """Stand-in for sentence embeddings: fp64 N(0, 0.5^2) clipped to [-3, 3]."""
+    return np.clip(rng(seed).normal(0.0, 0.5, size=(samples, dim)), -3.0, 3.0)
+
+
+def weights(seed: int, classes: int = 4, dim: int = 768) -> np.ndarray:
+    """Classifier weights: fp64 N(0, 0.05^2)."""
+    return rng(seed).normal(0.0, 0.05, size=(classes, dim))
+
+
+def mixed_levels(seed: int, count: int, lo: int = 8, hi: int = 24, max_log_offset: int = 14):
+    """Levels uniform in [lo, hi] and rotation offsets uniform in {2^0 .. 2^max_log_offset}."""
+    g = rng(seed)
+    levels = g.integers(lo, hi + 1, size=count)
+    offs = 1 << g.integers(0, max_log_offset + 1, size=count)
+    return [int(v) for v in levels], [int(v) for v in offs]
