@@ -1,0 +1,180 @@
+/*
+ * he.h -- C ABI of the MI355X RNS-CKKS ciphertext-arithmetic library.
+ *
+ * The paper (Section 2.2) builds its encrypted logistic regression from the CKKS
+ * operations Add, Mult (slot-wise product, one level consumed) and Rotate and
+ * defers the scheme itself to the CKKS literature.  This library implements the
+ * full-RNS form of those operations with hybrid key switching (dnum digits,
+ * K special primes): negacyclic NTT/iNTT, tensor product + relinearisation,
+ * slot rotation (ModUp, inner product with the evaluation key, ModDown),
+ * rescale, and rotate-and-sum.  Key generation, encoding, encryption and
+ * decryption run on the host; everything else runs in HIP kernels (gfx950) on
+ * device buffers owned by the caller.
+ *
+ * Conventions
+ *  - Moduli: q_0..q_{L-1} (ciphertext primes) then p_0..p_{K-1} (special primes),
+ *    all < 2^62, all = 1 mod 2N.  "Modulus index" i < L means q_i, L+k means p_k.
+ *  - level l = number of limbs present (1..L).  A limb is N uint64 residues in
+ *    [0, q).  Every buffer that crosses this interface holds canonical residues.
+ *  - NTT domain: out[k] = sum_j a[j] psi^((2 brv(k)+1) j) mod q (bit-reversed
+ *    evaluation order), psi = g^((q-1)/2N) with g the least primitive root of q.
+ *  - Ciphertext: uint64 [2][l][N], NTT domain, component 0 = c0, 1 = c1;
+ *    decryption is c0 + c1*s.  Evaluation key: uint64 [dnum][2][L+K][N],
+ *    component 0 = b, 1 = a.
+ *  - Slots: n = N/2 complex values; slot j is the evaluation at
+ *    exp(i pi 5^j / N).  Rotation by r is the left cyclic shift
+ *    out[j] = in[(j+r) mod n].
+ *  - Scale and level are tracked by the caller; the library checks levels only.
+ *  - "h_" arguments are host pointers, "d_" arguments are device pointers
+ *    (hipMalloc'ed or a torch tensor's data_ptr), contiguous and 16-byte aligned,
+ *    owned by the caller.  `stream` is a hipStream_t passed as void* (NULL = the
+ *    default stream).  Device functions only enqueue work: they never
+ *    synchronise and never allocate; results are valid once the stream reaches
+ *    the end of the enqueued work.  Output buffers may alias an input only
+ *    where stated.
+ *  - Every function returns HE_OK (0) or a negative error code; nothing throws
+ *    or aborts.  Handles are freed with the matching _destroy.
+ */
+#ifndef HE_H_
+#define HE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HE_OK 0
+#define HE_EINVAL (-1)     /* null pointer, bad size, modulus not = 1 mod 2N, ... */
+#define HE_ELEVEL (-2)     /* level out of range, or level 1 cannot be rescaled */
+#define HE_ENOKEY (-3)     /* key handle missing or of the wrong kind */
+#define HE_EWORKSPACE (-4) /* workspace too small */
+#define HE_EHIP (-5)       /* a HIP call failed; see he_last_hip_error */
+#define HE_ENODEV (-6)     /* device function called on a host-only context */
+#define HE_ENOMEM (-7)
+
+typedef struct he_ctx he_ctx;
+typedef struct he_sk he_sk;
+typedef struct he_evk he_evk;
+
+typedef struct {
+    int32_t logN;      /* ring degree N = 2^logN; device kernels support logN = 12 and 16 */
+    int32_t L;         /* number of ciphertext primes */
+    int32_t K;         /* number of special primes */
+    int32_t dnum;      /* number of key-switching digits; alpha = ceil(L/dnum) primes per digit */
+    const uint64_t *q; /* [L] */
+    const uint64_t *p; /* [K] */
+} he_params;
+
+/* ---- context -------------------------------------------------------------------------- */
+
+/* Builds all tables (roots of unity, twiddles, base-conversion constants) on the host and,
+ * when device >= 0, uploads them to that HIP device.  device = -1 gives a host-only context on
+ * which the host functions work and every device function returns HE_ENODEV. */
+int32_t he_ctx_create(const he_params *params, int32_t device, he_ctx **out);
+void he_ctx_destroy(he_ctx *ctx);
+const char *he_strerror(int32_t code);
+/* Text of the last HIP error seen by this context ("" if none).  Owned by the context. */
+const char *he_last_hip_error(const he_ctx *ctx);
+/* Modulus i and its 2N-th root of unity psi_i. */
+int32_t he_ctx_modulus(const he_ctx *ctx, int32_t i, uint64_t *modulus, uint64_t *psi);
+/* Galois element 5^r mod 2N of a left rotation by r slots (r may be negative). */
+int32_t he_galois_element(const he_ctx *ctx, int32_t r, uint64_t *g);
+/* The 38 cumulative thresholds of the discrete Gaussian sampler (sigma 3.2, support [-19,19]). */
+int32_t he_gauss_cdt(uint64_t out[38]);
+/* Bytes of device workspace that hmult_relin / hrot / rescale / rotate_sum need at `level`;
+ * max_hoist = largest `count` passed to he_hrot_many (1 if unused). */
+int32_t he_workspace_bytes(const he_ctx *ctx, int32_t level, int32_t max_hoist, size_t *out);
+
+/* ---- host: keys, encoding, encryption (the user side; Section 2.2) ----------------------- */
+
+/* Randomness: word i of stream (seed, tag) is mix(key + (i+1)*G), key = mix(mix(seed+G) + tag*G),
+ * mix = the SplitMix64 finaliser, G = 0x9E3779B97F4A7C15; tag = kind<<32 | digit<<16 | modulus
+ * index, kinds 1 secret, 2 key mask, 3 key error, 4 encryption mask, 5 encryption error.
+ * Uniform residues keep the low bitlen(q) bits of a word and reject values >= q; ternary values
+ * reject words >= 3*floor(2^64/3) and map word mod 3 = 0,1,2 to 0,+1,-1; Gaussian values are
+ * -19 + #{thresholds <= word}. */
+
+/* Ternary secret key. */
+int32_t he_keygen_secret(he_ctx *ctx, uint64_t seed, he_sk **out);
+void he_sk_destroy(he_sk *sk);
+/* Copies the N secret coefficients (-1, 0, +1). */
+int32_t he_sk_coeffs(const he_sk *sk, int8_t *h_out);
+
+/* Switching keys to s: from s^2 (relinearisation) or from sigma_g(s), g = 5^r mod 2N (rotation
+ * by r slots).  For digit j and modulus i: a uniform, e Gaussian,
+ * b = -a*s + e + (q_i in digit j ? P * s' : 0).  The key is kept on the host and, if the
+ * context has a device, uploaded to it. */
+int32_t he_keygen_relin(he_ctx *ctx, const he_sk *sk, uint64_t seed, he_evk **out);
+int32_t he_keygen_rot(he_ctx *ctx, const he_sk *sk, int32_t r, uint64_t seed, he_evk **out);
+/* Wraps a caller-made key-shaped buffer [dnum][2][L+K][N] (host memory, copied) as a key for the
+ * Galois element g (1 = relinearisation): used for throughput runs on synthetic residues. */
+int32_t he_evk_from_host(he_ctx *ctx, const uint64_t *h_evk, uint64_t g, he_evk **out);
+/* Copies the key to host memory, [dnum][2][L+K][N]. */
+int32_t he_evk_to_host(const he_evk *evk, uint64_t *h_out);
+void he_evk_destroy(he_evk *evk);
+
+/* Encode: m_k = rint(scale * (2/N) * Re sum_j z_j zeta_j^(-k)), z zero-padded from n_used to N/2
+ * slots; h_im may be NULL.  Decode is the inverse map on (centred) coefficients given as doubles. */
+int32_t he_encode(const he_ctx *ctx, const double *h_re, const double *h_im, int32_t n_used, double scale,
+                  int64_t *h_coeffs_out);
+int32_t he_decode(const he_ctx *ctx, const double *h_coeffs, double scale, double *h_re, double *h_im);
+/* Integer polynomial -> NTT-domain plaintext [level][N] for he_pmult. */
+int32_t he_plain_to_ntt(const he_ctx *ctx, const int64_t *h_coeffs, int32_t level, uint64_t *h_out);
+/* Symmetric encryption of an integer polynomial: c1 = a uniform, c0 = -a*s + e + m.  Output
+ * [2][level][N] in host memory. */
+int32_t he_encrypt_coeffs(const he_ctx *ctx, const he_sk *sk, const int64_t *h_coeffs, int32_t level, uint64_t seed,
+                          uint64_t *h_ct_out);
+/* c0 + c1*s, inverse NTT, CRT over the first min(level,3) limbs, centred lift -> N doubles. */
+int32_t he_decrypt_coeffs(const he_ctx *ctx, const he_sk *sk, const uint64_t *h_ct, int32_t level, double *h_coeffs);
+/* he_decrypt_coeffs followed by he_decode; h_re / h_im receive N/2 values (h_im may be NULL). */
+int32_t he_decrypt(const he_ctx *ctx, const he_sk *sk, const uint64_t *h_ct, int32_t level, double scale, double *h_re,
+                   double *h_im);
+
+/* ---- device: polynomial arithmetic ---------------------------------------------------------- */
+
+/* In-place forward / inverse negacyclic NTT of `batch` limbs stored back to back at d_limbs
+ * ([batch][N]); limb b is taken modulo modulus index h_mod_idx[b] (host array, read before
+ * return). */
+int32_t he_ntt(he_ctx *ctx, uint64_t *d_limbs, const int32_t *h_mod_idx, int32_t batch, void *stream);
+int32_t he_intt(he_ctx *ctx, uint64_t *d_limbs, const int32_t *h_mod_idx, int32_t batch, void *stream);
+
+/* Add / Sub of two level-`level` ciphertexts (Section 2.2, Add).  d_out may alias d_a or d_b. */
+int32_t he_add(he_ctx *ctx, const uint64_t *d_a, const uint64_t *d_b, uint64_t *d_out, int32_t level, void *stream);
+int32_t he_sub(he_ctx *ctx, const uint64_t *d_a, const uint64_t *d_b, uint64_t *d_out, int32_t level, void *stream);
+/* Ciphertext times NTT-domain plaintext [level][N]; d_out may alias d_ct. */
+int32_t he_pmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *d_pt, uint64_t *d_out, int32_t level,
+                 void *stream);
+/* Ciphertext times one residue per limb (h_scalar[i] in [0,q_i), host array read before return). */
+int32_t he_cmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out, int32_t level,
+                 void *stream);
+
+/* ---- device: the hot path -------------------------------------------------------------------- */
+
+/* Mult without the rescale (Section 2.2, Mult): tensor product d0 = a0 b0, d1 = a0 b1 + a1 b0,
+ * d2 = a1 b1, key switch of d2 with the relinearisation key, out = (d0 + k0, d1 + k1), level
+ * unchanged.  d_out [2][level][N] may alias d_a or d_b. */
+int32_t he_hmult_relin(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a, const uint64_t *d_b, uint64_t *d_out,
+                       int32_t level, void *d_ws, size_t ws_bytes, void *stream);
+/* Drops the last limb with centred rounding: out[i] = (c[i] - [c_last centred]_{q_i}) / q_last.
+ * d_out is [2][level-1][N] and must not alias d_ct. */
+int32_t he_rescale(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level, void *d_ws, size_t ws_bytes,
+                   void *stream);
+/* Rotate: the digits of c1 are raised un-rotated, the automorphism sigma_g is applied to the
+ * raised digits and to c0, then inner product with the key and ModDown:
+ * out = (sigma_g(c0) + k0, k1).  d_out must not alias d_ct. */
+int32_t he_hrot(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level, void *d_ws,
+                size_t ws_bytes, void *stream);
+/* `count` rotations of one ciphertext sharing a single decomposition + ModUp (hoisting);
+ * h_d_outs is a host array of `count` device pointers.  Bit-identical to `count` he_hrot calls. */
+int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t count, const uint64_t *d_ct,
+                     uint64_t *const *h_d_outs, int32_t level, void *d_ws, size_t ws_bytes, void *stream);
+/* for k < count: ct <- ct + Rotate(ct, shift0 * 2^k), in place; rots[k] is the key of that shift. */
+int32_t he_rotate_sum(he_ctx *ctx, const he_evk *const *rots, int32_t count, uint64_t *d_ct, int32_t level,
+                      void *d_ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HE_H_ */

@@ -134,10 +134,14 @@ orc_ctx *orc_ctx_create(int logN, int L, const u64 *q, int K, const u64 *p, int 
         u64 ipsi = invmod(psi, t);
         c->psi[i] = psi;
         c->ninv[i] = invmod(N % t, t);
-        for (u64 k = 0; k < N; k++) {
-            u64 e = bitrev(k, logN);
-            c->psi_br[(u64)i * N + k] = powmod(psi, e, t);
-            c->ipsi_br[(u64)i * N + k] = powmod(ipsi, e, t);
+        /* psi^e for e = 0..N-1, stored at position brv(e) */
+        u64 pw = 1, ipw = 1;
+        for (u64 e = 0; e < N; e++) {
+            u64 k = bitrev(e, logN);
+            c->psi_br[(u64)i * N + k] = pw;
+            c->ipsi_br[(u64)i * N + k] = ipw;
+            pw = mulmod(pw, psi, t);
+            ipw = mulmod(ipw, ipsi, t);
         }
     }
     return c;

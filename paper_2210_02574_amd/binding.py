@@ -1,0 +1,410 @@
+"""ctypes binding of the C ABI declared in include/he.h.
+
+Argument marshalling only: every computation runs inside the shared library.  Device buffers
+are torch int64 tensors on the GPU (their bits are the uint64 residues); host buffers are
+numpy arrays.  The library is loaded from the package directory and a missing build is an
+error, never a fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhe_gfx950.so")
+
+HE_OK = 0
+ERRORS = {
+    -1: "HE_EINVAL", -2: "HE_ELEVEL", -3: "HE_ENOKEY", -4: "HE_EWORKSPACE",
+    -5: "HE_EHIP", -6: "HE_ENODEV", -7: "HE_ENOMEM",
+}
+
+# every symbol include/he.h declares
+SYMBOLS = [
+    "he_ctx_create", "he_ctx_destroy", "he_strerror", "he_last_hip_error", "he_ctx_modulus",
+    "he_galois_element", "he_gauss_cdt", "he_workspace_bytes",
+    "he_keygen_secret", "he_sk_destroy", "he_sk_coeffs", "he_keygen_relin", "he_keygen_rot",
+    "he_evk_from_host", "he_evk_to_host", "he_evk_destroy",
+    "he_encode", "he_decode", "he_plain_to_ntt", "he_encrypt_coeffs", "he_decrypt_coeffs", "he_decrypt",
+    "he_ntt", "he_intt", "he_add", "he_sub", "he_pmult", "he_cmult",
+    "he_hmult_relin", "he_rescale", "he_hrot", "he_hrot_many", "he_rotate_sum",
+]
+
+
+class HeError(RuntimeError):
+    def __init__(self, code: int, where: str, detail: str = ""):
+        self.code = code
+        super().__init__(f"{where}: {ERRORS.get(code, code)}" + (f" ({detail})" if detail else ""))
+
+
+class he_params(ctypes.Structure):
+    _fields_ = [
+        ("logN", ctypes.c_int32), ("L", ctypes.c_int32), ("K", ctypes.c_int32), ("dnum", ctypes.c_int32),
+        ("q", ctypes.POINTER(ctypes.c_uint64)), ("p", ctypes.POINTER(ctypes.c_uint64)),
+    ]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the in-tree HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2210_02574_amd.build` "
+                "(hipcc --offload-arch=gfx950); there is no fallback path"
+            )
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, u64, sz, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint64, ctypes.c_size_t, ctypes.c_double
+        sig = {
+            "he_ctx_create": [ctypes.POINTER(he_params), i32, ctypes.POINTER(vp)],
+            "he_ctx_destroy": [vp],
+            "he_strerror": [i32],
+            "he_last_hip_error": [vp],
+            "he_ctx_modulus": [vp, i32, ctypes.POINTER(u64), ctypes.POINTER(u64)],
+            "he_galois_element": [vp, i32, ctypes.POINTER(u64)],
+            "he_gauss_cdt": [vp],
+            "he_workspace_bytes": [vp, i32, i32, ctypes.POINTER(sz)],
+            "he_keygen_secret": [vp, u64, ctypes.POINTER(vp)],
+            "he_sk_destroy": [vp],
+            "he_sk_coeffs": [vp, vp],
+            "he_keygen_relin": [vp, vp, u64, ctypes.POINTER(vp)],
+            "he_keygen_rot": [vp, vp, i32, u64, ctypes.POINTER(vp)],
+            "he_evk_from_host": [vp, vp, u64, ctypes.POINTER(vp)],
+            "he_evk_to_host": [vp, vp],
+            "he_evk_destroy": [vp],
+            "he_encode": [vp, vp, vp, i32, dbl, vp],
+            "he_decode": [vp, vp, dbl, vp, vp],
+            "he_plain_to_ntt": [vp, vp, i32, vp],
+            "he_encrypt_coeffs": [vp, vp, vp, i32, u64, vp],
+            "he_decrypt_coeffs": [vp, vp, vp, i32, vp],
+            "he_decrypt": [vp, vp, vp, i32, dbl, vp, vp],
+            "he_ntt": [vp, vp, vp, i32, vp],
+            "he_intt": [vp, vp, vp, i32, vp],
+            "he_add": [vp, vp, vp, vp, i32, vp],
+            "he_sub": [vp, vp, vp, vp, i32, vp],
+            "he_pmult": [vp, vp, vp, vp, i32, vp],
+            "he_cmult": [vp, vp, vp, vp, i32, vp],
+            "he_hmult_relin": [vp, vp, vp, vp, vp, i32, vp, sz, vp],
+            "he_rescale": [vp, vp, vp, i32, vp, sz, vp],
+            "he_hrot": [vp, vp, vp, vp, i32, vp, sz, vp],
+            "he_hrot_many": [vp, vp, i32, vp, vp, i32, vp, sz, vp],
+            "he_rotate_sum": [vp, vp, i32, vp, i32, vp, sz, vp],
+        }
+        for name in SYMBOLS:
+            fn = getattr(lib, name)
+            fn.argtypes = sig[name]
+            fn.restype = i32
+        lib.he_strerror.restype = ctypes.c_char_p
+        lib.he_last_hip_error.restype = ctypes.c_char_p
+        for name in ("he_ctx_destroy", "he_sk_destroy", "he_evk_destroy"):
+            getattr(lib, name).restype = None
+        _lib = lib
+    return _lib
+
+
+def _hp(a: np.ndarray):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+class SecretKey:
+    def __init__(self, he, handle):
+        self.he, self.handle = he, handle
+
+    def coeffs(self) -> np.ndarray:
+        out = np.empty(self.he.N, dtype=np.int8)
+        self.he._chk(self.he.lib.he_sk_coeffs(self.handle, _hp(out)), "he_sk_coeffs")
+        return out
+
+    def __del__(self):
+        try:
+            self.he.lib.he_sk_destroy(self.handle)
+        except Exception:
+            pass
+
+
+class EvalKey:
+    def __init__(self, he, handle):
+        self.he, self.handle = he, handle
+
+    def to_host(self) -> np.ndarray:
+        he = self.he
+        out = np.empty((he.dnum, 2, he.M, he.N), dtype=np.uint64)
+        he._chk(he.lib.he_evk_to_host(self.handle, _hp(out)), "he_evk_to_host")
+        return out
+
+    def __del__(self):
+        try:
+            self.he.lib.he_evk_destroy(self.handle)
+        except Exception:
+            pass
+
+
+class HE:
+    """One library context.  device = -1: host functions only; device >= 0: that GPU."""
+
+    def __init__(self, logN: int, q: Sequence[int], p: Sequence[int], dnum: int, device: int = -1):
+        self.lib = load_library()
+        self.logN, self.N, self.n = logN, 1 << logN, 1 << (logN - 1)
+        self.q, self.p = [int(v) for v in q], [int(v) for v in p]
+        self.L, self.K, self.M, self.dnum = len(self.q), len(self.p), len(self.q) + len(self.p), dnum
+        self.alpha = -(-self.L // dnum)
+        self.device = device
+        self._qa = (ctypes.c_uint64 * self.L)(*self.q)
+        self._pa = (ctypes.c_uint64 * self.K)(*self.p)
+        prm = he_params(logN, self.L, self.K, dnum, self._qa, self._pa)
+        h = ctypes.c_void_p()
+        rc = self.lib.he_ctx_create(ctypes.byref(prm), device, ctypes.byref(h))
+        if rc != HE_OK:
+            raise HeError(rc, "he_ctx_create")
+        self.ctx = h
+        self._ws = None
+
+    @classmethod
+    def from_params(cls, params, device: int = -1):
+        return cls(params.logN, params.q, params.p, params.dnum, device)
+
+    def __del__(self):
+        try:
+            self._ws = None
+            self.lib.he_ctx_destroy(self.ctx)
+        except Exception:
+            pass
+
+    def _chk(self, rc: int, where: str):
+        if rc != HE_OK:
+            detail = self.lib.he_last_hip_error(self.ctx).decode() if rc == -5 else ""
+            raise HeError(rc, where, detail)
+
+    # ---- context queries --------------------------------------------------------------------
+    def modulus(self, i: int):
+        m, psi = ctypes.c_uint64(), ctypes.c_uint64()
+        self._chk(self.lib.he_ctx_modulus(self.ctx, i, ctypes.byref(m), ctypes.byref(psi)), "he_ctx_modulus")
+        return int(m.value), int(psi.value)
+
+    def galois_element(self, r: int) -> int:
+        g = ctypes.c_uint64()
+        self._chk(self.lib.he_galois_element(self.ctx, r, ctypes.byref(g)), "he_galois_element")
+        return int(g.value)
+
+    def gauss_cdt(self) -> List[int]:
+        out = np.empty(38, dtype=np.uint64)
+        self._chk(self.lib.he_gauss_cdt(_hp(out)), "he_gauss_cdt")
+        return [int(v) for v in out]
+
+    def workspace_bytes(self, level: int, max_hoist: int = 1) -> int:
+        out = ctypes.c_size_t()
+        self._chk(self.lib.he_workspace_bytes(self.ctx, level, max_hoist, ctypes.byref(out)), "he_workspace_bytes")
+        return int(out.value)
+
+    # ---- host: keys ----------------------------------------------------------------------------
+    def keygen_secret(self, seed: int) -> SecretKey:
+        h = ctypes.c_void_p()
+        self._chk(self.lib.he_keygen_secret(self.ctx, seed, ctypes.byref(h)), "he_keygen_secret")
+        return SecretKey(self, h)
+
+    def keygen_relin(self, sk: SecretKey, seed: int) -> EvalKey:
+        h = ctypes.c_void_p()
+        self._chk(self.lib.he_keygen_relin(self.ctx, sk.handle, seed, ctypes.byref(h)), "he_keygen_relin")
+        return EvalKey(self, h)
+
+    def keygen_rot(self, sk: SecretKey, r: int, seed: int) -> EvalKey:
+        h = ctypes.c_void_p()
+        self._chk(self.lib.he_keygen_rot(self.ctx, sk.handle, r, seed, ctypes.byref(h)), "he_keygen_rot")
+        return EvalKey(self, h)
+
+    def evk_from_host(self, evk: np.ndarray, g: int = 1) -> EvalKey:
+        evk = np.ascontiguousarray(evk, dtype=np.uint64)
+        assert evk.shape == (self.dnum, 2, self.M, self.N)
+        h = ctypes.c_void_p()
+        self._chk(self.lib.he_evk_from_host(self.ctx, _hp(evk), g, ctypes.byref(h)), "he_evk_from_host")
+        return EvalKey(self, h)
+
+    # ---- host: encode / encrypt / decrypt -----------------------------------------------------------
+    def encode(self, z, scale: float) -> np.ndarray:
+        z = np.asarray(z)
+        re = np.ascontiguousarray(z.real, dtype=np.float64)
+        im = np.ascontiguousarray(z.imag, dtype=np.float64) if np.iscomplexobj(z) else None
+        out = np.empty(self.N, dtype=np.int64)
+        self._chk(
+            self.lib.he_encode(self.ctx, _hp(re), _hp(im) if im is not None else None, re.shape[0], scale, _hp(out)),
+            "he_encode",
+        )
+        return out
+
+    def decode(self, coeffs, scale: float) -> np.ndarray:
+        m = np.ascontiguousarray(coeffs, dtype=np.float64)
+        re, im = np.empty(self.n), np.empty(self.n)
+        self._chk(self.lib.he_decode(self.ctx, _hp(m), scale, _hp(re), _hp(im)), "he_decode")
+        return re + 1j * im
+
+    def plain_to_ntt(self, coeffs: np.ndarray, level: int) -> np.ndarray:
+        m = np.ascontiguousarray(coeffs, dtype=np.int64)
+        out = np.empty((level, self.N), dtype=np.uint64)
+        self._chk(self.lib.he_plain_to_ntt(self.ctx, _hp(m), level, _hp(out)), "he_plain_to_ntt")
+        return out
+
+    def encrypt_coeffs(self, sk: SecretKey, coeffs: np.ndarray, level: int, seed: int) -> np.ndarray:
+        m = np.ascontiguousarray(coeffs, dtype=np.int64)
+        assert m.shape == (self.N,)
+        out = np.empty((2, level, self.N), dtype=np.uint64)
+        self._chk(self.lib.he_encrypt_coeffs(self.ctx, sk.handle, _hp(m), level, seed, _hp(out)), "he_encrypt_coeffs")
+        return out
+
+    def decrypt_coeffs(self, sk: SecretKey, ct: np.ndarray) -> np.ndarray:
+        ct = np.ascontiguousarray(ct, dtype=np.uint64)
+        level = ct.shape[1]
+        out = np.empty(self.N, dtype=np.float64)
+        self._chk(self.lib.he_decrypt_coeffs(self.ctx, sk.handle, _hp(ct), level, _hp(out)), "he_decrypt_coeffs")
+        return out
+
+    def decrypt(self, sk: SecretKey, ct: np.ndarray, scale: float) -> np.ndarray:
+        ct = np.ascontiguousarray(ct, dtype=np.uint64)
+        level = ct.shape[1]
+        re, im = np.empty(self.n), np.empty(self.n)
+        self._chk(self.lib.he_decrypt(self.ctx, sk.handle, _hp(ct), level, scale, _hp(re), _hp(im)), "he_decrypt")
+        return re + 1j * im
+
+    # ---- device plumbing (torch: memory and streams only) ----------------------------------------------
+    def to_device(self, a: np.ndarray):
+        import torch
+
+        a = np.ascontiguousarray(a, dtype=np.uint64)
+        return torch.from_numpy(a.view(np.int64)).to(f"cuda:{self.device}")
+
+    @staticmethod
+    def to_host(t) -> np.ndarray:
+        return t.detach().cpu().contiguous().numpy().view(np.uint64)
+
+    def empty_ct(self, level: int):
+        import torch
+
+        return torch.empty((2, level, self.N), dtype=torch.int64, device=f"cuda:{self.device}")
+
+    def _stream(self):
+        import torch
+
+        return ctypes.c_void_p(torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _workspace(self, level: int):
+        import torch
+
+        need = self.workspace_bytes(level)
+        if self._ws is None or self._ws.numel() * 8 < need:
+            self._ws = None
+            self._ws = torch.empty(need // 8, dtype=torch.int64, device=f"cuda:{self.device}")
+        return ctypes.c_void_p(self._ws.data_ptr()), self._ws.numel() * 8
+
+    @staticmethod
+    def _dp(t):
+        assert t.is_cuda and t.is_contiguous() and t.element_size() == 8
+        return ctypes.c_void_p(t.data_ptr())
+
+    # ---- device: polynomial arithmetic --------------------------------------------------------------------
+    def ntt(self, limbs, mod_idx: Sequence[int]):
+        mi = np.ascontiguousarray(mod_idx, dtype=np.int32)
+        assert limbs.numel() == mi.shape[0] * self.N
+        self._chk(self.lib.he_ntt(self.ctx, self._dp(limbs), _hp(mi), mi.shape[0], self._stream()), "he_ntt")
+        return limbs
+
+    def intt(self, limbs, mod_idx: Sequence[int]):
+        mi = np.ascontiguousarray(mod_idx, dtype=np.int32)
+        assert limbs.numel() == mi.shape[0] * self.N
+        self._chk(self.lib.he_intt(self.ctx, self._dp(limbs), _hp(mi), mi.shape[0], self._stream()), "he_intt")
+        return limbs
+
+    def _level(self, ct) -> int:
+        assert ct.dim() == 3 and ct.shape[0] == 2 and ct.shape[2] == self.N
+        return int(ct.shape[1])
+
+    def add(self, a, b, out=None):
+        level = self._level(a)
+        assert b.shape == a.shape
+        out = self.empty_ct(level) if out is None else out
+        self._chk(self.lib.he_add(self.ctx, self._dp(a), self._dp(b), self._dp(out), level, self._stream()), "he_add")
+        return out
+
+    def sub(self, a, b, out=None):
+        level = self._level(a)
+        assert b.shape == a.shape
+        out = self.empty_ct(level) if out is None else out
+        self._chk(self.lib.he_sub(self.ctx, self._dp(a), self._dp(b), self._dp(out), level, self._stream()), "he_sub")
+        return out
+
+    def pmult(self, ct, pt, out=None):
+        level = self._level(ct)
+        assert tuple(pt.shape) == (level, self.N)
+        out = self.empty_ct(level) if out is None else out
+        self._chk(
+            self.lib.he_pmult(self.ctx, self._dp(ct), self._dp(pt), self._dp(out), level, self._stream()), "he_pmult"
+        )
+        return out
+
+    def cmult(self, ct, scalars: Sequence[int], out=None):
+        level = self._level(ct)
+        sc = np.array([int(v) for v in scalars], dtype=np.uint64)
+        assert sc.shape == (level,)
+        out = self.empty_ct(level) if out is None else out
+        self._chk(self.lib.he_cmult(self.ctx, self._dp(ct), _hp(sc), self._dp(out), level, self._stream()), "he_cmult")
+        return out
+
+    # ---- device: hot path ----------------------------------------------------------------------------------------
+    def hmult_relin(self, relin: EvalKey, a, b, out=None):
+        level = self._level(a)
+        assert b.shape == a.shape
+        out = self.empty_ct(level) if out is None else out
+        ws, wsb = self._workspace(level)
+        self._chk(
+            self.lib.he_hmult_relin(
+                self.ctx, relin.handle, self._dp(a), self._dp(b), self._dp(out), level, ws, wsb, self._stream()
+            ),
+            "he_hmult_relin",
+        )
+        return out
+
+    def rescale(self, ct, out=None):
+        level = self._level(ct)
+        out = self.empty_ct(level - 1) if out is None else out
+        ws, wsb = self._workspace(level)
+        self._chk(
+            self.lib.he_rescale(self.ctx, self._dp(ct), self._dp(out), level, ws, wsb, self._stream()), "he_rescale"
+        )
+        return out
+
+    def hrot(self, rot: EvalKey, ct, out=None):
+        level = self._level(ct)
+        out = self.empty_ct(level) if out is None else out
+        ws, wsb = self._workspace(level)
+        self._chk(
+            self.lib.he_hrot(self.ctx, rot.handle, self._dp(ct), self._dp(out), level, ws, wsb, self._stream()),
+            "he_hrot",
+        )
+        return out
+
+    def hrot_many(self, rots: Sequence[EvalKey], ct, outs=None):
+        level = self._level(ct)
+        n = len(rots)
+        outs = [self.empty_ct(level) for _ in range(n)] if outs is None else outs
+        keys = (ctypes.c_void_p * n)(*[k.handle for k in rots])
+        ptrs = (ctypes.c_void_p * n)(*[o.data_ptr() for o in outs])
+        ws, wsb = self._workspace(level)
+        self._chk(
+            self.lib.he_hrot_many(self.ctx, keys, n, self._dp(ct), ptrs, level, ws, wsb, self._stream()),
+            "he_hrot_many",
+        )
+        return outs
+
+    def rotate_sum(self, rots: Sequence[EvalKey], ct):
+        level = self._level(ct)
+        n = len(rots)
+        keys = (ctypes.c_void_p * n)(*[k.handle for k in rots])
+        ws, wsb = self._workspace(level)
+        self._chk(
+            self.lib.he_rotate_sum(self.ctx, keys, n, self._dp(ct), level, ws, wsb, self._stream()), "he_rotate_sum"
+        )
+        return ct
