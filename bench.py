@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Benchmark of the RNS-CKKS hot path on one MI355X.
+
+One step = one pass of the whole hot path at N=2^16, L=24, K=4, dnum=6 over synthetic residues:
+  * 256 limb NTT + iNTT pairs (limb b modulo modulus b mod 28),
+  * 64 independent HMult + relinearisation + rescale on level-24 ciphertexts,
+  * 15 hoisted rotations of one level-24 ciphertext by 2^0 .. 2^14,
+  * 128 single rotations at mixed levels 8..24.
+Every step therefore performs 64 + 15 + 128 = 207 key switches; `value` is key switches per
+second over the whole step with all inputs resident in HBM.  The line also carries the roofline
+of the kernel that takes the most time (measured with HIP events inside the library over a
+repeat of the timed steps) and the CPU oracle timed on a bounded sample of the same workload.
+
+Contract: python bench.py --gpus 1 --steps K --warmup W  -> one JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+# HBM traffic per launch of the dominant kernels from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`
+# runs of this command (summaries under profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+class Workload:
+    """Device-resident synthetic inputs of one step and the step itself."""
+
+    N_NTT = 256
+    N_HMULT = 64
+    N_SINGLE = 128
+
+    def __init__(self, he, seed: int = 2, n_hmult: int = None, n_single: int = None, n_ntt: int = None):
+        import torch
+
+        self.torch = torch
+        self.he = he
+        p = self.params = wl.N16
+        self.n_hmult = self.N_HMULT if n_hmult is None else n_hmult
+        self.n_single = self.N_SINGLE if n_single is None else n_single
+        self.n_ntt = self.N_NTT if n_ntt is None else n_ntt
+        self.dev = torch.device(f"cuda:{he.device}")
+        self.gen = torch.Generator(device=self.dev)
+        self.gen.manual_seed(seed)
+        M = p.L + p.K
+        self.ntt_mods = [b % M for b in range(self.n_ntt)]
+        self.ntt_limbs = self._uniform(self.ntt_mods)
+        L = p.L
+        self.hm_a = [self._uniform_ct(L) for _ in range(self.n_hmult)]
+        self.hm_b = [self._uniform_ct(L) for _ in range(self.n_hmult)]
+        self.hm_out = [he.empty_ct(L) for _ in range(self.n_hmult)]
+        self.rs_out = [he.empty_ct(L - 1) for _ in range(self.n_hmult)]
+        # keys: uniform residues in key layout (throughput does not depend on the values)
+        self.key_host = {}
+        self.relin = self._key(1000, 1)
+        self.offsets = [1 << k for k in range(15)]
+        self.rot = [self._key(1001 + k, he.galois_element(r)) for k, r in enumerate(self.offsets)]
+        self.hoist_in = self._uniform_ct(L)
+        self.hoist_out = [he.empty_ct(L) for _ in self.offsets]
+        levels, offs = wl.mixed_levels(seed + 1, self.n_single)
+        self.single_levels = levels
+        self.single_keys = [self.offsets.index(o) for o in offs]
+        self.single_in = [self._uniform_ct(lv) for lv in levels]
+        self.single_out = [he.empty_ct(lv) for lv in levels]
+        self.key_switches = self.n_hmult + len(self.offsets) + self.n_single
+
+    def _uniform(self, mod_idx):
+        torch = self.torch
+        mods = self.params.moduli
+        out = torch.empty((len(mod_idx), self.params.N), dtype=torch.int64, device=self.dev)
+        for b, mi in enumerate(mod_idx):
+            out[b].random_(0, mods[mi], generator=self.gen)
+        return out
+
+    def _uniform_ct(self, level):
+        return self._uniform(list(range(level)) * 2).view(2, level, self.params.N)
+
+    def _key(self, seed, g):
+        evk = wl.uniform_evk(seed, self.params)
+        return self.he.evk_from_host(evk, g)
+
+    def step(self, marks=None):
+        he = self.he
+
+        def mark(name):
+            if marks is not None:
+                ev = self.torch.cuda.Event(enable_timing=True)
+                ev.record()
+                marks.append((name, ev))
+
+        mark("start")
+        he.ntt(self.ntt_limbs, self.ntt_mods)
+        he.intt(self.ntt_limbs, self.ntt_mods)
+        mark("ntt_pairs")
+        for i in range(self.n_hmult):
+            he.hmult_relin(self.relin, self.hm_a[i], self.hm_b[i], out=self.hm_out[i])
+            he.rescale(self.hm_out[i], out=self.rs_out[i])
+        mark("hmult_relin_rescale")
+        he.hrot_many(self.rot, self.hoist_in, outs=self.hoist_out)
+        mark("hrot_hoisted")
+        for i in range(self.n_single):
+            he.hrot(self.rot[self.single_keys[i]], self.single_in[i], out=self.single_out[i])
+        mark("hrot_single")
+
+
+def cpu_baseline(sample_hrot: int = 8, sample_hmult: int = 4, sample_ntt: int = 28):
+    """The oracle, as it stands, on a bounded sample of the step: NTT/iNTT pairs, HMult+relin+rescale
+    and HRot at level 24; reported in key switches per second."""
+    import oracle
+
+    p = wl.N16
+    o = oracle.Oracle(p.logN, p.q, p.p, p.dnum)
+    cores = int(o.lib.orc_num_threads())
+    mods = list(range(sample_ntt))
+    limbs = wl.uniform_limbs(11, p, mods)
+    evk = wl.uniform_evk(12, p)
+    a, b = wl.uniform_ct(13, p, p.L), wl.uniform_ct(14, p, p.L)
+    t0 = time.perf_counter()
+    f = o.ntt(limbs, mods)
+    o.intt(f, mods)
+    t_ntt = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for _ in range(sample_hmult):
+        o.rescale(o.hmult_relin(a, b, evk))
+    t_hm = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for _ in range(sample_hrot):
+        o.hrot(a, evk, 1)
+    t_rot = time.perf_counter() - t0
+    ks = sample_hmult + sample_hrot
+    return {
+        "value": ks / (t_hm + t_rot),
+        "unit": "key-switches/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"{sample_hmult} HMult+relin+rescale and {sample_hrot} HRot at level 24 (N=2^16, dnum=6), "
+                  f"plus {sample_ntt} limb NTT+iNTT pairs",
+        "seconds": round(t_ntt + t_hm + t_rot, 3),
+        "ntt_pairs_per_s": sample_ntt / t_ntt,
+        "hmult_relin_rescale_per_s": sample_hmult / t_hm,
+        "hrot_per_s": sample_hrot / t_rot,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2210_02574_amd as pkg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    he = pkg.HE.from_params(wl.N16, device=0)
+    w = Workload(he)
+    for _ in range(args.warmup):
+        w.step()
+    torch.cuda.synchronize()
+    marks = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        w.step(marks)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    # segment times from events on the launch stream
+    seg = {}
+    for (n0, e0), (n1, e1) in zip(marks[:-1], marks[1:]):
+        if n1 != "start":
+            seg[n1] = seg.get(n1, 0.0) + e0.elapsed_time(e1)
+    p = wl.N16
+    limb_bytes = p.N * 8
+    seg_s = {k: v / 1e3 / args.steps for k, v in seg.items()}
+    detail = {
+        "ntt_pairs_per_s": w.n_ntt / seg_s["ntt_pairs"],
+        # read + write of every limb, forward and inverse: the definition's bytes
+        "ntt_effective_GBps": w.n_ntt * 2 * 2 * limb_bytes / seg_s["ntt_pairs"] / 1e9,
+        "hmult_relin_rescale_per_s": w.n_hmult / seg_s["hmult_relin_rescale"],
+        "hrot_hoisted_per_s": len(w.offsets) / seg_s["hrot_hoisted"],
+        "hrot_single_mixed_levels_per_s": w.n_single / seg_s["hrot_single"],
+        "segment_ms": {k: round(v * 1e3, 3) for k, v in seg_s.items()},
+    }
+
+    # the same steps again with per-kernel HIP events inside the library
+    he.profile_start()
+    for _ in range(args.steps):
+        w.step()
+    stats = he.profile_stop()
+    dom = max(stats.items(), key=lambda kv: kv[1][1])
+    name, (launches, total_ms, nbytes) = dom
+    achieved = nbytes / (total_ms / 1e3) / 1e9
+    roofline = {
+        "kernel": name,
+        "bound": "hbm",
+        "achieved": achieved,
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+        "launches": launches,
+        "avg_launch_us": total_ms * 1e3 / launches,
+        "bytes_per_launch": nbytes / launches,
+    }
+    kernels = {
+        k: {"launches": v[0], "total_ms": round(v[1], 3), "GBps": round(v[2] / (v[1] / 1e3) / 1e9, 1) if v[1] else None}
+        for k, v in sorted(stats.items(), key=lambda kv: -kv[1][1])
+    }
+
+    out = {
+        "metric": "HRot key-switches/sec at N=2^16 L=24 (whole step: NTT pairs + HMult+relin+rescale + hoisted and "
+                  "single HRot)",
+        "value": w.key_switches * args.steps / dt,
+        "unit": "key-switches/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64",
+        "data": "synthetic",
+        "config": {
+            "workload": "N=2^16, L=24, K=4, dnum=6: 256 limb NTT+iNTT pairs, 64 HMult+relin+rescale at level 24, "
+                        "15 hoisted HRot (2^0..2^14) at level 24, 128 single HRot at levels 8..24",
+            "key_switches_per_step": w.key_switches,
+        },
+        "detail": detail,
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -174,6 +174,22 @@ int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t count, cons
 int32_t he_rotate_sum(he_ctx *ctx, const he_evk *const *rots, int32_t count, uint64_t *d_ct, int32_t level,
                       void *d_ws, size_t ws_bytes, void *stream);
 
+/* ---- measurement ------------------------------------------------------------------------- */
+
+/* Per-kernel timing for benchmarks: between start and stop every kernel the library launches is
+ * bracketed by a pair of HIP events on its stream.  Stop waits for the recorded events and fills
+ * `out` with one entry per kernel that ran: launch count, summed duration, and the summed bytes
+ * each launch has to move by the definition of its step (inputs read once + outputs written
+ * once).  Not thread safe; keep it off in production paths. */
+typedef struct {
+    char name[48];
+    int64_t launches;
+    double total_ms;
+    double bytes;
+} he_kernel_stat;
+int32_t he_profile_start(he_ctx *ctx);
+int32_t he_profile_stop(he_ctx *ctx, he_kernel_stat *out, int32_t max_out, int32_t *n_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,6 +22,7 @@
  * bit-reversed evaluation order.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -89,6 +90,9 @@ u64 orc_least_primitive_root(u64 t)
     }
     return 0;
 }
+
+/* number of OpenMP threads the limb-parallel loops use (reported by the benchmark) */
+int orc_num_threads(void) { return omp_get_max_threads(); }
 
 /* ---------------------------------------------------------------- context */
 

@@ -31,6 +31,7 @@ SYMBOLS = [
     "he_encode", "he_decode", "he_plain_to_ntt", "he_encrypt_coeffs", "he_decrypt_coeffs", "he_decrypt",
     "he_ntt", "he_intt", "he_add", "he_sub", "he_pmult", "he_cmult",
     "he_hmult_relin", "he_rescale", "he_hrot", "he_hrot_many", "he_rotate_sum",
+    "he_profile_start", "he_profile_stop",
 ]
 
 
@@ -38,6 +39,13 @@ class HeError(RuntimeError):
     def __init__(self, code: int, where: str, detail: str = ""):
         self.code = code
         super().__init__(f"{where}: {ERRORS.get(code, code)}" + (f" ({detail})" if detail else ""))
+
+
+class he_kernel_stat(ctypes.Structure):
+    _fields_ = [
+        ("name", ctypes.c_char * 48), ("launches", ctypes.c_int64), ("total_ms", ctypes.c_double),
+        ("bytes", ctypes.c_double),
+    ]
 
 
 class he_params(ctypes.Structure):
@@ -95,6 +103,8 @@ def load_library() -> ctypes.CDLL:
             "he_hrot": [vp, vp, vp, vp, i32, vp, sz, vp],
             "he_hrot_many": [vp, vp, i32, vp, vp, i32, vp, sz, vp],
             "he_rotate_sum": [vp, vp, i32, vp, i32, vp, sz, vp],
+            "he_profile_start": [vp],
+            "he_profile_stop": [vp, vp, i32, ctypes.POINTER(i32)],
         }
         for name in SYMBOLS:
             fn = getattr(lib, name)
@@ -408,3 +418,15 @@ class HE:
             self.lib.he_rotate_sum(self.ctx, keys, n, self._dp(ct), level, ws, wsb, self._stream()), "he_rotate_sum"
         )
         return ct
+
+    # ---- measurement -------------------------------------------------------------------------------------------------
+    def profile_start(self):
+        self._chk(self.lib.he_profile_start(self.ctx), "he_profile_start")
+
+    def profile_stop(self):
+        """Per-kernel {name: (launches, total_ms, bytes)} since profile_start."""
+        buf = (he_kernel_stat * 32)()
+        n = ctypes.c_int32()
+        self._chk(self.lib.he_profile_stop(self.ctx, buf, 32, ctypes.byref(n)), "he_profile_stop")
+        return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms), float(buf[i].bytes))
+                for i in range(n.value)}

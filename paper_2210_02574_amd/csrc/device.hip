@@ -541,6 +541,79 @@ extern "C" int32_t he_evk_to_host(const he_evk *evk, uint64_t *h_out)
     return HE_OK;
 }
 
+// ---- optional per-kernel timing with HIP events on the launch stream (he_profile_start/stop)
+enum KernelId {
+    KID_NTT_FWD_COLS, KID_NTT_FWD_BLOCKS, KID_NTT_INV_BLOCKS, KID_NTT_INV_COLS, KID_LIMBWISE, KID_CMULT, KID_TENSOR,
+    KID_MODUP, KID_INNER, KID_MODDOWN_CONV, KID_MODDOWN_FIN, KID_RESCALE_CONV, KID_RESCALE_FIN, KID_COPY, KID_COUNT
+};
+static const char *const kKernelNames[KID_COUNT] = {
+    "k_ntt_fwd_cols", "k_ntt_fwd_blocks", "k_ntt_inv_blocks", "k_ntt_inv_cols", "k_limbwise", "k_cmult", "k_tensor",
+    "k_modup", "k_inner", "k_moddown_conv", "k_moddown_fin", "k_rescale_conv", "k_rescale_fin", "copy"};
+
+static void prof_begin(he_ctx *c, hipStream_t st, int kid, double bytes)
+{
+    ProfRecord r;
+    r.kid = kid;
+    r.bytes = bytes;
+    r.a = r.b = nullptr;
+    if (hipEventCreate((hipEvent_t *)&r.a) != hipSuccess || hipEventCreate((hipEvent_t *)&r.b) != hipSuccess) return;
+    (void)hipEventRecord((hipEvent_t)r.a, st);
+    c->prof.push_back(r);
+}
+static void prof_end(he_ctx *c, hipStream_t st)
+{
+    if (!c->prof.empty()) (void)hipEventRecord((hipEvent_t)c->prof.back().b, st);
+}
+// Launch wrapper: `bytes` = bytes the launch has to move by the definition of its step
+#define KLAUNCH(c, st, kid, bytes, ...)                                                                              \
+    do {                                                                                                             \
+        if ((c)->prof_on) prof_begin((c), (st), (kid), (double)(bytes));                                             \
+        __VA_ARGS__;                                                                                                 \
+        if ((c)->prof_on) prof_end((c), (st));                                                                       \
+    } while (0)
+
+extern "C" int32_t he_profile_start(he_ctx *ctx)
+{
+    if (!ctx) return HE_EINVAL;
+    if (ctx->device < 0) return HE_ENODEV;
+    ctx->prof_on = true;
+    return HE_OK;
+}
+
+extern "C" int32_t he_profile_stop(he_ctx *ctx, he_kernel_stat *out, int32_t max_out, int32_t *n_out)
+{
+    if (!ctx || !out || !n_out || max_out < 0) return HE_EINVAL;
+    ctx->prof_on = false;
+    double ms[KID_COUNT] = {0}, bytes[KID_COUNT] = {0};
+    int64_t cnt[KID_COUNT] = {0};
+    int32_t rc = HE_OK;
+    for (ProfRecord &r : ctx->prof) {
+        float t = 0.f;
+        if (r.a && r.b && hipEventSynchronize((hipEvent_t)r.b) == hipSuccess &&
+            hipEventElapsedTime(&t, (hipEvent_t)r.a, (hipEvent_t)r.b) == hipSuccess) {
+            ms[r.kid] += t;
+            bytes[r.kid] += r.bytes;
+            cnt[r.kid]++;
+        } else
+            rc = HE_EHIP;
+        if (r.a) (void)hipEventDestroy((hipEvent_t)r.a);
+        if (r.b) (void)hipEventDestroy((hipEvent_t)r.b);
+    }
+    ctx->prof.clear();
+    int32_t n = 0;
+    for (int k = 0; k < KID_COUNT && n < max_out; k++) {
+        if (!cnt[k]) continue;
+        memset(&out[n], 0, sizeof(out[n]));
+        strncpy(out[n].name, kKernelNames[k], sizeof(out[n].name) - 1);
+        out[n].launches = cnt[k];
+        out[n].total_ms = ms[k];
+        out[n].bytes = bytes[k];
+        n++;
+    }
+    *n_out = n;
+    return rc;
+}
+
 static inline int32_t launch_ok(he_ctx *c)
 {
     hipError_t e = hipGetLastError();
@@ -563,21 +636,25 @@ static int32_t run_ntt(he_ctx *c, u64 *base, const std::vector<int> &slots, cons
             lb.slot[b] = (uint16_t)slots[off + b];
             lb.mod[b] = (uint8_t)mods[off + b];
         }
+        // each pass reads and writes every limb of the batch once
+        const double bytes = (double)nb * (double)c->N * 16.0;
         if (c->logN == 16) {
             if (!inverse) {
-                k_ntt_fwd_cols16<<<16 * nb, 256, 0, st>>>(base, c->dev, lb);
-                k_ntt_fwd_blocks<16><<<16 * nb, 256, 0, st>>>(base, c->dev, lb);
+                KLAUNCH(c, st, KID_NTT_FWD_COLS, bytes, k_ntt_fwd_cols16<<<16 * nb, 256, 0, st>>>(base, c->dev, lb));
+                KLAUNCH(c, st, KID_NTT_FWD_BLOCKS, bytes,
+                        k_ntt_fwd_blocks<16><<<16 * nb, 256, 0, st>>>(base, c->dev, lb));
             } else {
-                k_ntt_inv_blocks<16><<<16 * nb, 256, 0, st>>>(base, c->dev, lb);
-                k_ntt_inv_cols16<<<16 * nb, 256, 0, st>>>(base, c->dev, lb);
+                KLAUNCH(c, st, KID_NTT_INV_BLOCKS, bytes,
+                        k_ntt_inv_blocks<16><<<16 * nb, 256, 0, st>>>(base, c->dev, lb));
+                KLAUNCH(c, st, KID_NTT_INV_COLS, bytes, k_ntt_inv_cols16<<<16 * nb, 256, 0, st>>>(base, c->dev, lb));
             }
         } else {
             if (!inverse) {
-                k_ntt_fwd_cols12<<<nb, 256, 0, st>>>(base, c->dev, lb);
-                k_ntt_fwd_blocks<12><<<nb, 256, 0, st>>>(base, c->dev, lb);
+                KLAUNCH(c, st, KID_NTT_FWD_COLS, bytes, k_ntt_fwd_cols12<<<nb, 256, 0, st>>>(base, c->dev, lb));
+                KLAUNCH(c, st, KID_NTT_FWD_BLOCKS, bytes, k_ntt_fwd_blocks<12><<<nb, 256, 0, st>>>(base, c->dev, lb));
             } else {
-                k_ntt_inv_blocks<12><<<nb, 256, 0, st>>>(base, c->dev, lb);
-                k_ntt_inv_cols12<<<nb, 256, 0, st>>>(base, c->dev, lb);
+                KLAUNCH(c, st, KID_NTT_INV_BLOCKS, bytes, k_ntt_inv_blocks<12><<<nb, 256, 0, st>>>(base, c->dev, lb));
+                KLAUNCH(c, st, KID_NTT_INV_COLS, bytes, k_ntt_inv_cols12<<<nb, 256, 0, st>>>(base, c->dev, lb));
             }
         }
         int32_t rc = launch_ok(c);
@@ -639,7 +716,8 @@ static int32_t limbwise(he_ctx *c, const u64 *a, const u64 *b, u64 *out, int lev
     if (rc != HE_OK) return rc;
     if (!a || !b || !out) return HE_EINVAL;
     dim3 grid((unsigned)(c->N / 256), (unsigned)limbs);
-    k_limbwise<<<grid, 256, 0, (hipStream_t)stream>>>(a, b, out, c->dev, op, level, b_limbs, c->logN);
+    KLAUNCH(c, (hipStream_t)stream, KID_LIMBWISE, (double)(2 * limbs + b_limbs) * c->N * 8.0,
+            k_limbwise<<<grid, 256, 0, (hipStream_t)stream>>>(a, b, out, c->dev, op, level, b_limbs, c->logN));
     return launch_ok(c);
 }
 
@@ -672,7 +750,8 @@ extern "C" int32_t he_cmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h
         sc.s[i] = hostmath::shoup(h_scalar[i], ctx->mod[i]);
     }
     dim3 grid((unsigned)(ctx->N / 256), (unsigned)(2 * level));
-    k_cmult<<<grid, 256, 0, (hipStream_t)stream>>>(d_ct, d_out, ctx->dev, sc, level, ctx->logN);
+    KLAUNCH(ctx, (hipStream_t)stream, KID_CMULT, 4.0 * level * ctx->N * 8.0,
+            k_cmult<<<grid, 256, 0, (hipStream_t)stream>>>(d_ct, d_out, ctx->dev, sc, level, ctx->logN));
     return launch_ok(ctx);
 }
 
@@ -714,7 +793,10 @@ static int32_t ks_raise(he_ctx *c, const u64 *d_ntt, u64 *ws, const WsLayout &w,
     int32_t rc = run_ntt(c, ws + w.x * N, slots, mods, true, st);
     if (rc != HE_OK) return rc;
     dim3 grid((unsigned)(N / 256), (unsigned)beta);
-    k_modup<<<grid, 256, 0, st>>>(ws + w.x * N, d_ntt, ws + w.raised * N, c->dev, level, c->L, K, c->alpha, c->logN);
+    // reads the level coefficient-domain limbs (and the NTT-domain copies), writes beta*(level+K) limbs
+    KLAUNCH(c, st, KID_MODUP, (double)(2 * level + beta * Ma) * N * 8.0,
+            k_modup<<<grid, 256, 0, st>>>(ws + w.x * N, d_ntt, ws + w.raised * N, c->dev, level, c->L, K, c->alpha,
+                                          c->logN));
     if ((rc = launch_ok(c)) != HE_OK) return rc;
     slots.clear(), mods.clear();
     for (int j = 0; j < beta; j++) {
@@ -737,7 +819,10 @@ static int32_t ks_apply(he_ctx *c, const he_evk *evk, u64 *ws, const WsLayout &w
     const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha;
     const unsigned g = (unsigned)evk->galois;
     dim3 grid((unsigned)(N / 256), (unsigned)Ma);
-    k_inner<<<grid, 256, 0, st>>>(ws + w.raised * N, evk->dev, ws + w.u * N, c->dev, level, c->L, K, beta, g, c->logN);
+    // reads beta raised limbs and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
+    KLAUNCH(c, st, KID_INNER, (double)(3 * beta + 2) * Ma * N * 8.0,
+            k_inner<<<grid, 256, 0, st>>>(ws + w.raised * N, evk->dev, ws + w.u * N, c->dev, level, c->L, K, beta, g,
+                                          c->logN));
     int32_t rc = launch_ok(c);
     if (rc != HE_OK) return rc;
     std::vector<int> slots, mods;
@@ -745,14 +830,17 @@ static int32_t ks_apply(he_ctx *c, const he_evk *evk, u64 *ws, const WsLayout &w
         for (int k = 0; k < K; k++) slots.push_back(cc * Ma + level + k), mods.push_back(c->L + k);
     if ((rc = run_ntt(c, ws + w.u * N, slots, mods, true, st)) != HE_OK) return rc;
     dim3 grid2((unsigned)(N / 256), 2);
-    k_moddown_conv<<<grid2, 256, 0, st>>>(ws + w.u * N, ws + w.r * N, c->dev, level, c->L, K, c->logN);
+    KLAUNCH(c, st, KID_MODDOWN_CONV, (double)(2 * K + 2 * level) * N * 8.0,
+            k_moddown_conv<<<grid2, 256, 0, st>>>(ws + w.u * N, ws + w.r * N, c->dev, level, c->L, K, c->logN));
     if ((rc = launch_ok(c)) != HE_OK) return rc;
     slots.clear(), mods.clear();
     for (int cc = 0; cc < 2; cc++)
         for (int i = 0; i < level; i++) slots.push_back(cc * level + i), mods.push_back(i);
     if ((rc = run_ntt(c, ws + w.r * N, slots, mods, false, st)) != HE_OK) return rc;
     dim3 grid3((unsigned)(N / 256), (unsigned)(2 * level));
-    k_moddown_fin<<<grid3, 256, 0, st>>>(ws + w.u * N, ws + w.r * N, out, c0, c->dev, level, K, mode, g, c->logN);
+    KLAUNCH(c, st, KID_MODDOWN_FIN, (double)(6 * level + (mode == 1 ? 2 * level : mode == 2 ? level : 0)) * N * 8.0,
+            k_moddown_fin<<<grid3, 256, 0, st>>>(ws + w.u * N, ws + w.r * N, out, c0, c->dev, level, K, mode, g,
+                                                 c->logN));
     return launch_ok(c);
 }
 
@@ -778,7 +866,8 @@ extern "C" int32_t he_hmult_relin(he_ctx *ctx, const he_evk *relin, const uint64
     const WsLayout w = ws_layout(ctx, level);
     const size_t N = ctx->N;
     dim3 grid((unsigned)(N / 256), (unsigned)level);
-    k_tensor<<<grid, 256, 0, st>>>(d_a, d_b, d_out, ws + w.d * N, ws + w.x * N, ctx->dev, level, ctx->logN);
+    KLAUNCH(ctx, st, KID_TENSOR, 8.0 * level * N * 8.0,
+            k_tensor<<<grid, 256, 0, st>>>(d_a, d_b, d_out, ws + w.d * N, ws + w.x * N, ctx->dev, level, ctx->logN));
     if ((rc = launch_ok(ctx)) != HE_OK) return rc;
     if ((rc = ks_raise(ctx, ws + w.d * N, ws, w, level, st)) != HE_OK) return rc;
     return ks_apply(ctx, relin, ws, w, level, d_out, nullptr, 1, st);
@@ -861,13 +950,15 @@ extern "C" int32_t he_rescale(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out
     std::vector<int> slots{0, 1}, mods{level - 1, level - 1};
     if ((rc = run_ntt(ctx, t, slots, mods, true, st)) != HE_OK) return rc;
     dim3 grid((unsigned)(N / 256), 2);
-    k_rescale_conv<<<grid, 256, 0, st>>>(t, r, ctx->dev, level, ctx->logN);
+    KLAUNCH(ctx, st, KID_RESCALE_CONV, (double)(2 + 2 * (level - 1)) * N * 8.0,
+            k_rescale_conv<<<grid, 256, 0, st>>>(t, r, ctx->dev, level, ctx->logN));
     if ((rc = launch_ok(ctx)) != HE_OK) return rc;
     slots.clear(), mods.clear();
     for (int c = 0; c < 2; c++)
         for (int i = 0; i < level - 1; i++) slots.push_back(c * (level - 1) + i), mods.push_back(i);
     if ((rc = run_ntt(ctx, r, slots, mods, false, st)) != HE_OK) return rc;
     dim3 grid2((unsigned)(N / 256), (unsigned)(2 * (level - 1)));
-    k_rescale_fin<<<grid2, 256, 0, st>>>(d_ct, r, d_out, ctx->dev, level, ctx->L, ctx->logN);
+    KLAUNCH(ctx, st, KID_RESCALE_FIN, 6.0 * (level - 1) * N * 8.0,
+            k_rescale_fin<<<grid2, 256, 0, st>>>(d_ct, r, d_out, ctx->dev, level, ctx->L, ctx->logN));
     return launch_ok(ctx);
 }

@@ -41,6 +41,12 @@ struct DevTables {
     const ShoupConst *rs_inv;  // [L][L]
 };
 
+struct ProfRecord {
+    int kid;
+    double bytes;
+    void *a, *b; // hipEvent_t pair
+};
+
 struct he_ctx {
     int logN = 0, L = 0, K = 0, dnum = 0, alpha = 0, M = 0;
     u64 N = 0;
@@ -63,6 +69,8 @@ struct he_ctx {
     DevTables dev{};
     std::vector<void *> dev_allocs;
     mutable std::string hip_err;
+    bool prof_on = false;
+    std::vector<ProfRecord> prof;
 };
 
 struct he_sk {
