@@ -61,71 +61,180 @@ struct LimbBatch {
 // Each thread keeps 16 elements in registers and runs four stages on them (a radix-16 step);
 // between steps the work-group exchanges data through LDS.  A limb of N = 2^16 takes two
 // kernels: stages 0-7 on 16 columns x 256 rows (row stride 256 elements, 128-byte segments),
-// then stages 8-15 on 16 contiguous blocks of 256.  Values stay in [0, 4q) between stages
-// (inverse: [0, 2q)); only the last step writes canonical residues.
+// then stages 8-15 on 16 contiguous blocks of 256.
+//
+// Two arithmetic policies share the kernel bodies:
+//  * ArithFp, for primes below 2^50: residues are carried as doubles (exact integers below 2^53)
+//    and a modular product is an error-free FMA sequence -- h = y*w, l = fma(y,w,-h),
+//    c = rint(h/q), r = fma(-c,q,h) + l -- eight full-rate FP64 instructions per butterfly
+//    against about thirty-five for the 64-bit integer form.  Values are signed and grow by a
+//    bounded amount per stage; a reduction v - rint(v/q)*q every four forward stages (every second
+//    inverse stage on the sum path) keeps every magnitude below 8q < 2^53, so every operation
+//    is exact.
+//  * ArithInt, for any prime below 2^62 (the ~60-bit special primes): Shoup products on 32-bit
+//    integer multiplies with values in [0, 4q) between forward stages ([0, 2q) inverse).
+// Only the last step writes canonical residues; between the two kernels of a transform the
+// buffer holds the policy's internal form.
 
-__device__ __forceinline__ void bfly_fwd(u64 &x, u64 &y, ShoupConst w, u64 q, u64 q2)
+__device__ __forceinline__ double u2d(u64 v) { return __longlong_as_double(v | 0x4330000000000000ull) - 4503599627370496.0; }
+__device__ __forceinline__ u64 d2u(double v)
 {
-    const u64 u = csub(x, q2);
-    const u64 v = mul_shoup_lazy(y, w, q);
-    x = u + v;
-    y = u - v + q2;
+    return (u64)__double_as_longlong(v + 4503599627370496.0) & 0x000FFFFFFFFFFFFFull;
 }
 
-__device__ __forceinline__ void bfly_inv(u64 &x, u64 &y, ShoupConst w, u64 q, u64 q2)
+// error-free modular product of two exact-integer doubles, |y w / q| < 2^52: result within about
+// (1/2 + 3|y|/(16 q)) q of zero
+__device__ __forceinline__ double fp_mulmod(double y, double w, double q, double qinv)
 {
-    const u64 u = x, v = y;
-    x = csub(u + v, q2);
-    y = mul_shoup_lazy(u - v + q2, w, q);
+    const double h = y * w;
+    const double l = __builtin_fma(y, w, -h);
+    const double c = __builtin_rint(h * qinv);
+    return __builtin_fma(-c, q, h) + l;
+}
+__device__ __forceinline__ double fp_reduce(double v, double q, double qinv)
+{
+    return __builtin_fma(-__builtin_rint(v * qinv), q, v);
 }
 
-// four forward stages s_base .. s_base+3 on the 16 elements of one thread; G = index of the
-// thread's group at stage s_base
-__device__ __forceinline__ void fwd16(u64 (&a)[16], const ShoupConst *__restrict__ tw, unsigned s_base, unsigned G,
-                                      u64 q)
-{
-    const u64 q2 = 2 * q;
-#pragma unroll
-    for (int sp = 0; sp < 4; sp++) {
-        const int dist = 8 >> sp;
-        const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
-#pragma unroll
-        for (int g = 0; g < (1 << sp); g++) {
-            const ShoupConst w = tw[idx0 + g];
-#pragma unroll
-            for (int e = 0; e < dist; e++) bfly_fwd(a[g * 2 * dist + e], a[g * 2 * dist + e + dist], w, q, q2);
-        }
+struct ArithFp {
+    typedef double V;
+    double q, qinv;
+    const double *twf, *twi, *nv;
+    __device__ __forceinline__ V reduce(V v) const { return __builtin_fma(-__builtin_rint(v * qinv), q, v); }
+    __device__ __forceinline__ V mulmod(V y, V w) const
+    {
+        const double h = y * w;
+        const double l = __builtin_fma(y, w, -h);
+        const double c = __builtin_rint(h * qinv);
+        return __builtin_fma(-c, q, h) + l;
     }
-}
-
-// the inverse of fwd16: stages s_base+3 down to s_base.  When `last` is set, stage 0 also
-// multiplies by N^-1 (ninv[0] = N^-1, ninv[1] = N^-1 * twiddle).
-template <bool LAST>
-__device__ __forceinline__ void inv16(u64 (&a)[16], const ShoupConst *__restrict__ tw, unsigned s_base, unsigned G,
-                                      u64 q, const ShoupConst *__restrict__ ninv)
-{
-    const u64 q2 = 2 * q;
+    __device__ __forceinline__ V load(u64 m) const { return u2d(m); }
+    __device__ __forceinline__ V load_mid(u64 m) const { return __longlong_as_double(m); }
+    __device__ __forceinline__ u64 store_mid(V v) const { return (u64)__double_as_longlong(v); }
+    __device__ __forceinline__ u64 store_final(V v) const
+    {
+        const double r = reduce(v);
+        return d2u(r < 0.0 ? r + q : r);
+    }
+    __device__ __forceinline__ void fwd16(V (&a)[16], unsigned s_base, unsigned G, bool reduce_first) const
+    {
+        if (reduce_first) {
 #pragma unroll
-    for (int sp = 3; sp >= 0; sp--) {
-        const int dist = 8 >> sp;
-        const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
+            for (int k = 0; k < 16; k++) a[k] = reduce(a[k]);
+        }
 #pragma unroll
-        for (int g = 0; g < (1 << sp); g++) {
-            if (LAST && sp == 0) {
-                const ShoupConst n0 = ninv[0], n1 = ninv[1];
+        for (int sp = 0; sp < 4; sp++) {
+            const int dist = 8 >> sp;
+            const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
+#pragma unroll
+            for (int g = 0; g < (1 << sp); g++) {
+                const double w = twf[idx0 + g];
 #pragma unroll
                 for (int e = 0; e < dist; e++) {
-                    const u64 u = a[e], v = a[e + dist];
-                    a[e] = mul_shoup_lazy(u + v, n0, q);
-                    a[e + dist] = mul_shoup_lazy(u - v + q2, n1, q);
+                    const int k0 = g * 2 * dist + e, k1 = k0 + dist;
+                    const double t = mulmod(a[k1], w), x = a[k0];
+                    a[k0] = x + t;
+                    a[k1] = x - t;
                 }
-            } else {
-                const ShoupConst w = tw[idx0 + g];
-#pragma unroll
-                for (int e = 0; e < dist; e++) bfly_inv(a[g * 2 * dist + e], a[g * 2 * dist + e + dist], w, q, q2);
             }
         }
     }
+    template <bool LAST> __device__ __forceinline__ void inv16(V (&a)[16], unsigned s_base, unsigned G) const
+    {
+#pragma unroll
+        for (int sp = 3; sp >= 0; sp--) {
+            const int dist = 8 >> sp;
+            const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
+#pragma unroll
+            for (int g = 0; g < (1 << sp); g++) {
+                const bool fin = LAST && sp == 0;
+                const double w = fin ? nv[1] : twi[idx0 + g];
+#pragma unroll
+                for (int e = 0; e < dist; e++) {
+                    const int k0 = g * 2 * dist + e, k1 = k0 + dist;
+                    const double u = a[k0], v = a[k1];
+                    double s = u + v;
+                    if (fin)
+                        s = mulmod(s, nv[0]);
+                    else if (sp == 2 || sp == 0)
+                        s = reduce(s);
+                    a[k0] = s;
+                    a[k1] = mulmod(u - v, w);
+                }
+            }
+        }
+    }
+};
+
+struct ArithInt {
+    typedef u64 V;
+    u64 q, q2;
+    const ShoupConst *twf, *twi, *nv;
+    __device__ __forceinline__ V load(u64 m) const { return m; }
+    __device__ __forceinline__ V load_mid(u64 m) const { return m; }
+    __device__ __forceinline__ u64 store_mid(V v) const { return v; }
+    __device__ __forceinline__ u64 store_final(V v) const { return csub(csub(v, q2), q); }
+    __device__ __forceinline__ void fwd16(V (&a)[16], unsigned s_base, unsigned G, bool) const
+    {
+#pragma unroll
+        for (int sp = 0; sp < 4; sp++) {
+            const int dist = 8 >> sp;
+            const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
+#pragma unroll
+            for (int g = 0; g < (1 << sp); g++) {
+                const ShoupConst w = twf[idx0 + g];
+#pragma unroll
+                for (int e = 0; e < dist; e++) {
+                    const int k0 = g * 2 * dist + e, k1 = k0 + dist;
+                    const u64 u = csub(a[k0], q2);
+                    const u64 v = mul_shoup_lazy(a[k1], w, q);
+                    a[k0] = u + v;
+                    a[k1] = u - v + q2;
+                }
+            }
+        }
+    }
+    template <bool LAST> __device__ __forceinline__ void inv16(V (&a)[16], unsigned s_base, unsigned G) const
+    {
+#pragma unroll
+        for (int sp = 3; sp >= 0; sp--) {
+            const int dist = 8 >> sp;
+            const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
+#pragma unroll
+            for (int g = 0; g < (1 << sp); g++) {
+                const bool fin = LAST && sp == 0;
+                const ShoupConst w = fin ? nv[1] : twi[idx0 + g];
+#pragma unroll
+                for (int e = 0; e < dist; e++) {
+                    const int k0 = g * 2 * dist + e, k1 = k0 + dist;
+                    const u64 u = a[k0], v = a[k1];
+                    a[k0] = fin ? mul_shoup_lazy(u + v, nv[0], q) : csub(u + v, q2);
+                    a[k1] = mul_shoup_lazy(u - v + q2, w, q);
+                }
+            }
+        }
+    }
+};
+
+__device__ __forceinline__ ArithFp make_fp(const DevTables &T, unsigned mi, int logN)
+{
+    ArithFp A;
+    A.q = T.mod[mi].qd;
+    A.qinv = T.mod[mi].qinvd;
+    A.twf = T.twd_fwd + ((size_t)mi << logN);
+    A.twi = T.twd_inv + ((size_t)mi << logN);
+    A.nv = T.ninvd + 2 * mi;
+    return A;
+}
+__device__ __forceinline__ ArithInt make_int(const DevTables &T, unsigned mi, int logN)
+{
+    ArithInt A;
+    A.q = T.mod[mi].q;
+    A.q2 = 2 * A.q;
+    A.twf = T.tw_fwd + ((size_t)mi << logN);
+    A.twi = T.tw_inv + ((size_t)mi << logN);
+    A.nv = T.ninv + 2 * mi;
+    return A;
 }
 
 // LDS tile of 16 groups x 256 elements; one pad word per 16 elements and 16 pad words per group
@@ -133,9 +242,61 @@ __device__ __forceinline__ void inv16(u64 (&a)[16], const ShoupConst *__restrict
 #define TILE_GROUP 272
 #define TILE_WORDS (16 * TILE_GROUP)
 __device__ __forceinline__ unsigned tile_at(unsigned grp, unsigned i) { return grp * TILE_GROUP + i + (i >> 4); }
+// column pass: row r (0..255) of column c (0..15); 16 pad words after every 16 rows
+__device__ __forceinline__ unsigned col_at(unsigned r, unsigned c) { return (r >> 4) * TILE_GROUP + (r & 15) * 16 + c; }
 
 // ---- "block" pass: the last eight forward stages (first eight inverse stages) on 16 contiguous
-// blocks of 256 elements per work-group.  grid.x = (N/4096) * batch.
+// blocks of 256 elements per work-group.
+template <int LOGN, class A>
+__device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A &ar, u64 *lds, unsigned tile)
+{
+    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
+    const unsigned bg = tile * 16 + blk; // block index within the limb
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+        const u64 m = limb[bg * 256 + il + 16 * k];
+        a[k] = LOGN > 8 ? ar.load_mid(m) : ar.load(m);
+    }
+    ar.fwd16(a, LOGN - 8, bg, true);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = ar.store_mid(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, 16 * il + k)]);
+    ar.fwd16(a, LOGN - 4, bg * 16 + il, true);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_final(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = lds[tile_at(blk, il + 16 * k)];
+}
+
+template <int LOGN, class A>
+__device__ __forceinline__ void inv_blocks_body(u64 *__restrict__ limb, const A &ar, u64 *lds, unsigned tile)
+{
+    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
+    const unsigned bg = tile * 16 + blk;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = limb[bg * 256 + il + 16 * k];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load(lds[tile_at(blk, 16 * il + k)]);
+    ar.template inv16<false>(a, LOGN - 4, bg * 16 + il);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_mid(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, il + 16 * k)]);
+    ar.template inv16<false>(a, LOGN - 8, bg);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = ar.store_mid(a[k]); // the column pass finishes
+}
+
+// grid.x = (N/4096) * batch
 template <int LOGN>
 __global__ __launch_bounds__(256) void k_ntt_fwd_blocks(u64 *__restrict__ data, DevTables T, LimbBatch lb)
 {
@@ -144,26 +305,10 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_blocks(u64 *__restrict__ data, 
     const unsigned tile = blockIdx.x % TILES, b = blockIdx.x / TILES;
     const unsigned mi = lb.mod[b];
     u64 *limb = data + ((size_t)lb.slot[b] << LOGN);
-    const u64 q = T.mod[mi].q;
-    const ShoupConst *tw = T.tw_fwd + ((size_t)mi << LOGN);
-    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
-    const unsigned bg = tile * 16 + blk; // block index within the limb
-    u64 a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = limb[bg * 256 + il + 16 * k];
-    fwd16(a, tw, LOGN - 8, bg, q);
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = a[k];
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = lds[tile_at(blk, 16 * il + k)];
-    fwd16(a, tw, LOGN - 4, bg * 16 + il, q);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = csub(csub(a[k], 2 * q), q);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = lds[tile_at(blk, il + 16 * k)];
+    if (T.mod[mi].qd != 0.0)
+        fwd_blocks_body<LOGN>(limb, make_fp(T, mi, LOGN), lds, tile);
+    else
+        fwd_blocks_body<LOGN>(limb, make_int(T, mi, LOGN), lds, tile);
 }
 
 template <int LOGN>
@@ -174,54 +319,59 @@ __global__ __launch_bounds__(256) void k_ntt_inv_blocks(u64 *__restrict__ data, 
     const unsigned tile = blockIdx.x % TILES, b = blockIdx.x / TILES;
     const unsigned mi = lb.mod[b];
     u64 *limb = data + ((size_t)lb.slot[b] << LOGN);
-    const u64 q = T.mod[mi].q;
-    const ShoupConst *tw = T.tw_inv + ((size_t)mi << LOGN);
-    const ShoupConst *ninv = T.ninv + 2 * mi;
-    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
-    const unsigned bg = tile * 16 + blk;
-    u64 a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = limb[bg * 256 + il + 16 * k];
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = lds[tile_at(blk, 16 * il + k)];
-    inv16<false>(a, tw, LOGN - 4, bg * 16 + il, q, ninv);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = a[k];
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = lds[tile_at(blk, il + 16 * k)];
-    inv16<false>(a, tw, LOGN - 8, bg, q, ninv);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = a[k]; // in [0, 2q): the column pass finishes
+    if (T.mod[mi].qd != 0.0)
+        inv_blocks_body<LOGN>(limb, make_fp(T, mi, LOGN), lds, tile);
+    else
+        inv_blocks_body<LOGN>(limb, make_int(T, mi, LOGN), lds, tile);
 }
 
 // ---- "column" pass for N = 2^16: stages 0-7 on 256 rows x 16 columns per work-group (element
-// (r, c) at r*256 + c).  grid.x = 16 * batch.
+// (r, c) at r*256 + c).
+template <class A> __device__ __forceinline__ void fwd_cols16_body(u64 *__restrict__ limb, const A &ar, u64 *lds)
+{
+    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load(limb[(rl + 16 * k) * 256 + c]);
+    ar.fwd16(a, 0, 0, false);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(16 * rl + k, c)]);
+    ar.fwd16(a, 4, rl, true);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[(16 * rl + k) * 256 + c] = ar.store_mid(a[k]); // the block pass finishes
+}
+
+template <class A> __device__ __forceinline__ void inv_cols16_body(u64 *__restrict__ limb, const A &ar, u64 *lds)
+{
+    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[(16 * rl + k) * 256 + c]);
+    ar.template inv16<false>(a, 4, rl);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[col_at(16 * rl + k, c)] = ar.store_mid(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(rl + 16 * k, c)]);
+    ar.template inv16<true>(a, 0, 0);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[(rl + 16 * k) * 256 + c] = ar.store_final(a[k]);
+}
+
+// grid.x = 16 * batch
 __global__ __launch_bounds__(256) void k_ntt_fwd_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb)
 {
     __shared__ u64 lds[TILE_WORDS];
     const unsigned tile = blockIdx.x & 15, b = blockIdx.x >> 4;
     const unsigned mi = lb.mod[b];
     u64 *limb = data + ((size_t)lb.slot[b] << 16) + tile * 16;
-    const u64 q = T.mod[mi].q;
-    const ShoupConst *tw = T.tw_fwd + ((size_t)mi << 16);
-    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
-    u64 a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = limb[(rl + 16 * k) * 256 + c];
-    fwd16(a, tw, 0, 0, q);
-    // LDS index: row r of column c at (r>>4)*272 + (r&15)*17... reuse the tile helper with the
-    // roles (group = r>>4, element = (r&15)*16 + c)
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(k, rl * 16 + c)] = a[k];
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = lds[tile_at(rl, k * 16 + c)];
-    fwd16(a, tw, 4, rl, q);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[(16 * rl + k) * 256 + c] = a[k]; // in [0, 4q): the block pass finishes
+    if (T.mod[mi].qd != 0.0)
+        fwd_cols16_body(limb, make_fp(T, mi, 16), lds);
+    else
+        fwd_cols16_body(limb, make_int(T, mi, 16), lds);
 }
 
 __global__ __launch_bounds__(256) void k_ntt_inv_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb)
@@ -230,56 +380,52 @@ __global__ __launch_bounds__(256) void k_ntt_inv_cols16(u64 *__restrict__ data, 
     const unsigned tile = blockIdx.x & 15, b = blockIdx.x >> 4;
     const unsigned mi = lb.mod[b];
     u64 *limb = data + ((size_t)lb.slot[b] << 16) + tile * 16;
-    const u64 q = T.mod[mi].q;
-    const ShoupConst *tw = T.tw_inv + ((size_t)mi << 16);
-    const ShoupConst *ninv = T.ninv + 2 * mi;
-    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
-    u64 a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = limb[(16 * rl + k) * 256 + c];
-    inv16<false>(a, tw, 4, rl, q, ninv);
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(rl, k * 16 + c)] = a[k];
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = lds[tile_at(k, rl * 16 + c)];
-    inv16<true>(a, tw, 0, 0, q, ninv);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[(rl + 16 * k) * 256 + c] = csub(a[k], q);
+    if (T.mod[mi].qd != 0.0)
+        inv_cols16_body(limb, make_fp(T, mi, 16), lds);
+    else
+        inv_cols16_body(limb, make_int(T, mi, 16), lds);
 }
 
 // ---- "column" pass for N = 2^12: stages 0-3 on 16 rows x 256 columns, one thread per column.
+template <class A> __device__ __forceinline__ void fwd_cols12_body(u64 *__restrict__ limb, const A &ar)
+{
+    const unsigned c = threadIdx.x;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load(limb[k * 256 + c]);
+    ar.fwd16(a, 0, 0, false);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[k * 256 + c] = ar.store_mid(a[k]);
+}
+template <class A> __device__ __forceinline__ void inv_cols12_body(u64 *__restrict__ limb, const A &ar)
+{
+    const unsigned c = threadIdx.x;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[k * 256 + c]);
+    ar.template inv16<true>(a, 0, 0);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[k * 256 + c] = ar.store_final(a[k]);
+}
+
 __global__ __launch_bounds__(256) void k_ntt_fwd_cols12(u64 *__restrict__ data, DevTables T, LimbBatch lb)
 {
-    const unsigned b = blockIdx.x;
-    const unsigned mi = lb.mod[b];
-    u64 *limb = data + ((size_t)lb.slot[b] << 12);
-    const u64 q = T.mod[mi].q;
-    const ShoupConst *tw = T.tw_fwd + ((size_t)mi << 12);
-    const unsigned c = threadIdx.x;
-    u64 a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = limb[k * 256 + c];
-    fwd16(a, tw, 0, 0, q);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[k * 256 + c] = a[k];
+    const unsigned mi = lb.mod[blockIdx.x];
+    u64 *limb = data + ((size_t)lb.slot[blockIdx.x] << 12);
+    if (T.mod[mi].qd != 0.0)
+        fwd_cols12_body(limb, make_fp(T, mi, 12));
+    else
+        fwd_cols12_body(limb, make_int(T, mi, 12));
 }
 
 __global__ __launch_bounds__(256) void k_ntt_inv_cols12(u64 *__restrict__ data, DevTables T, LimbBatch lb)
 {
-    const unsigned b = blockIdx.x;
-    const unsigned mi = lb.mod[b];
-    u64 *limb = data + ((size_t)lb.slot[b] << 12);
-    const u64 q = T.mod[mi].q;
-    const ShoupConst *tw = T.tw_inv + ((size_t)mi << 12);
-    const ShoupConst *ninv = T.ninv + 2 * mi;
-    const unsigned c = threadIdx.x;
-    u64 a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = limb[k * 256 + c];
-    inv16<true>(a, tw, 0, 0, q, ninv);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[k * 256 + c] = csub(a[k], q);
+    const unsigned mi = lb.mod[blockIdx.x];
+    u64 *limb = data + ((size_t)lb.slot[blockIdx.x] << 12);
+    if (T.mod[mi].qd != 0.0)
+        inv_cols12_body(limb, make_fp(T, mi, 12));
+    else
+        inv_cols12_body(limb, make_int(T, mi, 12));
 }
 
 // ---------------------------------------------------------------------------------- elementwise
@@ -352,28 +498,58 @@ __device__ __forceinline__ unsigned galois_index(unsigned k, unsigned g, int log
 // the NTT domain.  For digit j = blockIdx.y: y_i = x_i (D/q_i)^-1 mod q_i, and for every active
 // modulus t outside the digit raised[j][a] = sum_i y_i (D/q_i mod t) mod t (coefficient domain,
 // no correction of the overshoot); inside the digit raised[j][a] = d[a] (already transformed).
+// blockIdx.z selects a contiguous share of the target limbs.  When all ciphertext primes are
+// below 2^50 (fp != 0) the products for targets below 2^50 are FP64 error-free products.
+template <int AMAX>
 __global__ __launch_bounds__(256) void k_modup(const u64 *__restrict__ x, const u64 *__restrict__ d,
                                                u64 *__restrict__ raised, DevTables T, int level, int L, int K,
-                                               int alpha, int logN)
+                                               int alpha, int logN, int fp)
 {
     const int j = blockIdx.y;
     const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
     const int M = L + K, Ma = level + K;
     const int lo = j * alpha, hi = min(lo + alpha, level), na = hi - lo;
     const size_t slot = (size_t)j * alpha + (na - 1);
-    u64 y[16];
-#pragma unroll 4
-    for (int ii = 0; ii < na; ii++) {
-        const u64 v = x[((size_t)(lo + ii) << logN) + n];
-        y[ii] = mul_shoup(v, T.up_inv[slot * alpha + ii], T.mod[lo + ii].q);
-        raised[(((size_t)j * Ma + lo + ii) << logN) + n] = d[((size_t)(lo + ii) << logN) + n];
+    const int per = (Ma + gridDim.z - 1) / gridDim.z;
+    const int a_lo = blockIdx.z * per, a_hi = min(a_lo + per, Ma);
+    u64 yi[AMAX];
+    double yd[AMAX];
+#pragma unroll
+    for (int ii = 0; ii < AMAX; ii++) {
+        yi[ii] = 0;
+        yd[ii] = 0.0;
+        if (ii < na) {
+            const u64 v = x[((size_t)(lo + ii) << logN) + n];
+            const ModConst m = T.mod[lo + ii];
+            if (fp) {
+                const double r = fp_reduce(fp_mulmod(u2d(v), T.up_inv_d[slot * alpha + ii], m.qd, m.qinvd), m.qd, m.qinvd);
+                yd[ii] = r < 0.0 ? r + m.qd : r;
+                yi[ii] = d2u(yd[ii]);
+            } else
+                yi[ii] = mul_shoup(v, T.up_inv[slot * alpha + ii], m.q);
+            if (blockIdx.z == 0) raised[(((size_t)j * Ma + lo + ii) << logN) + n] = d[((size_t)(lo + ii) << logN) + n];
+        }
     }
-    for (int a = 0; a < Ma; a++) {
+    for (int a = a_lo; a < a_hi; a++) {
         if (a >= lo && a < hi) continue;
         const int mi = active_mod(a, level, L);
-        U128 acc{0, 0};
-        for (int ii = 0; ii < na; ii++) mac128(acc, y[ii], T.up_hat[(slot * alpha + ii) * M + mi]);
-        raised[(((size_t)j * Ma + a) << logN) + n] = reduce128(acc, T.mod[mi]);
+        const ModConst m = T.mod[mi];
+        u64 out;
+        if (fp && m.qd != 0.0) {
+            double acc = 0.0;
+#pragma unroll
+            for (int ii = 0; ii < AMAX; ii++)
+                if (ii < na) acc += fp_mulmod(yd[ii], T.up_hat_d[(slot * alpha + ii) * M + mi], m.qd, m.qinvd);
+            const double r = fp_reduce(acc, m.qd, m.qinvd);
+            out = d2u(r < 0.0 ? r + m.qd : r);
+        } else {
+            U128 acc{0, 0};
+#pragma unroll
+            for (int ii = 0; ii < AMAX; ii++)
+                if (ii < na) mac128(acc, yi[ii], T.up_hat[(slot * alpha + ii) * M + mi]);
+            out = reduce128(acc, m);
+        }
+        raised[(((size_t)j * Ma + a) << logN) + n] = out;
     }
 }
 
@@ -409,12 +585,17 @@ __global__ __launch_bounds__(256) void k_moddown_conv(const u64 *__restrict__ u,
     const int c = blockIdx.y;
     const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
     const int Ma = level + K;
+    const int per = (level + gridDim.z - 1) / gridDim.z;
+    const int i_lo = blockIdx.z * per, i_hi = min(i_lo + per, level);
     u64 y[16];
-    for (int k = 0; k < K; k++)
-        y[k] = mul_shoup(u[(((size_t)c * Ma + level + k) << logN) + n], T.dn_inv[k], T.mod[L + k].q);
-    for (int i = 0; i < level; i++) {
+#pragma unroll
+    for (int k = 0; k < 16; k++)
+        y[k] = k < K ? mul_shoup(u[(((size_t)c * Ma + level + k) << logN) + n], T.dn_inv[k], T.mod[L + k].q) : 0;
+    for (int i = i_lo; i < i_hi; i++) {
         U128 acc{0, 0};
-        for (int k = 0; k < K; k++) mac128(acc, y[k], T.dn_hat[(size_t)k * L + i]);
+#pragma unroll
+        for (int k = 0; k < 16; k++)
+            if (k < K) mac128(acc, y[k], T.dn_hat[(size_t)k * L + i]);
         r[(((size_t)c * level + i) << logN) + n] = reduce128(acc, T.mod[i]);
     }
 }
@@ -502,7 +683,7 @@ int32_t dev_upload_tables(he_ctx *c)
 #define UP(field)                                                                                                    \
     if ((rc = upload(c, c->field, &c->dev.field)) != HE_OK) return rc;
     if ((rc = upload(c, c->modc, &c->dev.mod)) != HE_OK) return rc;
-    UP(tw_fwd) UP(tw_inv) UP(ninv) UP(up_inv) UP(up_hat) UP(dn_inv) UP(dn_hat) UP(dn_pinv) UP(rs_inv)
+    UP(tw_fwd) UP(tw_inv) UP(ninv) UP(twd_fwd) UP(twd_inv) UP(ninvd) UP(up_inv) UP(up_inv_d) UP(up_hat_d) UP(up_hat) UP(dn_inv) UP(dn_hat) UP(dn_pinv) UP(rs_inv)
 #undef UP
     return HE_OK;
 }
@@ -629,12 +810,16 @@ static int32_t run_ntt(he_ctx *c, u64 *base, const std::vector<int> &slots, cons
                        hipStream_t st)
 {
     const int total = (int)slots.size();
+    // limbs on the integer path take about three times longer: schedule them first
+    std::vector<int> order(total);
+    for (int b = 0; b < total; b++) order[b] = b;
+    std::stable_partition(order.begin(), order.end(), [&](int b) { return c->modc[mods[b]].qd == 0.0; });
     for (int off = 0; off < total; off += HE_MAXB) {
         const int nb = std::min(HE_MAXB, total - off);
         LimbBatch lb;
         for (int b = 0; b < nb; b++) {
-            lb.slot[b] = (uint16_t)slots[off + b];
-            lb.mod[b] = (uint8_t)mods[off + b];
+            lb.slot[b] = (uint16_t)slots[order[off + b]];
+            lb.mod[b] = (uint8_t)mods[order[off + b]];
         }
         // each pass reads and writes every limb of the batch once
         const double bytes = (double)nb * (double)c->N * 16.0;
@@ -794,9 +979,22 @@ static int32_t ks_raise(he_ctx *c, const u64 *d_ntt, u64 *ws, const WsLayout &w,
     if (rc != HE_OK) return rc;
     dim3 grid((unsigned)(N / 256), (unsigned)beta);
     // reads the level coefficient-domain limbs (and the NTT-domain copies), writes beta*(level+K) limbs
-    KLAUNCH(c, st, KID_MODUP, (double)(2 * level + beta * Ma) * N * 8.0,
-            k_modup<<<grid, 256, 0, st>>>(ws + w.x * N, d_ntt, ws + w.raised * N, c->dev, level, c->L, K, c->alpha,
-                                          c->logN));
+    grid.z = 4;
+#define MODUP_LAUNCH(AMAX)                                                                                           \
+    KLAUNCH(c, st, KID_MODUP, (double)(2 * level + beta * Ma) * N * 8.0,                                             \
+            k_modup<AMAX><<<grid, 256, 0, st>>>(ws + w.x * N, d_ntt, ws + w.raised * N, c->dev, level, c->L, K,      \
+                                                c->alpha, c->logN, c->conv_fp ? 1 : 0))
+    if (c->alpha <= 1)
+        MODUP_LAUNCH(1);
+    else if (c->alpha <= 2)
+        MODUP_LAUNCH(2);
+    else if (c->alpha <= 4)
+        MODUP_LAUNCH(4);
+    else if (c->alpha <= 8)
+        MODUP_LAUNCH(8);
+    else
+        MODUP_LAUNCH(16);
+#undef MODUP_LAUNCH
     if ((rc = launch_ok(c)) != HE_OK) return rc;
     slots.clear(), mods.clear();
     for (int j = 0; j < beta; j++) {
@@ -829,7 +1027,7 @@ static int32_t ks_apply(he_ctx *c, const he_evk *evk, u64 *ws, const WsLayout &w
     for (int cc = 0; cc < 2; cc++)
         for (int k = 0; k < K; k++) slots.push_back(cc * Ma + level + k), mods.push_back(c->L + k);
     if ((rc = run_ntt(c, ws + w.u * N, slots, mods, true, st)) != HE_OK) return rc;
-    dim3 grid2((unsigned)(N / 256), 2);
+    dim3 grid2((unsigned)(N / 256), 2, (unsigned)std::min(level, 6));
     KLAUNCH(c, st, KID_MODDOWN_CONV, (double)(2 * K + 2 * level) * N * 8.0,
             k_moddown_conv<<<grid2, 256, 0, st>>>(ws + w.u * N, ws + w.r * N, c->dev, level, c->L, K, c->logN));
     if ((rc = launch_ok(c)) != HE_OK) return rc;

@@ -22,6 +22,8 @@ struct ModConst {
     u64 q;
     u64 one_p;    // floor(2^64 / q): reduces any 64-bit word to [0, 2q)
     ShoupConst r; // 2^64 mod q: folds the high word of a 128-bit sum
+    double qd;    // q as a double when q < 2^50 (the FP64 arithmetic applies), else 0
+    double qinvd; // 1/q rounded to nearest
 };
 
 // Device image of all tables.  Pointers are device pointers.
@@ -30,9 +32,15 @@ struct DevTables {
     const ShoupConst *tw_fwd;  // [M][N]  psi^brv(i)
     const ShoupConst *tw_inv;  // [M][N]  psi^-brv(i)
     const ShoupConst *ninv;    // [M][2]  N^-1 and psi^-brv(1) * N^-1 (last inverse stage)
+    // the same three tables as balanced residues in (-q/2, q/2) stored as doubles (moduli < 2^50)
+    const double *twd_fwd;     // [M][N]
+    const double *twd_inv;     // [M][N]
+    const double *ninvd;       // [M][2]
     // ModUp constants for digit j holding a active limbs (1 <= a <= alpha), slot (j*alpha + a-1):
     const ShoupConst *up_inv;  // [dnum*alpha][alpha]      (D/q_i)^-1 mod q_i
     const u64 *up_hat;         // [dnum*alpha][alpha][M]   (D/q_i) mod t
+    const double *up_inv_d;    // the same two tables, balanced, as doubles (0 where the modulus is >= 2^50)
+    const double *up_hat_d;
     // ModDown constants
     const ShoupConst *dn_inv;  // [K]      (P/p_k)^-1 mod p_k
     const u64 *dn_hat;         // [K][L]   (P/p_k) mod q_i
@@ -57,8 +65,11 @@ struct he_ctx {
     std::vector<ShoupConst> tw_fwd;  // [M][N]
     std::vector<ShoupConst> tw_inv;  // [M][N]
     std::vector<ShoupConst> ninv;    // [M][2]
+    std::vector<double> twd_fwd, twd_inv, ninvd;
     std::vector<ShoupConst> up_inv;
     std::vector<u64> up_hat;
+    std::vector<double> up_inv_d, up_hat_d;
+    bool conv_fp = false; // every ciphertext prime is below 2^50: base conversion may use FP64 products
     std::vector<ShoupConst> dn_inv;
     std::vector<u64> dn_hat;
     std::vector<ShoupConst> dn_pinv;

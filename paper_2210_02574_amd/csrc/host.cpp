@@ -213,6 +213,9 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
         c->tw_fwd.resize((size_t)M * N);
         c->tw_inv.resize((size_t)M * N);
         c->ninv.resize((size_t)M * 2);
+        c->twd_fwd.assign((size_t)M * N, 0.0);
+        c->twd_inv.assign((size_t)M * N, 0.0);
+        c->ninvd.assign((size_t)M * 2, 0.0);
     } catch (...) {
         delete c;
         return HE_ENOMEM;
@@ -243,6 +246,20 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
         const u64 ni = inv_mod(N % t, t);
         c->ninv[(size_t)i * 2 + 0] = shoup(ni, t);
         c->ninv[(size_t)i * 2 + 1] = shoup(mul_mod(ni, c->tw_inv[(size_t)i * N + 1].w, t), t);
+        c->modc[i].qd = 0.0;
+        c->modc[i].qinvd = 0.0;
+        if (t < ((u64)1 << 50)) {
+            // balanced representatives as doubles for the FP64 butterflies
+            auto bal = [t](u64 w) { return w > t / 2 ? -(double)(t - w) : (double)w; };
+            c->modc[i].qd = (double)t;
+            c->modc[i].qinvd = 1.0 / (double)t;
+            for (u64 e = 0; e < N; e++) {
+                c->twd_fwd[(size_t)i * N + e] = bal(c->tw_fwd[(size_t)i * N + e].w);
+                c->twd_inv[(size_t)i * N + e] = bal(c->tw_inv[(size_t)i * N + e].w);
+            }
+            c->ninvd[(size_t)i * 2 + 0] = bal(c->ninv[(size_t)i * 2 + 0].w);
+            c->ninvd[(size_t)i * 2 + 1] = bal(c->ninv[(size_t)i * 2 + 1].w);
+        }
     });
     if (bad) {
         delete c;
@@ -263,6 +280,25 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
                     c->up_hat[(slot * alpha + ii) * M + m] = prod_mod_excluding(c->mod, lo, hi, lo + ii, c->mod[m]);
             }
         }
+    c->conv_fp = true;
+    for (int i = 0; i < L; i++) c->conv_fp = c->conv_fp && c->mod[i] < ((u64)1 << 50);
+    c->up_inv_d.assign(c->up_inv.size(), 0.0);
+    c->up_hat_d.assign(c->up_hat.size(), 0.0);
+    if (c->conv_fp) {
+        auto bal = [](u64 w, u64 t) { return w > t / 2 ? -(double)(t - w) : (double)w; };
+        for (int j = 0; j < c->dnum; j++)
+            for (int a = 1; a <= alpha; a++) {
+                const int lo = j * alpha;
+                if (lo + a > L) break;
+                const size_t slot = (size_t)j * alpha + (a - 1);
+                for (int ii = 0; ii < a; ii++) {
+                    c->up_inv_d[slot * alpha + ii] = bal(c->up_inv[slot * alpha + ii].w, c->mod[lo + ii]);
+                    for (int m = 0; m < M; m++)
+                        if (c->mod[m] < ((u64)1 << 50))
+                            c->up_hat_d[(slot * alpha + ii) * M + m] = bal(c->up_hat[(slot * alpha + ii) * M + m], c->mod[m]);
+                }
+            }
+    }
     // ModDown constants
     c->dn_inv.resize(K);
     c->dn_hat.resize((size_t)K * L);

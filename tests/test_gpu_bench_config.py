@@ -1,0 +1,47 @@
+"""Parity at the benchmark's full sizes and launch configuration: the step that bench.py times
+(N=2^16, L=24, dnum=6) is run once on a reduced count of operations and whole outputs of each kind of
+operation are compared with the oracle bit for bit."""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def test_bench_step_outputs_match_oracle(oracle_mod):
+    import torch
+
+    import bench
+    import paper_2210_02574_amd as pkg
+
+    assert torch.cuda.is_available()
+    p = wl.N16
+    he = pkg.HE.from_params(p, device=0)
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    w = bench.Workload(he, seed=2, n_hmult=2, n_single=6, n_ntt=56)
+    ntt_in = he.to_host(w.ntt_limbs).copy()
+    w.step()
+    torch.cuda.synchronize()
+    # NTT followed by iNTT returns the input; the forward result itself is checked on a second pass
+    assert np.array_equal(he.to_host(w.ntt_limbs), ntt_in)
+    he.ntt(w.ntt_limbs, w.ntt_mods)
+    fwd = he.to_host(w.ntt_limbs)
+    for b in (0, 23, 24, 27, 55):
+        assert np.array_equal(fwd[b], o.ntt(ntt_in[b], w.ntt_mods[b])), b
+    he.intt(w.ntt_limbs, w.ntt_mods)
+    relin = wl.uniform_evk(1000, p)
+    a, b = he.to_host(w.hm_a[1]), he.to_host(w.hm_b[1])
+    want = o.hmult_relin(a, b, relin)
+    assert np.array_equal(he.to_host(w.hm_out[1]), want)
+    assert np.array_equal(he.to_host(w.rs_out[1]), o.rescale(want))
+    ct = he.to_host(w.hoist_in)
+    for k in (0, 7, 14):
+        evk = wl.uniform_evk(1001 + k, p)
+        assert np.array_equal(he.to_host(w.hoist_out[k]), o.hrot(ct, evk, w.offsets[k])), k
+    for i in (0, 5):
+        k = w.single_keys[i]
+        evk = wl.uniform_evk(1001 + k, p)
+        got = he.to_host(w.single_out[i])
+        assert got.shape[1] == w.single_levels[i]
+        assert np.array_equal(got, o.hrot(he.to_host(w.single_in[i]), evk, w.offsets[k])), i
