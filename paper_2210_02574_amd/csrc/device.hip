@@ -1,9 +1,17 @@
-// HIP kernels (gfx950) and device-side entry points of the RNS-CKKS library.
+// Device-side entry points of the RNS-CKKS library: table upload, kernel launch sequences of
+// NTT, Mult (tensor product + relinearisation), Rotate (hybrid key switching), rescale and
+// rotate-and-sum.  The kernels are in kernels_ntt.h and kernels_ks.h.
 //
-// All arithmetic is on 64-bit residues of primes below 2^62, built from 32-bit integer
-// multiplies: Shoup products for multiplications by table constants, and 128-bit
-// accumulation with one final reduction for sums of products of two variable residues.
-// Every buffer leaving a public entry point holds canonical residues in [0, q).
+// Key switch of a polynomial d (NTT domain, `level` limbs) with key evk, Galois element g:
+//   1. inverse NTT of d, its column pass also multiplying limb i by (D/q_i)^-1      -> y  (ws.x)
+//   2. forward NTT of every raised limb (digit j, modulus t outside the digit), the
+//      column pass summing y_i (D/q_i mod t) on the fly (ModUp)                     -> raised
+//   3. inner product with the key, reading the digits through the index map of g
+//      and the digit's own limbs straight from d                                     -> u
+//   4. inverse NTT of the special limbs of u, scaled by (P/p_k)^-1                   (in place)
+//   5. forward NTT of the 2*level ModDown corrections, column pass summing
+//      y_k (P/p_k mod q_i), block pass finishing out = (u - ntt) P^-1 + addend       -> out
+// Hoisted rotations share steps 1-2.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -11,648 +19,7 @@
 #include <functional>
 #include <vector>
 
-#include "he_internal.h"
-
-// ------------------------------------------------------------------------------- modular helpers
-
-__device__ __forceinline__ u64 mulhi64(u64 a, u64 b) { return __umul64hi(a, b); }
-__device__ __forceinline__ u64 csub(u64 x, u64 q) { return x >= q ? x - q : x; }
-// w*x mod q up to one extra q, for any 64-bit x; w < q with wp = floor(w 2^64 / q)
-__device__ __forceinline__ u64 mul_shoup_lazy(u64 x, ShoupConst w, u64 q) { return x * w.w - mulhi64(x, w.wp) * q; }
-__device__ __forceinline__ u64 mul_shoup(u64 x, ShoupConst w, u64 q) { return csub(mul_shoup_lazy(x, w, q), q); }
-
-struct U128 {
-    u64 lo, hi;
-};
-__device__ __forceinline__ void mac128(U128 &acc, u64 a, u64 b)
-{
-    const u64 lo = a * b;
-    const u64 hi = mulhi64(a, b);
-    acc.lo += lo;
-    acc.hi += hi + (acc.lo < lo ? 1 : 0);
-}
-// (hi 2^64 + lo) mod q for any 128-bit value
-__device__ __forceinline__ u64 reduce128(U128 v, const ModConst &m)
-{
-    const u64 a = mul_shoup_lazy(v.hi, m.r, m.q);       // hi * (2^64 mod q)   in [0, 2q)
-    const u64 b = v.lo - mulhi64(v.lo, m.one_p) * m.q;  // lo mod q            in [0, 2q)
-    return csub(csub(a + b, 2 * m.q), m.q);
-}
-__device__ __forceinline__ u64 reduce64(u64 v, const ModConst &m) { return csub(v - mulhi64(v, m.one_p) * m.q, m.q); }
-__device__ __forceinline__ u64 mul_mod(u64 a, u64 b, const ModConst &m)
-{
-    U128 p{a * b, mulhi64(a, b)};
-    return reduce128(p, m);
-}
-
-// ------------------------------------------------------------------------------------ limb lists
-
-#define HE_MAXB 512
-// A launch works on up to HE_MAXB limbs: limb b lives at base + slot[b]*N and uses modulus mod[b].
-struct LimbBatch {
-    uint16_t slot[HE_MAXB];
-    uint8_t mod[HE_MAXB];
-};
-
-// ------------------------------------------------------------------------------------------ NTT
-//
-// Forward transform = decimation in time with the powers of psi in bit-reversed order; stage s
-// (s = 0 .. logN-1) pairs elements N/2^(s+1) apart and uses twiddle index 2^s + (j >> (logN-s)).
-// Each thread keeps 16 elements in registers and runs four stages on them (a radix-16 step);
-// between steps the work-group exchanges data through LDS.  A limb of N = 2^16 takes two
-// kernels: stages 0-7 on 16 columns x 256 rows (row stride 256 elements, 128-byte segments),
-// then stages 8-15 on 16 contiguous blocks of 256.
-//
-// Two arithmetic policies share the kernel bodies:
-//  * ArithFp, for primes below 2^50: residues are carried as doubles (exact integers below 2^53)
-//    and a modular product is an error-free FMA sequence -- h = y*w, l = fma(y,w,-h),
-//    c = rint(h/q), r = fma(-c,q,h) + l -- eight full-rate FP64 instructions per butterfly
-//    against about thirty-five for the 64-bit integer form.  Values are signed and grow by a
-//    bounded amount per stage; a reduction v - rint(v/q)*q every four forward stages (every second
-//    inverse stage on the sum path) keeps every magnitude below 8q < 2^53, so every operation
-//    is exact.
-//  * ArithInt, for any prime below 2^62 (the ~60-bit special primes): Shoup products on 32-bit
-//    integer multiplies with values in [0, 4q) between forward stages ([0, 2q) inverse).
-// Only the last step writes canonical residues; between the two kernels of a transform the
-// buffer holds the policy's internal form.
-
-__device__ __forceinline__ double u2d(u64 v) { return __longlong_as_double(v | 0x4330000000000000ull) - 4503599627370496.0; }
-__device__ __forceinline__ u64 d2u(double v)
-{
-    return (u64)__double_as_longlong(v + 4503599627370496.0) & 0x000FFFFFFFFFFFFFull;
-}
-
-// error-free modular product of two exact-integer doubles, |y w / q| < 2^52: result within about
-// (1/2 + 3|y|/(16 q)) q of zero
-__device__ __forceinline__ double fp_mulmod(double y, double w, double q, double qinv)
-{
-    const double h = y * w;
-    const double l = __builtin_fma(y, w, -h);
-    const double c = __builtin_rint(h * qinv);
-    return __builtin_fma(-c, q, h) + l;
-}
-__device__ __forceinline__ double fp_reduce(double v, double q, double qinv)
-{
-    return __builtin_fma(-__builtin_rint(v * qinv), q, v);
-}
-
-struct ArithFp {
-    typedef double V;
-    double q, qinv;
-    const double *twf, *twi, *nv;
-    __device__ __forceinline__ V reduce(V v) const { return __builtin_fma(-__builtin_rint(v * qinv), q, v); }
-    __device__ __forceinline__ V mulmod(V y, V w) const
-    {
-        const double h = y * w;
-        const double l = __builtin_fma(y, w, -h);
-        const double c = __builtin_rint(h * qinv);
-        return __builtin_fma(-c, q, h) + l;
-    }
-    __device__ __forceinline__ V load(u64 m) const { return u2d(m); }
-    __device__ __forceinline__ V load_mid(u64 m) const { return __longlong_as_double(m); }
-    __device__ __forceinline__ u64 store_mid(V v) const { return (u64)__double_as_longlong(v); }
-    __device__ __forceinline__ u64 store_final(V v) const
-    {
-        const double r = reduce(v);
-        return d2u(r < 0.0 ? r + q : r);
-    }
-    __device__ __forceinline__ void fwd16(V (&a)[16], unsigned s_base, unsigned G, bool reduce_first) const
-    {
-        if (reduce_first) {
-#pragma unroll
-            for (int k = 0; k < 16; k++) a[k] = reduce(a[k]);
-        }
-#pragma unroll
-        for (int sp = 0; sp < 4; sp++) {
-            const int dist = 8 >> sp;
-            const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
-#pragma unroll
-            for (int g = 0; g < (1 << sp); g++) {
-                const double w = twf[idx0 + g];
-#pragma unroll
-                for (int e = 0; e < dist; e++) {
-                    const int k0 = g * 2 * dist + e, k1 = k0 + dist;
-                    const double t = mulmod(a[k1], w), x = a[k0];
-                    a[k0] = x + t;
-                    a[k1] = x - t;
-                }
-            }
-        }
-    }
-    template <bool LAST> __device__ __forceinline__ void inv16(V (&a)[16], unsigned s_base, unsigned G) const
-    {
-#pragma unroll
-        for (int sp = 3; sp >= 0; sp--) {
-            const int dist = 8 >> sp;
-            const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
-#pragma unroll
-            for (int g = 0; g < (1 << sp); g++) {
-                const bool fin = LAST && sp == 0;
-                const double w = fin ? nv[1] : twi[idx0 + g];
-#pragma unroll
-                for (int e = 0; e < dist; e++) {
-                    const int k0 = g * 2 * dist + e, k1 = k0 + dist;
-                    const double u = a[k0], v = a[k1];
-                    double s = u + v;
-                    if (fin)
-                        s = mulmod(s, nv[0]);
-                    else if (sp == 2 || sp == 0)
-                        s = reduce(s);
-                    a[k0] = s;
-                    a[k1] = mulmod(u - v, w);
-                }
-            }
-        }
-    }
-};
-
-struct ArithInt {
-    typedef u64 V;
-    u64 q, q2;
-    const ShoupConst *twf, *twi, *nv;
-    __device__ __forceinline__ V load(u64 m) const { return m; }
-    __device__ __forceinline__ V load_mid(u64 m) const { return m; }
-    __device__ __forceinline__ u64 store_mid(V v) const { return v; }
-    __device__ __forceinline__ u64 store_final(V v) const { return csub(csub(v, q2), q); }
-    __device__ __forceinline__ void fwd16(V (&a)[16], unsigned s_base, unsigned G, bool) const
-    {
-#pragma unroll
-        for (int sp = 0; sp < 4; sp++) {
-            const int dist = 8 >> sp;
-            const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
-#pragma unroll
-            for (int g = 0; g < (1 << sp); g++) {
-                const ShoupConst w = twf[idx0 + g];
-#pragma unroll
-                for (int e = 0; e < dist; e++) {
-                    const int k0 = g * 2 * dist + e, k1 = k0 + dist;
-                    const u64 u = csub(a[k0], q2);
-                    const u64 v = mul_shoup_lazy(a[k1], w, q);
-                    a[k0] = u + v;
-                    a[k1] = u - v + q2;
-                }
-            }
-        }
-    }
-    template <bool LAST> __device__ __forceinline__ void inv16(V (&a)[16], unsigned s_base, unsigned G) const
-    {
-#pragma unroll
-        for (int sp = 3; sp >= 0; sp--) {
-            const int dist = 8 >> sp;
-            const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
-#pragma unroll
-            for (int g = 0; g < (1 << sp); g++) {
-                const bool fin = LAST && sp == 0;
-                const ShoupConst w = fin ? nv[1] : twi[idx0 + g];
-#pragma unroll
-                for (int e = 0; e < dist; e++) {
-                    const int k0 = g * 2 * dist + e, k1 = k0 + dist;
-                    const u64 u = a[k0], v = a[k1];
-                    a[k0] = fin ? mul_shoup_lazy(u + v, nv[0], q) : csub(u + v, q2);
-                    a[k1] = mul_shoup_lazy(u - v + q2, w, q);
-                }
-            }
-        }
-    }
-};
-
-__device__ __forceinline__ ArithFp make_fp(const DevTables &T, unsigned mi, int logN)
-{
-    ArithFp A;
-    A.q = T.mod[mi].qd;
-    A.qinv = T.mod[mi].qinvd;
-    A.twf = T.twd_fwd + ((size_t)mi << logN);
-    A.twi = T.twd_inv + ((size_t)mi << logN);
-    A.nv = T.ninvd + 2 * mi;
-    return A;
-}
-__device__ __forceinline__ ArithInt make_int(const DevTables &T, unsigned mi, int logN)
-{
-    ArithInt A;
-    A.q = T.mod[mi].q;
-    A.q2 = 2 * A.q;
-    A.twf = T.tw_fwd + ((size_t)mi << logN);
-    A.twi = T.tw_inv + ((size_t)mi << logN);
-    A.nv = T.ninv + 2 * mi;
-    return A;
-}
-
-// LDS tile of 16 groups x 256 elements; one pad word per 16 elements and 16 pad words per group
-// keep both the "stride-16" and the "16 consecutive" access patterns free of bank conflicts.
-#define TILE_GROUP 272
-#define TILE_WORDS (16 * TILE_GROUP)
-__device__ __forceinline__ unsigned tile_at(unsigned grp, unsigned i) { return grp * TILE_GROUP + i + (i >> 4); }
-// column pass: row r (0..255) of column c (0..15); 16 pad words after every 16 rows
-__device__ __forceinline__ unsigned col_at(unsigned r, unsigned c) { return (r >> 4) * TILE_GROUP + (r & 15) * 16 + c; }
-
-// ---- "block" pass: the last eight forward stages (first eight inverse stages) on 16 contiguous
-// blocks of 256 elements per work-group.
-template <int LOGN, class A>
-__device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A &ar, u64 *lds, unsigned tile)
-{
-    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
-    const unsigned bg = tile * 16 + blk; // block index within the limb
-    typename A::V a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) {
-        const u64 m = limb[bg * 256 + il + 16 * k];
-        a[k] = LOGN > 8 ? ar.load_mid(m) : ar.load(m);
-    }
-    ar.fwd16(a, LOGN - 8, bg, true);
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = ar.store_mid(a[k]);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, 16 * il + k)]);
-    ar.fwd16(a, LOGN - 4, bg * 16 + il, true);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_final(a[k]);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = lds[tile_at(blk, il + 16 * k)];
-}
-
-template <int LOGN, class A>
-__device__ __forceinline__ void inv_blocks_body(u64 *__restrict__ limb, const A &ar, u64 *lds, unsigned tile)
-{
-    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
-    const unsigned bg = tile * 16 + blk;
-    typename A::V a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = limb[bg * 256 + il + 16 * k];
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load(lds[tile_at(blk, 16 * il + k)]);
-    ar.template inv16<false>(a, LOGN - 4, bg * 16 + il);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_mid(a[k]);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, il + 16 * k)]);
-    ar.template inv16<false>(a, LOGN - 8, bg);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = ar.store_mid(a[k]); // the column pass finishes
-}
-
-// grid.x = (N/4096) * batch
-template <int LOGN>
-__global__ __launch_bounds__(256) void k_ntt_fwd_blocks(u64 *__restrict__ data, DevTables T, LimbBatch lb)
-{
-    __shared__ u64 lds[TILE_WORDS];
-    constexpr unsigned TILES = (1u << LOGN) / 4096;
-    const unsigned tile = blockIdx.x % TILES, b = blockIdx.x / TILES;
-    const unsigned mi = lb.mod[b];
-    u64 *limb = data + ((size_t)lb.slot[b] << LOGN);
-    if (T.mod[mi].qd != 0.0)
-        fwd_blocks_body<LOGN>(limb, make_fp(T, mi, LOGN), lds, tile);
-    else
-        fwd_blocks_body<LOGN>(limb, make_int(T, mi, LOGN), lds, tile);
-}
-
-template <int LOGN>
-__global__ __launch_bounds__(256) void k_ntt_inv_blocks(u64 *__restrict__ data, DevTables T, LimbBatch lb)
-{
-    __shared__ u64 lds[TILE_WORDS];
-    constexpr unsigned TILES = (1u << LOGN) / 4096;
-    const unsigned tile = blockIdx.x % TILES, b = blockIdx.x / TILES;
-    const unsigned mi = lb.mod[b];
-    u64 *limb = data + ((size_t)lb.slot[b] << LOGN);
-    if (T.mod[mi].qd != 0.0)
-        inv_blocks_body<LOGN>(limb, make_fp(T, mi, LOGN), lds, tile);
-    else
-        inv_blocks_body<LOGN>(limb, make_int(T, mi, LOGN), lds, tile);
-}
-
-// ---- "column" pass for N = 2^16: stages 0-7 on 256 rows x 16 columns per work-group (element
-// (r, c) at r*256 + c).
-template <class A> __device__ __forceinline__ void fwd_cols16_body(u64 *__restrict__ limb, const A &ar, u64 *lds)
-{
-    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
-    typename A::V a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load(limb[(rl + 16 * k) * 256 + c]);
-    ar.fwd16(a, 0, 0, false);
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a[k]);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(16 * rl + k, c)]);
-    ar.fwd16(a, 4, rl, true);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[(16 * rl + k) * 256 + c] = ar.store_mid(a[k]); // the block pass finishes
-}
-
-template <class A> __device__ __forceinline__ void inv_cols16_body(u64 *__restrict__ limb, const A &ar, u64 *lds)
-{
-    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
-    typename A::V a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[(16 * rl + k) * 256 + c]);
-    ar.template inv16<false>(a, 4, rl);
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[col_at(16 * rl + k, c)] = ar.store_mid(a[k]);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(rl + 16 * k, c)]);
-    ar.template inv16<true>(a, 0, 0);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[(rl + 16 * k) * 256 + c] = ar.store_final(a[k]);
-}
-
-// grid.x = 16 * batch
-__global__ __launch_bounds__(256) void k_ntt_fwd_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb)
-{
-    __shared__ u64 lds[TILE_WORDS];
-    const unsigned tile = blockIdx.x & 15, b = blockIdx.x >> 4;
-    const unsigned mi = lb.mod[b];
-    u64 *limb = data + ((size_t)lb.slot[b] << 16) + tile * 16;
-    if (T.mod[mi].qd != 0.0)
-        fwd_cols16_body(limb, make_fp(T, mi, 16), lds);
-    else
-        fwd_cols16_body(limb, make_int(T, mi, 16), lds);
-}
-
-__global__ __launch_bounds__(256) void k_ntt_inv_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb)
-{
-    __shared__ u64 lds[TILE_WORDS];
-    const unsigned tile = blockIdx.x & 15, b = blockIdx.x >> 4;
-    const unsigned mi = lb.mod[b];
-    u64 *limb = data + ((size_t)lb.slot[b] << 16) + tile * 16;
-    if (T.mod[mi].qd != 0.0)
-        inv_cols16_body(limb, make_fp(T, mi, 16), lds);
-    else
-        inv_cols16_body(limb, make_int(T, mi, 16), lds);
-}
-
-// ---- "column" pass for N = 2^12: stages 0-3 on 16 rows x 256 columns, one thread per column.
-template <class A> __device__ __forceinline__ void fwd_cols12_body(u64 *__restrict__ limb, const A &ar)
-{
-    const unsigned c = threadIdx.x;
-    typename A::V a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load(limb[k * 256 + c]);
-    ar.fwd16(a, 0, 0, false);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[k * 256 + c] = ar.store_mid(a[k]);
-}
-template <class A> __device__ __forceinline__ void inv_cols12_body(u64 *__restrict__ limb, const A &ar)
-{
-    const unsigned c = threadIdx.x;
-    typename A::V a[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[k * 256 + c]);
-    ar.template inv16<true>(a, 0, 0);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[k * 256 + c] = ar.store_final(a[k]);
-}
-
-__global__ __launch_bounds__(256) void k_ntt_fwd_cols12(u64 *__restrict__ data, DevTables T, LimbBatch lb)
-{
-    const unsigned mi = lb.mod[blockIdx.x];
-    u64 *limb = data + ((size_t)lb.slot[blockIdx.x] << 12);
-    if (T.mod[mi].qd != 0.0)
-        fwd_cols12_body(limb, make_fp(T, mi, 12));
-    else
-        fwd_cols12_body(limb, make_int(T, mi, 12));
-}
-
-__global__ __launch_bounds__(256) void k_ntt_inv_cols12(u64 *__restrict__ data, DevTables T, LimbBatch lb)
-{
-    const unsigned mi = lb.mod[blockIdx.x];
-    u64 *limb = data + ((size_t)lb.slot[blockIdx.x] << 12);
-    if (T.mod[mi].qd != 0.0)
-        inv_cols12_body(limb, make_fp(T, mi, 12));
-    else
-        inv_cols12_body(limb, make_int(T, mi, 12));
-}
-
-// ---------------------------------------------------------------------------------- elementwise
-
-// op 0 add, 1 sub, 2 mul.  Limb l of the flat [limbs][N] buffers uses modulus l % level;
-// b_limbs = number of limbs of b before it repeats (pmult: the plaintext has `level` limbs).
-__global__ __launch_bounds__(256) void k_limbwise(const u64 *__restrict__ a, const u64 *__restrict__ b,
-                                                  u64 *__restrict__ out, DevTables T, int op, int level, int b_limbs,
-                                                  int logN)
-{
-    const unsigned l = blockIdx.y;
-    const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const ModConst m = T.mod[l % level];
-    const u64 x = a[((size_t)l << logN) + n], y = b[((size_t)(l % b_limbs) << logN) + n];
-    u64 r;
-    if (op == 0)
-        r = csub(x + y, m.q);
-    else if (op == 1)
-        r = csub(x + m.q - y, m.q);
-    else
-        r = mul_mod(x, y, m);
-    out[((size_t)l << logN) + n] = r;
-}
-
-struct ScalarArgs {
-    ShoupConst s[64];
-};
-__global__ __launch_bounds__(256) void k_cmult(const u64 *__restrict__ a, u64 *__restrict__ out, DevTables T,
-                                               ScalarArgs sc, int level, int logN)
-{
-    const unsigned l = blockIdx.y;
-    const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const unsigned i = l % level;
-    out[((size_t)l << logN) + n] = mul_shoup(a[((size_t)l << logN) + n], sc.s[i], T.mod[i].q);
-}
-
-// Tensor product: d0 = a0 b0, d1 = a0 b1 + a1 b0 -> out (may alias A or B); d2 = a1 b1 -> d2 and d2copy.
-__global__ __launch_bounds__(256) void k_tensor(const u64 *A, const u64 *B, u64 *out, u64 *__restrict__ d2,
-                                                u64 *__restrict__ d2copy, DevTables T, int level, int logN)
-{
-    const unsigned i = blockIdx.y;
-    const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const ModConst m = T.mod[i];
-    const size_t o0 = ((size_t)i << logN) + n, o1 = ((size_t)(level + i) << logN) + n;
-    const u64 a0 = A[o0], a1 = A[o1], b0 = B[o0], b1 = B[o1];
-    U128 acc{0, 0};
-    mac128(acc, a0, b1);
-    mac128(acc, a1, b0);
-    const u64 r0 = mul_mod(a0, b0, m), r1 = reduce128(acc, m), r2 = mul_mod(a1, b1, m);
-    out[o0] = r0;
-    out[o1] = r1;
-    d2[o0] = r2;
-    d2copy[o0] = r2;
-}
-
-// ----------------------------------------------------------------------------------- key switch
-
-__device__ __forceinline__ int active_mod(int a, int level, int L) { return a < level ? a : L + (a - level); }
-
-// NTT-domain index of the automorphism sigma_g: out[k] = in[k'] with
-// 2 brv(k') + 1 = (2 brv(k) + 1) g mod 2N.
-__device__ __forceinline__ unsigned galois_index(unsigned k, unsigned g, int logN)
-{
-    const unsigned b = __brev(k) >> (32 - logN);
-    const unsigned e = ((2 * b + 1) * g) & ((2u << logN) - 1);
-    return __brev((e - 1) >> 1) >> (32 - logN);
-}
-
-// Digit decomposition + ModUp.  x: coefficient-domain limbs [level][N]; d: the same polynomial in
-// the NTT domain.  For digit j = blockIdx.y: y_i = x_i (D/q_i)^-1 mod q_i, and for every active
-// modulus t outside the digit raised[j][a] = sum_i y_i (D/q_i mod t) mod t (coefficient domain,
-// no correction of the overshoot); inside the digit raised[j][a] = d[a] (already transformed).
-// blockIdx.z selects a contiguous share of the target limbs.  When all ciphertext primes are
-// below 2^50 (fp != 0) the products for targets below 2^50 are FP64 error-free products.
-template <int AMAX>
-__global__ __launch_bounds__(256) void k_modup(const u64 *__restrict__ x, const u64 *__restrict__ d,
-                                               u64 *__restrict__ raised, DevTables T, int level, int L, int K,
-                                               int alpha, int logN, int fp)
-{
-    const int j = blockIdx.y;
-    const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const int M = L + K, Ma = level + K;
-    const int lo = j * alpha, hi = min(lo + alpha, level), na = hi - lo;
-    const size_t slot = (size_t)j * alpha + (na - 1);
-    const int per = (Ma + gridDim.z - 1) / gridDim.z;
-    const int a_lo = blockIdx.z * per, a_hi = min(a_lo + per, Ma);
-    u64 yi[AMAX];
-    double yd[AMAX];
-#pragma unroll
-    for (int ii = 0; ii < AMAX; ii++) {
-        yi[ii] = 0;
-        yd[ii] = 0.0;
-        if (ii < na) {
-            const u64 v = x[((size_t)(lo + ii) << logN) + n];
-            const ModConst m = T.mod[lo + ii];
-            if (fp) {
-                const double r = fp_reduce(fp_mulmod(u2d(v), T.up_inv_d[slot * alpha + ii], m.qd, m.qinvd), m.qd, m.qinvd);
-                yd[ii] = r < 0.0 ? r + m.qd : r;
-                yi[ii] = d2u(yd[ii]);
-            } else
-                yi[ii] = mul_shoup(v, T.up_inv[slot * alpha + ii], m.q);
-            if (blockIdx.z == 0) raised[(((size_t)j * Ma + lo + ii) << logN) + n] = d[((size_t)(lo + ii) << logN) + n];
-        }
-    }
-    for (int a = a_lo; a < a_hi; a++) {
-        if (a >= lo && a < hi) continue;
-        const int mi = active_mod(a, level, L);
-        const ModConst m = T.mod[mi];
-        u64 out;
-        if (fp && m.qd != 0.0) {
-            double acc = 0.0;
-#pragma unroll
-            for (int ii = 0; ii < AMAX; ii++)
-                if (ii < na) acc += fp_mulmod(yd[ii], T.up_hat_d[(slot * alpha + ii) * M + mi], m.qd, m.qinvd);
-            const double r = fp_reduce(acc, m.qd, m.qinvd);
-            out = d2u(r < 0.0 ? r + m.qd : r);
-        } else {
-            U128 acc{0, 0};
-#pragma unroll
-            for (int ii = 0; ii < AMAX; ii++)
-                if (ii < na) mac128(acc, yi[ii], T.up_hat[(slot * alpha + ii) * M + mi]);
-            out = reduce128(acc, m);
-        }
-        raised[(((size_t)j * Ma + a) << logN) + n] = out;
-    }
-}
-
-// Inner product with the evaluation key on active limb a = blockIdx.y:
-// u[c][a][n] = sum_j raised[j][a][pi_g(n)] * evk[j][c][mod(a)][n].
-__global__ __launch_bounds__(256) void k_inner(const u64 *__restrict__ raised, const u64 *__restrict__ evk,
-                                               u64 *__restrict__ u, DevTables T, int level, int L, int K, int beta,
-                                               unsigned g, int logN)
-{
-    const int a = blockIdx.y;
-    const unsigned n = blockIdx.x * 256 + threadIdx.x;
-    const int M = L + K, Ma = level + K;
-    const int mi = active_mod(a, level, L);
-    const unsigned src = g == 1 ? n : galois_index(n, g, logN);
-    U128 acc0{0, 0}, acc1{0, 0};
-    for (int j = 0; j < beta; j++) {
-        const u64 dv = raised[(((size_t)j * Ma + a) << logN) + src];
-        const u64 kb = evk[((((size_t)j * 2 + 0) * M + mi) << logN) + n];
-        const u64 ka = evk[((((size_t)j * 2 + 1) * M + mi) << logN) + n];
-        mac128(acc0, dv, kb);
-        mac128(acc1, dv, ka);
-    }
-    const ModConst m = T.mod[mi];
-    u[(((size_t)0 * Ma + a) << logN) + n] = reduce128(acc0, m);
-    u[(((size_t)1 * Ma + a) << logN) + n] = reduce128(acc1, m);
-}
-
-// ModDown, conversion step.  u: [2][level+K][N] whose special limbs are in the coefficient
-// domain.  y_k = w_k (P/p_k)^-1 mod p_k; r[c][i] = sum_k y_k (P/p_k mod q_i) mod q_i.
-__global__ __launch_bounds__(256) void k_moddown_conv(const u64 *__restrict__ u, u64 *__restrict__ r, DevTables T,
-                                                      int level, int L, int K, int logN)
-{
-    const int c = blockIdx.y;
-    const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const int Ma = level + K;
-    const int per = (level + gridDim.z - 1) / gridDim.z;
-    const int i_lo = blockIdx.z * per, i_hi = min(i_lo + per, level);
-    u64 y[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++)
-        y[k] = k < K ? mul_shoup(u[(((size_t)c * Ma + level + k) << logN) + n], T.dn_inv[k], T.mod[L + k].q) : 0;
-    for (int i = i_lo; i < i_hi; i++) {
-        U128 acc{0, 0};
-#pragma unroll
-        for (int k = 0; k < 16; k++)
-            if (k < K) mac128(acc, y[k], T.dn_hat[(size_t)k * L + i]);
-        r[(((size_t)c * level + i) << logN) + n] = reduce128(acc, T.mod[i]);
-    }
-}
-
-// ModDown, final step: out[c][i] = (u[c][i] - r[c][i]) P^-1 + addend, all in the NTT domain.
-// addend: mode 0 none; 1 out itself (hmult: d0, d1 already there); 2 rotation: component 0 gets
-// c0 read through pi_g, component 1 nothing.
-__global__ __launch_bounds__(256) void k_moddown_fin(const u64 *__restrict__ u, const u64 *__restrict__ r,
-                                                     u64 *out, const u64 *__restrict__ c0, DevTables T, int level,
-                                                     int K, int mode, unsigned g, int logN)
-{
-    const int ci = blockIdx.y; // c * level + i
-    const int c = ci / level, i = ci % level;
-    const unsigned n = blockIdx.x * 256 + threadIdx.x;
-    const int Ma = level + K;
-    const u64 q = T.mod[i].q;
-    const u64 uv = u[(((size_t)c * Ma + i) << logN) + n];
-    const u64 rv = r[((size_t)ci << logN) + n];
-    u64 v = mul_shoup(uv + q - rv, T.dn_pinv[i], q);
-    if (mode == 1)
-        v = csub(v + out[((size_t)ci << logN) + n], q);
-    else if (mode == 2 && c == 0)
-        v = csub(v + c0[((size_t)i << logN) + galois_index(n, g, logN)], q);
-    out[((size_t)ci << logN) + n] = v;
-}
-
-// Rescale, conversion: t[c] = last limb in the coefficient domain; r[c][i] = centred(t) mod q_i.
-__global__ __launch_bounds__(256) void k_rescale_conv(const u64 *__restrict__ t, u64 *__restrict__ r, DevTables T,
-                                                      int level, int logN)
-{
-    const int c = blockIdx.y;
-    const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const u64 ql = T.mod[level - 1].q;
-    const u64 v = t[((size_t)c << logN) + n];
-    const bool neg = v > (ql - 1) / 2;
-    const u64 mag = neg ? ql - v : v;
-    for (int i = 0; i < level - 1; i++) {
-        const ModConst m = T.mod[i];
-        const u64 w = reduce64(mag, m);
-        r[(((size_t)c * (level - 1) + i) << logN) + n] = neg ? (w ? m.q - w : 0) : w;
-    }
-}
-
-// Rescale, final: out[c][i] = (ct[c][i] - r[c][i]) q_last^-1.
-__global__ __launch_bounds__(256) void k_rescale_fin(const u64 *__restrict__ ct, const u64 *__restrict__ r,
-                                                     u64 *__restrict__ out, DevTables T, int level, int L, int logN)
-{
-    const int ci = blockIdx.y; // c * (level-1) + i
-    const int c = ci / (level - 1), i = ci % (level - 1);
-    const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const u64 q = T.mod[i].q;
-    const u64 cv = ct[(((size_t)c * level + i) << logN) + n];
-    const u64 rv = r[((size_t)ci << logN) + n];
-    out[((size_t)ci << logN) + n] = mul_shoup(cv + q - rv, T.rs_inv[(size_t)(level - 1) * L + i], q);
-}
-
-// ===================================================================================== host side
+#include "kernels_ks.h"
 
 #define HIP_TRY(ctx, expr)                                                                                           \
     do {                                                                                                             \
@@ -677,14 +44,19 @@ template <class Tv> static int32_t upload(he_ctx *c, const std::vector<Tv> &v, c
 int32_t dev_upload_tables(he_ctx *c)
 {
     if (c->logN != 12 && c->logN != 16) return HE_EINVAL;
-    if (c->alpha > 16 || c->K > 16 || c->M > 64) return HE_EINVAL;
+    if (c->alpha > 8 || c->K > 8 || c->M > 64) return HE_EINVAL; // conversion kernels are built for up to 8 sources
     HIP_TRY(c, hipSetDevice(c->device));
     int32_t rc;
 #define UP(field)                                                                                                    \
     if ((rc = upload(c, c->field, &c->dev.field)) != HE_OK) return rc;
     if ((rc = upload(c, c->modc, &c->dev.mod)) != HE_OK) return rc;
-    UP(tw_fwd) UP(tw_inv) UP(ninv) UP(twd_fwd) UP(twd_inv) UP(ninvd) UP(up_inv) UP(up_inv_d) UP(up_hat_d) UP(up_hat) UP(dn_inv) UP(dn_hat) UP(dn_pinv) UP(rs_inv)
+    UP(tw_fwd) UP(tw_inv) UP(ninv) UP(twd_fwd) UP(twd_inv) UP(ninvd)
+    UP(up_inv) UP(up_hat) UP(up_inv_d) UP(up_hat_d) UP(up_hat_dh)
+    UP(dn_inv) UP(dn_hat) UP(dn_pinv) UP(dn_inv_d) UP(dn_hat_d) UP(dn_hat_dh) UP(dn_pinv_d)
+    UP(rs_inv) UP(rs_inv_d)
 #undef UP
+    c->dev.up_split = c->up_split ? 1 : 0;
+    c->dev.dn_split = c->dn_split ? 1 : 0;
     return HE_OK;
 }
 
@@ -724,12 +96,12 @@ extern "C" int32_t he_evk_to_host(const he_evk *evk, uint64_t *h_out)
 
 // ---- optional per-kernel timing with HIP events on the launch stream (he_profile_start/stop)
 enum KernelId {
-    KID_NTT_FWD_COLS, KID_NTT_FWD_BLOCKS, KID_NTT_INV_BLOCKS, KID_NTT_INV_COLS, KID_LIMBWISE, KID_CMULT, KID_TENSOR,
-    KID_MODUP, KID_INNER, KID_MODDOWN_CONV, KID_MODDOWN_FIN, KID_RESCALE_CONV, KID_RESCALE_FIN, KID_COPY, KID_COUNT
+    KID_FWD_COLS, KID_FWD_COLS_MODUP, KID_FWD_COLS_MODDOWN, KID_FWD_COLS_RESCALE, KID_FWD_BLOCKS, KID_FWD_BLOCKS_FIN,
+    KID_INV_BLOCKS, KID_INV_COLS, KID_LIMBWISE, KID_CMULT, KID_TENSOR, KID_INNER, KID_COUNT
 };
 static const char *const kKernelNames[KID_COUNT] = {
-    "k_ntt_fwd_cols", "k_ntt_fwd_blocks", "k_ntt_inv_blocks", "k_ntt_inv_cols", "k_limbwise", "k_cmult", "k_tensor",
-    "k_modup", "k_inner", "k_moddown_conv", "k_moddown_fin", "k_rescale_conv", "k_rescale_fin", "copy"};
+    "k_ntt_fwd_cols", "k_ntt_fwd_cols_modup", "k_ntt_fwd_cols_moddown", "k_ntt_fwd_cols_rescale", "k_ntt_fwd_blocks",
+    "k_ntt_fwd_blocks_fin", "k_ntt_inv_blocks", "k_ntt_inv_cols", "k_limbwise", "k_cmult", "k_tensor", "k_inner"};
 
 static void prof_begin(he_ctx *c, hipStream_t st, int kid, double bytes)
 {
@@ -805,47 +177,138 @@ static inline int32_t launch_ok(he_ctx *c)
     return HE_OK;
 }
 
-// NTT of the limbs listed in (slots, mods), all relative to `base`
-static int32_t run_ntt(he_ctx *c, u64 *base, const std::vector<int> &slots, const std::vector<int> &mods, bool inverse,
-                       hipStream_t st)
+// ---- limb lists -----------------------------------------------------------------------------------
+
+struct LimbList {
+    std::vector<int> slot, src, mod;
+    void add(int s, int m) { slot.push_back(s), src.push_back(s), mod.push_back(m); }
+    void add(int s, int from, int m) { slot.push_back(s), src.push_back(from), mod.push_back(m); }
+    int size() const { return (int)slot.size(); }
+};
+
+// calls launch(batch, count) for chunks of at most HE_MAXB limbs; limbs on the integer path (moduli
+// of 2^50 and above) take about three times longer and are scheduled first
+template <class F> static int32_t for_batches(he_ctx *c, const LimbList &l, F launch)
 {
-    const int total = (int)slots.size();
-    // limbs on the integer path take about three times longer: schedule them first
+    const int total = l.size();
     std::vector<int> order(total);
     for (int b = 0; b < total; b++) order[b] = b;
-    std::stable_partition(order.begin(), order.end(), [&](int b) { return c->modc[mods[b]].qd == 0.0; });
+    std::stable_partition(order.begin(), order.end(), [&](int b) { return c->modc[l.mod[b]].qd == 0.0; });
     for (int off = 0; off < total; off += HE_MAXB) {
         const int nb = std::min(HE_MAXB, total - off);
         LimbBatch lb;
         for (int b = 0; b < nb; b++) {
-            lb.slot[b] = (uint16_t)slots[order[off + b]];
-            lb.mod[b] = (uint8_t)mods[order[off + b]];
+            const int o = order[off + b];
+            lb.slot[b] = (uint16_t)l.slot[o];
+            lb.src[b] = (uint16_t)l.src[o];
+            lb.mod[b] = (uint8_t)l.mod[o];
         }
-        // each pass reads and writes every limb of the batch once
-        const double bytes = (double)nb * (double)c->N * 16.0;
-        if (c->logN == 16) {
-            if (!inverse) {
-                KLAUNCH(c, st, KID_NTT_FWD_COLS, bytes, k_ntt_fwd_cols16<<<16 * nb, 256, 0, st>>>(base, c->dev, lb));
-                KLAUNCH(c, st, KID_NTT_FWD_BLOCKS, bytes,
-                        k_ntt_fwd_blocks<16><<<16 * nb, 256, 0, st>>>(base, c->dev, lb));
-            } else {
-                KLAUNCH(c, st, KID_NTT_INV_BLOCKS, bytes,
-                        k_ntt_inv_blocks<16><<<16 * nb, 256, 0, st>>>(base, c->dev, lb));
-                KLAUNCH(c, st, KID_NTT_INV_COLS, bytes, k_ntt_inv_cols16<<<16 * nb, 256, 0, st>>>(base, c->dev, lb));
-            }
-        } else {
-            if (!inverse) {
-                KLAUNCH(c, st, KID_NTT_FWD_COLS, bytes, k_ntt_fwd_cols12<<<nb, 256, 0, st>>>(base, c->dev, lb));
-                KLAUNCH(c, st, KID_NTT_FWD_BLOCKS, bytes, k_ntt_fwd_blocks<12><<<nb, 256, 0, st>>>(base, c->dev, lb));
-            } else {
-                KLAUNCH(c, st, KID_NTT_INV_BLOCKS, bytes, k_ntt_inv_blocks<12><<<nb, 256, 0, st>>>(base, c->dev, lb));
-                KLAUNCH(c, st, KID_NTT_INV_COLS, bytes, k_ntt_inv_cols12<<<nb, 256, 0, st>>>(base, c->dev, lb));
-            }
-        }
+        launch(lb, nb);
         int32_t rc = launch_ok(c);
         if (rc != HE_OK) return rc;
     }
     return HE_OK;
+}
+
+static ConvArgs conv_args(const he_ctx *c, const u64 *src, int level)
+{
+    ConvArgs cv;
+    cv.src = src;
+    cv.level = level;
+    cv.L = c->L;
+    cv.K = c->K;
+    cv.alpha = c->alpha;
+    return cv;
+}
+
+static const FinArgs kNoFin = {nullptr, nullptr, nullptr, nullptr, nullptr, 0, 1, 0, 1u};
+
+// Forward NTT of the listed limbs of `data`.  pro selects what the column pass transforms (the
+// limb's own content, or a base conversion of cv.src); with fin != nullptr the block pass writes
+// (u - ntt) * const + addend to fin->out instead of the transform itself.
+// src_limbs = number of source limbs the prologue reads in total (for the byte count).
+static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList &l, int pro, const ConvArgs &cv,
+                           const FinArgs *fin, int src_limbs)
+{
+    const bool wide = std::max(c->alpha, c->K) > 4;
+    const double N8 = (double)c->N * 8.0;
+    return for_batches(c, l, [&](const LimbBatch &lb, int nb) {
+        const double cols_bytes = pro == PRO_LOAD ? 2.0 * nb * N8 : (double)(src_limbs + nb) * N8;
+        const int kid_cols = pro == PRO_LOAD      ? KID_FWD_COLS
+                             : pro == PRO_MODUP   ? KID_FWD_COLS_MODUP
+                             : pro == PRO_MODDOWN ? KID_FWD_COLS_MODDOWN
+                                                  : KID_FWD_COLS_RESCALE;
+#define COLS1(KERN, GRID, P, NS)                                                                                     \
+    KLAUNCH(c, st, kid_cols, cols_bytes, KERN<P, NS><<<GRID, 256, 0, st>>>(data, c->dev, lb, cv))
+#define COLS(KERN, GRID)                                                                                             \
+    switch (pro) {                                                                                                   \
+    case PRO_LOAD: COLS1(KERN, GRID, PRO_LOAD, 4); break;                                                            \
+    case PRO_MODUP:                                                                                                  \
+        if (wide)                                                                                                    \
+            COLS1(KERN, GRID, PRO_MODUP, 8);                                                                        \
+        else                                                                                                         \
+            COLS1(KERN, GRID, PRO_MODUP, 4);                                                                         \
+        break;                                                                                                       \
+    case PRO_MODDOWN:                                                                                                \
+        if (wide)                                                                                                    \
+            COLS1(KERN, GRID, PRO_MODDOWN, 8);                                                                      \
+        else                                                                                                         \
+            COLS1(KERN, GRID, PRO_MODDOWN, 4);                                                                       \
+        break;                                                                                                       \
+    default: COLS1(KERN, GRID, PRO_RESCALE, 4); break;                                                               \
+    }
+        if (c->logN == 16) {
+            COLS(k_ntt_fwd_cols16, 16 * nb)
+        } else {
+            COLS(k_ntt_fwd_cols12, nb)
+        }
+#undef COLS
+#undef COLS1
+        if (fin) {
+            // reads the transform's input, the minuend and the addend, writes the result
+            const double b = (double)nb * N8 * (3.0 + (fin->mode == 1 ? 1.0 : fin->mode == 2 ? 0.5 : 0.0));
+            if (c->logN == 16)
+                KLAUNCH(c, st, KID_FWD_BLOCKS_FIN, b,
+                        k_ntt_fwd_blocks<16, EPI_FIN><<<16 * nb, 256, 0, st>>>(data, c->dev, lb, *fin));
+            else
+                KLAUNCH(c, st, KID_FWD_BLOCKS_FIN, b,
+                        k_ntt_fwd_blocks<12, EPI_FIN><<<nb, 256, 0, st>>>(data, c->dev, lb, *fin));
+        } else {
+            if (c->logN == 16)
+                KLAUNCH(c, st, KID_FWD_BLOCKS, 2.0 * nb * N8,
+                        k_ntt_fwd_blocks<16, EPI_STORE><<<16 * nb, 256, 0, st>>>(data, c->dev, lb, kNoFin));
+            else
+                KLAUNCH(c, st, KID_FWD_BLOCKS, 2.0 * nb * N8,
+                        k_ntt_fwd_blocks<12, EPI_STORE><<<nb, 256, 0, st>>>(data, c->dev, lb, kNoFin));
+        }
+    });
+}
+
+// Inverse NTT: limb b read at src + l.src[b]*N, result at dst + l.slot[b]*N; scale folds a base
+// conversion constant into the final 1/N.
+static int32_t ntt_inverse(he_ctx *c, hipStream_t st, const u64 *src, u64 *dst, const LimbList &l, int scale,
+                           const ConvArgs &cv)
+{
+    const double N8 = (double)c->N * 8.0;
+    return for_batches(c, l, [&](const LimbBatch &lb, int nb) {
+        const double bytes = 2.0 * nb * N8;
+#define ICOLS1(KERN, GRID, S) KLAUNCH(c, st, KID_INV_COLS, bytes, KERN<S><<<GRID, 256, 0, st>>>(dst, c->dev, lb, cv))
+#define ICOLS(KERN, GRID)                                                                                            \
+    switch (scale) {                                                                                                 \
+    case SCALE_NONE: ICOLS1(KERN, GRID, SCALE_NONE); break;                                                          \
+    case SCALE_MODUP: ICOLS1(KERN, GRID, SCALE_MODUP); break;                                                        \
+    default: ICOLS1(KERN, GRID, SCALE_MODDOWN); break;                                                               \
+    }
+        if (c->logN == 16) {
+            KLAUNCH(c, st, KID_INV_BLOCKS, bytes, k_ntt_inv_blocks<16><<<16 * nb, 256, 0, st>>>(src, dst, c->dev, lb));
+            ICOLS(k_ntt_inv_cols16, 16 * nb)
+        } else {
+            KLAUNCH(c, st, KID_INV_BLOCKS, bytes, k_ntt_inv_blocks<12><<<nb, 256, 0, st>>>(src, dst, c->dev, lb));
+            ICOLS(k_ntt_inv_cols12, nb)
+        }
+#undef ICOLS
+#undef ICOLS1
+    });
 }
 
 static int32_t dev_guard(he_ctx *c)
@@ -862,16 +325,16 @@ static int32_t ntt_api(he_ctx *ctx, uint64_t *d_limbs, const int32_t *h_mod_idx,
     if (!d_limbs || !h_mod_idx || batch < 0) return HE_EINVAL;
     for (int b = 0; b < batch; b++)
         if (h_mod_idx[b] < 0 || h_mod_idx[b] >= ctx->M) return HE_EINVAL;
-    // slots are 16-bit: walk the buffer in windows
+    const ConvArgs cv = conv_args(ctx, nullptr, 1);
+    // limb slots are 16-bit: walk the buffer in windows
     const int WIN = 32768;
     for (int off = 0; off < batch; off += WIN) {
         const int nb = std::min(WIN, batch - off);
-        std::vector<int> slots(nb), mods(nb);
-        for (int b = 0; b < nb; b++) {
-            slots[b] = b;
-            mods[b] = h_mod_idx[off + b];
-        }
-        rc = run_ntt(ctx, d_limbs + (size_t)off * ctx->N, slots, mods, inv, (hipStream_t)stream);
+        LimbList l;
+        for (int b = 0; b < nb; b++) l.add(b, h_mod_idx[off + b]);
+        u64 *base = d_limbs + (size_t)off * ctx->N;
+        rc = inv ? ntt_inverse(ctx, (hipStream_t)stream, base, base, l, SCALE_NONE, cv)
+                 : ntt_forward(ctx, (hipStream_t)stream, base, l, PRO_LOAD, cv, nullptr, 0);
         if (rc != HE_OK) return rc;
     }
     return HE_OK;
@@ -949,12 +412,12 @@ static WsLayout ws_layout(const he_ctx *c, int level)
     const size_t Ma = level + c->K, beta = (level + c->alpha - 1) / c->alpha;
     WsLayout w;
     size_t o = 0;
-    w.x = o, o += level;
-    w.d = o, o += level;
-    w.raised = o, o += beta * Ma;
-    w.u = o, o += 2 * Ma;
-    w.r = o, o += 2 * level;
-    w.tmp = o, o += 2 * level;
+    w.x = o, o += std::max(level, 2); // y: inverse transform of the switched polynomial, scaled
+    w.d = o, o += level;              // d2 of the tensor product (NTT domain)
+    w.raised = o, o += beta * Ma;     // raised digits (slots of a digit's own limbs stay unused)
+    w.u = o, o += 2 * Ma;             // inner products
+    w.r = o, o += 2 * level;          // ModDown / rescale corrections
+    w.tmp = o, o += 2 * level;        // rotate_sum: the rotated ciphertext
     w.total = o;
     return w;
 }
@@ -967,79 +430,60 @@ extern "C" int32_t he_workspace_bytes(const he_ctx *ctx, int32_t level, int32_t 
     return HE_OK;
 }
 
-// Steps 1-2 of the key switch: x (a copy of d at ws.x, NTT domain) -> iNTT -> ModUp -> NTT of the
-// limbs outside each digit.  d_ntt: the polynomial in the NTT domain.
+// Steps 1-2 of the key switch.  d_ntt: the polynomial in the NTT domain (level limbs).
 static int32_t ks_raise(he_ctx *c, const u64 *d_ntt, u64 *ws, const WsLayout &w, int level, hipStream_t st)
 {
     const size_t N = c->N;
     const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha;
-    std::vector<int> slots, mods;
-    for (int i = 0; i < level; i++) slots.push_back(i), mods.push_back(i);
-    int32_t rc = run_ntt(c, ws + w.x * N, slots, mods, true, st);
+    LimbList l;
+    for (int i = 0; i < level; i++) l.add(i, i);
+    const ConvArgs cv = conv_args(c, ws + w.x * N, level);
+    int32_t rc = ntt_inverse(c, st, d_ntt, ws + w.x * N, l, SCALE_MODUP, cv);
     if (rc != HE_OK) return rc;
-    dim3 grid((unsigned)(N / 256), (unsigned)beta);
-    // reads the level coefficient-domain limbs (and the NTT-domain copies), writes beta*(level+K) limbs
-    grid.z = 4;
-#define MODUP_LAUNCH(AMAX)                                                                                           \
-    KLAUNCH(c, st, KID_MODUP, (double)(2 * level + beta * Ma) * N * 8.0,                                             \
-            k_modup<AMAX><<<grid, 256, 0, st>>>(ws + w.x * N, d_ntt, ws + w.raised * N, c->dev, level, c->L, K,      \
-                                                c->alpha, c->logN, c->conv_fp ? 1 : 0))
-    if (c->alpha <= 1)
-        MODUP_LAUNCH(1);
-    else if (c->alpha <= 2)
-        MODUP_LAUNCH(2);
-    else if (c->alpha <= 4)
-        MODUP_LAUNCH(4);
-    else if (c->alpha <= 8)
-        MODUP_LAUNCH(8);
-    else
-        MODUP_LAUNCH(16);
-#undef MODUP_LAUNCH
-    if ((rc = launch_ok(c)) != HE_OK) return rc;
-    slots.clear(), mods.clear();
+    LimbList r;
     for (int j = 0; j < beta; j++) {
         const int lo = j * c->alpha, hi = std::min(lo + c->alpha, level);
         for (int a = 0; a < Ma; a++) {
             if (a >= lo && a < hi) continue;
-            slots.push_back(j * Ma + a);
-            mods.push_back(a < level ? a : c->L + (a - level));
+            r.add(j * Ma + a, a < level ? a : c->L + (a - level));
         }
     }
-    return run_ntt(c, ws + w.raised * N, slots, mods, false, st);
+    return ntt_forward(c, st, ws + w.raised * N, r, PRO_MODUP, cv, nullptr, level);
 }
 
-// Steps 3-5: inner product through pi_g, ModDown of both components into `out` with the addend
-// selected by mode (see k_moddown_fin).
-static int32_t ks_apply(he_ctx *c, const he_evk *evk, u64 *ws, const WsLayout &w, int level, u64 *out, const u64 *c0,
-                        int mode, hipStream_t st)
+// Steps 3-5.  mode / c0: the addend of the final step (see FinArgs).
+static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, u64 *ws, const WsLayout &w, int level, u64 *out,
+                        const u64 *c0, int mode, hipStream_t st)
 {
     const size_t N = c->N;
     const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha;
     const unsigned g = (unsigned)evk->galois;
     dim3 grid((unsigned)(N / 256), (unsigned)Ma);
-    // reads beta raised limbs and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
+    // reads beta digits and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
     KLAUNCH(c, st, KID_INNER, (double)(3 * beta + 2) * Ma * N * 8.0,
-            k_inner<<<grid, 256, 0, st>>>(ws + w.raised * N, evk->dev, ws + w.u * N, c->dev, level, c->L, K, beta, g,
-                                          c->logN));
+            k_inner<<<grid, 256, 0, st>>>(ws + w.raised * N, d_ntt, evk->dev, ws + w.u * N, c->dev, level, c->L, K,
+                                          c->alpha, beta, g, c->logN));
     int32_t rc = launch_ok(c);
     if (rc != HE_OK) return rc;
-    std::vector<int> slots, mods;
+    LimbList sp;
     for (int cc = 0; cc < 2; cc++)
-        for (int k = 0; k < K; k++) slots.push_back(cc * Ma + level + k), mods.push_back(c->L + k);
-    if ((rc = run_ntt(c, ws + w.u * N, slots, mods, true, st)) != HE_OK) return rc;
-    dim3 grid2((unsigned)(N / 256), 2, (unsigned)std::min(level, 6));
-    KLAUNCH(c, st, KID_MODDOWN_CONV, (double)(2 * K + 2 * level) * N * 8.0,
-            k_moddown_conv<<<grid2, 256, 0, st>>>(ws + w.u * N, ws + w.r * N, c->dev, level, c->L, K, c->logN));
-    if ((rc = launch_ok(c)) != HE_OK) return rc;
-    slots.clear(), mods.clear();
+        for (int k = 0; k < K; k++) sp.add(cc * Ma + level + k, c->L + k);
+    const ConvArgs cv = conv_args(c, ws + w.u * N, level);
+    if ((rc = ntt_inverse(c, st, ws + w.u * N, ws + w.u * N, sp, SCALE_MODDOWN, cv)) != HE_OK) return rc;
+    LimbList r;
     for (int cc = 0; cc < 2; cc++)
-        for (int i = 0; i < level; i++) slots.push_back(cc * level + i), mods.push_back(i);
-    if ((rc = run_ntt(c, ws + w.r * N, slots, mods, false, st)) != HE_OK) return rc;
-    dim3 grid3((unsigned)(N / 256), (unsigned)(2 * level));
-    KLAUNCH(c, st, KID_MODDOWN_FIN, (double)(6 * level + (mode == 1 ? 2 * level : mode == 2 ? level : 0)) * N * 8.0,
-            k_moddown_fin<<<grid3, 256, 0, st>>>(ws + w.u * N, ws + w.r * N, out, c0, c->dev, level, K, mode, g,
-                                                 c->logN));
-    return launch_ok(c);
+        for (int i = 0; i < level; i++) r.add(cc * level + i, i);
+    FinArgs fa;
+    fa.u = ws + w.u * N;
+    fa.out = out;
+    fa.add = c0;
+    fa.cst = c->dev.dn_pinv;
+    fa.cst_d = c->dev.dn_pinv_d;
+    fa.u_cstride = Ma;
+    fa.nl = level;
+    fa.mode = mode;
+    fa.g = g;
+    return ntt_forward(c, st, ws + w.r * N, r, PRO_MODDOWN, cv, &fa, 2 * K);
 }
 
 static int32_t ks_guard(he_ctx *c, const he_evk *evk, int level, void *ws, size_t ws_bytes)
@@ -1064,11 +508,11 @@ extern "C" int32_t he_hmult_relin(he_ctx *ctx, const he_evk *relin, const uint64
     const WsLayout w = ws_layout(ctx, level);
     const size_t N = ctx->N;
     dim3 grid((unsigned)(N / 256), (unsigned)level);
-    KLAUNCH(ctx, st, KID_TENSOR, 8.0 * level * N * 8.0,
-            k_tensor<<<grid, 256, 0, st>>>(d_a, d_b, d_out, ws + w.d * N, ws + w.x * N, ctx->dev, level, ctx->logN));
+    KLAUNCH(ctx, st, KID_TENSOR, 7.0 * level * N * 8.0,
+            k_tensor<<<grid, 256, 0, st>>>(d_a, d_b, d_out, ws + w.d * N, ctx->dev, level, ctx->logN));
     if ((rc = launch_ok(ctx)) != HE_OK) return rc;
     if ((rc = ks_raise(ctx, ws + w.d * N, ws, w, level, st)) != HE_OK) return rc;
-    return ks_apply(ctx, relin, ws, w, level, d_out, nullptr, 1, st);
+    return ks_apply(ctx, relin, ws + w.d * N, ws, w, level, d_out, nullptr, 1, st);
 }
 
 extern "C" int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t count, const uint64_t *d_ct,
@@ -1085,16 +529,10 @@ extern "C" int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t 
     hipStream_t st = (hipStream_t)stream;
     u64 *ws = (u64 *)d_ws;
     const WsLayout w = ws_layout(ctx, level);
-    const size_t N = ctx->N;
-    const u64 *c1 = d_ct + (size_t)level * N;
-    hipError_t e = hipMemcpyAsync(ws + w.x * N, c1, (size_t)level * N * sizeof(u64), hipMemcpyDeviceToDevice, st);
-    if (e != hipSuccess) {
-        ctx->hip_err = std::string("hipMemcpyAsync: ") + hipGetErrorString(e);
-        return HE_EHIP;
-    }
+    const u64 *c1 = d_ct + (size_t)level * ctx->N;
     if ((rc = ks_raise(ctx, c1, ws, w, level, st)) != HE_OK) return rc;
     for (int r = 0; r < count; r++)
-        if ((rc = ks_apply(ctx, rots[r], ws, w, level, h_d_outs[r], d_ct, 2, st)) != HE_OK) return rc;
+        if ((rc = ks_apply(ctx, rots[r], c1, ws, w, level, h_d_outs[r], d_ct, 2, st)) != HE_OK) return rc;
     return HE_OK;
 }
 
@@ -1135,28 +573,24 @@ extern "C" int32_t he_rescale(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out
     hipStream_t st = (hipStream_t)stream;
     u64 *ws = (u64 *)d_ws;
     const size_t N = ctx->N;
-    u64 *t = ws + w.x * N; // two limbs: the last limb of each component
+    u64 *t = ws + w.x * N; // two limbs: the dropped limb of each component, coefficient domain
     u64 *r = ws + w.r * N; // [2][level-1][N]
-    for (int c = 0; c < 2; c++) {
-        hipError_t e = hipMemcpyAsync(t + c * N, d_ct + ((size_t)c * level + level - 1) * N, N * sizeof(u64),
-                                      hipMemcpyDeviceToDevice, st);
-        if (e != hipSuccess) {
-            ctx->hip_err = std::string("hipMemcpyAsync: ") + hipGetErrorString(e);
-            return HE_EHIP;
-        }
-    }
-    std::vector<int> slots{0, 1}, mods{level - 1, level - 1};
-    if ((rc = run_ntt(ctx, t, slots, mods, true, st)) != HE_OK) return rc;
-    dim3 grid((unsigned)(N / 256), 2);
-    KLAUNCH(ctx, st, KID_RESCALE_CONV, (double)(2 + 2 * (level - 1)) * N * 8.0,
-            k_rescale_conv<<<grid, 256, 0, st>>>(t, r, ctx->dev, level, ctx->logN));
-    if ((rc = launch_ok(ctx)) != HE_OK) return rc;
-    slots.clear(), mods.clear();
+    LimbList last;
+    for (int c = 0; c < 2; c++) last.add(c, c * level + level - 1, level - 1);
+    const ConvArgs cv = conv_args(ctx, t, level);
+    if ((rc = ntt_inverse(ctx, st, d_ct, t, last, SCALE_NONE, cv)) != HE_OK) return rc;
+    LimbList l;
     for (int c = 0; c < 2; c++)
-        for (int i = 0; i < level - 1; i++) slots.push_back(c * (level - 1) + i), mods.push_back(i);
-    if ((rc = run_ntt(ctx, r, slots, mods, false, st)) != HE_OK) return rc;
-    dim3 grid2((unsigned)(N / 256), (unsigned)(2 * (level - 1)));
-    KLAUNCH(ctx, st, KID_RESCALE_FIN, 6.0 * (level - 1) * N * 8.0,
-            k_rescale_fin<<<grid2, 256, 0, st>>>(d_ct, r, d_out, ctx->dev, level, ctx->L, ctx->logN));
-    return launch_ok(ctx);
+        for (int i = 0; i < level - 1; i++) l.add(c * (level - 1) + i, i);
+    FinArgs fa;
+    fa.u = d_ct;
+    fa.out = d_out;
+    fa.add = nullptr;
+    fa.cst = ctx->dev.rs_inv + (size_t)(level - 1) * ctx->L;
+    fa.cst_d = ctx->dev.rs_inv_d + (size_t)(level - 1) * ctx->L;
+    fa.u_cstride = level;
+    fa.nl = level - 1;
+    fa.mode = 0;
+    fa.g = 1;
+    return ntt_forward(ctx, st, r, l, PRO_RESCALE, cv, &fa, 2);
 }

@@ -39,14 +39,22 @@ struct DevTables {
     // ModUp constants for digit j holding a active limbs (1 <= a <= alpha), slot (j*alpha + a-1):
     const ShoupConst *up_inv;  // [dnum*alpha][alpha]      (D/q_i)^-1 mod q_i
     const u64 *up_hat;         // [dnum*alpha][alpha][M]   (D/q_i) mod t
-    const double *up_inv_d;    // the same two tables, balanced, as doubles (0 where the modulus is >= 2^50)
+    const double *up_inv_d;    // balanced doubles of the same (0 where the modulus is >= 2^50)
     const double *up_hat_d;
+    const double *up_hat_dh;   // (D/q_i) 2^31 mod t, for sources split at bit 31
+    int up_split;              // some ciphertext prime is >= 2^50: FP64 targets split their sources
     // ModDown constants
     const ShoupConst *dn_inv;  // [K]      (P/p_k)^-1 mod p_k
     const u64 *dn_hat;         // [K][L]   (P/p_k) mod q_i
     const ShoupConst *dn_pinv; // [L]      P^-1 mod q_i
+    const double *dn_inv_d;    // [K]
+    const double *dn_hat_d;    // [K][L]
+    const double *dn_hat_dh;   // [K][L]   (P/p_k) 2^31 mod q_i
+    const double *dn_pinv_d;   // [L]
+    int dn_split;              // some special prime is >= 2^50
     // Rescale: q_l^-1 mod q_i
     const ShoupConst *rs_inv;  // [L][L]
+    const double *rs_inv_d;    // [L][L]
 };
 
 struct ProfRecord {
@@ -68,8 +76,8 @@ struct he_ctx {
     std::vector<double> twd_fwd, twd_inv, ninvd;
     std::vector<ShoupConst> up_inv;
     std::vector<u64> up_hat;
-    std::vector<double> up_inv_d, up_hat_d;
-    bool conv_fp = false; // every ciphertext prime is below 2^50: base conversion may use FP64 products
+    std::vector<double> up_inv_d, up_hat_d, up_hat_dh, dn_inv_d, dn_hat_d, dn_hat_dh, dn_pinv_d, rs_inv_d;
+    bool up_split = false, dn_split = false;
     std::vector<ShoupConst> dn_inv;
     std::vector<u64> dn_hat;
     std::vector<ShoupConst> dn_pinv;

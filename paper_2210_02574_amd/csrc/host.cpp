@@ -280,25 +280,6 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
                     c->up_hat[(slot * alpha + ii) * M + m] = prod_mod_excluding(c->mod, lo, hi, lo + ii, c->mod[m]);
             }
         }
-    c->conv_fp = true;
-    for (int i = 0; i < L; i++) c->conv_fp = c->conv_fp && c->mod[i] < ((u64)1 << 50);
-    c->up_inv_d.assign(c->up_inv.size(), 0.0);
-    c->up_hat_d.assign(c->up_hat.size(), 0.0);
-    if (c->conv_fp) {
-        auto bal = [](u64 w, u64 t) { return w > t / 2 ? -(double)(t - w) : (double)w; };
-        for (int j = 0; j < c->dnum; j++)
-            for (int a = 1; a <= alpha; a++) {
-                const int lo = j * alpha;
-                if (lo + a > L) break;
-                const size_t slot = (size_t)j * alpha + (a - 1);
-                for (int ii = 0; ii < a; ii++) {
-                    c->up_inv_d[slot * alpha + ii] = bal(c->up_inv[slot * alpha + ii].w, c->mod[lo + ii]);
-                    for (int m = 0; m < M; m++)
-                        if (c->mod[m] < ((u64)1 << 50))
-                            c->up_hat_d[(slot * alpha + ii) * M + m] = bal(c->up_hat[(slot * alpha + ii) * M + m], c->mod[m]);
-                }
-            }
-    }
     // ModDown constants
     c->dn_inv.resize(K);
     c->dn_hat.resize((size_t)K * L);
@@ -317,6 +298,55 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
     for (int l = 0; l < L; l++)
         for (int i = 0; i < L; i++)
             if (i != l) c->rs_inv[(size_t)l * L + i] = shoup(inv_mod(c->mod[l] % c->mod[i], c->mod[i]), c->mod[i]);
+    // balanced-double images of the conversion constants for moduli below 2^50
+    {
+        const u64 kFp = (u64)1 << 50;
+        auto bal = [](u64 w, u64 t) { return w > t / 2 ? -(double)(t - w) : (double)w; };
+        for (int i = 0; i < L; i++) c->up_split = c->up_split || c->mod[i] >= kFp;
+        for (int k = 0; k < K; k++) c->dn_split = c->dn_split || c->mod[L + k] >= kFp;
+        c->up_inv_d.assign(c->up_inv.size(), 0.0);
+        c->up_hat_d.assign(c->up_hat.size(), 0.0);
+        c->up_hat_dh.assign(c->up_hat.size(), 0.0);
+        for (int j = 0; j < c->dnum; j++)
+            for (int a = 1; a <= alpha; a++) {
+                const int lo = j * alpha;
+                if (lo + a > L) break;
+                const size_t slot = (size_t)j * alpha + (a - 1);
+                for (int ii = 0; ii < a; ii++) {
+                    const u64 qi = c->mod[lo + ii];
+                    if (qi < kFp) c->up_inv_d[slot * alpha + ii] = bal(c->up_inv[slot * alpha + ii].w, qi);
+                    for (int m = 0; m < M; m++) {
+                        const u64 t = c->mod[m];
+                        if (t >= kFp) continue;
+                        const u64 h = c->up_hat[(slot * alpha + ii) * M + m];
+                        c->up_hat_d[(slot * alpha + ii) * M + m] = bal(h, t);
+                        c->up_hat_dh[(slot * alpha + ii) * M + m] = bal(mul_mod(h, ((u64)1 << 31) % t, t), t);
+                    }
+                }
+            }
+        c->dn_inv_d.assign(K, 0.0);
+        c->dn_hat_d.assign((size_t)K * L, 0.0);
+        c->dn_hat_dh.assign((size_t)K * L, 0.0);
+        c->dn_pinv_d.assign(L, 0.0);
+        c->rs_inv_d.assign((size_t)L * L, 0.0);
+        for (int k = 0; k < K; k++) {
+            if (c->mod[L + k] < kFp) c->dn_inv_d[k] = bal(c->dn_inv[k].w, c->mod[L + k]);
+            for (int i = 0; i < L; i++) {
+                const u64 t = c->mod[i];
+                if (t >= kFp) continue;
+                const u64 h = c->dn_hat[(size_t)k * L + i];
+                c->dn_hat_d[(size_t)k * L + i] = bal(h, t);
+                c->dn_hat_dh[(size_t)k * L + i] = bal(mul_mod(h, ((u64)1 << 31) % t, t), t);
+            }
+        }
+        for (int i = 0; i < L; i++) {
+            const u64 t = c->mod[i];
+            if (t >= kFp) continue;
+            c->dn_pinv_d[i] = bal(c->dn_pinv[i].w, t);
+            for (int l = 0; l < L; l++)
+                if (l != i) c->rs_inv_d[(size_t)l * L + i] = bal(c->rs_inv[(size_t)l * L + i].w, t);
+        }
+    }
     // encode/decode tables
     c->root_re.resize(2 * N);
     c->root_im.resize(2 * N);

@@ -1,0 +1,428 @@
+// Negacyclic NTT kernels with fused base-conversion prologues and ModDown/rescale epilogues.
+//
+// Forward transform = decimation in time with the powers of psi in bit-reversed order; stage s
+// (s = 0 .. logN-1) pairs elements N/2^(s+1) apart and uses twiddle index 2^s + (j >> (logN-s)).
+// Each thread keeps 16 elements in registers and runs four stages on them (a radix-16 step);
+// between steps the 256-thread work-group exchanges data through LDS.  A limb of N = 2^16 takes
+// two kernels: the column pass (stages 0-7 on 16 columns x 256 rows, row stride 256 elements,
+// 128-byte global segments) and the block pass (stages 8-15 on 16 contiguous blocks of 256).
+// N = 2^12 uses a four-stage column pass (one thread per column) and the same block pass.
+// The inverse runs the block pass first and the column pass last.
+//
+// Fusions, all bit-identical to the unfused steps:
+//  * the forward column pass can build its input on the fly: ModUp (sum over the digit's limbs of
+//    y_i * (D/q_i mod t)), ModDown (sum over the special limbs of y_k * (P/p_k mod q_i)) or the
+//    centred residue of a dropped limb (rescale);
+//  * the inverse column pass can fold (D/q_i)^-1 or (P/p_k)^-1 into its 1/N scaling, so it emits
+//    the y values those sums need;
+//  * the forward block pass can finish ModDown / rescale: out = (u - ntt) * const + addend.
+#pragma once
+#include "arith.h"
+
+#define HE_MAXB 256
+// A launch works on up to HE_MAXB limbs: limb b is written at dst + slot[b]*N, read (inverse block
+// pass only) at src + src[b]*N, and uses modulus index mod[b].
+struct LimbBatch {
+    uint16_t slot[HE_MAXB];
+    uint16_t src[HE_MAXB];
+    uint8_t mod[HE_MAXB];
+};
+
+enum { PRO_LOAD = 0, PRO_MODUP = 1, PRO_MODDOWN = 2, PRO_RESCALE = 3 };
+enum { SCALE_NONE = 0, SCALE_MODUP = 1, SCALE_MODDOWN = 2 };
+enum { EPI_STORE = 0, EPI_FIN = 1 };
+
+struct ConvArgs {
+    const u64 *src; // ModUp: y limbs [level][N]; ModDown: u [2][level+K][N]; rescale: t [2][N]
+    int level, L, K, alpha;
+};
+
+struct FinArgs {
+    const u64 *u;   // minuend limbs, component stride u_cstride limbs
+    u64 *out;       // [2][nl][N]
+    const u64 *add; // mode 2: c0 limbs [nl][N], read through the automorphism index map
+    const ShoupConst *cst;
+    const double *cst_d;
+    int u_cstride, nl, mode; // mode 0: no addend; 1: add what `out` holds; 2: add sigma_g(c0) to component 0
+    unsigned g;
+};
+
+__device__ __forceinline__ int active_mod(int a, int level, int L) { return a < level ? a : L + (a - level); }
+
+// NTT-domain index of the automorphism sigma_g: out[k] = in[k'] with
+// 2 brv(k') + 1 = (2 brv(k) + 1) g mod 2N.
+__device__ __forceinline__ unsigned galois_index(unsigned k, unsigned g, int logN)
+{
+    const unsigned b = __brev(k) >> (32 - logN);
+    const unsigned e = ((2 * b + 1) * g) & ((2u << logN) - 1);
+    return __brev((e - 1) >> 1) >> (32 - logN);
+}
+
+// ---- prologues: element `pos` of the limb the column pass is about to transform ----------------------
+
+template <int NSMAX> struct ConvSetup {
+    const u64 *sp[NSMAX];         // source limbs; entries past the real count repeat entry 0 with zero constants
+    double cd[NSMAX], cdh[NSMAX]; // constants as balanced doubles (cdh: constant * 2^31)
+    u64 ci[NSMAX];                // constants as residues (integer targets)
+    // rescale
+    u64 ql, half;
+    double qld;
+};
+
+// slot = position of the limb in the destination buffer; mi = its modulus index
+template <int PRO, int NSMAX, int LOGN>
+__device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const DevTables &T, unsigned slot, unsigned mi)
+{
+    ConvSetup<NSMAX> S;
+    S.ql = S.half = 0;
+    S.qld = 0.0;
+    const int M = cv.L + cv.K, Ma = cv.level + cv.K;
+#pragma unroll
+    for (int s = 0; s < NSMAX; s++) {
+        S.sp[s] = cv.src;
+        S.ci[s] = 0;
+        S.cd[s] = S.cdh[s] = 0.0;
+    }
+    if (PRO == PRO_MODUP) {
+        const int j = slot / Ma;
+        const int lo = j * cv.alpha, hi = min(lo + cv.alpha, cv.level);
+        const int ns = hi - lo;
+        const size_t cs = ((size_t)j * cv.alpha + (ns - 1)) * cv.alpha;
+#pragma unroll
+        for (int s = 0; s < NSMAX; s++) {
+            const bool on = s < ns;
+            const size_t ci = (cs + (on ? s : 0)) * M + mi;
+            S.sp[s] = cv.src + ((size_t)(lo + (on ? s : 0)) << LOGN);
+            S.ci[s] = on ? T.up_hat[ci] : 0;
+            S.cd[s] = on ? T.up_hat_d[ci] : 0.0;
+            S.cdh[s] = on ? T.up_hat_dh[ci] : 0.0;
+        }
+    } else if (PRO == PRO_MODDOWN) {
+        const int c = slot / cv.level, i = slot % cv.level;
+#pragma unroll
+        for (int s = 0; s < NSMAX; s++) {
+            const bool on = s < cv.K;
+            const size_t ci = (size_t)(on ? s : 0) * cv.L + i;
+            S.sp[s] = cv.src + (((size_t)c * Ma + cv.level + (on ? s : 0)) << LOGN);
+            S.ci[s] = on ? T.dn_hat[ci] : 0;
+            S.cd[s] = on ? T.dn_hat_d[ci] : 0.0;
+            S.cdh[s] = on ? T.dn_hat_dh[ci] : 0.0;
+        }
+    } else if (PRO == PRO_RESCALE) {
+        const int c = slot / (cv.level - 1);
+        S.sp[0] = cv.src + ((size_t)c << LOGN);
+        S.ql = T.mod[cv.level - 1].q;
+        S.half = (S.ql - 1) / 2;
+        S.qld = T.mod[cv.level - 1].qd;
+    }
+    return S;
+}
+
+// SPLIT: the sources may be 2^50 or larger, so an FP64 target splits each at bit 31
+template <int PRO, bool SPLIT, int NSMAX>
+__device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const ArithFp &ar, const ModConst &m, unsigned pos)
+{
+    if (PRO == PRO_RESCALE) {
+        const u64 tv = S.sp[0][pos];
+        if (S.qld != 0.0) return u2d(tv) - (tv > S.half ? S.qld : 0.0); // centred value, |v| < q_last / 2
+        const bool neg = tv > S.half; // q_last >= 2^50: reduce the magnitude with integers first
+        const double w = u2d(reduce64(neg ? S.ql - tv : tv, m));
+        return neg ? -w : w;
+    }
+    double acc = 0.0;
+#pragma unroll
+    for (int s = 0; s < NSMAX; s++) {
+        const u64 y = S.sp[s][pos];
+        if (!SPLIT)
+            acc += ar.mulmod(u2d(y), S.cd[s]);
+        else {
+            const double yh = (double)(unsigned)(y >> 31), yl = (double)(unsigned)(y & 0x7FFFFFFFu);
+            acc += ar.mulmod(yh, S.cdh[s]) + ar.mulmod(yl, S.cd[s]);
+        }
+        if ((s & 3) == 3 && s + 1 < NSMAX) acc = ar.reduce(acc);
+    }
+    return acc;
+}
+
+template <int PRO, bool SPLIT, int NSMAX>
+__device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithInt &, const ModConst &m, unsigned pos)
+{
+    if (PRO == PRO_RESCALE) {
+        const u64 tv = S.sp[0][pos];
+        const bool neg = tv > S.half;
+        const u64 w = reduce64(neg ? S.ql - tv : tv, m);
+        return neg ? (w ? m.q - w : 0) : w;
+    }
+    U128 acc{0, 0};
+#pragma unroll
+    for (int s = 0; s < NSMAX; s++) mac128(acc, S.sp[s][pos], S.ci[s]);
+    return reduce128(acc, m);
+}
+
+// ---- epilogue: what the forward block pass does with a finished (canonical) NTT value ---------------------
+
+template <int LOGN>
+__device__ __forceinline__ void fin_store(const FinArgs &fa, const DevTables &T, unsigned slot, unsigned pos, u64 rv)
+{
+    const unsigned c = slot / fa.nl, i = slot % fa.nl;
+    const ModConst m = T.mod[i];
+    const size_t o = ((size_t)slot << LOGN) + pos;
+    const u64 uv = fa.u[(((size_t)c * fa.u_cstride + i) << LOGN) + pos];
+    u64 av = 0;
+    if (fa.mode == 1)
+        av = fa.out[o];
+    else if (fa.mode == 2 && c == 0)
+        av = fa.add[((size_t)i << LOGN) + galois_index(pos, fa.g, LOGN)];
+    u64 res;
+    if (m.qd != 0.0)
+        res = fp_canon(fp_mulmod(u2d(uv) - u2d(rv), fa.cst_d[i], m.qd, m.qinvd) + u2d(av), m.qd, m.qinvd);
+    else
+        res = csub(mul_shoup(uv + m.q - rv, fa.cst[i], m.q) + av, m.q);
+    fa.out[o] = res;
+}
+
+// LDS tile of 16 groups x 256 elements; one pad word per 16 elements and 16 pad words per group
+// keep both the "stride-16" and the "16 consecutive" access patterns free of bank conflicts.
+#define TILE_GROUP 272
+#define TILE_WORDS (16 * TILE_GROUP)
+__device__ __forceinline__ unsigned tile_at(unsigned grp, unsigned i) { return grp * TILE_GROUP + i + (i >> 4); }
+// column pass: row r (0..255) of column c (0..15); 16 pad words after every 16 rows
+__device__ __forceinline__ unsigned col_at(unsigned r, unsigned c) { return (r >> 4) * TILE_GROUP + (r & 15) * 16 + c; }
+
+// ---- block pass ---------------------------------------------------------------------------------------------
+
+template <int LOGN, int EPI, class A>
+__device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A &ar, u64 *lds, unsigned tile,
+                                                const FinArgs &fa, const DevTables &T, unsigned slot)
+{
+    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
+    const unsigned bg = tile * 16 + blk; // block index within the limb
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[bg * 256 + il + 16 * k]);
+    ar.fwd16(a, LOGN - 8, bg, true);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = ar.store_mid(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, 16 * il + k)]);
+    ar.fwd16(a, LOGN - 4, bg * 16 + il, true);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_final(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+        const unsigned pos = bg * 256 + il + 16 * k;
+        const u64 v = lds[tile_at(blk, il + 16 * k)];
+        if (EPI == EPI_FIN)
+            fin_store<LOGN>(fa, T, slot, pos, v);
+        else
+            limb[pos] = v;
+    }
+}
+
+template <int LOGN, class A>
+__device__ __forceinline__ void inv_blocks_body(const u64 *in, u64 *limb, const A &ar,
+                                                u64 *lds, unsigned tile)
+{
+    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
+    const unsigned bg = tile * 16 + blk;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = in[bg * 256 + il + 16 * k];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load(lds[tile_at(blk, 16 * il + k)]);
+    ar.template inv16<false>(a, LOGN - 4, bg * 16 + il);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_mid(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, il + 16 * k)]);
+    ar.template inv16<false>(a, LOGN - 8, bg);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = ar.store_mid(a[k]); // the column pass finishes
+}
+
+// grid.x = (N/4096) * batch
+template <int LOGN, int EPI>
+__global__ __launch_bounds__(256) void k_ntt_fwd_blocks(u64 *__restrict__ data, DevTables T, LimbBatch lb, FinArgs fa)
+{
+    __shared__ u64 lds[TILE_WORDS];
+    constexpr unsigned TILES = (1u << LOGN) / 4096;
+    const unsigned tile = blockIdx.x % TILES, b = blockIdx.x / TILES;
+    const unsigned mi = lb.mod[b], slot = lb.slot[b];
+    u64 *limb = data + ((size_t)slot << LOGN);
+    if (T.mod[mi].qd != 0.0)
+        fwd_blocks_body<LOGN, EPI>(limb, make_fp(T, mi, LOGN), lds, tile, fa, T, slot);
+    else
+        fwd_blocks_body<LOGN, EPI>(limb, make_int(T, mi, LOGN), lds, tile, fa, T, slot);
+}
+
+template <int LOGN>
+__global__ __launch_bounds__(256) void k_ntt_inv_blocks(const u64 *src, u64 *dst,
+                                                        DevTables T, LimbBatch lb)
+{
+    __shared__ u64 lds[TILE_WORDS];
+    constexpr unsigned TILES = (1u << LOGN) / 4096;
+    const unsigned tile = blockIdx.x % TILES, b = blockIdx.x / TILES;
+    const unsigned mi = lb.mod[b];
+    const u64 *in = src + ((size_t)lb.src[b] << LOGN);
+    u64 *limb = dst + ((size_t)lb.slot[b] << LOGN);
+    if (T.mod[mi].qd != 0.0)
+        inv_blocks_body<LOGN>(in, limb, make_fp(T, mi, LOGN), lds, tile);
+    else
+        inv_blocks_body<LOGN>(in, limb, make_int(T, mi, LOGN), lds, tile);
+}
+
+// ---- column pass, N = 2^16: 256 rows x 16 columns per work-group (element (r, c) at r*256 + c) ----------------
+
+template <int PRO, bool SPLIT, int NSMAX, class A>
+__device__ __forceinline__ void fwd_cols16_body(u64 *__restrict__ limb, unsigned col0, const A &ar, u64 *lds,
+                                                const ConvSetup<NSMAX> &S, const ModConst &m)
+{
+    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+        const unsigned pos = (rl + 16 * k) * 256 + col0 + c;
+        a[k] = PRO == PRO_LOAD ? ar.load(limb[pos]) : conv_get<PRO, SPLIT>(S, ar, m, pos);
+    }
+    ar.fwd16(a, 0, 0, PRO != PRO_LOAD);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(16 * rl + k, c)]);
+    ar.fwd16(a, 4, rl, true);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[(16 * rl + k) * 256 + col0 + c] = ar.store_mid(a[k]); // the block pass finishes
+}
+
+template <class A>
+__device__ __forceinline__ void inv_cols16_body(u64 *__restrict__ limb, unsigned col0, const A &ar, u64 *lds)
+{
+    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[(16 * rl + k) * 256 + col0 + c]);
+    ar.template inv16<false>(a, 4, rl);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[col_at(16 * rl + k, c)] = ar.store_mid(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(rl + 16 * k, c)]);
+    ar.template inv16<true>(a, 0, 0);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[(rl + 16 * k) * 256 + col0 + c] = ar.store_final(a[k]);
+}
+
+// grid.x = 16 * batch
+template <int PRO, int NSMAX>
+__global__ __launch_bounds__(256) void k_ntt_fwd_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
+{
+    __shared__ u64 lds[TILE_WORDS];
+    const unsigned tile = blockIdx.x & 15, b = blockIdx.x >> 4;
+    const unsigned mi = lb.mod[b], slot = lb.slot[b];
+    u64 *limb = data + ((size_t)slot << 16);
+    const ModConst m = T.mod[mi];
+    const ConvSetup<NSMAX> S = conv_setup<PRO, NSMAX, 16>(cv, T, slot, mi);
+    const bool split = PRO == PRO_MODUP ? T.up_split != 0 : PRO == PRO_MODDOWN ? T.dn_split != 0 : false;
+    if (m.qd == 0.0)
+        fwd_cols16_body<PRO, false>(limb, tile * 16, make_int(T, mi, 16), lds, S, m);
+    else if (split)
+        fwd_cols16_body<PRO, true>(limb, tile * 16, make_fp(T, mi, 16), lds, S, m);
+    else
+        fwd_cols16_body<PRO, false>(limb, tile * 16, make_fp(T, mi, 16), lds, S, m);
+}
+
+// extra constant of the inverse column pass for modulus index mi
+__device__ __forceinline__ void scale_consts(int scale, const ConvArgs &cv, const DevTables &T, unsigned mi,
+                                             ShoupConst &ci, double &cd)
+{
+    ci = ShoupConst{0, 0};
+    cd = 0.0;
+    if (scale == SCALE_MODUP) {
+        const int j = mi / cv.alpha, ii = mi - j * cv.alpha;
+        const int na = min(cv.alpha, cv.level - j * cv.alpha);
+        const size_t idx = ((size_t)j * cv.alpha + (na - 1)) * cv.alpha + ii;
+        ci = T.up_inv[idx];
+        cd = T.up_inv_d[idx];
+    } else if (scale == SCALE_MODDOWN) {
+        ci = T.dn_inv[mi - cv.L];
+        cd = T.dn_inv_d[mi - cv.L];
+    }
+}
+
+template <int SCALE>
+__global__ __launch_bounds__(256) void k_ntt_inv_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
+{
+    __shared__ u64 lds[TILE_WORDS];
+    const unsigned tile = blockIdx.x & 15, b = blockIdx.x >> 4;
+    const unsigned mi = lb.mod[b];
+    u64 *limb = data + ((size_t)lb.slot[b] << 16);
+    ShoupConst ci;
+    double cd;
+    scale_consts(SCALE, cv, T, mi, ci, cd);
+    if (T.mod[mi].qd != 0.0)
+        inv_cols16_body(limb, tile * 16, make_fp(T, mi, 16, cd), lds);
+    else
+        inv_cols16_body(limb, tile * 16, make_int(T, mi, 16, ci), lds);
+}
+
+// ---- column pass, N = 2^12: 16 rows x 256 columns, one thread per column --------------------------------------
+
+template <int PRO, bool SPLIT, int NSMAX, class A>
+__device__ __forceinline__ void fwd_cols12_body(u64 *__restrict__ limb, const A &ar, const ConvSetup<NSMAX> &S,
+                                                const ModConst &m)
+{
+    const unsigned c = threadIdx.x;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = PRO == PRO_LOAD ? ar.load(limb[k * 256 + c]) : conv_get<PRO, SPLIT>(S, ar, m, k * 256 + c);
+    ar.fwd16(a, 0, 0, PRO != PRO_LOAD);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[k * 256 + c] = ar.store_mid(a[k]);
+}
+template <class A> __device__ __forceinline__ void inv_cols12_body(u64 *__restrict__ limb, const A &ar)
+{
+    const unsigned c = threadIdx.x;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[k * 256 + c]);
+    ar.template inv16<true>(a, 0, 0);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[k * 256 + c] = ar.store_final(a[k]);
+}
+
+template <int PRO, int NSMAX>
+__global__ __launch_bounds__(256) void k_ntt_fwd_cols12(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
+{
+    const unsigned mi = lb.mod[blockIdx.x], slot = lb.slot[blockIdx.x];
+    u64 *limb = data + ((size_t)slot << 12);
+    const ModConst m = T.mod[mi];
+    const ConvSetup<NSMAX> S = conv_setup<PRO, NSMAX, 12>(cv, T, slot, mi);
+    const bool split = PRO == PRO_MODUP ? T.up_split != 0 : PRO == PRO_MODDOWN ? T.dn_split != 0 : false;
+    if (m.qd == 0.0)
+        fwd_cols12_body<PRO, false>(limb, make_int(T, mi, 12), S, m);
+    else if (split)
+        fwd_cols12_body<PRO, true>(limb, make_fp(T, mi, 12), S, m);
+    else
+        fwd_cols12_body<PRO, false>(limb, make_fp(T, mi, 12), S, m);
+}
+
+template <int SCALE>
+__global__ __launch_bounds__(256) void k_ntt_inv_cols12(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
+{
+    const unsigned mi = lb.mod[blockIdx.x];
+    u64 *limb = data + ((size_t)lb.slot[blockIdx.x] << 12);
+    ShoupConst ci;
+    double cd;
+    scale_consts(SCALE, cv, T, mi, ci, cd);
+    if (T.mod[mi].qd != 0.0)
+        inv_cols12_body(limb, make_fp(T, mi, 12, cd));
+    else
+        inv_cols12_body(limb, make_int(T, mi, 12, ci));
+}
