@@ -646,10 +646,14 @@ void orc_modup(const orc_ctx *c, const u64 *x, int lvl, u64 *out)
     }
 }
 
-/* ModDown of one polynomial u given in the NTT domain on lvl+K limbs:
- *   w_k = iNTT(u[p_k]);  y_k = w_k * [Phat_k^{-1}]_{p_k} mod p_k   (in [0,p_k))
- *   r_i = sum_k y_k * [Phat_k]_{q_i} mod q_i                       (uncorrected)
+/* ModDown of one polynomial u given in the NTT domain on lvl+K limbs, with centred conversion
+ * digits:
+ *   w_k = iNTT(u[p_k]);  y_k = w_k * [Phat_k^{-1}]_{p_k} mod p_k, then centred:
+ *         y_k - p_k if y_k > (p_k-1)/2
+ *   r_i = sum_k y_k * [Phat_k]_{q_i} mod q_i               (per coefficient, uncorrected)
  *   out[i] = (u[i] - NTT_i(r_i)) * [P^{-1}]_{q_i} mod q_i.
+ * As integers r = [u]_P + v P with r in (-K P/2, K P/2), so out = (u - r)/P = u/P - r/P: the
+ * error r/P is symmetric about zero (no systematic bias), |r/P| < K/2.
  * out: NTT domain, [lvl][N]. */
 void orc_moddown(const orc_ctx *c, const u64 *u, int lvl, u64 *out)
 {
@@ -675,10 +679,19 @@ void orc_moddown(const orc_ctx *c, const u64 *u, int lvl, u64 *out)
         for (int k = 0; k < K; k++) Pmod = mulmod(Pmod, c->mod[L + k] % qi, qi);
         u64 Pinv = invmod(Pmod, qi);
         for (int k = 0; k < K; k++) {
+            u64 pk = c->mod[L + k];
             u64 phat_q = 1;
             for (int k2 = 0; k2 < K; k2++)
                 if (k2 != k) phat_q = mulmod(phat_q, c->mod[L + k2] % qi, qi);
-            for (u64 n = 0; n < N; n++) r[n] = addmod(r[n], mulmod(y[(u64)k * N + n] % qi, phat_q, qi), qi);
+            for (u64 n = 0; n < N; n++) {
+                u64 yk = y[(u64)k * N + n];
+                u64 term;
+                if (yk > (pk - 1) / 2) /* negative digit y_k - p_k */
+                    term = submod(0, mulmod((pk - yk) % qi, phat_q, qi), qi);
+                else
+                    term = mulmod(yk % qi, phat_q, qi);
+                r[n] = addmod(r[n], term, qi);
+            }
         }
         orc_ntt(c, i, r);
         for (u64 n = 0; n < N; n++) out[(u64)i * N + n] = mulmod(submod(u[(u64)i * N + n], r[n], qi), Pinv, qi);

@@ -1,0 +1,51 @@
+"""Encrypted inference (the C4 workload): 32 synthetic 768-dimensional embeddings in one ciphertext at
+N=2^16, level 24, scale 2^40, four classes.  The device sequence is compared bit for bit with the oracle's
+own composition and the decrypted logits with the fp64 product X W^T (bound 2^-15 at scale 2^40)."""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def test_inference_matches_oracle_and_plaintext(oracle_mod):
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from oracle import classifier as oc
+    from paper_2210_02574_amd import classifier as cl
+
+    assert torch.cuda.is_available()
+    p = wl.N16
+    he = pkg.HE.from_params(p, device=0)
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    level, scale = 24, 2.0**40
+    X = wl.embeddings(41, he.n // 1024)
+    W = wl.weights(42)
+    sk, s = he.keygen_secret(43), o.keygen_secret(43)
+    inf = cl.EncryptedInference(he, level)
+    keys = inf.make_keys(sk, 100)
+    okeys = {r: o.keygen_rot(s, r, 100 + k) for k, r in enumerate(list(cl.INFER_HOISTED) + list(cl.INFER_SUM_SHIFTS))}
+    z = cl.pack_samples(X, he.n)
+    assert np.array_equal(z, oc.pack(X, o.n))
+    m = o.encode(z, scale)
+    ct = he.encrypt_coeffs(sk, m, level, 44)
+    assert np.array_equal(ct, o.encrypt_coeffs(s, m, level, 44))
+    pts = inf.encode_weights(W)
+    # plaintext diagonals: both encoders, within one unit; the device run uses the oracle's encodings
+    for i, pt in enumerate(pts):
+        want = o.encode(oc.diagonal(W, i, o.n), float(p.q[level - 1]))
+        got = he.encode(cl.weight_diagonals(W, he.n)[i], float(p.q[level - 1]))
+        assert np.abs(got - want).max() <= 1
+        pts[i] = he.to_device(o.coeffs_to_ntt(want, level))
+    out = inf.run(he.to_device(ct), pts, keys)
+    got = he.to_host(out)
+    want = oc.infer(o, ct, W, level, okeys)
+    assert got.shape == (2, level - 1, p.N)
+    assert np.array_equal(got, want)
+    logits = cl.logits_from_slots(he.decrypt(sk, got, scale))
+    ref = X @ W.T
+    err = np.abs(logits - ref).max()
+    print("inference max abs error %.3g (bound %.3g)" % (err, 2.0**-15))
+    assert err <= 2.0**-15
