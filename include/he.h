@@ -150,6 +150,16 @@ int32_t he_pmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *d_pt, uint64
 int32_t he_cmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out, int32_t level,
                  void *stream);
 
+/* Ciphertext plus a plaintext constant given as one residue per limb (h_scalar[i] in [0,q_i)): a
+ * constant polynomial has that value at every evaluation point, so it is added to every word of
+ * c0.  d_out may alias d_ct. */
+int32_t he_add_const(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out, int32_t level,
+                     void *stream);
+/* Drops limbs: copies the first out_level limbs of both components of a level-in_level
+ * ciphertext into d_out [2][out_level][N] (no arithmetic; the scale is unchanged). */
+int32_t he_moddrop(he_ctx *ctx, const uint64_t *d_ct, int32_t in_level, uint64_t *d_out, int32_t out_level,
+                   void *stream);
+
 /* ---- device: the hot path -------------------------------------------------------------------- */
 
 /* Mult without the rescale (Section 2.2, Mult): tensor product d0 = a0 b0, d1 = a0 b1 + a1 b0,

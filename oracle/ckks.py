@@ -315,6 +315,20 @@ class Oracle:
         self.lib.orc_cmult(self.ctx, _p(ct, _u64p), _p(sc, _u64p), level, _p(out, _u64p))
         return out
 
+    def add_const(self, ct, scalars):
+        ct = np.ascontiguousarray(ct, dtype=np.uint64)
+        level = ct.shape[1]
+        sc = np.array([int(v) for v in scalars], dtype=np.uint64)
+        assert sc.shape == (level,)
+        out = np.empty_like(ct)
+        self.lib.orc_add_const(self.ctx, _p(ct, _u64p), _p(sc, _u64p), level, _p(out, _u64p))
+        return out
+
+    @staticmethod
+    def moddrop(ct, level):
+        """Keep the first `level` limbs of both components."""
+        return np.ascontiguousarray(ct[:, :level])
+
     def tensor(self, a, b):
         a = np.ascontiguousarray(a, dtype=np.uint64)
         b = np.ascontiguousarray(b, dtype=np.uint64)

@@ -577,6 +577,18 @@ void orc_cmult(const orc_ctx *c, const u64 *ct, const u64 *scalar, int lvl, u64 
         }
 }
 
+/* ct + constant: a constant polynomial c has the value c at every evaluation point, so adding the
+ * plaintext constant scalar[i] (a residue of q_i) adds it to every NTT coefficient of c0. */
+void orc_add_const(const orc_ctx *c, const u64 *ct, const u64 *scalar, int lvl, u64 *out)
+{
+    u64 N = c->N;
+    memcpy(out, ct, sizeof(u64) * 2 * lvl * N);
+    for (int i = 0; i < lvl; i++) {
+        u64 t = c->mod[i];
+        for (u64 x = 0; x < N; x++) out[(u64)i * N + x] = addmod(ct[(u64)i * N + x], scalar[i] % t, t);
+    }
+}
+
 /* Tensor product of two level-lvl ciphertexts, NTT domain:
  * d0 = a0*b0, d1 = a0*b1 + a1*b0, d2 = a1*b1.  out [3][lvl][N]. */
 void orc_tensor(const orc_ctx *c, const u64 *A, const u64 *B, int lvl, u64 *out)

@@ -42,3 +42,76 @@ def infer(o, ct, W, level, rot_keys):
     for k in range(8):
         out = o.add(out, o.hrot(out, rot_keys[4 << k], 4 << k))
     return out
+
+
+# ---- one gradient-descent step of logistic regression, oracle composition ----------------------------------
+
+def logistic_poly_coeffs():
+    """Least-squares degree-7 polynomial of 1/(1+exp(-x)) on [-8,8], as monomial coefficients in x.
+    Normal equations of the continuous L2 problem in t = x/8 with the monomial basis 1, t, .., t^7,
+    integrals by a fine composite Simpson rule."""
+    n = 200001
+    t = np.linspace(-1.0, 1.0, n)
+    w = np.ones(n)
+    w[1:-1:2] = 4.0
+    w[2:-1:2] = 2.0
+    w *= (t[1] - t[0]) / 3.0
+    f = 1.0 / (1.0 + np.exp(-8.0 * t))
+    A = np.array([[np.sum(w * t ** (i + j)) for j in range(8)] for i in range(8)])
+    b = np.array([np.sum(w * f * t**i) for i in range(8)])
+    c = np.linalg.solve(A, b)
+    return [c[k] / 8.0**k for k in range(8)]
+
+
+def _const(o, value, scale, level):
+    v = int(round(value * scale))
+    return [v % o.q[i] for i in range(level)]
+
+
+def train_step(o, X, W, Y, relin, rot, level, scale, lr, n_samples, a=None):
+    """X: list of ciphertexts, W: list (per class), Y[c][i]; rot: dict shift -> key.  Returns new W list.
+    Same level/scale schedule as the device driver, derived here from the rescale rule
+    (scale after a rescale = scale before / dropped prime)."""
+    q = [float(v) for v in o.q]
+    a = logistic_poly_coeffs() if a is None else a  # monomial coefficients in x
+    mask = np.zeros(o.n)
+    mask[::1024] = 1.0
+    new_w = []
+    for c, w in enumerate(W):
+        G = None
+        for i, x in enumerate(X):
+            # logits: block sums of x*w
+            m = o.rescale(o.hmult_relin(x, w, relin))  # level-1
+            s1 = scale * scale / q[level - 1]
+            for k in range(10):
+                m = o.add(m, o.hrot(m, rot[1 << k], 1 << k))
+            pt = o.coeffs_to_ntt(o.encode(mask, q[level - 2]), level - 1)
+            z = o.rescale(o.pmult(m, pt))  # level-2, scale s1
+            for k in range(10):
+                z = o.add(z, o.hrot(z, rot[-(1 << k)], -(1 << k)))
+            # polynomial 0.5 + z (a1 + a3 z^2 + a5 z^4 + a7 z^6) = 0.5 + z ((a1 + a3 z^2) + z^4 (a5 + a7 z^2))
+            z2 = o.rescale(o.hmult_relin(z, z, relin))  # level-3
+            s2 = s1 * s1 / q[level - 3]
+            z4 = o.rescale(o.hmult_relin(z2, z2, relin))  # level-4
+            s4 = s2 * s2 / q[level - 4]
+            tu = scale
+            u = o.rescale(o.cmult(z2, _const(o, a[7], tu * q[level - 4] / s2, level - 3)))
+            u = o.add_const(u, _const(o, a[5], tu, level - 4))
+            zu = o.rescale(o.hmult_relin(z4, u, relin))  # level-5
+            tv = s4 * tu / q[level - 5]
+            v = o.rescale(o.cmult(z2, _const(o, a[3], tv * q[level - 4] / s2, level - 3)))
+            v = o.add_const(v, _const(o, a[1], tv, level - 4))
+            inner = o.add(zu, o.moddrop(v, level - 5))
+            p = o.rescale(o.hmult_relin(o.moddrop(z, level - 5), inner, relin))  # level-6
+            tp = s1 * tv / q[level - 6]
+            p = o.add_const(p, _const(o, 0.5, tp, level - 6))
+            e = o.sub(p, Y[c][i])
+            g = o.hmult_relin(e, o.moddrop(x, level - 6), relin)
+            G = g if G is None else o.add(G, g)
+        G = o.rescale(G)  # level-7
+        tg = tp * scale / q[level - 7]
+        for k in range(5):
+            G = o.add(G, o.hrot(G, rot[1024 << k], 1024 << k))
+        upd = o.rescale(o.cmult(G, _const(o, lr / n_samples, scale * q[level - 8] / tg, level - 7)))
+        new_w.append(o.sub(o.moddrop(w, level - 8), upd))
+    return new_w

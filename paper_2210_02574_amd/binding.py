@@ -29,7 +29,7 @@ SYMBOLS = [
     "he_keygen_secret", "he_sk_destroy", "he_sk_coeffs", "he_keygen_relin", "he_keygen_rot",
     "he_evk_from_host", "he_evk_to_host", "he_evk_destroy",
     "he_encode", "he_decode", "he_plain_to_ntt", "he_encrypt_coeffs", "he_decrypt_coeffs", "he_decrypt",
-    "he_ntt", "he_intt", "he_add", "he_sub", "he_pmult", "he_cmult",
+    "he_ntt", "he_intt", "he_add", "he_sub", "he_pmult", "he_cmult", "he_add_const", "he_moddrop",
     "he_hmult_relin", "he_rescale", "he_hrot", "he_hrot_many", "he_rotate_sum",
     "he_profile_start", "he_profile_stop",
 ]
@@ -98,6 +98,8 @@ def load_library() -> ctypes.CDLL:
             "he_sub": [vp, vp, vp, vp, i32, vp],
             "he_pmult": [vp, vp, vp, vp, i32, vp],
             "he_cmult": [vp, vp, vp, vp, i32, vp],
+            "he_add_const": [vp, vp, vp, vp, i32, vp],
+            "he_moddrop": [vp, vp, i32, vp, i32, vp],
             "he_hmult_relin": [vp, vp, vp, vp, vp, i32, vp, sz, vp],
             "he_rescale": [vp, vp, vp, i32, vp, sz, vp],
             "he_hrot": [vp, vp, vp, vp, i32, vp, sz, vp],
@@ -361,6 +363,26 @@ class HE:
         assert sc.shape == (level,)
         out = self.empty_ct(level) if out is None else out
         self._chk(self.lib.he_cmult(self.ctx, self._dp(ct), _hp(sc), self._dp(out), level, self._stream()), "he_cmult")
+        return out
+
+    def add_const(self, ct, scalars: Sequence[int], out=None):
+        level = self._level(ct)
+        sc = np.array([int(v) for v in scalars], dtype=np.uint64)
+        assert sc.shape == (level,)
+        out = self.empty_ct(level) if out is None else out
+        self._chk(
+            self.lib.he_add_const(self.ctx, self._dp(ct), _hp(sc), self._dp(out), level, self._stream()), "he_add_const"
+        )
+        return out
+
+    def moddrop(self, ct, level: int, out=None):
+        in_level = self._level(ct)
+        if level == in_level and out is None:
+            return ct
+        out = self.empty_ct(level) if out is None else out
+        self._chk(
+            self.lib.he_moddrop(self.ctx, self._dp(ct), in_level, self._dp(out), level, self._stream()), "he_moddrop"
+        )
         return out
 
     # ---- device: hot path ----------------------------------------------------------------------------------------

@@ -82,3 +82,133 @@ class EncryptedInference:
 def logits_from_slots(z: np.ndarray, classes: int = 4) -> np.ndarray:
     nb = z.shape[0] // BLOCK
     return np.stack([z[b * BLOCK: b * BLOCK + classes].real for b in range(nb)])
+
+
+# ---- one encrypted gradient-descent step of one-vs-rest logistic regression ----------------------------
+
+def sigmoid_ls_coeffs(degree: int = 7, radius: float = 8.0) -> np.ndarray:
+    """Monomial coefficients in t = x/radius of the least-squares polynomial approximation of the
+    logistic function on [-radius, radius] (continuous L2, by Legendre projection).  The paper evaluates
+    the logistic function through a polynomial (Section 2.2: minimax, degree 15 on [-12, 12]); the training
+    workload here prescribes degree 7, least squares, on [-8, 8]."""
+    from numpy.polynomial import legendre as leg
+
+    xs, ws = leg.leggauss(400)
+    f = 1.0 / (1.0 + np.exp(-radius * xs))
+    c = [(2 * k + 1) / 2.0 * np.sum(ws * f * leg.legval(xs, [0] * k + [1])) for k in range(degree + 1)]
+    mono = leg.leg2poly(c)
+    mono[0] = 0.5
+    mono[2::2] = 0.0  # logistic - 1/2 is odd: the even terms vanish up to quadrature round-off
+    return mono
+
+
+TRAIN_SUM_SHIFTS = tuple(1 << k for k in range(10))          # block sum: +1 .. +512
+TRAIN_FILL_SHIFTS = tuple(-(1 << k) for k in range(10))      # replicate slot 0 of a block: -1 .. -512
+TRAIN_BLOCK_SHIFTS = tuple(BLOCK << k for k in range(5))     # sum over the 32 blocks: 1024 .. 16384
+
+
+class TrainPlan:
+    """Levels and scales of every intermediate of one step, fixed by the parameter set."""
+
+    def __init__(self, q: Sequence[int], level: int, scale: float, lr: float, n_samples: int, coeffs=None):
+        qf = [float(v) for v in q]
+        self.level, self.scale = level, scale
+        l = level
+        self.s1 = scale * scale / qf[l - 1]                 # x*w, level l-1
+        self.mask_scale = qf[l - 2]                         # mask product rescales back to s1, level l-2
+        self.s2 = self.s1 * self.s1 / qf[l - 3]             # z^2, level l-3
+        self.s4 = self.s2 * self.s2 / qf[l - 4]             # z^4, level l-4
+        self.t_u = scale                                    # a7 z^2 + a5, level l-4
+        self.c_u = self.t_u * qf[l - 4] / self.s2
+        self.t_v = self.s4 * self.t_u / qf[l - 5]           # z^4 * u and a3 z^2 + a1, level l-5
+        self.c_v = self.t_v * qf[l - 4] / self.s2
+        self.t_p = self.s1 * self.t_v / qf[l - 6]           # p(z), level l-6
+        self.label_level, self.label_scale = l - 6, self.t_p
+        self.t_g = self.t_p * scale / qf[l - 7]             # gradient after rescale, level l-7
+        self.c_w = scale * qf[l - 8] / self.t_g             # update constant; result at level l-8, `scale`
+        self.out_level = l - 8
+        self.step = lr / n_samples
+        c = sigmoid_ls_coeffs() if coeffs is None else coeffs  # monomial coefficients in t = x/8
+        self.a1, self.a3, self.a5, self.a7 = c[1] / 8.0, c[3] / 8.0**3, c[5] / 8.0**5, c[7] / 8.0**7
+
+
+def _residues(value: float, scale: float, q: Sequence[int], level: int) -> List[int]:
+    v = int(round(value * scale))
+    return [v % int(q[i]) for i in range(level)]
+
+
+class EncryptedTrainStep:
+    """W_c <- W_c - (lr/n) sum_samples (p(<x, w_c>) - y_c) x for every class c, all under encryption.
+
+    X[i]: ciphertexts of packed samples (level `level`, scale `scale`); W[c]: weights replicated in every
+    block at the feature offsets (same level and scale); Y[c][i]: labels replicated over each block at
+    plan.label_level / plan.label_scale.  Per (class, ciphertext): 6 HMult and 20 HRot; per class 5 more HRot."""
+
+    def __init__(self, he, level: int, scale: float, lr: float, n_samples: int, coeffs=None):
+        self.he = he
+        self.plan = TrainPlan(he.q, level, scale, lr, n_samples, coeffs)
+
+    def rotation_shifts(self):
+        return list(TRAIN_SUM_SHIFTS) + list(TRAIN_FILL_SHIFTS) + list(TRAIN_BLOCK_SHIFTS)
+
+    def make_keys(self, sk, seed: int):
+        rot = {r: self.he.keygen_rot(sk, r, seed + 1 + k) for k, r in enumerate(self.rotation_shifts())}
+        return self.he.keygen_relin(sk, seed), rot
+
+    def mask_slots(self) -> np.ndarray:
+        m = np.zeros(self.he.n)
+        m[::BLOCK] = 1.0
+        return m
+
+    def encode_mask(self):
+        he, p = self.he, self.plan
+        return he.to_device(he.plain_to_ntt(he.encode(self.mask_slots(), p.mask_scale), p.level - 1))
+
+    def _mul(self, relin, a, b):
+        return self.he.rescale(self.he.hmult_relin(relin, a, b))
+
+    def _affine(self, ct, coeff: float, c_scale: float, const: float, t_scale: float):
+        """rescale(coeff * ct) + const, landing on scale t_scale one level down."""
+        he = self.he
+        level = int(ct.shape[1])
+        out = he.rescale(he.cmult(ct, _residues(coeff, c_scale, he.q, level)))
+        return he.add_const(out, _residues(const, t_scale, he.q, level - 1), out=out)
+
+    def logistic(self, relin, z):
+        """p(z) for z at level l-2, scale s1 -> level l-6, scale t_p."""
+        he, p = self.he, self.plan
+        z2 = self._mul(relin, z, z)
+        z4 = self._mul(relin, z2, z2)
+        u = self._affine(z2, p.a7, p.c_u, p.a5, p.t_u)
+        zu = self._mul(relin, z4, u)
+        v = he.moddrop(self._affine(z2, p.a3, p.c_v, p.a1, p.t_v), p.level - 5)
+        inner = he.add(zu, v, out=zu)
+        out = self._mul(relin, he.moddrop(z, p.level - 5), inner)
+        return he.add_const(out, _residues(0.5, p.t_p, he.q, p.level - 6), out=out)
+
+    def gradient_term(self, relin, rot, mask_pt, x, x_low, w, y):
+        """(p(<x, w>) - y) * x for one ciphertext of samples: level l-6, scale t_p * scale, not rescaled."""
+        he = self.he
+        m = self._mul(relin, x, w)
+        he.rotate_sum([rot[r] for r in TRAIN_SUM_SHIFTS], m)
+        z = he.rescale(he.pmult(m, mask_pt))
+        he.rotate_sum([rot[r] for r in TRAIN_FILL_SHIFTS], z)
+        e = self.logistic(relin, z)
+        he.sub(e, y, out=e)
+        return he.hmult_relin(relin, e, x_low)
+
+    def run(self, relin, rot, mask_pt, X, W, Y):
+        he, p = self.he, self.plan
+        X_low = [he.moddrop(x, p.label_level) for x in X]
+        out = []
+        for c, w in enumerate(W):
+            G = None
+            for i, x in enumerate(X):
+                g = self.gradient_term(relin, rot, mask_pt, x, X_low[i], w, Y[c][i])
+                G = g if G is None else he.add(G, g, out=G)
+            G = he.rescale(G)
+            he.rotate_sum([rot[r] for r in TRAIN_BLOCK_SHIFTS], G)
+            level = int(G.shape[1])
+            upd = he.rescale(he.cmult(G, _residues(p.step, p.c_w, he.q, level)))
+            out.append(he.sub(he.moddrop(w, p.out_level), upd))
+        return out

@@ -10,7 +10,7 @@
 //      and the digit's own limbs straight from d                                     -> u
 //   4. inverse NTT of the special limbs of u, scaled by (P/p_k)^-1                   (in place)
 //   5. forward NTT of the 2*level ModDown corrections, column pass summing
-//      y_k (P/p_k mod q_i), block pass finishing out = (u - ntt) P^-1 + addend       -> out
+//      y_k (P/p_k mod q_i) over centred digits y_k, block pass finishing out = (u - ntt) P^-1 + addend       -> out
 // Hoisted rotations share steps 1-2.
 #include <hip/hip_runtime.h>
 
@@ -52,7 +52,7 @@ int32_t dev_upload_tables(he_ctx *c)
     if ((rc = upload(c, c->modc, &c->dev.mod)) != HE_OK) return rc;
     UP(tw_fwd) UP(tw_inv) UP(ninv) UP(twd_fwd) UP(twd_inv) UP(ninvd)
     UP(up_inv) UP(up_hat) UP(up_inv_d) UP(up_hat_d) UP(up_hat_dh)
-    UP(dn_inv) UP(dn_hat) UP(dn_pinv) UP(dn_inv_d) UP(dn_hat_d) UP(dn_hat_dh) UP(dn_pinv_d)
+    UP(dn_inv) UP(dn_hat) UP(dn_pinv) UP(dn_inv_d) UP(dn_hat_d) UP(dn_hat_dh) UP(dn_pinv_d) UP(dn_pmod) UP(dn_pmod_d)
     UP(rs_inv) UP(rs_inv_d)
 #undef UP
     c->dev.up_split = c->up_split ? 1 : 0;
@@ -401,6 +401,43 @@ extern "C" int32_t he_cmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h
     KLAUNCH(ctx, (hipStream_t)stream, KID_CMULT, 4.0 * level * ctx->N * 8.0,
             k_cmult<<<grid, 256, 0, (hipStream_t)stream>>>(d_ct, d_out, ctx->dev, sc, level, ctx->logN));
     return launch_ok(ctx);
+}
+
+extern "C" int32_t he_add_const(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out,
+                                int32_t level, void *stream)
+{
+    int32_t rc = level_guard(ctx, level);
+    if (rc != HE_OK) return rc;
+    if (!d_ct || !h_scalar || !d_out) return HE_EINVAL;
+    ScalarArgs sc;
+    memset(&sc, 0, sizeof(sc));
+    for (int i = 0; i < level; i++) {
+        if (h_scalar[i] >= ctx->mod[i]) return HE_EINVAL;
+        sc.s[i].w = h_scalar[i];
+    }
+    dim3 grid((unsigned)(ctx->N / 256), (unsigned)(2 * level));
+    KLAUNCH(ctx, (hipStream_t)stream, KID_LIMBWISE, 4.0 * level * ctx->N * 8.0,
+            k_addconst<<<grid, 256, 0, (hipStream_t)stream>>>(d_ct, d_out, ctx->dev, sc, level, ctx->logN));
+    return launch_ok(ctx);
+}
+
+extern "C" int32_t he_moddrop(he_ctx *ctx, const uint64_t *d_ct, int32_t in_level, uint64_t *d_out, int32_t out_level,
+                              void *stream)
+{
+    int32_t rc = level_guard(ctx, in_level);
+    if (rc != HE_OK) return rc;
+    if (out_level < 1 || out_level > in_level) return HE_ELEVEL;
+    if (!d_ct || !d_out || d_ct == d_out) return HE_EINVAL;
+    const size_t N = ctx->N;
+    for (int c = 0; c < 2; c++) {
+        hipError_t e = hipMemcpyAsync(d_out + (size_t)c * out_level * N, d_ct + (size_t)c * in_level * N,
+                                      (size_t)out_level * N * sizeof(u64), hipMemcpyDeviceToDevice, (hipStream_t)stream);
+        if (e != hipSuccess) {
+            ctx->hip_err = std::string("hipMemcpyAsync: ") + hipGetErrorString(e);
+            return HE_EHIP;
+        }
+    }
+    return HE_OK;
 }
 
 // ---- workspace layout (in limbs of N words)

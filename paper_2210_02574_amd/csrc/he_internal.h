@@ -51,6 +51,8 @@ struct DevTables {
     const double *dn_hat_d;    // [K][L]
     const double *dn_hat_dh;   // [K][L]   (P/p_k) 2^31 mod q_i
     const double *dn_pinv_d;   // [L]
+    const u64 *dn_pmod;        // [L]      P mod q_i
+    const double *dn_pmod_d;   // [L]
     int dn_split;              // some special prime is >= 2^50
     // Rescale: q_l^-1 mod q_i
     const ShoupConst *rs_inv;  // [L][L]
@@ -76,7 +78,8 @@ struct he_ctx {
     std::vector<double> twd_fwd, twd_inv, ninvd;
     std::vector<ShoupConst> up_inv;
     std::vector<u64> up_hat;
-    std::vector<double> up_inv_d, up_hat_d, up_hat_dh, dn_inv_d, dn_hat_d, dn_hat_dh, dn_pinv_d, rs_inv_d;
+    std::vector<double> up_inv_d, up_hat_d, up_hat_dh, dn_inv_d, dn_hat_d, dn_hat_dh, dn_pinv_d, dn_pmod_d, rs_inv_d;
+    std::vector<u64> dn_pmod;
     bool up_split = false, dn_split = false;
     std::vector<ShoupConst> dn_inv;
     std::vector<u64> dn_hat;

@@ -328,6 +328,9 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
         c->dn_hat_d.assign((size_t)K * L, 0.0);
         c->dn_hat_dh.assign((size_t)K * L, 0.0);
         c->dn_pinv_d.assign(L, 0.0);
+        c->dn_pmod.assign(L, 0);
+        c->dn_pmod_d.assign(L, 0.0);
+        for (int i = 0; i < L; i++) c->dn_pmod[i] = prod_mod_excluding(c->mod, L, M, -1, c->mod[i]);
         c->rs_inv_d.assign((size_t)L * L, 0.0);
         for (int k = 0; k < K; k++) {
             if (c->mod[L + k] < kFp) c->dn_inv_d[k] = bal(c->dn_inv[k].w, c->mod[L + k]);
@@ -343,6 +346,7 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
             const u64 t = c->mod[i];
             if (t >= kFp) continue;
             c->dn_pinv_d[i] = bal(c->dn_pinv[i].w, t);
+            c->dn_pmod_d[i] = bal(c->dn_pmod[i], t);
             for (int l = 0; l < L; l++)
                 if (l != i) c->rs_inv_d[(size_t)l * L + i] = bal(c->rs_inv[(size_t)l * L + i].w, t);
         }

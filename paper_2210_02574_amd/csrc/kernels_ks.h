@@ -35,6 +35,16 @@ __global__ __launch_bounds__(256) void k_cmult(const u64 *__restrict__ a, u64 *_
     out[((size_t)l << logN) + n] = mul_shoup(a[((size_t)l << logN) + n], sc.s[i], T.mod[i].q);
 }
 
+// c0 += constant (one residue per limb), c1 copied
+__global__ __launch_bounds__(256) void k_addconst(const u64 *__restrict__ a, u64 *__restrict__ out, DevTables T,
+                                                  ScalarArgs sc, int level, int logN)
+{
+    const unsigned l = blockIdx.y;
+    const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const u64 v = a[((size_t)l << logN) + n];
+    out[((size_t)l << logN) + n] = l < (unsigned)level ? csub(v + sc.s[l].w, T.mod[l].q) : v;
+}
+
 // Tensor product: d0 = a0 b0, d1 = a0 b1 + a1 b0 -> out (may alias A or B); d2 = a1 b1 -> d2.
 __global__ __launch_bounds__(256) void k_tensor(const u64 *A, const u64 *B, u64 *out, u64 *__restrict__ d2,
                                                 DevTables T, int level, int logN)

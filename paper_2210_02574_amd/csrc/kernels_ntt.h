@@ -64,6 +64,10 @@ template <int NSMAX> struct ConvSetup {
     const u64 *sp[NSMAX];         // source limbs; entries past the real count repeat entry 0 with zero constants
     double cd[NSMAX], cdh[NSMAX]; // constants as balanced doubles (cdh: constant * 2^31)
     u64 ci[NSMAX];                // constants as residues (integer targets)
+    // ModDown: source digit s counts as y - p_s when y > hs[s]; each such digit subtracts P mod q_i
+    u64 hs[NSMAX];
+    u64 pm_i;
+    double pm_d;
     // rescale
     u64 ql, half;
     double qld;
@@ -76,12 +80,15 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
     ConvSetup<NSMAX> S;
     S.ql = S.half = 0;
     S.qld = 0.0;
+    S.pm_i = 0;
+    S.pm_d = 0.0;
     const int M = cv.L + cv.K, Ma = cv.level + cv.K;
 #pragma unroll
     for (int s = 0; s < NSMAX; s++) {
         S.sp[s] = cv.src;
         S.ci[s] = 0;
         S.cd[s] = S.cdh[s] = 0.0;
+        S.hs[s] = ~(u64)0;
     }
     if (PRO == PRO_MODUP) {
         const int j = slot / Ma;
@@ -107,7 +114,10 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
             S.ci[s] = on ? T.dn_hat[ci] : 0;
             S.cd[s] = on ? T.dn_hat_d[ci] : 0.0;
             S.cdh[s] = on ? T.dn_hat_dh[ci] : 0.0;
+            S.hs[s] = on ? (T.mod[cv.L + s].q - 1) / 2 : ~(u64)0;
         }
+        S.pm_i = T.dn_pmod[i];
+        S.pm_d = T.dn_pmod_d[i];
     } else if (PRO == PRO_RESCALE) {
         const int c = slot / (cv.level - 1);
         S.sp[0] = cv.src + ((size_t)c << LOGN);
@@ -130,9 +140,11 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
         return neg ? -w : w;
     }
     double acc = 0.0;
+    int neg = 0; // ModDown: number of digits that stand for y - p
 #pragma unroll
     for (int s = 0; s < NSMAX; s++) {
         const u64 y = S.sp[s][pos];
+        if (PRO == PRO_MODDOWN) neg += y > S.hs[s] ? 1 : 0;
         if (!SPLIT)
             acc += ar.mulmod(u2d(y), S.cd[s]);
         else {
@@ -140,6 +152,10 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
             acc += ar.mulmod(yh, S.cdh[s]) + ar.mulmod(yl, S.cd[s]);
         }
         if ((s & 3) == 3 && s + 1 < NSMAX) acc = ar.reduce(acc);
+    }
+    if (PRO == PRO_MODDOWN) {
+        if (NSMAX > 4) acc = ar.reduce(acc);
+        acc -= (double)neg * S.pm_d; // p_s * (P/p_s) = P for every centred digit
     }
     return acc;
 }
@@ -154,9 +170,15 @@ __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithIn
         return neg ? (w ? m.q - w : 0) : w;
     }
     U128 acc{0, 0};
+    u64 corr = 0;
 #pragma unroll
-    for (int s = 0; s < NSMAX; s++) mac128(acc, S.sp[s][pos], S.ci[s]);
-    return reduce128(acc, m);
+    for (int s = 0; s < NSMAX; s++) {
+        const u64 y = S.sp[s][pos];
+        mac128(acc, y, S.ci[s]);
+        if (PRO == PRO_MODDOWN) corr = csub(corr + (y > S.hs[s] ? S.pm_i : 0), m.q);
+    }
+    const u64 r = reduce128(acc, m);
+    return PRO == PRO_MODDOWN ? csub(r + m.q - corr, m.q) : r;
 }
 
 // ---- epilogue: what the forward block pass does with a finished (canonical) NTT value ---------------------

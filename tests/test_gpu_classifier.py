@@ -49,3 +49,56 @@ def test_inference_matches_oracle_and_plaintext(oracle_mod):
     err = np.abs(logits - ref).max()
     print("inference max abs error %.3g (bound %.3g)" % (err, 2.0**-15))
     assert err <= 2.0**-15
+
+
+def test_train_step_slice_matches_oracle_and_plaintext(oracle_mod):
+    """One gradient step of one class on one ciphertext of 32 samples (6 HMult, 25 HRot, levels 24 -> 16,
+    scale 2^50): bit-exact against the oracle's own composition, and the decrypted updated weights against
+    the fp64 evaluation of the same polynomial step."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from oracle import classifier as oc
+    from paper_2210_02574_amd import classifier as cl
+
+    assert torch.cuda.is_available()
+    p = wl.N16
+    he = pkg.HE.from_params(p, device=0)
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    level, scale, lr = 24, 2.0**50, 1.0
+    nb = he.n // 1024
+    n_samples = nb
+    X = wl.embeddings(51, nb)
+    W0 = wl.weights(52)[:1]
+    Wstar = wl.weights(53)
+    labels = (np.argmax(X @ Wstar.T, axis=1) == 0).astype(np.float64)
+    coeffs = cl.sigmoid_ls_coeffs()
+    step = cl.EncryptedTrainStep(he, level, scale, lr, n_samples, coeffs)
+    plan = step.plan
+    sk, s = he.keygen_secret(54), o.keygen_secret(54)
+    relin, rot = step.make_keys(sk, 200)
+    orelin = o.keygen_relin(s, 200)
+    orot = {r: o.keygen_rot(s, r, 201 + k) for k, r in enumerate(step.rotation_shifts())}
+    zx = cl.pack_samples(X, he.n)
+    zw = np.tile(np.concatenate([np.zeros(4), W0[0], np.zeros(1024 - 772)]), nb)
+    zy = np.repeat(labels, 1024)
+    cx = o.encrypt_coeffs(s, o.encode(zx, scale), level, 55)
+    cw = o.encrypt_coeffs(s, o.encode(zw, scale), level, 56)
+    cy = o.encrypt_coeffs(s, o.encode(zy, plan.label_scale), plan.label_level, 57)
+    mask_pt = he.to_device(o.coeffs_to_ntt(o.encode(step.mask_slots(), plan.mask_scale), level - 1))
+    a_x = [coeffs[k] / 8.0**k for k in range(8)]
+    got = step.run(relin, rot, mask_pt, [he.to_device(cx)], [he.to_device(cw)], [[he.to_device(cy)]])
+    got = he.to_host(got[0])
+    want = oc.train_step(o, [cx], [cw], [[cy]], orelin, orot, level, scale, lr, n_samples, a_x)[0]
+    assert got.shape == (2, plan.out_level, p.N)
+    assert np.array_equal(got, want)
+    dec = he.decrypt(sk, got, scale).real
+    z = X @ W0[0]
+    pz = np.polyval(coeffs[::-1], z / 8.0)
+    ref = W0[0] - lr / n_samples * ((pz - labels) @ X)
+    w_new = dec[4:772]
+    err = np.abs(w_new - ref).max()
+    print("train-step slice: max abs error of updated weights %.3g (bound %.3g)" % (err, 2.0**-15))
+    assert err <= 2.0**-15
+    # every block carries the same updated weights
+    assert np.abs(dec[1024 + 4: 1024 + 772] - ref).max() <= 2.0**-15
