@@ -31,9 +31,19 @@ import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 
-# HBM traffic per launch of the dominant kernels from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`
-# runs of this command (summaries under profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM traffic per launch (bytes, averaged over the launches of one step) from `rocprofv3 --pmc FETCH_SIZE` and
+# `--pmc WRITE_SIZE` runs of this command with --streams 1, scaled by the copy-kernel calibration
+# (2 x FETCH_SIZE + 1 x WRITE_SIZE; summary and calibration under profiles/).
+MEASURED_TRAFFIC_BYTES = {
+    "k_inner": 213533491,
+    "k_ntt_fwd_blocks_fin": 84031488,
+    "k_ntt_fwd_blocks": 132389683,
+    "k_ntt_fwd_cols_modup": 65295360,
+    "k_ntt_fwd_cols_moddown": 24819098,
+    "k_ntt_fwd_cols_rescale": 25800704,
+    "k_tensor": 88134451,
+    "k_ntt_inv_blocks": 19033600,
+}
 
 
 class Workload:
@@ -43,11 +53,14 @@ class Workload:
     N_HMULT = 64
     N_SINGLE = 128
 
-    def __init__(self, he, seed: int = 2, n_hmult: int = None, n_single: int = None, n_ntt: int = None):
+    def __init__(self, he, seed: int = 2, n_hmult: int = None, n_single: int = None, n_ntt: int = None,
+                 n_streams: int = 1):
         import torch
 
         self.torch = torch
         self.he = he
+        # independent operations are spread over this many HIP streams (default priority)
+        self.streams = [torch.cuda.Stream(device=he.device) for _ in range(n_streams)] if n_streams > 1 else []
         p = self.params = wl.N16
         self.n_hmult = self.N_HMULT if n_hmult is None else n_hmult
         self.n_single = self.N_SINGLE if n_single is None else n_single
@@ -105,18 +118,66 @@ class Workload:
         he.ntt(self.ntt_limbs, self.ntt_mods)
         he.intt(self.ntt_limbs, self.ntt_mods)
         mark("ntt_pairs")
-        for i in range(self.n_hmult):
-            he.hmult_relin(self.relin, self.hm_a[i], self.hm_b[i], out=self.hm_out[i])
-            he.rescale(self.hm_out[i], out=self.rs_out[i])
+        self._spread(self.n_hmult, self._hmult_one)
         mark("hmult_relin_rescale")
         he.hrot_many(self.rot, self.hoist_in, outs=self.hoist_out)
         mark("hrot_hoisted")
-        for i in range(self.n_single):
-            he.hrot(self.rot[self.single_keys[i]], self.single_in[i], out=self.single_out[i])
+        self._spread(self.n_single, self._single_one)
         mark("hrot_single")
 
+    def _hmult_one(self, i):
+        self.he.hmult_relin(self.relin, self.hm_a[i], self.hm_b[i], out=self.hm_out[i])
+        self.he.rescale(self.hm_out[i], out=self.rs_out[i])
 
-def cpu_baseline(sample_hrot: int = 8, sample_hmult: int = 4, sample_ntt: int = 28):
+    def _single_one(self, i):
+        self.he.hrot(self.rot[self.single_keys[i]], self.single_in[i], out=self.single_out[i])
+
+    def _spread(self, count, fn):
+        """Runs fn(0..count-1); with side streams the independent calls are dealt round-robin to them and
+        joined back into the current stream."""
+        torch = self.torch
+        if not self.streams:
+            for i in range(count):
+                fn(i)
+            return
+        cur = torch.cuda.current_stream(self.he.device)
+        for st in self.streams:
+            st.wait_stream(cur)
+        for i in range(count):
+            with torch.cuda.stream(self.streams[i % len(self.streams)]):
+                fn(i)
+        for st in self.streams:
+            cur.wait_stream(st)
+
+
+def train_step_ms(he, w: "Workload") -> float:
+    """One full encrypted gradient-descent step (4 classes x 32 ciphertexts of 32 samples = 1024 samples x 768
+    features, degree-7 polynomial logistic function, levels 24 -> 16) on uniform residues: 768 HMult and
+    2580 HRot.  Returns milliseconds for the step."""
+    import torch
+
+    from paper_2210_02574_amd import classifier as cl
+
+    step = cl.EncryptedTrainStep(he, wl.N16.L, 2.0**50, 1.0, 1024)
+    plan = step.plan
+    rot = {}
+    for k, r in enumerate(w.offsets):  # +2^0 .. +2^14 cover the block-sum and cross-block shifts
+        rot[r] = w.rot[k]
+    for k, r in enumerate(cl.TRAIN_FILL_SHIFTS):
+        rot[r] = w._key(2000 + k, he.galois_element(r))
+    X = [w._uniform_ct(plan.level) for _ in range(32)]
+    W = [w._uniform_ct(plan.level) for _ in range(4)]
+    Y = [[w._uniform_ct(plan.label_level) for _ in range(32)] for _ in range(4)]
+    mask = w._uniform(list(range(plan.level - 1)))
+    step.run(w.relin, rot, mask, X[:1], W[:1], [Y[0][:1]])  # warm-up slice
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    step.run(w.relin, rot, mask, X, W, Y)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3
+
+
+def cpu_baseline(sample_hrot: int = 32, sample_hmult: int = 16, sample_ntt: int = 112):
     """The oracle, as it stands, on a bounded sample of the step: NTT/iNTT pairs, HMult+relin+rescale
     and HRot at level 24; reported in key switches per second."""
     import oracle
@@ -124,7 +185,7 @@ def cpu_baseline(sample_hrot: int = 8, sample_hmult: int = 4, sample_ntt: int = 
     p = wl.N16
     o = oracle.Oracle(p.logN, p.q, p.p, p.dnum)
     cores = int(o.lib.orc_num_threads())
-    mods = list(range(sample_ntt))
+    mods = [b % (p.L + p.K) for b in range(sample_ntt)]
     limbs = wl.uniform_limbs(11, p, mods)
     evk = wl.uniform_evk(12, p)
     a, b = wl.uniform_ct(13, p, p.L), wl.uniform_ct(14, p, p.L)
@@ -161,6 +222,8 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-train-step", action="store_true")
+    ap.add_argument("--streams", type=int, default=2, help="HIP streams for the independent operations of a step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
@@ -175,7 +238,7 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     he = pkg.HE.from_params(wl.N16, device=0)
-    w = Workload(he)
+    w = Workload(he, n_streams=args.streams)
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()
@@ -247,11 +310,15 @@ def main():
             "workload": "N=2^16, L=24, K=4, dnum=6: 256 limb NTT+iNTT pairs, 64 HMult+relin+rescale at level 24, "
                         "15 hoisted HRot (2^0..2^14) at level 24, 128 single HRot at levels 8..24",
             "key_switches_per_step": w.key_switches,
+            "streams": args.streams,
         },
         "detail": detail,
         "roofline": roofline,
         "kernels": kernels,
     }
+    if not args.no_train_step:
+        out["detail"]["train_step_ms"] = train_step_ms(he, w)
+        out["detail"]["train_step_workload"] = "1024 samples x 768 features, 4 classes, 768 HMult + 2580 HRot"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

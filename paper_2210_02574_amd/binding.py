@@ -304,13 +304,18 @@ class HE:
         return ctypes.c_void_p(torch.cuda.current_stream(self.device).cuda_stream)
 
     def _workspace(self, level: int):
+        """One workspace per stream: calls enqueued on different streams may run concurrently."""
         import torch
 
         need = self.workspace_bytes(level)
-        if self._ws is None or self._ws.numel() * 8 < need:
-            self._ws = None
-            self._ws = torch.empty(need // 8, dtype=torch.int64, device=f"cuda:{self.device}")
-        return ctypes.c_void_p(self._ws.data_ptr()), self._ws.numel() * 8
+        key = torch.cuda.current_stream(self.device).cuda_stream
+        if self._ws is None:
+            self._ws = {}
+        ws = self._ws.get(key)
+        if ws is None or ws.numel() * 8 < need:
+            self._ws[key] = None
+            ws = self._ws[key] = torch.empty(need // 8, dtype=torch.int64, device=f"cuda:{self.device}")
+        return ctypes.c_void_p(ws.data_ptr()), ws.numel() * 8
 
     @staticmethod
     def _dp(t):

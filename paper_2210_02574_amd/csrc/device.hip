@@ -13,6 +13,7 @@
 //      y_k (P/p_k mod q_i) over centred digits y_k, block pass finishing out = (u - ntt) P^-1 + addend       -> out
 // Hoisted rotations share steps 1-2.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cstring>
@@ -103,27 +104,34 @@ static const char *const kKernelNames[KID_COUNT] = {
     "k_ntt_fwd_cols", "k_ntt_fwd_cols_modup", "k_ntt_fwd_cols_moddown", "k_ntt_fwd_cols_rescale", "k_ntt_fwd_blocks",
     "k_ntt_fwd_blocks_fin", "k_ntt_inv_blocks", "k_ntt_inv_cols", "k_limbwise", "k_cmult", "k_tensor", "k_inner"};
 
-static void prof_begin(he_ctx *c, hipStream_t st, int kid, double bytes)
+static bool prof_events(he_ctx *c, int kid, double bytes, ProfRecord &r)
 {
-    ProfRecord r;
     r.kid = kid;
     r.bytes = bytes;
     r.a = r.b = nullptr;
-    if (hipEventCreate((hipEvent_t *)&r.a) != hipSuccess || hipEventCreate((hipEvent_t *)&r.b) != hipSuccess) return;
-    (void)hipEventRecord((hipEvent_t)r.a, st);
+    if (hipEventCreate((hipEvent_t *)&r.a) != hipSuccess) return false;
+    if (hipEventCreate((hipEvent_t *)&r.b) != hipSuccess) {
+        (void)hipEventDestroy((hipEvent_t)r.a);
+        return false;
+    }
     c->prof.push_back(r);
+    return true;
 }
-static void prof_end(he_ctx *c, hipStream_t st)
-{
-    if (!c->prof.empty()) (void)hipEventRecord((hipEvent_t)c->prof.back().b, st);
-}
-// Launch wrapper: `bytes` = bytes the launch has to move by the definition of its step
-#define KLAUNCH(c, st, kid, bytes, ...)                                                                              \
+// Launch wrapper (256 threads per group): `bytes` = bytes the launch has to move by the definition of
+// its step.  While profiling, the launch carries a start and a stop event that take the kernel's own
+// begin and end timestamps.
+#define KLAUNCH_T(c, st, kid, bytes, kernel, grid, threads, ...)                                                    \
     do {                                                                                                             \
-        if ((c)->prof_on) prof_begin((c), (st), (kid), (double)(bytes));                                             \
-        __VA_ARGS__;                                                                                                 \
-        if ((c)->prof_on) prof_end((c), (st));                                                                       \
+        ProfRecord pr_;                                                                                              \
+        if ((c)->prof_on && prof_events((c), (kid), (double)(bytes), pr_))                                           \
+            hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, (st), (hipEvent_t)pr_.a, (hipEvent_t)pr_.b,   \
+                                  0, __VA_ARGS__);                                                                   \
+        else                                                                                                         \
+            hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, (st), __VA_ARGS__);                             \
     } while (0)
+#define KLAUNCH(c, st, kid, bytes, kernel, grid, ...) KLAUNCH_T(c, st, kid, bytes, kernel, grid, 256, __VA_ARGS__)
+// work-groups per limb of the block pass
+#define BLK_TILES(c) ((int)((c)->N / (256 * BLK_PER_WG)))
 
 extern "C" int32_t he_profile_start(he_ctx *ctx)
 {
@@ -239,7 +247,7 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
                              : pro == PRO_MODDOWN ? KID_FWD_COLS_MODDOWN
                                                   : KID_FWD_COLS_RESCALE;
 #define COLS1(KERN, GRID, P, NS)                                                                                     \
-    KLAUNCH(c, st, kid_cols, cols_bytes, KERN<P, NS><<<GRID, 256, 0, st>>>(data, c->dev, lb, cv))
+    KLAUNCH(c, st, kid_cols, cols_bytes, (KERN<P, NS>), GRID, data, c->dev, lb, cv)
 #define COLS(KERN, GRID)                                                                                             \
     switch (pro) {                                                                                                   \
     case PRO_LOAD: COLS1(KERN, GRID, PRO_LOAD, 4); break;                                                            \
@@ -268,18 +276,14 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
             // reads the transform's input, the minuend and the addend, writes the result
             const double b = (double)nb * N8 * (3.0 + (fin->mode == 1 ? 1.0 : fin->mode == 2 ? 0.5 : 0.0));
             if (c->logN == 16)
-                KLAUNCH(c, st, KID_FWD_BLOCKS_FIN, b,
-                        k_ntt_fwd_blocks<16, EPI_FIN><<<16 * nb, 256, 0, st>>>(data, c->dev, lb, *fin));
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<16, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin);
             else
-                KLAUNCH(c, st, KID_FWD_BLOCKS_FIN, b,
-                        k_ntt_fwd_blocks<12, EPI_FIN><<<nb, 256, 0, st>>>(data, c->dev, lb, *fin));
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<12, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin);
         } else {
             if (c->logN == 16)
-                KLAUNCH(c, st, KID_FWD_BLOCKS, 2.0 * nb * N8,
-                        k_ntt_fwd_blocks<16, EPI_STORE><<<16 * nb, 256, 0, st>>>(data, c->dev, lb, kNoFin));
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nb * N8, (k_ntt_fwd_blocks<16, EPI_STORE>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, kNoFin);
             else
-                KLAUNCH(c, st, KID_FWD_BLOCKS, 2.0 * nb * N8,
-                        k_ntt_fwd_blocks<12, EPI_STORE><<<nb, 256, 0, st>>>(data, c->dev, lb, kNoFin));
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nb * N8, (k_ntt_fwd_blocks<12, EPI_STORE>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, kNoFin);
         }
     });
 }
@@ -292,7 +296,7 @@ static int32_t ntt_inverse(he_ctx *c, hipStream_t st, const u64 *src, u64 *dst, 
     const double N8 = (double)c->N * 8.0;
     return for_batches(c, l, [&](const LimbBatch &lb, int nb) {
         const double bytes = 2.0 * nb * N8;
-#define ICOLS1(KERN, GRID, S) KLAUNCH(c, st, KID_INV_COLS, bytes, KERN<S><<<GRID, 256, 0, st>>>(dst, c->dev, lb, cv))
+#define ICOLS1(KERN, GRID, S) KLAUNCH(c, st, KID_INV_COLS, bytes, (KERN<S>), GRID, dst, c->dev, lb, cv)
 #define ICOLS(KERN, GRID)                                                                                            \
     switch (scale) {                                                                                                 \
     case SCALE_NONE: ICOLS1(KERN, GRID, SCALE_NONE); break;                                                          \
@@ -300,10 +304,10 @@ static int32_t ntt_inverse(he_ctx *c, hipStream_t st, const u64 *src, u64 *dst, 
     default: ICOLS1(KERN, GRID, SCALE_MODDOWN); break;                                                               \
     }
         if (c->logN == 16) {
-            KLAUNCH(c, st, KID_INV_BLOCKS, bytes, k_ntt_inv_blocks<16><<<16 * nb, 256, 0, st>>>(src, dst, c->dev, lb));
+            KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<16>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
             ICOLS(k_ntt_inv_cols16, 16 * nb)
         } else {
-            KLAUNCH(c, st, KID_INV_BLOCKS, bytes, k_ntt_inv_blocks<12><<<nb, 256, 0, st>>>(src, dst, c->dev, lb));
+            KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<12>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
             ICOLS(k_ntt_inv_cols12, nb)
         }
 #undef ICOLS
@@ -364,8 +368,7 @@ static int32_t limbwise(he_ctx *c, const u64 *a, const u64 *b, u64 *out, int lev
     if (rc != HE_OK) return rc;
     if (!a || !b || !out) return HE_EINVAL;
     dim3 grid((unsigned)(c->N / 256), (unsigned)limbs);
-    KLAUNCH(c, (hipStream_t)stream, KID_LIMBWISE, (double)(2 * limbs + b_limbs) * c->N * 8.0,
-            k_limbwise<<<grid, 256, 0, (hipStream_t)stream>>>(a, b, out, c->dev, op, level, b_limbs, c->logN));
+    KLAUNCH(c, (hipStream_t)stream, KID_LIMBWISE, (double)(2 * limbs + b_limbs) * c->N * 8.0, (k_limbwise), grid, a, b, out, c->dev, op, level, b_limbs, c->logN);
     return launch_ok(c);
 }
 
@@ -398,8 +401,7 @@ extern "C" int32_t he_cmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h
         sc.s[i] = hostmath::shoup(h_scalar[i], ctx->mod[i]);
     }
     dim3 grid((unsigned)(ctx->N / 256), (unsigned)(2 * level));
-    KLAUNCH(ctx, (hipStream_t)stream, KID_CMULT, 4.0 * level * ctx->N * 8.0,
-            k_cmult<<<grid, 256, 0, (hipStream_t)stream>>>(d_ct, d_out, ctx->dev, sc, level, ctx->logN));
+    KLAUNCH(ctx, (hipStream_t)stream, KID_CMULT, 4.0 * level * ctx->N * 8.0, (k_cmult), grid, d_ct, d_out, ctx->dev, sc, level, ctx->logN);
     return launch_ok(ctx);
 }
 
@@ -416,8 +418,7 @@ extern "C" int32_t he_add_const(he_ctx *ctx, const uint64_t *d_ct, const uint64_
         sc.s[i].w = h_scalar[i];
     }
     dim3 grid((unsigned)(ctx->N / 256), (unsigned)(2 * level));
-    KLAUNCH(ctx, (hipStream_t)stream, KID_LIMBWISE, 4.0 * level * ctx->N * 8.0,
-            k_addconst<<<grid, 256, 0, (hipStream_t)stream>>>(d_ct, d_out, ctx->dev, sc, level, ctx->logN));
+    KLAUNCH(ctx, (hipStream_t)stream, KID_LIMBWISE, 4.0 * level * ctx->N * 8.0, (k_addconst), grid, d_ct, d_out, ctx->dev, sc, level, ctx->logN);
     return launch_ok(ctx);
 }
 
@@ -497,9 +498,8 @@ static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, u64 *ws,
     const unsigned g = (unsigned)evk->galois;
     dim3 grid((unsigned)(N / 256), (unsigned)Ma);
     // reads beta digits and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
-    KLAUNCH(c, st, KID_INNER, (double)(3 * beta + 2) * Ma * N * 8.0,
-            k_inner<<<grid, 256, 0, st>>>(ws + w.raised * N, d_ntt, evk->dev, ws + w.u * N, c->dev, level, c->L, K,
-                                          c->alpha, beta, g, c->logN));
+    KLAUNCH(c, st, KID_INNER, (double)(3 * beta + 2) * Ma * N * 8.0, (k_inner), grid, ws + w.raised * N, d_ntt, evk->dev, ws + w.u * N, c->dev, level, c->L, K,
+                                          c->alpha, beta, g, c->logN);
     int32_t rc = launch_ok(c);
     if (rc != HE_OK) return rc;
     LimbList sp;
@@ -545,8 +545,7 @@ extern "C" int32_t he_hmult_relin(he_ctx *ctx, const he_evk *relin, const uint64
     const WsLayout w = ws_layout(ctx, level);
     const size_t N = ctx->N;
     dim3 grid((unsigned)(N / 256), (unsigned)level);
-    KLAUNCH(ctx, st, KID_TENSOR, 7.0 * level * N * 8.0,
-            k_tensor<<<grid, 256, 0, st>>>(d_a, d_b, d_out, ws + w.d * N, ctx->dev, level, ctx->logN));
+    KLAUNCH(ctx, st, KID_TENSOR, 7.0 * level * N * 8.0, (k_tensor), grid, d_a, d_b, d_out, ws + w.d * N, ctx->dev, level, ctx->logN);
     if ((rc = launch_ok(ctx)) != HE_OK) return rc;
     if ((rc = ks_raise(ctx, ws + w.d * N, ws, w, level, st)) != HE_OK) return rc;
     return ks_apply(ctx, relin, ws + w.d * N, ws, w, level, d_out, nullptr, 1, st);

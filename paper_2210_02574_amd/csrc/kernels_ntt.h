@@ -207,6 +207,11 @@ __device__ __forceinline__ void fin_store(const FinArgs &fa, const DevTables &T,
 // keep both the "stride-16" and the "16 consecutive" access patterns free of bank conflicts.
 #define TILE_GROUP 272
 #define TILE_WORDS (16 * TILE_GROUP)
+// threads per work-group of the block pass: 16 threads per 256-element block
+#ifndef BLK_THREADS
+#define BLK_THREADS 256
+#endif
+#define BLK_PER_WG (BLK_THREADS / 16)
 __device__ __forceinline__ unsigned tile_at(unsigned grp, unsigned i) { return grp * TILE_GROUP + i + (i >> 4); }
 // column pass: row r (0..255) of column c (0..15); 16 pad words after every 16 rows
 __device__ __forceinline__ unsigned col_at(unsigned r, unsigned c) { return (r >> 4) * TILE_GROUP + (r & 15) * 16 + c; }
@@ -218,7 +223,7 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
                                                 const FinArgs &fa, const DevTables &T, unsigned slot)
 {
     const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
-    const unsigned bg = tile * 16 + blk; // block index within the limb
+    const unsigned bg = tile * BLK_PER_WG + blk; // block index within the limb
     typename A::V a[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[bg * 256 + il + 16 * k]);
@@ -249,7 +254,7 @@ __device__ __forceinline__ void inv_blocks_body(const u64 *in, u64 *limb, const 
                                                 u64 *lds, unsigned tile)
 {
     const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
-    const unsigned bg = tile * 16 + blk;
+    const unsigned bg = tile * BLK_PER_WG + blk;
     typename A::V a[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = in[bg * 256 + il + 16 * k];
@@ -270,10 +275,10 @@ __device__ __forceinline__ void inv_blocks_body(const u64 *in, u64 *limb, const 
 
 // grid.x = (N/4096) * batch
 template <int LOGN, int EPI>
-__global__ __launch_bounds__(256) void k_ntt_fwd_blocks(u64 *__restrict__ data, DevTables T, LimbBatch lb, FinArgs fa)
+__global__ __launch_bounds__(BLK_THREADS) void k_ntt_fwd_blocks(u64 *__restrict__ data, DevTables T, LimbBatch lb, FinArgs fa)
 {
-    __shared__ u64 lds[TILE_WORDS];
-    constexpr unsigned TILES = (1u << LOGN) / 4096;
+    __shared__ u64 lds[BLK_PER_WG * TILE_GROUP];
+    constexpr unsigned TILES = (1u << LOGN) / (256 * BLK_PER_WG);
     const unsigned tile = blockIdx.x % TILES, b = blockIdx.x / TILES;
     const unsigned mi = lb.mod[b], slot = lb.slot[b];
     u64 *limb = data + ((size_t)slot << LOGN);
@@ -284,11 +289,11 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_blocks(u64 *__restrict__ data, 
 }
 
 template <int LOGN>
-__global__ __launch_bounds__(256) void k_ntt_inv_blocks(const u64 *src, u64 *dst,
+__global__ __launch_bounds__(BLK_THREADS) void k_ntt_inv_blocks(const u64 *src, u64 *dst,
                                                         DevTables T, LimbBatch lb)
 {
-    __shared__ u64 lds[TILE_WORDS];
-    constexpr unsigned TILES = (1u << LOGN) / 4096;
+    __shared__ u64 lds[BLK_PER_WG * TILE_GROUP];
+    constexpr unsigned TILES = (1u << LOGN) / (256 * BLK_PER_WG);
     const unsigned tile = blockIdx.x % TILES, b = blockIdx.x / TILES;
     const unsigned mi = lb.mod[b];
     const u64 *in = src + ((size_t)lb.src[b] << LOGN);

@@ -9,7 +9,8 @@ import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-def test_bench_step_outputs_match_oracle(oracle_mod):
+@pytest.mark.parametrize("n_streams", [1, 2])
+def test_bench_step_outputs_match_oracle(oracle_mod, n_streams):
     import torch
 
     import bench
@@ -19,7 +20,7 @@ def test_bench_step_outputs_match_oracle(oracle_mod):
     p = wl.N16
     he = pkg.HE.from_params(p, device=0)
     o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
-    w = bench.Workload(he, seed=2, n_hmult=2, n_single=6, n_ntt=56)
+    w = bench.Workload(he, seed=2, n_hmult=2, n_single=6, n_ntt=56, n_streams=n_streams)
     ntt_in = he.to_host(w.ntt_limbs).copy()
     w.step()
     torch.cuda.synchronize()
