@@ -83,9 +83,9 @@ int32_t he_ctx_modulus(const he_ctx *ctx, int32_t i, uint64_t *modulus, uint64_t
 int32_t he_galois_element(const he_ctx *ctx, int32_t r, uint64_t *g);
 /* The 38 cumulative thresholds of the discrete Gaussian sampler (sigma 3.2, support [-19,19]). */
 int32_t he_gauss_cdt(uint64_t out[38]);
-/* Bytes of device workspace that hmult_relin / hrot / rescale / rotate_sum need at `level`;
- * max_hoist = largest `count` passed to he_hrot_many (1 if unused). */
-int32_t he_workspace_bytes(const he_ctx *ctx, int32_t level, int32_t max_hoist, size_t *out);
+/* Bytes of device workspace that hmult_relin / hrot / hrot_many / rescale / rotate_sum need at
+ * `level` for `count` ciphertexts processed by one batched call (1 for the single-ciphertext calls). */
+int32_t he_workspace_bytes(const he_ctx *ctx, int32_t level, int32_t count, size_t *out);
 
 /* ---- host: keys, encoding, encryption (the user side; Section 2.2) ----------------------- */
 
@@ -183,6 +183,36 @@ int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t count, cons
 /* for k < count: ct <- ct + Rotate(ct, shift0 * 2^k), in place; rots[k] is the key of that shift. */
 int32_t he_rotate_sum(he_ctx *ctx, const he_evk *const *rots, int32_t count, uint64_t *d_ct, int32_t level,
                       void *d_ws, size_t ws_bytes, void *stream);
+
+/* ---- device: batches of independent ciphertexts ----------------------------------------------- */
+
+/* The same operations on `count` ciphertexts stored back to back ([count][2][level][N]), all at
+ * the same level and, for key switching, with the same key: every kernel is launched once over
+ * the whole batch, which keeps the launches large.  Results are bit-identical to `count` single
+ * calls.  The workspace must hold he_workspace_bytes(level, count); count * workspace limbs must
+ * stay below 65536 (HE_EINVAL otherwise).  Aliasing rules are those of the single calls. */
+int32_t he_add_batch(he_ctx *ctx, const uint64_t *d_a, const uint64_t *d_b, uint64_t *d_out, int32_t level,
+                     int32_t count, void *stream);
+int32_t he_sub_batch(he_ctx *ctx, const uint64_t *d_a, const uint64_t *d_b, uint64_t *d_out, int32_t level,
+                     int32_t count, void *stream);
+/* one plaintext [level][N] for the whole batch */
+int32_t he_pmult_batch(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *d_pt, uint64_t *d_out, int32_t level,
+                       int32_t count, void *stream);
+int32_t he_cmult_batch(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out, int32_t level,
+                       int32_t count, void *stream);
+int32_t he_add_const_batch(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out,
+                           int32_t level, int32_t count, void *stream);
+int32_t he_moddrop_batch(he_ctx *ctx, const uint64_t *d_ct, int32_t in_level, uint64_t *d_out, int32_t out_level,
+                         int32_t count, void *stream);
+int32_t he_hmult_relin_batch(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a, const uint64_t *d_b,
+                             uint64_t *d_out, int32_t level, int32_t count, void *d_ws, size_t ws_bytes, void *stream);
+int32_t he_rescale_batch(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level, int32_t count, void *d_ws,
+                         size_t ws_bytes, void *stream);
+int32_t he_hrot_batch(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level,
+                      int32_t count, void *d_ws, size_t ws_bytes, void *stream);
+/* n_rot sequential rotate-and-add steps applied to every ciphertext of the batch, in place */
+int32_t he_rotate_sum_batch(he_ctx *ctx, const he_evk *const *rots, int32_t n_rot, uint64_t *d_ct, int32_t level,
+                            int32_t count, void *d_ws, size_t ws_bytes, void *stream);
 
 /* ---- measurement ------------------------------------------------------------------------- */
 

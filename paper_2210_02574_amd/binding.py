@@ -31,6 +31,8 @@ SYMBOLS = [
     "he_encode", "he_decode", "he_plain_to_ntt", "he_encrypt_coeffs", "he_decrypt_coeffs", "he_decrypt",
     "he_ntt", "he_intt", "he_add", "he_sub", "he_pmult", "he_cmult", "he_add_const", "he_moddrop",
     "he_hmult_relin", "he_rescale", "he_hrot", "he_hrot_many", "he_rotate_sum",
+    "he_add_batch", "he_sub_batch", "he_pmult_batch", "he_cmult_batch", "he_add_const_batch", "he_moddrop_batch",
+    "he_hmult_relin_batch", "he_rescale_batch", "he_hrot_batch", "he_rotate_sum_batch",
     "he_profile_start", "he_profile_stop",
 ]
 
@@ -105,6 +107,16 @@ def load_library() -> ctypes.CDLL:
             "he_hrot": [vp, vp, vp, vp, i32, vp, sz, vp],
             "he_hrot_many": [vp, vp, i32, vp, vp, i32, vp, sz, vp],
             "he_rotate_sum": [vp, vp, i32, vp, i32, vp, sz, vp],
+            "he_add_batch": [vp, vp, vp, vp, i32, i32, vp],
+            "he_sub_batch": [vp, vp, vp, vp, i32, i32, vp],
+            "he_pmult_batch": [vp, vp, vp, vp, i32, i32, vp],
+            "he_cmult_batch": [vp, vp, vp, vp, i32, i32, vp],
+            "he_add_const_batch": [vp, vp, vp, vp, i32, i32, vp],
+            "he_moddrop_batch": [vp, vp, i32, vp, i32, i32, vp],
+            "he_hmult_relin_batch": [vp, vp, vp, vp, vp, i32, i32, vp, sz, vp],
+            "he_rescale_batch": [vp, vp, vp, i32, i32, vp, sz, vp],
+            "he_hrot_batch": [vp, vp, vp, vp, i32, i32, vp, sz, vp],
+            "he_rotate_sum_batch": [vp, vp, i32, vp, i32, i32, vp, sz, vp],
             "he_profile_start": [vp],
             "he_profile_stop": [vp, vp, i32, ctypes.POINTER(i32)],
         }
@@ -209,9 +221,9 @@ class HE:
         self._chk(self.lib.he_gauss_cdt(_hp(out)), "he_gauss_cdt")
         return [int(v) for v in out]
 
-    def workspace_bytes(self, level: int, max_hoist: int = 1) -> int:
+    def workspace_bytes(self, level: int, count: int = 1) -> int:
         out = ctypes.c_size_t()
-        self._chk(self.lib.he_workspace_bytes(self.ctx, level, max_hoist, ctypes.byref(out)), "he_workspace_bytes")
+        self._chk(self.lib.he_workspace_bytes(self.ctx, level, count, ctypes.byref(out)), "he_workspace_bytes")
         return int(out.value)
 
     # ---- host: keys ----------------------------------------------------------------------------
@@ -303,11 +315,11 @@ class HE:
 
         return ctypes.c_void_p(torch.cuda.current_stream(self.device).cuda_stream)
 
-    def _workspace(self, level: int):
+    def _workspace(self, level: int, count: int = 1):
         """One workspace per stream: calls enqueued on different streams may run concurrently."""
         import torch
 
-        need = self.workspace_bytes(level)
+        need = self.workspace_bytes(level, count)
         key = torch.cuda.current_stream(self.device).cuda_stream
         if self._ws is None:
             self._ws = {}
@@ -445,6 +457,101 @@ class HE:
             self.lib.he_rotate_sum(self.ctx, keys, n, self._dp(ct), level, ws, wsb, self._stream()), "he_rotate_sum"
         )
         return ct
+
+    # ---- device: batches [count][2][level][N] ---------------------------------------------------------------------
+    def _blevel(self, cts):
+        assert cts.dim() == 4 and cts.shape[1] == 2 and cts.shape[3] == self.N and cts.is_contiguous()
+        return int(cts.shape[2]), int(cts.shape[0])
+
+    def empty_batch(self, count: int, level: int):
+        import torch
+
+        return torch.empty((count, 2, level, self.N), dtype=torch.int64, device=f"cuda:{self.device}")
+
+    def add_batch(self, a, b, out=None):
+        level, count = self._blevel(a)
+        assert b.shape == a.shape
+        out = self.empty_batch(count, level) if out is None else out
+        self._chk(self.lib.he_add_batch(self.ctx, self._dp(a), self._dp(b), self._dp(out), level, count, self._stream()),
+                  "he_add_batch")
+        return out
+
+    def sub_batch(self, a, b, out=None):
+        level, count = self._blevel(a)
+        assert b.shape == a.shape
+        out = self.empty_batch(count, level) if out is None else out
+        self._chk(self.lib.he_sub_batch(self.ctx, self._dp(a), self._dp(b), self._dp(out), level, count, self._stream()),
+                  "he_sub_batch")
+        return out
+
+    def pmult_batch(self, cts, pt, out=None):
+        level, count = self._blevel(cts)
+        assert tuple(pt.shape) == (level, self.N)
+        out = self.empty_batch(count, level) if out is None else out
+        self._chk(self.lib.he_pmult_batch(self.ctx, self._dp(cts), self._dp(pt), self._dp(out), level, count,
+                                          self._stream()), "he_pmult_batch")
+        return out
+
+    def cmult_batch(self, cts, scalars: Sequence[int], out=None):
+        level, count = self._blevel(cts)
+        sc = np.array([int(v) for v in scalars], dtype=np.uint64)
+        assert sc.shape == (level,)
+        out = self.empty_batch(count, level) if out is None else out
+        self._chk(self.lib.he_cmult_batch(self.ctx, self._dp(cts), _hp(sc), self._dp(out), level, count, self._stream()),
+                  "he_cmult_batch")
+        return out
+
+    def add_const_batch(self, cts, scalars: Sequence[int], out=None):
+        level, count = self._blevel(cts)
+        sc = np.array([int(v) for v in scalars], dtype=np.uint64)
+        assert sc.shape == (level,)
+        out = self.empty_batch(count, level) if out is None else out
+        self._chk(self.lib.he_add_const_batch(self.ctx, self._dp(cts), _hp(sc), self._dp(out), level, count,
+                                              self._stream()), "he_add_const_batch")
+        return out
+
+    def moddrop_batch(self, cts, level: int, out=None):
+        in_level, count = self._blevel(cts)
+        if level == in_level and out is None:
+            return cts
+        out = self.empty_batch(count, level) if out is None else out
+        self._chk(self.lib.he_moddrop_batch(self.ctx, self._dp(cts), in_level, self._dp(out), level, count,
+                                            self._stream()), "he_moddrop_batch")
+        return out
+
+    def hmult_relin_batch(self, relin: EvalKey, a, b, out=None):
+        level, count = self._blevel(a)
+        assert b.shape == a.shape
+        out = self.empty_batch(count, level) if out is None else out
+        ws, wsb = self._workspace(level, count)
+        self._chk(self.lib.he_hmult_relin_batch(self.ctx, relin.handle, self._dp(a), self._dp(b), self._dp(out), level,
+                                                count, ws, wsb, self._stream()), "he_hmult_relin_batch")
+        return out
+
+    def rescale_batch(self, cts, out=None):
+        level, count = self._blevel(cts)
+        out = self.empty_batch(count, level - 1) if out is None else out
+        ws, wsb = self._workspace(level, count)
+        self._chk(self.lib.he_rescale_batch(self.ctx, self._dp(cts), self._dp(out), level, count, ws, wsb,
+                                            self._stream()), "he_rescale_batch")
+        return out
+
+    def hrot_batch(self, rot: EvalKey, cts, out=None):
+        level, count = self._blevel(cts)
+        out = self.empty_batch(count, level) if out is None else out
+        ws, wsb = self._workspace(level, count)
+        self._chk(self.lib.he_hrot_batch(self.ctx, rot.handle, self._dp(cts), self._dp(out), level, count, ws, wsb,
+                                         self._stream()), "he_hrot_batch")
+        return out
+
+    def rotate_sum_batch(self, rots: Sequence[EvalKey], cts):
+        level, count = self._blevel(cts)
+        n = len(rots)
+        keys = (ctypes.c_void_p * n)(*[k.handle for k in rots])
+        ws, wsb = self._workspace(level, count)
+        self._chk(self.lib.he_rotate_sum_batch(self.ctx, keys, n, self._dp(cts), level, count, ws, wsb, self._stream()),
+                  "he_rotate_sum_batch")
+        return cts
 
     # ---- measurement -------------------------------------------------------------------------------------------------
     def profile_start(self):

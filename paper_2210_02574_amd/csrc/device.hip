@@ -218,7 +218,7 @@ template <class F> static int32_t for_batches(he_ctx *c, const LimbList &l, F la
     return HE_OK;
 }
 
-static ConvArgs conv_args(const he_ctx *c, const u64 *src, int level)
+static ConvArgs conv_args(const he_ctx *c, const u64 *src, int level, int dst_stride = 1 << 30, int src_stride = 0)
 {
     ConvArgs cv;
     cv.src = src;
@@ -226,10 +226,12 @@ static ConvArgs conv_args(const he_ctx *c, const u64 *src, int level)
     cv.L = c->L;
     cv.K = c->K;
     cv.alpha = c->alpha;
+    cv.dst_stride = dst_stride;
+    cv.src_stride = src_stride;
     return cv;
 }
 
-static const FinArgs kNoFin = {nullptr, nullptr, nullptr, nullptr, nullptr, 0, 1, 0, 1u};
+static const FinArgs kNoFin = {nullptr, nullptr, nullptr, nullptr, nullptr, 0, 1, 0, 1u, 1 << 30, 0, 0, 0};
 
 // Forward NTT of the listed limbs of `data`.  pro selects what the column pass transforms (the
 // limb's own content, or a base conversion of cv.src); with fin != nullptr the block pass writes
@@ -361,87 +363,131 @@ static int32_t level_guard(he_ctx *c, int level)
     return HE_OK;
 }
 
+// a, b, out: [count] operations of `limbs` limbs each, strides sa / sb / so limbs between operations
 static int32_t limbwise(he_ctx *c, const u64 *a, const u64 *b, u64 *out, int level, int op, int limbs, int b_limbs,
-                        void *stream)
+                        void *stream, int count = 1, int sa = 0, int sb = 0, int so = 0)
 {
     int32_t rc = level_guard(c, level);
     if (rc != HE_OK) return rc;
-    if (!a || !b || !out) return HE_EINVAL;
-    dim3 grid((unsigned)(c->N / 256), (unsigned)limbs);
-    KLAUNCH(c, (hipStream_t)stream, KID_LIMBWISE, (double)(2 * limbs + b_limbs) * c->N * 8.0, (k_limbwise), grid, a, b, out, c->dev, op, level, b_limbs, c->logN);
+    if (!a || !b || !out || count < 1 || limbs > 65535 || count > 65535) return HE_EINVAL;
+    dim3 grid((unsigned)(c->N / 256), (unsigned)limbs, (unsigned)count);
+    KLAUNCH(c, (hipStream_t)stream, KID_LIMBWISE, (double)count * (2 * limbs + b_limbs) * c->N * 8.0, (k_limbwise), grid, a,
+            b, out, c->dev, op, level, b_limbs, c->logN, sa, sb, so);
     return launch_ok(c);
 }
 
+static bool count_ok(int level, int count) { return count >= 1 && (long)count * 2 * level <= 65535; }
+
+extern "C" int32_t he_add_batch(he_ctx *ctx, const uint64_t *d_a, const uint64_t *d_b, uint64_t *d_out, int32_t level,
+                                int32_t count, void *stream)
+{
+    if (!count_ok(level, count)) return HE_EINVAL;
+    return limbwise(ctx, d_a, d_b, d_out, level, 0, count * 2 * level, count * 2 * level, stream);
+}
+extern "C" int32_t he_sub_batch(he_ctx *ctx, const uint64_t *d_a, const uint64_t *d_b, uint64_t *d_out, int32_t level,
+                                int32_t count, void *stream)
+{
+    if (!count_ok(level, count)) return HE_EINVAL;
+    return limbwise(ctx, d_a, d_b, d_out, level, 1, count * 2 * level, count * 2 * level, stream);
+}
+extern "C" int32_t he_pmult_batch(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *d_pt, uint64_t *d_out,
+                                  int32_t level, int32_t count, void *stream)
+{
+    if (!count_ok(level, count)) return HE_EINVAL;
+    return limbwise(ctx, d_ct, d_pt, d_out, level, 2, count * 2 * level, level, stream);
+}
 extern "C" int32_t he_add(he_ctx *ctx, const uint64_t *d_a, const uint64_t *d_b, uint64_t *d_out, int32_t level,
                           void *stream)
 {
-    return limbwise(ctx, d_a, d_b, d_out, level, 0, 2 * level, 2 * level, stream);
+    return he_add_batch(ctx, d_a, d_b, d_out, level, 1, stream);
 }
 extern "C" int32_t he_sub(he_ctx *ctx, const uint64_t *d_a, const uint64_t *d_b, uint64_t *d_out, int32_t level,
                           void *stream)
 {
-    return limbwise(ctx, d_a, d_b, d_out, level, 1, 2 * level, 2 * level, stream);
+    return he_sub_batch(ctx, d_a, d_b, d_out, level, 1, stream);
 }
 extern "C" int32_t he_pmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *d_pt, uint64_t *d_out, int32_t level,
                             void *stream)
 {
-    return limbwise(ctx, d_ct, d_pt, d_out, level, 2, 2 * level, level, stream);
+    return he_pmult_batch(ctx, d_ct, d_pt, d_out, level, 1, stream);
 }
 
-extern "C" int32_t he_cmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out, int32_t level,
-                            void *stream)
+static int32_t scalar_args(he_ctx *ctx, const uint64_t *h_scalar, int level, bool with_companion, ScalarArgs &sc)
 {
-    int32_t rc = level_guard(ctx, level);
-    if (rc != HE_OK) return rc;
-    if (!d_ct || !h_scalar || !d_out) return HE_EINVAL;
-    ScalarArgs sc;
     memset(&sc, 0, sizeof(sc));
     for (int i = 0; i < level; i++) {
         if (h_scalar[i] >= ctx->mod[i]) return HE_EINVAL;
-        sc.s[i] = hostmath::shoup(h_scalar[i], ctx->mod[i]);
-    }
-    dim3 grid((unsigned)(ctx->N / 256), (unsigned)(2 * level));
-    KLAUNCH(ctx, (hipStream_t)stream, KID_CMULT, 4.0 * level * ctx->N * 8.0, (k_cmult), grid, d_ct, d_out, ctx->dev, sc, level, ctx->logN);
-    return launch_ok(ctx);
-}
-
-extern "C" int32_t he_add_const(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out,
-                                int32_t level, void *stream)
-{
-    int32_t rc = level_guard(ctx, level);
-    if (rc != HE_OK) return rc;
-    if (!d_ct || !h_scalar || !d_out) return HE_EINVAL;
-    ScalarArgs sc;
-    memset(&sc, 0, sizeof(sc));
-    for (int i = 0; i < level; i++) {
-        if (h_scalar[i] >= ctx->mod[i]) return HE_EINVAL;
-        sc.s[i].w = h_scalar[i];
-    }
-    dim3 grid((unsigned)(ctx->N / 256), (unsigned)(2 * level));
-    KLAUNCH(ctx, (hipStream_t)stream, KID_LIMBWISE, 4.0 * level * ctx->N * 8.0, (k_addconst), grid, d_ct, d_out, ctx->dev, sc, level, ctx->logN);
-    return launch_ok(ctx);
-}
-
-extern "C" int32_t he_moddrop(he_ctx *ctx, const uint64_t *d_ct, int32_t in_level, uint64_t *d_out, int32_t out_level,
-                              void *stream)
-{
-    int32_t rc = level_guard(ctx, in_level);
-    if (rc != HE_OK) return rc;
-    if (out_level < 1 || out_level > in_level) return HE_ELEVEL;
-    if (!d_ct || !d_out || d_ct == d_out) return HE_EINVAL;
-    const size_t N = ctx->N;
-    for (int c = 0; c < 2; c++) {
-        hipError_t e = hipMemcpyAsync(d_out + (size_t)c * out_level * N, d_ct + (size_t)c * in_level * N,
-                                      (size_t)out_level * N * sizeof(u64), hipMemcpyDeviceToDevice, (hipStream_t)stream);
-        if (e != hipSuccess) {
-            ctx->hip_err = std::string("hipMemcpyAsync: ") + hipGetErrorString(e);
-            return HE_EHIP;
-        }
+        if (with_companion)
+            sc.s[i] = hostmath::shoup(h_scalar[i], ctx->mod[i]);
+        else
+            sc.s[i].w = h_scalar[i];
     }
     return HE_OK;
 }
 
-// ---- workspace layout (in limbs of N words)
+extern "C" int32_t he_cmult_batch(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out,
+                                  int32_t level, int32_t count, void *stream)
+{
+    int32_t rc = level_guard(ctx, level);
+    if (rc != HE_OK) return rc;
+    if (!d_ct || !h_scalar || !d_out || !count_ok(level, count)) return HE_EINVAL;
+    ScalarArgs sc;
+    if ((rc = scalar_args(ctx, h_scalar, level, true, sc)) != HE_OK) return rc;
+    dim3 grid((unsigned)(ctx->N / 256), (unsigned)(count * 2 * level));
+    KLAUNCH(ctx, (hipStream_t)stream, KID_CMULT, 4.0 * count * level * ctx->N * 8.0, (k_cmult), grid, d_ct, d_out, ctx->dev,
+            sc, level, ctx->logN);
+    return launch_ok(ctx);
+}
+extern "C" int32_t he_cmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out, int32_t level,
+                            void *stream)
+{
+    return he_cmult_batch(ctx, d_ct, h_scalar, d_out, level, 1, stream);
+}
+
+extern "C" int32_t he_add_const_batch(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out,
+                                      int32_t level, int32_t count, void *stream)
+{
+    int32_t rc = level_guard(ctx, level);
+    if (rc != HE_OK) return rc;
+    if (!d_ct || !h_scalar || !d_out || !count_ok(level, count)) return HE_EINVAL;
+    ScalarArgs sc;
+    if ((rc = scalar_args(ctx, h_scalar, level, false, sc)) != HE_OK) return rc;
+    dim3 grid((unsigned)(ctx->N / 256), (unsigned)(count * 2 * level));
+    KLAUNCH(ctx, (hipStream_t)stream, KID_LIMBWISE, 4.0 * count * level * ctx->N * 8.0, (k_addconst), grid, d_ct, d_out,
+            ctx->dev, sc, level, ctx->logN);
+    return launch_ok(ctx);
+}
+extern "C" int32_t he_add_const(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out,
+                                int32_t level, void *stream)
+{
+    return he_add_const_batch(ctx, d_ct, h_scalar, d_out, level, 1, stream);
+}
+
+extern "C" int32_t he_moddrop_batch(he_ctx *ctx, const uint64_t *d_ct, int32_t in_level, uint64_t *d_out,
+                                    int32_t out_level, int32_t count, void *stream)
+{
+    int32_t rc = level_guard(ctx, in_level);
+    if (rc != HE_OK) return rc;
+    if (out_level < 1 || out_level > in_level) return HE_ELEVEL;
+    if (!d_ct || !d_out || d_ct == d_out || count < 1) return HE_EINVAL;
+    const size_t N = ctx->N;
+    // one row per (operation, component): the first out_level limbs of in_level
+    hipError_t e = hipMemcpy2DAsync(d_out, (size_t)out_level * N * sizeof(u64), d_ct, (size_t)in_level * N * sizeof(u64),
+                                    (size_t)out_level * N * sizeof(u64), (size_t)count * 2, hipMemcpyDeviceToDevice,
+                                    (hipStream_t)stream);
+    if (e != hipSuccess) {
+        ctx->hip_err = std::string("hipMemcpy2DAsync: ") + hipGetErrorString(e);
+        return HE_EHIP;
+    }
+    return HE_OK;
+}
+extern "C" int32_t he_moddrop(he_ctx *ctx, const uint64_t *d_ct, int32_t in_level, uint64_t *d_out, int32_t out_level,
+                              void *stream)
+{
+    return he_moddrop_batch(ctx, d_ct, in_level, d_out, out_level, 1, stream);
+}
+
+// ---- workspace layout (in limbs of N words), per operation of a batch
 struct WsLayout {
     size_t x, d, raised, u, r, tmp, total;
 };
@@ -460,56 +506,67 @@ static WsLayout ws_layout(const he_ctx *c, int level)
     return w;
 }
 
-extern "C" int32_t he_workspace_bytes(const he_ctx *ctx, int32_t level, int32_t max_hoist, size_t *out)
+extern "C" int32_t he_workspace_bytes(const he_ctx *ctx, int32_t level, int32_t count, size_t *out)
 {
-    if (!ctx || !out || max_hoist < 1) return HE_EINVAL;
+    if (!ctx || !out || count < 1) return HE_EINVAL;
     if (level < 1 || level > ctx->L) return HE_ELEVEL;
-    *out = ws_layout(ctx, level).total * ctx->N * sizeof(u64);
+    *out = ws_layout(ctx, level).total * (size_t)count * ctx->N * sizeof(u64);
     return HE_OK;
 }
 
-// Steps 1-2 of the key switch.  d_ntt: the polynomial in the NTT domain (level limbs).
-static int32_t ks_raise(he_ctx *c, const u64 *d_ntt, u64 *ws, const WsLayout &w, int level, hipStream_t st)
+// limb slots are 16-bit offsets from a buffer's base
+static bool batch_fits(const WsLayout &w, int count) { return count >= 1 && w.total * (size_t)count <= 65535; }
+
+// Steps 1-2 of the key switch for `count` polynomials: operation o reads its NTT-domain input at
+// d_ntt + o*d_stride limbs and works in ws + o*w.total limbs.
+static int32_t ks_raise(he_ctx *c, const u64 *d_ntt, int d_stride, u64 *ws, const WsLayout &w, int level, int count,
+                        hipStream_t st)
 {
     const size_t N = c->N;
-    const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha;
+    const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha, W = (int)w.total;
     LimbList l;
-    for (int i = 0; i < level; i++) l.add(i, i);
-    const ConvArgs cv = conv_args(c, ws + w.x * N, level);
+    for (int o = 0; o < count; o++)
+        for (int i = 0; i < level; i++) l.add(o * W + i, o * d_stride + i, i);
+    const ConvArgs cv = conv_args(c, ws + w.x * N, level, W, W);
     int32_t rc = ntt_inverse(c, st, d_ntt, ws + w.x * N, l, SCALE_MODUP, cv);
     if (rc != HE_OK) return rc;
     LimbList r;
-    for (int j = 0; j < beta; j++) {
-        const int lo = j * c->alpha, hi = std::min(lo + c->alpha, level);
-        for (int a = 0; a < Ma; a++) {
-            if (a >= lo && a < hi) continue;
-            r.add(j * Ma + a, a < level ? a : c->L + (a - level));
+    for (int o = 0; o < count; o++)
+        for (int j = 0; j < beta; j++) {
+            const int lo = j * c->alpha, hi = std::min(lo + c->alpha, level);
+            for (int a = 0; a < Ma; a++) {
+                if (a >= lo && a < hi) continue;
+                r.add(o * W + j * Ma + a, a < level ? a : c->L + (a - level));
+            }
         }
-    }
-    return ntt_forward(c, st, ws + w.raised * N, r, PRO_MODUP, cv, nullptr, level);
+    return ntt_forward(c, st, ws + w.raised * N, r, PRO_MODUP, cv, nullptr, level * count);
 }
 
-// Steps 3-5.  mode / c0: the addend of the final step (see FinArgs).
-static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, u64 *ws, const WsLayout &w, int level, u64 *out,
-                        const u64 *c0, int mode, hipStream_t st)
+// Steps 3-5.  Operation o writes out + o*out_stride limbs; mode / c0 (+ o*c0_stride): the addend of
+// the final step (see FinArgs).
+static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_stride, u64 *ws, const WsLayout &w,
+                        int level, int count, u64 *out, int out_stride, const u64 *c0, int c0_stride, int mode,
+                        hipStream_t st)
 {
     const size_t N = c->N;
-    const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha;
+    const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha, W = (int)w.total;
     const unsigned g = (unsigned)evk->galois;
-    dim3 grid((unsigned)(N / 256), (unsigned)Ma);
+    dim3 grid((unsigned)(N / 256), (unsigned)Ma, (unsigned)count);
     // reads beta digits and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
-    KLAUNCH(c, st, KID_INNER, (double)(3 * beta + 2) * Ma * N * 8.0, (k_inner), grid, ws + w.raised * N, d_ntt, evk->dev, ws + w.u * N, c->dev, level, c->L, K,
-                                          c->alpha, beta, g, c->logN);
+    KLAUNCH(c, st, KID_INNER, (double)count * (3 * beta + 2) * Ma * N * 8.0, (k_inner), grid, ws + w.raised * N, d_ntt,
+            evk->dev, ws + w.u * N, c->dev, level, c->L, K, c->alpha, beta, g, c->logN, W, d_stride);
     int32_t rc = launch_ok(c);
     if (rc != HE_OK) return rc;
     LimbList sp;
-    for (int cc = 0; cc < 2; cc++)
-        for (int k = 0; k < K; k++) sp.add(cc * Ma + level + k, c->L + k);
-    const ConvArgs cv = conv_args(c, ws + w.u * N, level);
+    for (int o = 0; o < count; o++)
+        for (int cc = 0; cc < 2; cc++)
+            for (int k = 0; k < K; k++) sp.add(o * W + cc * Ma + level + k, c->L + k);
+    const ConvArgs cv = conv_args(c, ws + w.u * N, level, W, W);
     if ((rc = ntt_inverse(c, st, ws + w.u * N, ws + w.u * N, sp, SCALE_MODDOWN, cv)) != HE_OK) return rc;
     LimbList r;
-    for (int cc = 0; cc < 2; cc++)
-        for (int i = 0; i < level; i++) r.add(cc * level + i, i);
+    for (int o = 0; o < count; o++)
+        for (int cc = 0; cc < 2; cc++)
+            for (int i = 0; i < level; i++) r.add(o * W + cc * level + i, i);
     FinArgs fa;
     fa.u = ws + w.u * N;
     fa.out = out;
@@ -520,23 +577,30 @@ static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, u64 *ws,
     fa.nl = level;
     fa.mode = mode;
     fa.g = g;
-    return ntt_forward(c, st, ws + w.r * N, r, PRO_MODDOWN, cv, &fa, 2 * K);
+    fa.dst_stride = W;
+    fa.u_stride = W;
+    fa.out_stride = out_stride;
+    fa.add_stride = c0_stride;
+    return ntt_forward(c, st, ws + w.r * N, r, PRO_MODDOWN, cv, &fa, 2 * K * count);
 }
 
-static int32_t ks_guard(he_ctx *c, const he_evk *evk, int level, void *ws, size_t ws_bytes)
+static int32_t ks_guard(he_ctx *c, const he_evk *evk, int level, int count, void *ws, size_t ws_bytes)
 {
     int32_t rc = level_guard(c, level);
     if (rc != HE_OK) return rc;
     if (!evk || evk->ctx != c || !evk->dev) return HE_ENOKEY;
     if (!ws) return HE_EINVAL;
-    if (ws_bytes < ws_layout(c, level).total * c->N * sizeof(u64)) return HE_EWORKSPACE;
+    const WsLayout w = ws_layout(c, level);
+    if (!batch_fits(w, count)) return HE_EINVAL;
+    if (ws_bytes < w.total * (size_t)count * c->N * sizeof(u64)) return HE_EWORKSPACE;
     return HE_OK;
 }
 
-extern "C" int32_t he_hmult_relin(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a, const uint64_t *d_b,
-                                  uint64_t *d_out, int32_t level, void *d_ws, size_t ws_bytes, void *stream)
+extern "C" int32_t he_hmult_relin_batch(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a, const uint64_t *d_b,
+                                        uint64_t *d_out, int32_t level, int32_t count, void *d_ws, size_t ws_bytes,
+                                        void *stream)
 {
-    int32_t rc = ks_guard(ctx, relin, level, d_ws, ws_bytes);
+    int32_t rc = ks_guard(ctx, relin, level, count, d_ws, ws_bytes);
     if (rc != HE_OK) return rc;
     if (relin->galois != 1) return HE_ENOKEY;
     if (!d_a || !d_b || !d_out) return HE_EINVAL;
@@ -544,11 +608,19 @@ extern "C" int32_t he_hmult_relin(he_ctx *ctx, const he_evk *relin, const uint64
     u64 *ws = (u64 *)d_ws;
     const WsLayout w = ws_layout(ctx, level);
     const size_t N = ctx->N;
-    dim3 grid((unsigned)(N / 256), (unsigned)level);
-    KLAUNCH(ctx, st, KID_TENSOR, 7.0 * level * N * 8.0, (k_tensor), grid, d_a, d_b, d_out, ws + w.d * N, ctx->dev, level, ctx->logN);
+    const int W = (int)w.total;
+    dim3 grid((unsigned)(N / 256), (unsigned)level, (unsigned)count);
+    KLAUNCH(ctx, st, KID_TENSOR, 7.0 * count * level * N * 8.0, (k_tensor), grid, d_a, d_b, d_out, ws + w.d * N, ctx->dev,
+            level, ctx->logN, W);
     if ((rc = launch_ok(ctx)) != HE_OK) return rc;
-    if ((rc = ks_raise(ctx, ws + w.d * N, ws, w, level, st)) != HE_OK) return rc;
-    return ks_apply(ctx, relin, ws + w.d * N, ws, w, level, d_out, nullptr, 1, st);
+    if ((rc = ks_raise(ctx, ws + w.d * N, W, ws, w, level, count, st)) != HE_OK) return rc;
+    return ks_apply(ctx, relin, ws + w.d * N, W, ws, w, level, count, d_out, 2 * level, nullptr, 0, 1, st);
+}
+
+extern "C" int32_t he_hmult_relin(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a, const uint64_t *d_b,
+                                  uint64_t *d_out, int32_t level, void *d_ws, size_t ws_bytes, void *stream)
+{
+    return he_hmult_relin_batch(ctx, relin, d_a, d_b, d_out, level, 1, d_ws, ws_bytes, stream);
 }
 
 extern "C" int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t count, const uint64_t *d_ct,
@@ -557,7 +629,7 @@ extern "C" int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t 
     if (!rots || count < 1 || !h_d_outs) return HE_EINVAL;
     int32_t rc;
     for (int r = 0; r < count; r++) {
-        if ((rc = ks_guard(ctx, rots[r], level, d_ws, ws_bytes)) != HE_OK) return rc;
+        if ((rc = ks_guard(ctx, rots[r], level, 1, d_ws, ws_bytes)) != HE_OK) return rc;
         if (rots[r]->galois == 1) return HE_ENOKEY;
         if (!h_d_outs[r] || h_d_outs[r] == d_ct) return HE_EINVAL;
     }
@@ -566,58 +638,92 @@ extern "C" int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t 
     u64 *ws = (u64 *)d_ws;
     const WsLayout w = ws_layout(ctx, level);
     const u64 *c1 = d_ct + (size_t)level * ctx->N;
-    if ((rc = ks_raise(ctx, c1, ws, w, level, st)) != HE_OK) return rc;
+    if ((rc = ks_raise(ctx, c1, 0, ws, w, level, 1, st)) != HE_OK) return rc;
     for (int r = 0; r < count; r++)
-        if ((rc = ks_apply(ctx, rots[r], c1, ws, w, level, h_d_outs[r], d_ct, 2, st)) != HE_OK) return rc;
+        if ((rc = ks_apply(ctx, rots[r], c1, 0, ws, w, level, 1, h_d_outs[r], 0, d_ct, 0, 2, st)) != HE_OK) return rc;
     return HE_OK;
+}
+
+// out: operation o at d_out + o*out_stride limbs
+static int32_t hrot_batch_to(he_ctx *ctx, const he_evk *rot, const u64 *d_ct, u64 *d_out, int out_stride, int level,
+                             int count, void *d_ws, size_t ws_bytes, hipStream_t st)
+{
+    int32_t rc = ks_guard(ctx, rot, level, count, d_ws, ws_bytes);
+    if (rc != HE_OK) return rc;
+    if (rot->galois == 1) return HE_ENOKEY;
+    if (!d_ct || !d_out || d_ct == d_out) return HE_EINVAL;
+    u64 *ws = (u64 *)d_ws;
+    const WsLayout w = ws_layout(ctx, level);
+    const u64 *c1 = d_ct + (size_t)level * ctx->N;
+    if ((rc = ks_raise(ctx, c1, 2 * level, ws, w, level, count, st)) != HE_OK) return rc;
+    return ks_apply(ctx, rot, c1, 2 * level, ws, w, level, count, d_out, out_stride, d_ct, 2 * level, 2, st);
+}
+
+extern "C" int32_t he_hrot_batch(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level,
+                                 int32_t count, void *d_ws, size_t ws_bytes, void *stream)
+{
+    return hrot_batch_to(ctx, rot, d_ct, d_out, 2 * level, level, count, d_ws, ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int32_t he_hrot(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level,
                            void *d_ws, size_t ws_bytes, void *stream)
 {
-    uint64_t *outs[1] = {d_out};
-    const he_evk *keys[1] = {rot};
-    return he_hrot_many(ctx, keys, 1, d_ct, outs, level, d_ws, ws_bytes, stream);
+    return he_hrot_batch(ctx, rot, d_ct, d_out, level, 1, d_ws, ws_bytes, stream);
+}
+
+extern "C" int32_t he_rotate_sum_batch(he_ctx *ctx, const he_evk *const *rots, int32_t n_rot, uint64_t *d_ct,
+                                       int32_t level, int32_t count, void *d_ws, size_t ws_bytes, void *stream)
+{
+    if (!rots || n_rot < 0) return HE_EINVAL;
+    int32_t rc = level_guard(ctx, level);
+    if (rc != HE_OK) return rc;
+    if (!d_ws || !d_ct) return HE_EINVAL;
+    const WsLayout w = ws_layout(ctx, level);
+    if (!batch_fits(w, count)) return HE_EINVAL;
+    if (ws_bytes < w.total * (size_t)count * ctx->N * sizeof(u64)) return HE_EWORKSPACE;
+    u64 *tmp = (u64 *)d_ws + w.tmp * ctx->N; // operation o's rotated ciphertext at tmp + o*w.total limbs
+    for (int k = 0; k < n_rot; k++) {
+        if ((rc = hrot_batch_to(ctx, rots[k], d_ct, tmp, (int)w.total, level, count, d_ws, ws_bytes, (hipStream_t)stream)) !=
+            HE_OK)
+            return rc;
+        if ((rc = limbwise(ctx, d_ct, tmp, d_ct, level, 0, 2 * level, 2 * level, stream, count, 2 * level, (int)w.total,
+                           2 * level)) != HE_OK)
+            return rc;
+    }
+    return HE_OK;
 }
 
 extern "C" int32_t he_rotate_sum(he_ctx *ctx, const he_evk *const *rots, int32_t count, uint64_t *d_ct, int32_t level,
                                  void *d_ws, size_t ws_bytes, void *stream)
 {
-    if (!rots || count < 0) return HE_EINVAL;
-    int32_t rc = level_guard(ctx, level);
-    if (rc != HE_OK) return rc;
-    if (!d_ws || !d_ct) return HE_EINVAL;
-    const WsLayout w = ws_layout(ctx, level);
-    if (ws_bytes < w.total * ctx->N * sizeof(u64)) return HE_EWORKSPACE;
-    u64 *tmp = (u64 *)d_ws + w.tmp * ctx->N;
-    for (int k = 0; k < count; k++) {
-        if ((rc = he_hrot(ctx, rots[k], d_ct, tmp, level, d_ws, ws_bytes, stream)) != HE_OK) return rc;
-        if ((rc = he_add(ctx, d_ct, tmp, d_ct, level, stream)) != HE_OK) return rc;
-    }
-    return HE_OK;
+    return he_rotate_sum_batch(ctx, rots, count, d_ct, level, 1, d_ws, ws_bytes, stream);
 }
 
-extern "C" int32_t he_rescale(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level, void *d_ws,
-                              size_t ws_bytes, void *stream)
+extern "C" int32_t he_rescale_batch(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level, int32_t count,
+                                    void *d_ws, size_t ws_bytes, void *stream)
 {
     int32_t rc = level_guard(ctx, level);
     if (rc != HE_OK) return rc;
     if (level < 2) return HE_ELEVEL;
     if (!d_ct || !d_out || !d_ws || d_ct == d_out) return HE_EINVAL;
     const WsLayout w = ws_layout(ctx, level);
-    if (ws_bytes < w.total * ctx->N * sizeof(u64)) return HE_EWORKSPACE;
+    if (!batch_fits(w, count)) return HE_EINVAL;
+    if (ws_bytes < w.total * (size_t)count * ctx->N * sizeof(u64)) return HE_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     u64 *ws = (u64 *)d_ws;
     const size_t N = ctx->N;
-    u64 *t = ws + w.x * N; // two limbs: the dropped limb of each component, coefficient domain
-    u64 *r = ws + w.r * N; // [2][level-1][N]
+    const int W = (int)w.total;
+    u64 *t = ws + w.x * N; // per operation two limbs: the dropped limb of each component, coefficient domain
+    u64 *r = ws + w.r * N; // per operation [2][level-1][N]
     LimbList last;
-    for (int c = 0; c < 2; c++) last.add(c, c * level + level - 1, level - 1);
-    const ConvArgs cv = conv_args(ctx, t, level);
+    for (int o = 0; o < count; o++)
+        for (int c = 0; c < 2; c++) last.add(o * W + c, o * 2 * level + c * level + level - 1, level - 1);
+    const ConvArgs cv = conv_args(ctx, t, level, W, W);
     if ((rc = ntt_inverse(ctx, st, d_ct, t, last, SCALE_NONE, cv)) != HE_OK) return rc;
     LimbList l;
-    for (int c = 0; c < 2; c++)
-        for (int i = 0; i < level - 1; i++) l.add(c * (level - 1) + i, i);
+    for (int o = 0; o < count; o++)
+        for (int c = 0; c < 2; c++)
+            for (int i = 0; i < level - 1; i++) l.add(o * W + c * (level - 1) + i, i);
     FinArgs fa;
     fa.u = d_ct;
     fa.out = d_out;
@@ -628,5 +734,15 @@ extern "C" int32_t he_rescale(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out
     fa.nl = level - 1;
     fa.mode = 0;
     fa.g = 1;
-    return ntt_forward(ctx, st, r, l, PRO_RESCALE, cv, &fa, 2);
+    fa.dst_stride = W;
+    fa.u_stride = 2 * level;
+    fa.out_stride = 2 * (level - 1);
+    fa.add_stride = 0;
+    return ntt_forward(ctx, st, r, l, PRO_RESCALE, cv, &fa, 2 * count);
+}
+
+extern "C" int32_t he_rescale(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level, void *d_ws,
+                              size_t ws_bytes, void *stream)
+{
+    return he_rescale_batch(ctx, d_ct, d_out, level, 1, d_ws, ws_bytes, stream);
 }

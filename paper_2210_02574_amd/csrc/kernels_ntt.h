@@ -32,9 +32,13 @@ enum { PRO_LOAD = 0, PRO_MODUP = 1, PRO_MODDOWN = 2, PRO_RESCALE = 3 };
 enum { SCALE_NONE = 0, SCALE_MODUP = 1, SCALE_MODDOWN = 2 };
 enum { EPI_STORE = 0, EPI_FIN = 1 };
 
+// Batches: `count` independent ciphertexts are laid out with fixed strides (in limbs); a limb's slot
+// is op * stride + local index, so op = slot / stride and the local index keeps its single-op meaning.
 struct ConvArgs {
     const u64 *src; // ModUp: y limbs [level][N]; ModDown: u [2][level+K][N]; rescale: t [2][N]
     int level, L, K, alpha;
+    int dst_stride; // limbs between two operations in the buffer being transformed
+    int src_stride; // limbs between two operations in src
 };
 
 struct FinArgs {
@@ -45,6 +49,7 @@ struct FinArgs {
     const double *cst_d;
     int u_cstride, nl, mode; // mode 0: no addend; 1: add what `out` holds; 2: add sigma_g(c0) to component 0
     unsigned g;
+    int dst_stride, u_stride, out_stride, add_stride; // limbs between two operations in each buffer
 };
 
 __device__ __forceinline__ int active_mod(int a, int level, int L) { return a < level ? a : L + (a - level); }
@@ -83,9 +88,12 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
     S.pm_i = 0;
     S.pm_d = 0.0;
     const int M = cv.L + cv.K, Ma = cv.level + cv.K;
+    const unsigned op = slot / (unsigned)cv.dst_stride;
+    slot -= op * (unsigned)cv.dst_stride;
+    const u64 *src = cv.src + (((size_t)op * cv.src_stride) << LOGN);
 #pragma unroll
     for (int s = 0; s < NSMAX; s++) {
-        S.sp[s] = cv.src;
+        S.sp[s] = src;
         S.ci[s] = 0;
         S.cd[s] = S.cdh[s] = 0.0;
         S.hs[s] = ~(u64)0;
@@ -99,7 +107,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
         for (int s = 0; s < NSMAX; s++) {
             const bool on = s < ns;
             const size_t ci = (cs + (on ? s : 0)) * M + mi;
-            S.sp[s] = cv.src + ((size_t)(lo + (on ? s : 0)) << LOGN);
+            S.sp[s] = src + ((size_t)(lo + (on ? s : 0)) << LOGN);
             S.ci[s] = on ? T.up_hat[ci] : 0;
             S.cd[s] = on ? T.up_hat_d[ci] : 0.0;
             S.cdh[s] = on ? T.up_hat_dh[ci] : 0.0;
@@ -110,7 +118,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
         for (int s = 0; s < NSMAX; s++) {
             const bool on = s < cv.K;
             const size_t ci = (size_t)(on ? s : 0) * cv.L + i;
-            S.sp[s] = cv.src + (((size_t)c * Ma + cv.level + (on ? s : 0)) << LOGN);
+            S.sp[s] = src + (((size_t)c * Ma + cv.level + (on ? s : 0)) << LOGN);
             S.ci[s] = on ? T.dn_hat[ci] : 0;
             S.cd[s] = on ? T.dn_hat_d[ci] : 0.0;
             S.cdh[s] = on ? T.dn_hat_dh[ci] : 0.0;
@@ -120,7 +128,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
         S.pm_d = T.dn_pmod_d[i];
     } else if (PRO == PRO_RESCALE) {
         const int c = slot / (cv.level - 1);
-        S.sp[0] = cv.src + ((size_t)c << LOGN);
+        S.sp[0] = src + ((size_t)c << LOGN);
         S.ql = T.mod[cv.level - 1].q;
         S.half = (S.ql - 1) / 2;
         S.qld = T.mod[cv.level - 1].qd;
@@ -186,15 +194,17 @@ __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithIn
 template <int LOGN>
 __device__ __forceinline__ void fin_store(const FinArgs &fa, const DevTables &T, unsigned slot, unsigned pos, u64 rv)
 {
+    const unsigned op = slot / (unsigned)fa.dst_stride;
+    slot -= op * (unsigned)fa.dst_stride;
     const unsigned c = slot / fa.nl, i = slot % fa.nl;
     const ModConst m = T.mod[i];
-    const size_t o = ((size_t)slot << LOGN) + pos;
-    const u64 uv = fa.u[(((size_t)c * fa.u_cstride + i) << LOGN) + pos];
+    const size_t o = (((size_t)op * fa.out_stride + slot) << LOGN) + pos;
+    const u64 uv = fa.u[(((size_t)op * fa.u_stride + (size_t)c * fa.u_cstride + i) << LOGN) + pos];
     u64 av = 0;
     if (fa.mode == 1)
         av = fa.out[o];
     else if (fa.mode == 2 && c == 0)
-        av = fa.add[((size_t)i << LOGN) + galois_index(pos, fa.g, LOGN)];
+        av = fa.add[(((size_t)op * fa.add_stride + i) << LOGN) + galois_index(pos, fa.g, LOGN)];
     u64 res;
     if (m.qd != 0.0)
         res = fp_canon(fp_mulmod(u2d(uv) - u2d(rv), fa.cst_d[i], m.qd, m.qinvd) + u2d(av), m.qd, m.qinvd);

@@ -206,3 +206,40 @@ def test_error_codes_on_device_context(env):
                         1, ctypes.c_void_p(a.data_ptr()), 16, None)
     assert rc == -4  # workspace too small
     _sync()
+
+
+def test_batched_calls_equal_single_calls(env):
+    """Every batched entry point on [count][2][level][N] gives, ciphertext by ciphertext, the bits of the
+    single-ciphertext call (which the other tests compare with the oracle)."""
+    import torch
+
+    he, o, p = env.he, env.o, env.params
+    level = 3 if p.logN == 12 else 23  # partial last digit at N = 2^16
+    count = 5
+    relin, _ = env.synth_key(301, 1)
+    rkeys = [env.synth_key(700 + r, o.galois_element(r))[0] for r in (4, 8)]
+    a = torch.stack([he.to_device(wl.uniform_ct(1100 + i, p, level)) for i in range(count)])
+    b = torch.stack([he.to_device(wl.uniform_ct(1200 + i, p, level)) for i in range(count)])
+    pt = he.to_device(wl.uniform_limbs(1300, p, list(range(level))))
+    sc = [int(v) for v in wl.uniform_limbs(1301, p, list(range(level)))[:, 0]]
+
+    def same(batched, single):
+        for i in range(count):
+            assert torch.equal(batched[i], single(i)), i
+
+    same(he.add_batch(a, b), lambda i: he.add(a[i], b[i]))
+    same(he.sub_batch(a, b), lambda i: he.sub(a[i], b[i]))
+    same(he.pmult_batch(a, pt), lambda i: he.pmult(a[i], pt))
+    same(he.cmult_batch(a, sc), lambda i: he.cmult(a[i], sc))
+    same(he.add_const_batch(a, sc), lambda i: he.add_const(a[i], sc))
+    if level > 1:
+        same(he.moddrop_batch(a, level - 1), lambda i: he.moddrop(a[i], level - 1))
+        same(he.rescale_batch(a), lambda i: he.rescale(a[i]))
+    same(he.hmult_relin_batch(relin, a, b), lambda i: he.hmult_relin(relin, a[i], b[i]))
+    same(he.hrot_batch(rkeys[0], a), lambda i: he.hrot(rkeys[0], a[i]))
+    rs = he.rotate_sum_batch(rkeys, a.clone())
+    same(rs, lambda i: he.rotate_sum(rkeys, a[i].clone()))
+    # in place
+    c = a.clone()
+    he.hmult_relin_batch(relin, c, b, out=c)
+    same(c, lambda i: he.hmult_relin(relin, a[i], b[i]))
