@@ -54,7 +54,7 @@ class Workload:
     N_SINGLE = 128
 
     def __init__(self, he, seed: int = 2, n_hmult: int = None, n_single: int = None, n_ntt: int = None,
-                 n_streams: int = 1):
+                 n_streams: int = 1, hm_chunk: int = 16):
         import torch
 
         self.torch = torch
@@ -72,10 +72,12 @@ class Workload:
         self.ntt_mods = [b % M for b in range(self.n_ntt)]
         self.ntt_limbs = self._uniform(self.ntt_mods)
         L = p.L
-        self.hm_a = [self._uniform_ct(L) for _ in range(self.n_hmult)]
-        self.hm_b = [self._uniform_ct(L) for _ in range(self.n_hmult)]
-        self.hm_out = [he.empty_ct(L) for _ in range(self.n_hmult)]
-        self.rs_out = [he.empty_ct(L - 1) for _ in range(self.n_hmult)]
+        # the independent HMult operands, stored back to back so that one batched call covers them
+        self.hm_a = torch.stack([self._uniform_ct(L) for _ in range(self.n_hmult)])
+        self.hm_b = torch.stack([self._uniform_ct(L) for _ in range(self.n_hmult)])
+        self.hm_out = he.empty_batch(self.n_hmult, L)
+        self.rs_out = he.empty_batch(self.n_hmult, L - 1)
+        self.hm_chunk = hm_chunk
         # keys: uniform residues in key layout (throughput does not depend on the values)
         self.key_host = {}
         self.relin = self._key(1000, 1)
@@ -118,16 +120,15 @@ class Workload:
         he.ntt(self.ntt_limbs, self.ntt_mods)
         he.intt(self.ntt_limbs, self.ntt_mods)
         mark("ntt_pairs")
-        self._spread(self.n_hmult, self._hmult_one)
+        for lo in range(0, self.n_hmult, self.hm_chunk):  # batched calls of hm_chunk ciphertext pairs
+            hi = min(lo + self.hm_chunk, self.n_hmult)
+            he.hmult_relin_batch(self.relin, self.hm_a[lo:hi], self.hm_b[lo:hi], out=self.hm_out[lo:hi])
+            he.rescale_batch(self.hm_out[lo:hi], out=self.rs_out[lo:hi])
         mark("hmult_relin_rescale")
         he.hrot_many(self.rot, self.hoist_in, outs=self.hoist_out)
         mark("hrot_hoisted")
         self._spread(self.n_single, self._single_one)
         mark("hrot_single")
-
-    def _hmult_one(self, i):
-        self.he.hmult_relin(self.relin, self.hm_a[i], self.hm_b[i], out=self.hm_out[i])
-        self.he.rescale(self.hm_out[i], out=self.rs_out[i])
 
     def _single_one(self, i):
         self.he.hrot(self.rot[self.single_keys[i]], self.single_in[i], out=self.single_out[i])
@@ -169,10 +170,13 @@ def train_step_ms(he, w: "Workload") -> float:
     W = [w._uniform_ct(plan.level) for _ in range(4)]
     Y = [[w._uniform_ct(plan.label_level) for _ in range(32)] for _ in range(4)]
     mask = w._uniform(list(range(plan.level - 1)))
-    step.run(w.relin, rot, mask, X[:1], W[:1], [Y[0][:1]])  # warm-up slice
+    Xb = torch.stack(X)
+    Yb = [torch.stack(y) for y in Y]
+    del X, Y
+    step.run_batched(w.relin, rot, mask, Xb, W[:1], Yb[:1])  # warm-up: one class
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    step.run(w.relin, rot, mask, X, W, Y)
+    step.run_batched(w.relin, rot, mask, Xb, W, Yb)
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3
 
@@ -223,6 +227,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-train-step", action="store_true")
+    ap.add_argument("--hmult-batch", type=int, default=16, help="ciphertext pairs per batched HMult call")
     ap.add_argument("--streams", type=int, default=2, help="HIP streams for the independent operations of a step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -238,7 +243,7 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     he = pkg.HE.from_params(wl.N16, device=0)
-    w = Workload(he, n_streams=args.streams)
+    w = Workload(he, n_streams=args.streams, hm_chunk=args.hmult_batch)
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()
@@ -311,6 +316,7 @@ def main():
                         "15 hoisted HRot (2^0..2^14) at level 24, 128 single HRot at levels 8..24",
             "key_switches_per_step": w.key_switches,
             "streams": args.streams,
+            "hmult_batch": args.hmult_batch,
         },
         "detail": detail,
         "roofline": roofline,

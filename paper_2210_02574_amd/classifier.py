@@ -212,3 +212,54 @@ class EncryptedTrainStep:
             upd = he.rescale(he.cmult(G, _residues(p.step, p.c_w, he.q, level)))
             out.append(he.sub(he.moddrop(w, p.out_level), upd))
         return out
+
+    # ---- the same step with all ciphertexts of a class processed as one batch per library call ----------------
+
+    def _mul_b(self, relin, a, b):
+        return self.he.rescale_batch(self.he.hmult_relin_batch(relin, a, b))
+
+    def _affine_b(self, cts, coeff: float, c_scale: float, const: float, t_scale: float):
+        he = self.he
+        level = int(cts.shape[2])
+        out = he.rescale_batch(he.cmult_batch(cts, _residues(coeff, c_scale, he.q, level)))
+        return he.add_const_batch(out, _residues(const, t_scale, he.q, level - 1), out=out)
+
+    def _logistic_b(self, relin, z):
+        he, p = self.he, self.plan
+        z2 = self._mul_b(relin, z, z)
+        z4 = self._mul_b(relin, z2, z2)
+        u = self._affine_b(z2, p.a7, p.c_u, p.a5, p.t_u)
+        zu = self._mul_b(relin, z4, u)
+        v = he.moddrop_batch(self._affine_b(z2, p.a3, p.c_v, p.a1, p.t_v), p.level - 5)
+        inner = he.add_batch(zu, v, out=zu)
+        out = self._mul_b(relin, he.moddrop_batch(z, p.level - 5), inner)
+        return he.add_const_batch(out, _residues(0.5, p.t_p, he.q, p.level - 6), out=out)
+
+    def run_batched(self, relin, rot, mask_pt, X, W, Y):
+        """X: [n][2][level][N]; W: list of [2][level][N]; Y: list (per class) of [n][2][label_level][N].
+        Same arithmetic as run(); the sum over the ciphertexts is a pairwise tree (modular addition is
+        associative, so the residues are identical)."""
+        he, p = self.he, self.plan
+        n = int(X.shape[0])
+        X_low = he.moddrop_batch(X, p.label_level)
+        out = []
+        for c, w in enumerate(W):
+            wb = w.unsqueeze(0).expand(n, -1, -1, -1).contiguous()
+            m = self._mul_b(relin, X, wb)
+            he.rotate_sum_batch([rot[r] for r in TRAIN_SUM_SHIFTS], m)
+            z = he.rescale_batch(he.pmult_batch(m, mask_pt))
+            he.rotate_sum_batch([rot[r] for r in TRAIN_FILL_SHIFTS], z)
+            e = self._logistic_b(relin, z)
+            he.sub_batch(e, Y[c], out=e)
+            g = he.hmult_relin_batch(relin, e, X_low)
+            k = n
+            while k > 1:  # pairwise sum over the batch
+                h = k // 2
+                he.add_batch(g[:h], g[k - h:k], out=g[:h])
+                k -= h
+            G = he.rescale(g[0])
+            he.rotate_sum([rot[r] for r in TRAIN_BLOCK_SHIFTS], G)
+            level = int(G.shape[1])
+            upd = he.rescale(he.cmult(G, _residues(p.step, p.c_w, he.q, level)))
+            out.append(he.sub(he.moddrop(w, p.out_level), upd))
+        return out

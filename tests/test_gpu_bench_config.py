@@ -20,7 +20,7 @@ def test_bench_step_outputs_match_oracle(oracle_mod, n_streams):
     p = wl.N16
     he = pkg.HE.from_params(p, device=0)
     o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
-    w = bench.Workload(he, seed=2, n_hmult=2, n_single=6, n_ntt=56, n_streams=n_streams)
+    w = bench.Workload(he, seed=2, n_hmult=3, n_single=6, n_ntt=56, n_streams=n_streams, hm_chunk=2)
     ntt_in = he.to_host(w.ntt_limbs).copy()
     w.step()
     torch.cuda.synchronize()
@@ -32,6 +32,11 @@ def test_bench_step_outputs_match_oracle(oracle_mod, n_streams):
         assert np.array_equal(fwd[b], o.ntt(ntt_in[b], w.ntt_mods[b])), b
     he.intt(w.ntt_limbs, w.ntt_mods)
     relin = wl.uniform_evk(1000, p)
+    for i in (1, 2):
+        a, b = he.to_host(w.hm_a[i]), he.to_host(w.hm_b[i])
+        want = o.hmult_relin(a, b, relin)
+        assert np.array_equal(he.to_host(w.hm_out[i]), want), i
+        assert np.array_equal(he.to_host(w.rs_out[i]), o.rescale(want)), i
     a, b = he.to_host(w.hm_a[1]), he.to_host(w.hm_b[1])
     want = o.hmult_relin(a, b, relin)
     assert np.array_equal(he.to_host(w.hm_out[1]), want)

@@ -102,3 +102,27 @@ def test_train_step_slice_matches_oracle_and_plaintext(oracle_mod):
     assert err <= 2.0**-15
     # every block carries the same updated weights
     assert np.abs(dec[1024 + 4: 1024 + 772] - ref).max() <= 2.0**-15
+
+
+def test_batched_train_step_equals_sequential():
+    """The batched driver (one library call per step over all ciphertexts of a class) gives the bits of
+    the sequential driver, on three ciphertexts of uniform residues (odd count: uneven pairwise sum)."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from paper_2210_02574_amd import classifier as cl
+
+    p = wl.N16
+    he = pkg.HE.from_params(p, device=0)
+    step = cl.EncryptedTrainStep(he, p.L, 2.0**50, 1.0, 96)
+    plan = step.plan
+    relin = he.evk_from_host(wl.uniform_evk(1, p), 1)
+    rot = {r: he.evk_from_host(wl.uniform_evk(2 + k, p), he.galois_element(r))
+           for k, r in enumerate(step.rotation_shifts())}
+    X = [he.to_device(wl.uniform_ct(100 + i, p, plan.level)) for i in range(3)]
+    W = [he.to_device(wl.uniform_ct(200, p, plan.level))]
+    Y = [[he.to_device(wl.uniform_ct(300 + i, p, plan.label_level)) for i in range(3)]]
+    mask = he.to_device(wl.uniform_limbs(400, p, list(range(plan.level - 1))))
+    seq = step.run(relin, rot, mask, X, W, Y)
+    bat = step.run_batched(relin, rot, mask, torch.stack(X), W, [torch.stack(Y[0])])
+    assert torch.equal(seq[0], bat[0])
