@@ -236,6 +236,9 @@ def main():
 
     import torch
 
+    from paper_2210_02574_amd.build import ensure_built
+
+    ensure_built()
     import paper_2210_02574_amd as pkg
 
     if not torch.cuda.is_available():

@@ -36,5 +36,10 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Builds the library only if no built library is there (tests, smoke and bench call this)."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))

@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # load what is built; compile (hipcc, gfx950) only when nothing is
+    from paper_2210_02574_amd.build import ensure_built
+
+    ensure_built()
 
 
 @pytest.fixture(scope="session")
