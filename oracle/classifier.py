@@ -115,3 +115,63 @@ def train_step(o, X, W, Y, relin, rot, level, scale, lr, n_samples, a=None):
         upd = o.rescale(o.cmult(G, _const(o, lr / n_samples, scale * q[level - 8] / tg, level - 7)))
         new_w.append(o.sub(o.moddrop(w, level - 8), upd))
     return new_w
+
+
+# ---- degree-15 odd minimax approximation of the logistic function on [-12, 12] ----------------------------
+
+def minimax15_by_linear_program(radius=12.0, grid=1201):
+    """The same minimax problem posed on a grid as a linear program (scipy): minimise E subject to
+    |sum_k c_k t^(2k+1) - (sigma(radius t) - 1/2)| <= E at every grid point of [0, 1].
+    Returns (coefficients c_k of t^(2k+1), E)."""
+    from scipy.optimize import linprog
+
+    t = np.linspace(0.0, 1.0, grid)
+    g = 1.0 / (1.0 + np.exp(-radius * t)) - 0.5
+    P = np.stack([t ** (2 * k + 1) for k in range(8)], axis=1)
+    ones = np.ones((grid, 1))
+    A = np.vstack([np.hstack([P, -ones]), np.hstack([-P, -ones])])
+    b = np.concatenate([g, -g])
+    cost = np.zeros(9)
+    cost[8] = 1.0
+    res = linprog(cost, A_ub=A, b_ub=b, bounds=[(None, None)] * 8 + [(0, None)], method="highs")
+    return res.x[:8], float(res.x[8])
+
+
+def logistic15(o, t, relin, level, scale, c):
+    """1/2 + t Q(t^2) on a ciphertext of t at (level, scale); c = monomial coefficients (length 16).
+    Horner-free split: Q = A + y^4 B with A = (c1 + c3 y) + y^2 (c5 + c7 y), B = (c9 + c11 y) + y^2 (c13 + c15 y)."""
+    q = [float(v) for v in o.q]
+
+    def mul(a, b):
+        return o.rescale(o.hmult_relin(a, b, relin))
+
+    def const(v, s, lvl):
+        iv = int(round(v * s))
+        return [iv % o.q[i] for i in range(lvl)]
+
+    def lin(y, lvl, s_in, c0, c1, target):
+        out = o.rescale(o.cmult(y, const(c1, target * q[lvl - 1] / s_in, lvl)))
+        return o.add_const(out, const(c0, target, lvl - 1))
+
+    l = level
+    y = mul(t, t)
+    s_y = scale * scale / q[l - 1]
+    y2 = mul(y, y)
+    s_y2 = s_y * s_y / q[l - 2]
+    y4 = mul(y2, y2)
+    s_y4 = s_y2 * s_y2 / q[l - 3]
+    # scales: B is built at t_b, Q = y^4 B + A lands at t_q, so A is built at exactly t_q
+    t_hi = scale
+    t_b = s_y2 * t_hi / q[l - 3]
+    t_q = s_y4 * t_b / q[l - 4]
+    t_hi_a = t_q * q[l - 3] / s_y2
+    a_hi = lin(y, l - 1, s_y, c[5], c[7], t_hi_a)
+    b_hi = lin(y, l - 1, s_y, c[13], c[15], t_hi)
+    a_lo = o.moddrop(lin(y, l - 1, s_y, c[1], c[3], t_q), l - 3)
+    b_lo = o.moddrop(lin(y, l - 1, s_y, c[9], c[11], t_b), l - 3)
+    A = o.add(mul(y2, a_hi), a_lo)
+    B = o.add(mul(y2, b_hi), b_lo)
+    Q = o.add(mul(y4, B), o.moddrop(A, l - 4))
+    t_p = scale * t_q / q[l - 5]
+    p = mul(o.moddrop(t, l - 4), Q)
+    return o.add_const(p, const(0.5, t_p, l - 5)), t_p

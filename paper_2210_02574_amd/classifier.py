@@ -263,3 +263,103 @@ class EncryptedTrainStep:
             upd = he.rescale(he.cmult(G, _residues(p.step, p.c_w, he.q, level)))
             out.append(he.sub(he.moddrop(w, p.out_level), upd))
         return out
+
+
+# ---- the paper's logistic approximation: odd minimax polynomial of degree 15 on [-12, 12] -------------------
+
+def minimax_logistic_coeffs(degree: int = 15, radius: float = 12.0, iters: int = 60):
+    """Remez exchange for the odd polynomial sum_k c_k t^(2k+1), t = x/radius, that minimises the maximum
+    error against 1/(1+exp(-x)) - 1/2 on [-radius, radius] (Section 2.2 of the paper uses degree 15 on
+    [-12, 12] and quotes an error within 0.00614).  Returns (monomial coefficients in t, degree+1 long with
+    the constant 1/2, sup error)."""
+    m = (degree + 1) // 2
+    n = m + 1
+
+    def g(t):
+        return 1.0 / (1.0 + np.exp(-radius * t)) - 0.5
+
+    x = np.sort(np.cos(np.pi * np.arange(n)[::-1] / (2 * n - 1)))
+    grid = np.linspace(0.0, 1.0, 200001)
+    powers = np.stack([grid ** (2 * k + 1) for k in range(m)], axis=1)
+    c = np.zeros(m)
+    for _ in range(iters):
+        A = np.zeros((n, n))
+        for k in range(m):
+            A[:, k] = x ** (2 * k + 1)
+        A[:, m] = (-1.0) ** np.arange(n)
+        sol = np.linalg.solve(A, g(x))
+        c = sol[:m]
+        err = powers @ c - g(grid)
+        d = np.diff(err)
+        ext = [i + 1 for i in range(len(d) - 1) if d[i] * d[i + 1] < 0] + [len(grid) - 1]
+        sel = []
+        for i in ext:  # keep one extremum per sign run
+            if sel and np.sign(err[i]) == np.sign(err[sel[-1]]):
+                if abs(err[i]) > abs(err[sel[-1]]):
+                    sel[-1] = i
+            else:
+                sel.append(i)
+        while len(sel) > n:
+            sel = sel[1:] if abs(err[sel[0]]) < abs(err[sel[-1]]) else sel[:-1]
+        if len(sel) < n:
+            break
+        new_x = grid[sel]
+        done = np.max(np.abs(new_x - x)) < 1e-9
+        x = new_x
+        if done:
+            break
+    mono = np.zeros(degree + 1)
+    mono[0] = 0.5
+    mono[1::2] = c
+    sup = float(np.abs(powers @ c - g(grid)).max())
+    return mono, sup
+
+
+class EncryptedLogistic15:
+    """p(t) = 1/2 + t Q(t^2), Q of degree 7, on a ciphertext holding t = x/12 (level l0, scale s): 7 HMult and
+    4 scalar products, five levels.  Q(y) = A(y) + y^4 B(y), A = (c1 + c3 y) + y^2 (c5 + c7 y),
+    B = (c9 + c11 y) + y^2 (c13 + c15 y)."""
+
+    def __init__(self, he, level: int, scale: float, coeffs=None):
+        self.he, self.level, self.scale = he, level, scale
+        self.c = minimax_logistic_coeffs()[0] if coeffs is None else np.asarray(coeffs, dtype=np.float64)
+        q = [float(v) for v in he.q]
+        l, s = level, scale
+        self.s_y = s * s / q[l - 1]                    # y = t^2, level l-1
+        self.s_y2 = self.s_y * self.s_y / q[l - 2]     # y^2, level l-2
+        self.s_y4 = self.s_y2 * self.s_y2 / q[l - 3]   # y^4, level l-3
+        self.t_hi = s                                  # c13 + c15 y, level l-2
+        self.t_b = self.s_y2 * self.t_hi / q[l - 3]    # B, level l-3
+        self.t_q = self.s_y4 * self.t_b / q[l - 4]     # Q = y^4 B + A, level l-4: A is built at exactly this scale
+        self.t_hi_a = self.t_q * q[l - 3] / self.s_y2  # c5 + c7 y, level l-2
+        self.t_p = s * self.t_q / q[l - 5]             # p, level l-5
+        self.out_level, self.out_scale = l - 5, self.t_p
+
+    def _lin(self, y, c0: float, c1: float, target: float, s_in: float):
+        """rescale(c1 * y) + c0 at scale `target`, one level below y."""
+        he = self.he
+        level = int(y.shape[1])
+        q_drop = float(he.q[level - 1])
+        out = he.rescale(he.cmult(y, _residues(c1, target * q_drop / s_in, he.q, level)))
+        return he.add_const(out, _residues(c0, target, he.q, level - 1), out=out)
+
+    def _mul(self, relin, a, b):
+        return self.he.rescale(self.he.hmult_relin(relin, a, b))
+
+    def run(self, relin, t):
+        he, c, l = self.he, self.c, self.level
+        y = self._mul(relin, t, t)
+        y2 = self._mul(relin, y, y)
+        y4 = self._mul(relin, y2, y2)
+        a_hi = self._lin(y, c[5], c[7], self.t_hi_a, self.s_y)
+        b_hi = self._lin(y, c[13], c[15], self.t_hi, self.s_y)
+        a_lo = he.moddrop(self._lin(y, c[1], c[3], self.t_q, self.s_y), l - 3)
+        b_lo = he.moddrop(self._lin(y, c[9], c[11], self.t_b, self.s_y), l - 3)
+        A = self._mul(relin, y2, a_hi)
+        he.add(A, a_lo, out=A)
+        B = self._mul(relin, y2, b_hi)
+        he.add(B, b_lo, out=B)
+        Q = self._mul(relin, y4, B)
+        he.add(Q, he.moddrop(A, l - 4), out=Q)
+        p = self._mul(relin, he.moddrop(t, l - 4), Q)
+        return he.add_const(p, _residues(0.5, self.t_p, he.q, l - 5), out=p)

@@ -126,3 +126,42 @@ def test_batched_train_step_equals_sequential():
     seq = step.run(relin, rot, mask, X, W, Y)
     bat = step.run_batched(relin, rot, mask, torch.stack(X), W, [torch.stack(Y[0])])
     assert torch.equal(seq[0], bat[0])
+
+
+def test_logistic15_matches_oracle_and_the_paper_bound(oracle_mod):
+    """The paper's activation (Section 2.2): the degree-15 minimax polynomial on [-12, 12], evaluated under
+    encryption on t = x/12 (7 HMult, five levels).  Bit-exact against the oracle's own composition with the
+    same coefficients; the decrypted values follow the fp64 polynomial to 1e-6 and the true logistic function
+    to the paper's 0.00614."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from oracle import classifier as oc
+    from paper_2210_02574_amd import classifier as cl
+
+    assert torch.cuda.is_available()
+    p = wl.N16
+    he = pkg.HE.from_params(p, device=0)
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    level, scale = 8, 2.0**50
+    coeffs, sup = cl.minimax_logistic_coeffs()
+    sk, s = he.keygen_secret(61), o.keygen_secret(61)
+    relin, orelin = he.keygen_relin(sk, 62), o.keygen_relin(s, 62)
+    x = 12.0 * wl.slots_uniform(63, he.n).real
+    x[:5] = [-12.0, 12.0, 0.0, 11.3, -0.4]
+    t = (x / 12.0).astype(np.complex128)
+    m = o.encode(t, scale)
+    ct = he.encrypt_coeffs(sk, m, level, 64)
+    ev = cl.EncryptedLogistic15(he, level, scale, coeffs)
+    got = he.to_host(ev.run(relin, he.to_device(ct)))
+    want, want_scale = oc.logistic15(o, ct, orelin, level, scale, coeffs)
+    assert got.shape == (2, level - 5, p.N)
+    assert ev.out_scale == want_scale
+    assert np.array_equal(got, want)
+    dec = he.decrypt(sk, got, ev.out_scale).real
+    poly = np.polyval(coeffs[::-1], x / 12.0)
+    err_poly = np.abs(dec - poly).max()
+    err_sig = np.abs(dec - 1.0 / (1.0 + np.exp(-x))).max()
+    print("logistic15: vs fp64 polynomial %.3g, vs logistic function %.4g (minimax error %.4g)" % (err_poly, err_sig, sup))
+    assert err_poly <= 1e-6
+    assert err_sig <= 0.00614 + 1e-6
