@@ -102,7 +102,7 @@ enum KernelId {
 };
 static const char *const kKernelNames[KID_COUNT] = {
     "k_ntt_fwd_cols", "k_ntt_fwd_cols_modup", "k_ntt_fwd_cols_moddown", "k_ntt_fwd_cols_rescale", "k_ntt_fwd_blocks",
-    "k_ntt_fwd_blocks_fin", "k_ntt_inv_blocks", "k_ntt_inv_cols", "k_limbwise", "k_cmult", "k_tensor", "k_inner"};
+    "k_ntt_fwd_blocks_fin", "k_ntt_inv_blocks", "k_ntt_inv_cols", "k_limbwise", "k_cmult", "k_tensor", "k_inner_blocks"};
 
 static bool prof_events(he_ctx *c, int kid, double bytes, ProfRecord &r)
 {
@@ -237,8 +237,10 @@ static const FinArgs kNoFin = {nullptr, nullptr, nullptr, nullptr, nullptr, 0, 1
 // limb's own content, or a base conversion of cv.src); with fin != nullptr the block pass writes
 // (u - ntt) * const + addend to fin->out instead of the transform itself.
 // src_limbs = number of source limbs the prologue reads in total (for the byte count).
+// int_blocks_only: the block pass runs only for limbs on the integer path (the others are finished by the
+// kernel that consumes them).
 static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList &l, int pro, const ConvArgs &cv,
-                           const FinArgs *fin, int src_limbs)
+                           const FinArgs *fin, int src_limbs, bool int_blocks_only = false)
 {
     const bool wide = std::max(c->alpha, c->K) > 4;
     const double N8 = (double)c->N * 8.0;
@@ -282,18 +284,23 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
             else
                 KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<12, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin);
         } else {
+            int nbb = nb; // integer-path limbs come first in a batch
+            if (int_blocks_only)
+                for (nbb = 0; nbb < nb && c->modc[lb.mod[nbb]].qd == 0.0;) nbb++;
+            if (nbb == 0) return;
             if (c->logN == 16)
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nb * N8, (k_ntt_fwd_blocks<16, EPI_STORE>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, kNoFin);
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<16, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin);
             else
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nb * N8, (k_ntt_fwd_blocks<12, EPI_STORE>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, kNoFin);
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<12, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin);
         }
     });
 }
 
 // Inverse NTT: limb b read at src + l.src[b]*N, result at dst + l.slot[b]*N; scale folds a base
 // conversion constant into the final 1/N.
+// blocks_done: the block pass has already been applied (by the inner-product kernel), in place in dst.
 static int32_t ntt_inverse(he_ctx *c, hipStream_t st, const u64 *src, u64 *dst, const LimbList &l, int scale,
-                           const ConvArgs &cv)
+                           const ConvArgs &cv, bool blocks_done = false)
 {
     const double N8 = (double)c->N * 8.0;
     return for_batches(c, l, [&](const LimbBatch &lb, int nb) {
@@ -306,10 +313,12 @@ static int32_t ntt_inverse(he_ctx *c, hipStream_t st, const u64 *src, u64 *dst, 
     default: ICOLS1(KERN, GRID, SCALE_MODDOWN); break;                                                               \
     }
         if (c->logN == 16) {
-            KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<16>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
+            if (!blocks_done)
+                KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<16>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
             ICOLS(k_ntt_inv_cols16, 16 * nb)
         } else {
-            KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<12>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
+            if (!blocks_done)
+                KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<12>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
             ICOLS(k_ntt_inv_cols12, nb)
         }
 #undef ICOLS
@@ -518,7 +527,8 @@ extern "C" int32_t he_workspace_bytes(const he_ctx *ctx, int32_t level, int32_t 
 static bool batch_fits(const WsLayout &w, int count) { return count >= 1 && w.total * (size_t)count <= 65535; }
 
 // Steps 1-2 of the key switch for `count` polynomials: operation o reads its NTT-domain input at
-// d_ntt + o*d_stride limbs and works in ws + o*w.total limbs.
+// d_ntt + o*d_stride limbs and works in ws + o*w.total limbs.  Raised limbs on the floating-point path
+// are left as the column pass wrote them (the inner-product kernel finishes them).
 static int32_t ks_raise(he_ctx *c, const u64 *d_ntt, int d_stride, u64 *ws, const WsLayout &w, int level, int count,
                         hipStream_t st)
 {
@@ -539,7 +549,7 @@ static int32_t ks_raise(he_ctx *c, const u64 *d_ntt, int d_stride, u64 *ws, cons
                 r.add(o * W + j * Ma + a, a < level ? a : c->L + (a - level));
             }
         }
-    return ntt_forward(c, st, ws + w.raised * N, r, PRO_MODUP, cv, nullptr, level * count);
+    return ntt_forward(c, st, ws + w.raised * N, r, PRO_MODUP, cv, nullptr, level * count, true);
 }
 
 // Steps 3-5.  Operation o writes out + o*out_stride limbs; mode / c0 (+ o*c0_stride): the addend of
@@ -551,10 +561,17 @@ static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
     const size_t N = c->N;
     const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha, W = (int)w.total;
     const unsigned g = (unsigned)evk->galois;
-    dim3 grid((unsigned)(N / 256), (unsigned)Ma, (unsigned)count);
+    dim3 grid((unsigned)(N / 4096), (unsigned)Ma, (unsigned)count);
+    InnerArgs ia;
+    ia.raised = ws + w.raised * N, ia.d = d_ntt, ia.evk = evk->dev, ia.u = ws + w.u * N;
+    ia.level = level, ia.L = c->L, ia.K = K, ia.alpha = c->alpha, ia.beta = beta;
+    ia.g = g, ia.ws_stride = W, ia.d_stride = d_stride, ia.inv_special = 1;
     // reads beta digits and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
-    KLAUNCH(c, st, KID_INNER, (double)count * (3 * beta + 2) * Ma * N * 8.0, (k_inner), grid, ws + w.raised * N, d_ntt,
-            evk->dev, ws + w.u * N, c->dev, level, c->L, K, c->alpha, beta, g, c->logN, W, d_stride);
+    const double inner_bytes = (double)count * (3 * beta + 2) * Ma * N * 8.0;
+    if (c->logN == 16)
+        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<16>), grid, ia, c->dev);
+    else
+        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<12>), grid, ia, c->dev);
     int32_t rc = launch_ok(c);
     if (rc != HE_OK) return rc;
     LimbList sp;
@@ -562,7 +579,7 @@ static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
         for (int cc = 0; cc < 2; cc++)
             for (int k = 0; k < K; k++) sp.add(o * W + cc * Ma + level + k, c->L + k);
     const ConvArgs cv = conv_args(c, ws + w.u * N, level, W, W);
-    if ((rc = ntt_inverse(c, st, ws + w.u * N, ws + w.u * N, sp, SCALE_MODDOWN, cv)) != HE_OK) return rc;
+    if ((rc = ntt_inverse(c, st, ws + w.u * N, ws + w.u * N, sp, SCALE_MODDOWN, cv, true)) != HE_OK) return rc;
     LimbList r;
     for (int o = 0; o < count; o++)
         for (int cc = 0; cc < 2; cc++)

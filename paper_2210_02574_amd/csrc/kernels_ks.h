@@ -80,52 +80,158 @@ __global__ __launch_bounds__(256) void k_tensor(const u64 *A, const u64 *B, u64 
     d2[o0] = r2;
 }
 
-// Inner product with the evaluation key on active limb a = blockIdx.y:
-// u[c][a][n] = sum_j D_j[a][pi_g(n)] * evk[j][c][mod(a)][n], where D_j[a] is the raised digit
-// (raised[j][a]) outside digit j and the NTT-domain input d[a] inside it.
-// blockIdx.z = operation of a batch (same key for all): raised / u buffers ws_stride limbs apart, d
-// buffers d_stride limbs apart.
-__global__ __launch_bounds__(256) void k_inner(const u64 *__restrict__ raised, const u64 *__restrict__ d,
-                                               const u64 *__restrict__ evk, u64 *__restrict__ u, DevTables T,
-                                               int level, int L, int K, int alpha, int beta, unsigned g, int logN,
-                                               int ws_stride, int d_stride)
+// ---- inner product with the evaluation key, block pass of the raised digits' forward NTT fused in -----------
+//
+// u[c][a][n] = sum_j D_j[a][pi_g(n)] * evk[j][c][mod(a)][n] on every active limb a, where D_j[a] is the
+// raised digit outside digit j and the NTT-domain input d[a] inside it.
+// One work-group produces 4096 consecutive outputs (16 blocks of 256) of one active limb.  The index map of
+// sigma_g sends aligned groups of 2^m consecutive NTT-domain indices to aligned groups (the low bits of
+// (2 brv(k) + 1) g depend only on the low bits of brv(k), i.e. on the high bits of k), so the sources of
+// these outputs are the 4096 indices of one input tile.  For a limb on the floating-point path the raised
+// digits arrive as the column pass left them; each is finished here (stages logN-8 .. logN-1) into LDS
+// and read back through the index map, so the transformed digits never travel to memory.  Limbs on
+// the integer path read digits that the block-pass kernel has finished.  With inv_special the special
+// limbs of u leave this kernel with the block pass of their inverse transform already applied.
+
+template <int LOGN, class A>
+__device__ __forceinline__ void inv_blocks_from_regs(const u64 (&r)[16], u64 *limb, const A &ar, u64 *lds, unsigned bg)
 {
-    const int a = blockIdx.y;
-    raised += ((size_t)blockIdx.z * ws_stride) << logN;
-    u += ((size_t)blockIdx.z * ws_stride) << logN;
-    d += ((size_t)blockIdx.z * d_stride) << logN;
-    const unsigned n = blockIdx.x * 256 + threadIdx.x;
-    const int M = L + K, Ma = level + K;
-    const int mi = active_mod(a, level, L);
-    const unsigned src = g == 1 ? n : galois_index(n, g, logN);
-    const int own = a < level ? a / alpha : -1;
+    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
+    typename A::V a[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = r[k];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load(lds[tile_at(blk, 16 * il + k)]);
+    ar.template inv16<false>(a, LOGN - 4, bg * 16 + il);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_mid(a[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, il + 16 * k)]);
+    ar.template inv16<false>(a, LOGN - 8, bg);
+#pragma unroll
+    for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = ar.store_mid(a[k]);
+    __syncthreads();
+}
+
+struct InnerArgs {
+    const u64 *raised, *d, *evk;
+    u64 *u;
+    int level, L, K, alpha, beta;
+    unsigned g;
+    int ws_stride, d_stride;
+    int inv_special;
+};
+
+// grid = (N / 4096, level + K, count)
+template <int LOGN> __global__ __launch_bounds__(256) void k_inner_blocks(InnerArgs ia, DevTables T)
+{
+    __shared__ u64 lds[16 * TILE_GROUP];
+    const int level = ia.level, M = ia.L + ia.K, Ma = level + ia.K;
+    const int a = Ma - 1 - (int)blockIdx.y; // special limbs (the slowest) first
+    const unsigned tile = blockIdx.x;
+    const u64 *raised = ia.raised + (((size_t)blockIdx.z * ia.ws_stride) << LOGN);
+    u64 *u = ia.u + (((size_t)blockIdx.z * ia.ws_stride) << LOGN);
+    const u64 *d = ia.d + (((size_t)blockIdx.z * ia.d_stride) << LOGN);
+    const unsigned g = ia.g;
+    const int mi = active_mod(a, level, ia.L);
+    const int own = a < level ? a / ia.alpha : -1;
     const ModConst m = T.mod[mi];
-    u64 r0, r1;
+    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
+    const unsigned bg = tile * 16 + blk;
+    const unsigned tile_in = g == 1 ? tile : galois_index(tile << 12, g, LOGN) >> 12;
+    const unsigned bg_in = tile_in * 16 + blk;
+    unsigned src[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+        const unsigned pos = bg * 256 + il + 16 * k;
+        src[k] = g == 1 ? pos : galois_index(pos, g, LOGN);
+    }
+    u64 r0[16], r1[16];
     if (m.qd != 0.0) {
-        double acc0 = 0.0, acc1 = 0.0;
-        for (int j = 0; j < beta; j++) {
-            const u64 *dj = j == own ? d + ((size_t)a << logN) : raised + (((size_t)j * Ma + a) << logN);
-            const double dv = u2d(dj[src]);
-            acc0 += fp_mulmod(dv, u2d(evk[((((size_t)j * 2 + 0) * M + mi) << logN) + n]), m.qd, m.qinvd);
-            acc1 += fp_mulmod(dv, u2d(evk[((((size_t)j * 2 + 1) * M + mi) << logN) + n]), m.qd, m.qinvd);
+        const ArithFp ar = make_fp(T, mi, LOGN);
+        double acc0[16], acc1[16];
+#pragma unroll
+        for (int k = 0; k < 16; k++) acc0[k] = acc1[k] = 0.0;
+        for (int j = 0; j < ia.beta; j++) {
+            double dv[16];
+            if (j == own) {
+                const u64 *dj = d + ((size_t)a << LOGN);
+#pragma unroll
+                for (int k = 0; k < 16; k++) dv[k] = u2d(dj[src[k]]);
+            } else {
+                const u64 *mid = raised + (((size_t)j * Ma + a) << LOGN);
+#pragma unroll
+                for (int k = 0; k < 16; k++) dv[k] = ar.load_mid(mid[bg_in * 256 + il + 16 * k]);
+                ar.fwd16(dv, LOGN - 8, bg_in, true);
+#pragma unroll
+                for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = ar.store_mid(dv[k]);
+                __syncthreads();
+#pragma unroll
+                for (int k = 0; k < 16; k++) dv[k] = ar.load_mid(lds[tile_at(blk, 16 * il + k)]);
+                ar.fwd16(dv, LOGN - 4, bg_in * 16 + il, true);
+#pragma unroll
+                for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_mid(ar.reduce(dv[k]));
+                __syncthreads();
+#pragma unroll
+                for (int k = 0; k < 16; k++) {
+                    const unsigned s = src[k] & 4095u;
+                    dv[k] = ar.load_mid(lds[tile_at(s >> 8, s & 255u)]);
+                }
+                __syncthreads();
+            }
+            const u64 *e0 = ia.evk + ((((size_t)j * 2 + 0) * M + mi) << LOGN) + bg * 256 + il;
+            const u64 *e1 = ia.evk + ((((size_t)j * 2 + 1) * M + mi) << LOGN) + bg * 256 + il;
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                acc0[k] += ar.mulmod(dv[k], u2d(e0[16 * k]));
+                acc1[k] += ar.mulmod(dv[k], u2d(e1[16 * k]));
+            }
             if ((j & 3) == 3) {
-                acc0 = fp_reduce(acc0, m.qd, m.qinvd);
-                acc1 = fp_reduce(acc1, m.qd, m.qinvd);
+#pragma unroll
+                for (int k = 0; k < 16; k++) acc0[k] = ar.reduce(acc0[k]), acc1[k] = ar.reduce(acc1[k]);
             }
         }
-        r0 = fp_canon(acc0, m.qd, m.qinvd);
-        r1 = fp_canon(acc1, m.qd, m.qinvd);
+#pragma unroll
+        for (int k = 0; k < 16; k++) r0[k] = fp_canon(acc0[k], m.qd, m.qinvd), r1[k] = fp_canon(acc1[k], m.qd, m.qinvd);
     } else {
-        U128 acc0{0, 0}, acc1{0, 0};
-        for (int j = 0; j < beta; j++) {
-            const u64 *dj = j == own ? d + ((size_t)a << logN) : raised + (((size_t)j * Ma + a) << logN);
-            const u64 dv = dj[src];
-            mac128(acc0, dv, evk[((((size_t)j * 2 + 0) * M + mi) << logN) + n]);
-            mac128(acc1, dv, evk[((((size_t)j * 2 + 1) * M + mi) << logN) + n]);
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            U128 acc0[8], acc1[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) acc0[k] = acc1[k] = U128{0, 0};
+            for (int j = 0; j < ia.beta; j++) {
+                const u64 *dj = j == own ? d + ((size_t)a << LOGN) : raised + (((size_t)j * Ma + a) << LOGN);
+                const u64 *e0 = ia.evk + ((((size_t)j * 2 + 0) * M + mi) << LOGN) + bg * 256 + il;
+                const u64 *e1 = ia.evk + ((((size_t)j * 2 + 1) * M + mi) << LOGN) + bg * 256 + il;
+#pragma unroll
+                for (int k = 0; k < 8; k++) {
+                    const u64 dv = dj[src[8 * h + k]];
+                    mac128(acc0[k], dv, e0[16 * (8 * h + k)]);
+                    mac128(acc1[k], dv, e1[16 * (8 * h + k)]);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 8; k++) r0[8 * h + k] = reduce128(acc0[k], m), r1[8 * h + k] = reduce128(acc1[k], m);
         }
-        r0 = reduce128(acc0, m);
-        r1 = reduce128(acc1, m);
     }
-    u[(((size_t)0 * Ma + a) << logN) + n] = r0;
-    u[(((size_t)1 * Ma + a) << logN) + n] = r1;
+    u64 *u0 = u + (((size_t)0 * Ma + a) << LOGN), *u1 = u + (((size_t)1 * Ma + a) << LOGN);
+    if (ia.inv_special && a >= level) {
+        if (m.qd != 0.0) {
+            const ArithFp ar = make_fp(T, mi, LOGN);
+            inv_blocks_from_regs<LOGN>(r0, u0, ar, lds, bg);
+            inv_blocks_from_regs<LOGN>(r1, u1, ar, lds, bg);
+        } else {
+            const ArithInt ar = make_int(T, mi, LOGN);
+            inv_blocks_from_regs<LOGN>(r0, u0, ar, lds, bg);
+            inv_blocks_from_regs<LOGN>(r1, u1, ar, lds, bg);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            u0[bg * 256 + il + 16 * k] = r0[k];
+            u1[bg * 256 + il + 16 * k] = r1[k];
+        }
+    }
 }

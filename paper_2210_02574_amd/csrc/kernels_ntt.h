@@ -191,25 +191,40 @@ __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithIn
 
 // ---- epilogue: what the forward block pass does with a finished (canonical) NTT value ---------------------
 
+// Operands of the epilogue for one output: issued before the transform so that the loads overlap it.
+struct FinOperands {
+    u64 uv, av;
+};
 template <int LOGN>
-__device__ __forceinline__ void fin_store(const FinArgs &fa, const DevTables &T, unsigned slot, unsigned pos, u64 rv)
+__device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, unsigned slot, unsigned pos)
 {
     const unsigned op = slot / (unsigned)fa.dst_stride;
     slot -= op * (unsigned)fa.dst_stride;
     const unsigned c = slot / fa.nl, i = slot % fa.nl;
+    FinOperands o;
+    o.uv = fa.u[(((size_t)op * fa.u_stride + (size_t)c * fa.u_cstride + i) << LOGN) + pos];
+    o.av = 0;
+    if (fa.mode == 1)
+        o.av = fa.out[(((size_t)op * fa.out_stride + slot) << LOGN) + pos];
+    else if (fa.mode == 2 && c == 0)
+        o.av = fa.add[(((size_t)op * fa.add_stride + i) << LOGN) + galois_index(pos, fa.g, LOGN)];
+    return o;
+}
+
+template <int LOGN>
+__device__ __forceinline__ void fin_store(const FinArgs &fa, const DevTables &T, unsigned slot, unsigned pos, u64 rv,
+                                          const FinOperands &fo)
+{
+    const unsigned op = slot / (unsigned)fa.dst_stride;
+    slot -= op * (unsigned)fa.dst_stride;
+    const unsigned i = slot % fa.nl;
     const ModConst m = T.mod[i];
     const size_t o = (((size_t)op * fa.out_stride + slot) << LOGN) + pos;
-    const u64 uv = fa.u[(((size_t)op * fa.u_stride + (size_t)c * fa.u_cstride + i) << LOGN) + pos];
-    u64 av = 0;
-    if (fa.mode == 1)
-        av = fa.out[o];
-    else if (fa.mode == 2 && c == 0)
-        av = fa.add[(((size_t)op * fa.add_stride + i) << LOGN) + galois_index(pos, fa.g, LOGN)];
     u64 res;
     if (m.qd != 0.0)
-        res = fp_canon(fp_mulmod(u2d(uv) - u2d(rv), fa.cst_d[i], m.qd, m.qinvd) + u2d(av), m.qd, m.qinvd);
+        res = fp_canon(fp_mulmod(u2d(fo.uv) - u2d(rv), fa.cst_d[i], m.qd, m.qinvd) + u2d(fo.av), m.qd, m.qinvd);
     else
-        res = csub(mul_shoup(uv + m.q - rv, fa.cst[i], m.q) + av, m.q);
+        res = csub(mul_shoup(fo.uv + m.q - rv, fa.cst[i], m.q) + fo.av, m.q);
     fa.out[o] = res;
 }
 
@@ -235,8 +250,13 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
     const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
     const unsigned bg = tile * BLK_PER_WG + blk; // block index within the limb
     typename A::V a[16];
+    FinOperands fo[EPI == EPI_FIN ? 16 : 1];
 #pragma unroll
     for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[bg * 256 + il + 16 * k]);
+    if (EPI == EPI_FIN) {
+#pragma unroll
+        for (int k = 0; k < 16; k++) fo[k] = fin_load<LOGN>(fa, slot, bg * 256 + il + 16 * k);
+    }
     ar.fwd16(a, LOGN - 8, bg, true);
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = ar.store_mid(a[k]);
@@ -253,7 +273,7 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
         const unsigned pos = bg * 256 + il + 16 * k;
         const u64 v = lds[tile_at(blk, il + 16 * k)];
         if (EPI == EPI_FIN)
-            fin_store<LOGN>(fa, T, slot, pos, v);
+            fin_store<LOGN>(fa, T, slot, pos, v, fo[k]);
         else
             limb[pos] = v;
     }
