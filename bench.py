@@ -35,14 +35,16 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # `--pmc WRITE_SIZE` runs of this command with --streams 1, scaled by the copy-kernel calibration
 # (2 x FETCH_SIZE + 1 x WRITE_SIZE; summary and calibration under profiles/).
 MEASURED_TRAFFIC_BYTES = {
-    "k_inner": 213533491,
-    "k_ntt_fwd_blocks_fin": 84031488,
-    "k_ntt_fwd_blocks": 132389683,
-    "k_ntt_fwd_cols_modup": 65295360,
-    "k_ntt_fwd_cols_moddown": 24819098,
-    "k_ntt_fwd_cols_rescale": 25800704,
-    "k_tensor": 88134451,
-    "k_ntt_inv_blocks": 19033600,
+    "k_inner_blocks": 366182604,
+    "k_ntt_fwd_blocks_fin": 141350502,
+    "k_ntt_fwd_blocks": 35458969,
+    "k_ntt_fwd_cols_modup": 79118745,
+    "k_ntt_fwd_cols_moddown": 32984268,
+    "k_ntt_fwd_cols_rescale": 135507865,
+    "k_ntt_fwd_cols": 269822361,
+    "k_tensor": 1409366425,
+    "k_ntt_inv_blocks": 40550604,
+    "k_ntt_inv_cols": 20910318,
 }
 
 
@@ -228,7 +230,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-train-step", action="store_true")
     ap.add_argument("--hmult-batch", type=int, default=16, help="ciphertext pairs per batched HMult call")
-    ap.add_argument("--streams", type=int, default=2, help="HIP streams for the independent operations of a step")
+    ap.add_argument("--streams", type=int, default=3, help="HIP streams for the independent operations of a step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
