@@ -77,7 +77,6 @@ class Workload:
         # the independent HMult operands, stored back to back so that one batched call covers them
         self.hm_a = torch.stack([self._uniform_ct(L) for _ in range(self.n_hmult)])
         self.hm_b = torch.stack([self._uniform_ct(L) for _ in range(self.n_hmult)])
-        self.hm_out = he.empty_batch(self.n_hmult, L)
         self.rs_out = he.empty_batch(self.n_hmult, L - 1)
         self.hm_chunk = hm_chunk
         # keys: uniform residues in key layout (throughput does not depend on the values)
@@ -124,8 +123,7 @@ class Workload:
         mark("ntt_pairs")
         for lo in range(0, self.n_hmult, self.hm_chunk):  # batched calls of hm_chunk ciphertext pairs
             hi = min(lo + self.hm_chunk, self.n_hmult)
-            he.hmult_relin_batch(self.relin, self.hm_a[lo:hi], self.hm_b[lo:hi], out=self.hm_out[lo:hi])
-            he.rescale_batch(self.hm_out[lo:hi], out=self.rs_out[lo:hi])
+            he.hmult_relin_rescale_batch(self.relin, self.hm_a[lo:hi], self.hm_b[lo:hi], out=self.rs_out[lo:hi])
         mark("hmult_relin_rescale")
         he.hrot_many(self.rot, self.hoist_in, outs=self.hoist_out)
         mark("hrot_hoisted")

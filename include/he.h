@@ -167,6 +167,13 @@ int32_t he_moddrop(he_ctx *ctx, const uint64_t *d_ct, int32_t in_level, uint64_t
  * unchanged.  d_out [2][level][N] may alias d_a or d_b. */
 int32_t he_hmult_relin(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a, const uint64_t *d_b, uint64_t *d_out,
                        int32_t level, void *d_ws, size_t ws_bytes, void *stream);
+/* Mult with the rescale that Section 2.2 attaches to it (level l -> l-1), in one call: the residues of
+ * he_rescale(he_hmult_relin(a, b)), bit for bit, with one forward transform per output limb instead of two
+ * (the ModDown and rescale corrections of a limb are transformed as one polynomial).  d_out is
+ * [2][level-1][N] and may alias d_a or d_b; level >= 2 (HE_ELEVEL otherwise).  Workspace as for
+ * he_hmult_relin (he_workspace_bytes). */
+int32_t he_hmult_relin_rescale(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a, const uint64_t *d_b,
+                               uint64_t *d_out, int32_t level, void *d_ws, size_t ws_bytes, void *stream);
 /* Drops the last limb with centred rounding: out[i] = (c[i] - [c_last centred]_{q_i}) / q_last.
  * d_out is [2][level-1][N] and must not alias d_ct. */
 int32_t he_rescale(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level, void *d_ws, size_t ws_bytes,
@@ -206,6 +213,10 @@ int32_t he_moddrop_batch(he_ctx *ctx, const uint64_t *d_ct, int32_t in_level, ui
                          int32_t count, void *stream);
 int32_t he_hmult_relin_batch(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a, const uint64_t *d_b,
                              uint64_t *d_out, int32_t level, int32_t count, void *d_ws, size_t ws_bytes, void *stream);
+/* Batched form of he_hmult_relin_rescale. */
+int32_t he_hmult_relin_rescale_batch(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a, const uint64_t *d_b,
+                                     uint64_t *d_out, int32_t level, int32_t count, void *d_ws, size_t ws_bytes,
+                                     void *stream);
 int32_t he_rescale_batch(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level, int32_t count, void *d_ws,
                          size_t ws_bytes, void *stream);
 int32_t he_hrot_batch(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level,

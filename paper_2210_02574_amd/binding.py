@@ -30,9 +30,9 @@ SYMBOLS = [
     "he_evk_from_host", "he_evk_to_host", "he_evk_destroy",
     "he_encode", "he_decode", "he_plain_to_ntt", "he_encrypt_coeffs", "he_decrypt_coeffs", "he_decrypt",
     "he_ntt", "he_intt", "he_add", "he_sub", "he_pmult", "he_cmult", "he_add_const", "he_moddrop",
-    "he_hmult_relin", "he_rescale", "he_hrot", "he_hrot_many", "he_rotate_sum",
+    "he_hmult_relin", "he_hmult_relin_rescale", "he_rescale", "he_hrot", "he_hrot_many", "he_rotate_sum",
     "he_add_batch", "he_sub_batch", "he_pmult_batch", "he_cmult_batch", "he_add_const_batch", "he_moddrop_batch",
-    "he_hmult_relin_batch", "he_rescale_batch", "he_hrot_batch", "he_rotate_sum_batch",
+    "he_hmult_relin_batch", "he_hmult_relin_rescale_batch", "he_rescale_batch", "he_hrot_batch", "he_rotate_sum_batch",
     "he_profile_start", "he_profile_stop",
 ]
 
@@ -103,6 +103,7 @@ def load_library() -> ctypes.CDLL:
             "he_add_const": [vp, vp, vp, vp, i32, vp],
             "he_moddrop": [vp, vp, i32, vp, i32, vp],
             "he_hmult_relin": [vp, vp, vp, vp, vp, i32, vp, sz, vp],
+            "he_hmult_relin_rescale": [vp, vp, vp, vp, vp, i32, vp, sz, vp],
             "he_rescale": [vp, vp, vp, i32, vp, sz, vp],
             "he_hrot": [vp, vp, vp, vp, i32, vp, sz, vp],
             "he_hrot_many": [vp, vp, i32, vp, vp, i32, vp, sz, vp],
@@ -114,6 +115,7 @@ def load_library() -> ctypes.CDLL:
             "he_add_const_batch": [vp, vp, vp, vp, i32, i32, vp],
             "he_moddrop_batch": [vp, vp, i32, vp, i32, i32, vp],
             "he_hmult_relin_batch": [vp, vp, vp, vp, vp, i32, i32, vp, sz, vp],
+            "he_hmult_relin_rescale_batch": [vp, vp, vp, vp, vp, i32, i32, vp, sz, vp],
             "he_rescale_batch": [vp, vp, vp, i32, i32, vp, sz, vp],
             "he_hrot_batch": [vp, vp, vp, vp, i32, i32, vp, sz, vp],
             "he_rotate_sum_batch": [vp, vp, i32, vp, i32, i32, vp, sz, vp],
@@ -416,6 +418,20 @@ class HE:
         )
         return out
 
+    def hmult_relin_rescale(self, relin: EvalKey, a, b, out=None):
+        """rescale(hmult_relin(a, b)) in one call (same residues)."""
+        level = self._level(a)
+        assert b.shape == a.shape
+        out = self.empty_ct(level - 1) if out is None else out
+        ws, wsb = self._workspace(level)
+        self._chk(
+            self.lib.he_hmult_relin_rescale(
+                self.ctx, relin.handle, self._dp(a), self._dp(b), self._dp(out), level, ws, wsb, self._stream()
+            ),
+            "he_hmult_relin_rescale",
+        )
+        return out
+
     def rescale(self, ct, out=None):
         level = self._level(ct)
         out = self.empty_ct(level - 1) if out is None else out
@@ -526,6 +542,16 @@ class HE:
         ws, wsb = self._workspace(level, count)
         self._chk(self.lib.he_hmult_relin_batch(self.ctx, relin.handle, self._dp(a), self._dp(b), self._dp(out), level,
                                                 count, ws, wsb, self._stream()), "he_hmult_relin_batch")
+        return out
+
+    def hmult_relin_rescale_batch(self, relin: EvalKey, a, b, out=None):
+        level, count = self._blevel(a)
+        assert b.shape == a.shape
+        out = self.empty_batch(count, level - 1) if out is None else out
+        ws, wsb = self._workspace(level, count)
+        self._chk(self.lib.he_hmult_relin_rescale_batch(self.ctx, relin.handle, self._dp(a), self._dp(b), self._dp(out),
+                                                        level, count, ws, wsb, self._stream()),
+                  "he_hmult_relin_rescale_batch")
         return out
 
     def rescale_batch(self, cts, out=None):

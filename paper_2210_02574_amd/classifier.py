@@ -165,7 +165,7 @@ class EncryptedTrainStep:
         return he.to_device(he.plain_to_ntt(he.encode(self.mask_slots(), p.mask_scale), p.level - 1))
 
     def _mul(self, relin, a, b):
-        return self.he.rescale(self.he.hmult_relin(relin, a, b))
+        return self.he.hmult_relin_rescale(relin, a, b)
 
     def _affine(self, ct, coeff: float, c_scale: float, const: float, t_scale: float):
         """rescale(coeff * ct) + const, landing on scale t_scale one level down."""
@@ -216,7 +216,7 @@ class EncryptedTrainStep:
     # ---- the same step with all ciphertexts of a class processed as one batch per library call ----------------
 
     def _mul_b(self, relin, a, b):
-        return self.he.rescale_batch(self.he.hmult_relin_batch(relin, a, b))
+        return self.he.hmult_relin_rescale_batch(relin, a, b)
 
     def _affine_b(self, cts, coeff: float, c_scale: float, const: float, t_scale: float):
         he = self.he
@@ -344,7 +344,7 @@ class EncryptedLogistic15:
         return he.add_const(out, _residues(c0, target, he.q, level - 1), out=out)
 
     def _mul(self, relin, a, b):
-        return self.he.rescale(self.he.hmult_relin(relin, a, b))
+        return self.he.hmult_relin_rescale(relin, a, b)
 
     def run(self, relin, t):
         he, c, l = self.he, self.c, self.level

@@ -54,7 +54,7 @@ int32_t dev_upload_tables(he_ctx *c)
     UP(tw_fwd) UP(tw_inv) UP(ninv) UP(twd_fwd) UP(twd_inv) UP(ninvd)
     UP(up_inv) UP(up_hat) UP(up_inv_d) UP(up_hat_d) UP(up_hat_dh)
     UP(dn_inv) UP(dn_hat) UP(dn_pinv) UP(dn_inv_d) UP(dn_hat_d) UP(dn_hat_dh) UP(dn_pinv_d) UP(dn_pmod) UP(dn_pmod_d)
-    UP(rs_inv) UP(rs_inv_d)
+    UP(rs_inv) UP(rs_inv_d) UP(rsp_inv) UP(rsp_inv_d)
 #undef UP
     c->dev.up_split = c->up_split ? 1 : 0;
     c->dev.dn_split = c->dn_split ? 1 : 0;
@@ -97,11 +97,13 @@ extern "C" int32_t he_evk_to_host(const he_evk *evk, uint64_t *h_out)
 
 // ---- optional per-kernel timing with HIP events on the launch stream (he_profile_start/stop)
 enum KernelId {
-    KID_FWD_COLS, KID_FWD_COLS_MODUP, KID_FWD_COLS_MODDOWN, KID_FWD_COLS_RESCALE, KID_FWD_BLOCKS, KID_FWD_BLOCKS_FIN,
+    KID_FWD_COLS, KID_FWD_COLS_MODUP, KID_FWD_COLS_MODDOWN, KID_FWD_COLS_RESCALE, KID_FWD_COLS_MODDOWN_RS, KID_FWD_BLOCKS,
+    KID_FWD_BLOCKS_FIN,
     KID_INV_BLOCKS, KID_INV_COLS, KID_LIMBWISE, KID_CMULT, KID_TENSOR, KID_INNER, KID_COUNT
 };
 static const char *const kKernelNames[KID_COUNT] = {
-    "k_ntt_fwd_cols", "k_ntt_fwd_cols_modup", "k_ntt_fwd_cols_moddown", "k_ntt_fwd_cols_rescale", "k_ntt_fwd_blocks",
+    "k_ntt_fwd_cols", "k_ntt_fwd_cols_modup", "k_ntt_fwd_cols_moddown", "k_ntt_fwd_cols_rescale", "k_ntt_fwd_cols_moddown_rescale",
+    "k_ntt_fwd_blocks",
     "k_ntt_fwd_blocks_fin", "k_ntt_inv_blocks", "k_ntt_inv_cols", "k_limbwise", "k_cmult", "k_tensor", "k_inner_blocks"};
 
 static bool prof_events(he_ctx *c, int kid, double bytes, ProfRecord &r)
@@ -228,10 +230,23 @@ static ConvArgs conv_args(const he_ctx *c, const u64 *src, int level, int dst_st
     cv.alpha = c->alpha;
     cv.dst_stride = dst_stride;
     cv.src_stride = src_stride;
+    cv.src2 = nullptr;
+    cv.src2_stride = 0;
     return cv;
 }
 
-static const FinArgs kNoFin = {nullptr, nullptr, nullptr, nullptr, nullptr, 0, 1, 0, 1u, 1 << 30, 0, 0, 0};
+static FinArgs fin_args(const u64 *u, u64 *out, const u64 *add, const ShoupConst *cst, const double *cst_d, int u_cstride,
+                        int nl, int mode, unsigned g, int dst_stride, int u_stride, int out_stride, int add_stride)
+{
+    FinArgs fa;
+    fa.u = u, fa.out = out, fa.add = add;
+    fa.cst = cst, fa.cst_d = cst_d, fa.cst2 = nullptr, fa.cst2_d = nullptr;
+    fa.u_cstride = u_cstride, fa.out_cstride = nl, fa.add_cstride = nl, fa.nl = nl, fa.mode = mode;
+    fa.g = g;
+    fa.dst_stride = dst_stride, fa.u_stride = u_stride, fa.out_stride = out_stride, fa.add_stride = add_stride;
+    return fa;
+}
+static const FinArgs kNoFin = fin_args(nullptr, nullptr, nullptr, nullptr, nullptr, 0, 1, 0, 1u, 1 << 30, 0, 0, 0);
 
 // Forward NTT of the listed limbs of `data`.  pro selects what the column pass transforms (the
 // limb's own content, or a base conversion of cv.src); with fin != nullptr the block pass writes
@@ -249,6 +264,7 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
         const int kid_cols = pro == PRO_LOAD      ? KID_FWD_COLS
                              : pro == PRO_MODUP   ? KID_FWD_COLS_MODUP
                              : pro == PRO_MODDOWN ? KID_FWD_COLS_MODDOWN
+                             : pro == PRO_MODDOWN_RS ? KID_FWD_COLS_MODDOWN_RS
                                                   : KID_FWD_COLS_RESCALE;
 #define COLS1(KERN, GRID, P, NS)                                                                                     \
     KLAUNCH(c, st, kid_cols, cols_bytes, (KERN<P, NS>), GRID, data, c->dev, lb, cv)
@@ -266,6 +282,12 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
             COLS1(KERN, GRID, PRO_MODDOWN, 8);                                                                      \
         else                                                                                                         \
             COLS1(KERN, GRID, PRO_MODDOWN, 4);                                                                       \
+        break;                                                                                                       \
+    case PRO_MODDOWN_RS:                                                                                             \
+        if (wide)                                                                                                    \
+            COLS1(KERN, GRID, PRO_MODDOWN_RS, 8);                                                                   \
+        else                                                                                                         \
+            COLS1(KERN, GRID, PRO_MODDOWN_RS, 4);                                                                    \
         break;                                                                                                       \
     default: COLS1(KERN, GRID, PRO_RESCALE, 4); break;                                                               \
     }
@@ -552,11 +574,9 @@ static int32_t ks_raise(he_ctx *c, const u64 *d_ntt, int d_stride, u64 *ws, cons
     return ntt_forward(c, st, ws + w.raised * N, r, PRO_MODUP, cv, nullptr, level * count, true);
 }
 
-// Steps 3-5.  Operation o writes out + o*out_stride limbs; mode / c0 (+ o*c0_stride): the addend of
-// the final step (see FinArgs).
-static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_stride, u64 *ws, const WsLayout &w,
-                        int level, int count, u64 *out, int out_stride, const u64 *c0, int c0_stride, int mode,
-                        hipStream_t st)
+// Step 3 and the inverse transform of step 4: u and, in its special limbs, the scaled coefficient-domain digits.
+static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_stride, u64 *ws, const WsLayout &w,
+                        int level, int count, hipStream_t st)
 {
     const size_t N = c->N;
     const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha, W = (int)w.total;
@@ -579,26 +599,27 @@ static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
         for (int cc = 0; cc < 2; cc++)
             for (int k = 0; k < K; k++) sp.add(o * W + cc * Ma + level + k, c->L + k);
     const ConvArgs cv = conv_args(c, ws + w.u * N, level, W, W);
-    if ((rc = ntt_inverse(c, st, ws + w.u * N, ws + w.u * N, sp, SCALE_MODDOWN, cv, true)) != HE_OK) return rc;
+    return ntt_inverse(c, st, ws + w.u * N, ws + w.u * N, sp, SCALE_MODDOWN, cv, true);
+}
+
+// Steps 3-5.  Operation o writes out + o*out_stride limbs; mode / c0 (+ o*c0_stride): the addend of
+// the final step (see FinArgs).
+static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_stride, u64 *ws, const WsLayout &w,
+                        int level, int count, u64 *out, int out_stride, const u64 *c0, int c0_stride, int mode,
+                        hipStream_t st)
+{
+    const size_t N = c->N;
+    const int Ma = level + c->K, W = (int)w.total;
+    int32_t rc = ks_inner(c, evk, d_ntt, d_stride, ws, w, level, count, st);
+    if (rc != HE_OK) return rc;
+    const ConvArgs cv = conv_args(c, ws + w.u * N, level, W, W);
     LimbList r;
     for (int o = 0; o < count; o++)
         for (int cc = 0; cc < 2; cc++)
             for (int i = 0; i < level; i++) r.add(o * W + cc * level + i, i);
-    FinArgs fa;
-    fa.u = ws + w.u * N;
-    fa.out = out;
-    fa.add = c0;
-    fa.cst = c->dev.dn_pinv;
-    fa.cst_d = c->dev.dn_pinv_d;
-    fa.u_cstride = Ma;
-    fa.nl = level;
-    fa.mode = mode;
-    fa.g = g;
-    fa.dst_stride = W;
-    fa.u_stride = W;
-    fa.out_stride = out_stride;
-    fa.add_stride = c0_stride;
-    return ntt_forward(c, st, ws + w.r * N, r, PRO_MODDOWN, cv, &fa, 2 * K * count);
+    const FinArgs fa = fin_args(ws + w.u * N, out, c0, c->dev.dn_pinv, c->dev.dn_pinv_d, Ma, level, mode,
+                                (unsigned)evk->galois, W, W, out_stride, c0_stride);
+    return ntt_forward(c, st, ws + w.r * N, r, PRO_MODDOWN, cv, &fa, 2 * c->K * count);
 }
 
 static int32_t ks_guard(he_ctx *c, const he_evk *evk, int level, int count, void *ws, size_t ws_bytes)
@@ -628,7 +649,7 @@ extern "C" int32_t he_hmult_relin_batch(he_ctx *ctx, const he_evk *relin, const 
     const int W = (int)w.total;
     dim3 grid((unsigned)(N / 256), (unsigned)level, (unsigned)count);
     KLAUNCH(ctx, st, KID_TENSOR, 7.0 * count * level * N * 8.0, (k_tensor), grid, d_a, d_b, d_out, ws + w.d * N, ctx->dev,
-            level, ctx->logN, W);
+            level, ctx->logN, W, 2 * level);
     if ((rc = launch_ok(ctx)) != HE_OK) return rc;
     if ((rc = ks_raise(ctx, ws + w.d * N, W, ws, w, level, count, st)) != HE_OK) return rc;
     return ks_apply(ctx, relin, ws + w.d * N, W, ws, w, level, count, d_out, 2 * level, nullptr, 0, 1, st);
@@ -638,6 +659,60 @@ extern "C" int32_t he_hmult_relin(he_ctx *ctx, const he_evk *relin, const uint64
                                   uint64_t *d_out, int32_t level, void *d_ws, size_t ws_bytes, void *stream)
 {
     return he_hmult_relin_batch(ctx, relin, d_a, d_b, d_out, level, 1, d_ws, ws_bytes, stream);
+}
+
+// Mult followed by rescale with one forward transform per output limb.  After the inner product: ModDown of
+// the last limb alone (c_last = (u - ntt(r)) P^-1 + d), its inverse transform t, then for every other limb
+// the column pass transforms r + P t_centred and the block pass finishes (u - ntt) (P q_l)^-1 + d q_l^-1.
+extern "C" int32_t he_hmult_relin_rescale_batch(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a,
+                                                const uint64_t *d_b, uint64_t *d_out, int32_t level, int32_t count,
+                                                void *d_ws, size_t ws_bytes, void *stream)
+{
+    int32_t rc = ks_guard(ctx, relin, level, count, d_ws, ws_bytes);
+    if (rc != HE_OK) return rc;
+    if (relin->galois != 1) return HE_ENOKEY;
+    if (level < 2) return HE_ELEVEL;
+    if (!d_a || !d_b || !d_out) return HE_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    u64 *ws = (u64 *)d_ws;
+    const WsLayout w = ws_layout(ctx, level);
+    const size_t N = ctx->N;
+    const int W = (int)w.total, K = ctx->K, Ma = level + K, L = ctx->L;
+    u64 *d01 = ws + w.tmp * N; // per operation [2][level][N]: d0, d1 of the tensor product
+    dim3 grid((unsigned)(N / 256), (unsigned)level, (unsigned)count);
+    KLAUNCH(ctx, st, KID_TENSOR, 7.0 * count * level * N * 8.0, (k_tensor), grid, d_a, d_b, d01, ws + w.d * N, ctx->dev,
+            level, ctx->logN, W, W);
+    if ((rc = launch_ok(ctx)) != HE_OK) return rc;
+    if ((rc = ks_raise(ctx, ws + w.d * N, W, ws, w, level, count, st)) != HE_OK) return rc;
+    if ((rc = ks_inner(ctx, relin, ws + w.d * N, W, ws, w, level, count, st)) != HE_OK) return rc;
+    u64 *rbuf = ws + w.r * N;
+    ConvArgs cv = conv_args(ctx, ws + w.u * N, level, W, W);
+    cv.src2 = rbuf;
+    cv.src2_stride = W;
+    // ModDown of the last limb of both components, in place in the correction buffer
+    LimbList last;
+    for (int o = 0; o < count; o++)
+        for (int cc = 0; cc < 2; cc++) last.add(o * W + cc * level + level - 1, level - 1);
+    FinArgs fl = fin_args(ws + w.u * N, rbuf, d01, ctx->dev.dn_pinv, ctx->dev.dn_pinv_d, Ma, level, 3, 1u, W, W, W, W);
+    if ((rc = ntt_forward(ctx, st, rbuf, last, PRO_MODDOWN, cv, &fl, 2 * K * count)) != HE_OK) return rc;
+    if ((rc = ntt_inverse(ctx, st, rbuf, rbuf, last, SCALE_NONE, cv)) != HE_OK) return rc;
+    // every other limb: ModDown and rescale corrections in one transform
+    LimbList rest;
+    for (int o = 0; o < count; o++)
+        for (int cc = 0; cc < 2; cc++)
+            for (int i = 0; i < level - 1; i++) rest.add(o * W + cc * level + i, i);
+    FinArgs fa = fin_args(ws + w.u * N, d_out, d01, ctx->dev.rsp_inv + (size_t)(level - 1) * L,
+                          ctx->dev.rsp_inv_d + (size_t)(level - 1) * L, Ma, level, 3, 1u, W, W, 2 * (level - 1), W);
+    fa.out_cstride = level - 1;
+    fa.cst2 = ctx->dev.rs_inv + (size_t)(level - 1) * L;
+    fa.cst2_d = ctx->dev.rs_inv_d + (size_t)(level - 1) * L;
+    return ntt_forward(ctx, st, rbuf, rest, PRO_MODDOWN_RS, cv, &fa, (2 * K + 2) * count);
+}
+
+extern "C" int32_t he_hmult_relin_rescale(he_ctx *ctx, const he_evk *relin, const uint64_t *d_a, const uint64_t *d_b,
+                                          uint64_t *d_out, int32_t level, void *d_ws, size_t ws_bytes, void *stream)
+{
+    return he_hmult_relin_rescale_batch(ctx, relin, d_a, d_b, d_out, level, 1, d_ws, ws_bytes, stream);
 }
 
 extern "C" int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t count, const uint64_t *d_ct,
@@ -741,20 +816,9 @@ extern "C" int32_t he_rescale_batch(he_ctx *ctx, const uint64_t *d_ct, uint64_t 
     for (int o = 0; o < count; o++)
         for (int c = 0; c < 2; c++)
             for (int i = 0; i < level - 1; i++) l.add(o * W + c * (level - 1) + i, i);
-    FinArgs fa;
-    fa.u = d_ct;
-    fa.out = d_out;
-    fa.add = nullptr;
-    fa.cst = ctx->dev.rs_inv + (size_t)(level - 1) * ctx->L;
-    fa.cst_d = ctx->dev.rs_inv_d + (size_t)(level - 1) * ctx->L;
-    fa.u_cstride = level;
-    fa.nl = level - 1;
-    fa.mode = 0;
-    fa.g = 1;
-    fa.dst_stride = W;
-    fa.u_stride = 2 * level;
-    fa.out_stride = 2 * (level - 1);
-    fa.add_stride = 0;
+    const FinArgs fa = fin_args(d_ct, d_out, nullptr, ctx->dev.rs_inv + (size_t)(level - 1) * ctx->L,
+                                ctx->dev.rs_inv_d + (size_t)(level - 1) * ctx->L, level, level - 1, 0, 1u, W, 2 * level,
+                                2 * (level - 1), 0);
     return ntt_forward(ctx, st, r, l, PRO_RESCALE, cv, &fa, 2 * count);
 }
 

@@ -57,6 +57,9 @@ struct DevTables {
     // Rescale: q_l^-1 mod q_i
     const ShoupConst *rs_inv;  // [L][L]
     const double *rs_inv_d;    // [L][L]
+    // ModDown and rescale in one step: (P q_l)^-1 mod q_i
+    const ShoupConst *rsp_inv; // [L][L]
+    const double *rsp_inv_d;   // [L][L]
 };
 
 struct ProfRecord {
@@ -78,13 +81,13 @@ struct he_ctx {
     std::vector<double> twd_fwd, twd_inv, ninvd;
     std::vector<ShoupConst> up_inv;
     std::vector<u64> up_hat;
-    std::vector<double> up_inv_d, up_hat_d, up_hat_dh, dn_inv_d, dn_hat_d, dn_hat_dh, dn_pinv_d, dn_pmod_d, rs_inv_d;
+    std::vector<double> up_inv_d, up_hat_d, up_hat_dh, dn_inv_d, dn_hat_d, dn_hat_dh, dn_pinv_d, dn_pmod_d, rs_inv_d, rsp_inv_d;
     std::vector<u64> dn_pmod;
     bool up_split = false, dn_split = false;
     std::vector<ShoupConst> dn_inv;
     std::vector<u64> dn_hat;
     std::vector<ShoupConst> dn_pinv;
-    std::vector<ShoupConst> rs_inv;
+    std::vector<ShoupConst> rs_inv, rsp_inv;
     // encode/decode tables
     std::vector<double> root_re, root_im; // exp(i pi e / N), e < 2N
     std::vector<uint32_t> slot_exp;       // 5^j mod 2N

@@ -298,6 +298,12 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
     for (int l = 0; l < L; l++)
         for (int i = 0; i < L; i++)
             if (i != l) c->rs_inv[(size_t)l * L + i] = shoup(inv_mod(c->mod[l] % c->mod[i], c->mod[i]), c->mod[i]);
+    c->rsp_inv.assign((size_t)L * L, ShoupConst{0, 0});
+    for (int l = 0; l < L; l++)
+        for (int i = 0; i < L; i++)
+            if (i != l)
+                c->rsp_inv[(size_t)l * L + i] =
+                    shoup(mul_mod(c->rs_inv[(size_t)l * L + i].w, c->dn_pinv[i].w, c->mod[i]), c->mod[i]);
     // balanced-double images of the conversion constants for moduli below 2^50
     {
         const u64 kFp = (u64)1 << 50;
@@ -332,6 +338,7 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
         c->dn_pmod_d.assign(L, 0.0);
         for (int i = 0; i < L; i++) c->dn_pmod[i] = prod_mod_excluding(c->mod, L, M, -1, c->mod[i]);
         c->rs_inv_d.assign((size_t)L * L, 0.0);
+        c->rsp_inv_d.assign((size_t)L * L, 0.0);
         for (int k = 0; k < K; k++) {
             if (c->mod[L + k] < kFp) c->dn_inv_d[k] = bal(c->dn_inv[k].w, c->mod[L + k]);
             for (int i = 0; i < L; i++) {
@@ -348,7 +355,10 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
             c->dn_pinv_d[i] = bal(c->dn_pinv[i].w, t);
             c->dn_pmod_d[i] = bal(c->dn_pmod[i], t);
             for (int l = 0; l < L; l++)
-                if (l != i) c->rs_inv_d[(size_t)l * L + i] = bal(c->rs_inv[(size_t)l * L + i].w, t);
+                if (l != i) {
+                    c->rs_inv_d[(size_t)l * L + i] = bal(c->rs_inv[(size_t)l * L + i].w, t);
+                    c->rsp_inv_d[(size_t)l * L + i] = bal(c->rsp_inv[(size_t)l * L + i].w, t);
+                }
         }
     }
     // encode/decode tables

@@ -51,15 +51,17 @@ __global__ __launch_bounds__(256) void k_addconst(const u64 *__restrict__ a, u64
 }
 
 // Tensor product: d0 = a0 b0, d1 = a0 b1 + a1 b0 -> out (may alias A or B); d2 = a1 b1 -> d2.
-// blockIdx.z = operation of a batch: ciphertexts 2*level limbs apart, d2 buffers d2_stride limbs apart.
+// blockIdx.z = operation of a batch: input ciphertexts 2*level limbs apart, out buffers out_stride and d2
+// buffers d2_stride limbs apart.
 __global__ __launch_bounds__(256) void k_tensor(const u64 *A, const u64 *B, u64 *out, u64 *__restrict__ d2,
-                                                DevTables T, int level, int logN, int d2_stride)
+                                                DevTables T, int level, int logN, int d2_stride, int out_stride)
 {
     const unsigned i = blockIdx.y;
     const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
     const ModConst m = T.mod[i];
     const size_t ct_off = ((size_t)blockIdx.z * 2 * level) << logN;
-    A += ct_off, B += ct_off, out += ct_off;
+    A += ct_off, B += ct_off;
+    out += ((size_t)blockIdx.z * out_stride) << logN;
     d2 += ((size_t)blockIdx.z * d2_stride) << logN;
     const size_t o0 = ((size_t)i << logN) + n, o1 = ((size_t)(level + i) << logN) + n;
     const u64 a0 = A[o0], a1 = A[o1], b0 = B[o0], b1 = B[o1];

@@ -15,7 +15,10 @@
 //    centred residue of a dropped limb (rescale);
 //  * the inverse column pass can fold (D/q_i)^-1 or (P/p_k)^-1 into its 1/N scaling, so it emits
 //    the y values those sums need;
-//  * the forward block pass can finish ModDown / rescale: out = (u - ntt) * const + addend.
+//  * the forward block pass can finish ModDown / rescale: out = (u - ntt) * const + addend;
+//  * ModDown followed by rescale takes one transform per limb instead of two: with t the centred dropped
+//    limb of the ModDown result, NTT(r) P^-1 + NTT(t) = NTT(r + P t) P^-1, so the column pass transforms
+//    r + P t and the block pass finishes out = (u - ntt) (P q_l)^-1 + d q_l^-1.
 #pragma once
 #include "arith.h"
 
@@ -28,7 +31,8 @@ struct LimbBatch {
     uint8_t mod[HE_MAXB];
 };
 
-enum { PRO_LOAD = 0, PRO_MODUP = 1, PRO_MODDOWN = 2, PRO_RESCALE = 3 };
+enum { PRO_LOAD = 0, PRO_MODUP = 1, PRO_MODDOWN = 2, PRO_RESCALE = 3, PRO_MODDOWN_RS = 4 };
+__host__ __device__ constexpr bool pro_is_moddown(int pro) { return pro == PRO_MODDOWN || pro == PRO_MODDOWN_RS; }
 enum { SCALE_NONE = 0, SCALE_MODUP = 1, SCALE_MODDOWN = 2 };
 enum { EPI_STORE = 0, EPI_FIN = 1 };
 
@@ -39,15 +43,22 @@ struct ConvArgs {
     int level, L, K, alpha;
     int dst_stride; // limbs between two operations in the buffer being transformed
     int src_stride; // limbs between two operations in src
+    // ModDown + rescale: the dropped limb of component c (coefficient domain) at src2 + (c*level + level-1) limbs
+    const u64 *src2;
+    int src2_stride;
 };
 
+// A limb's slot within its operation decodes as component c = slot / nl, limb i = slot % nl.
 struct FinArgs {
     const u64 *u;   // minuend limbs, component stride u_cstride limbs
-    u64 *out;       // [2][nl][N]
-    const u64 *add; // mode 2: c0 limbs [nl][N], read through the automorphism index map
-    const ShoupConst *cst;
-    const double *cst_d;
-    int u_cstride, nl, mode; // mode 0: no addend; 1: add what `out` holds; 2: add sigma_g(c0) to component 0
+    u64 *out;       // component stride out_cstride limbs
+    const u64 *add; // mode 2: c0 limbs [nl][N], read through the automorphism index map; mode 3: component
+                    // stride add_cstride limbs
+    const ShoupConst *cst, *cst2;
+    const double *cst_d, *cst2_d;
+    // mode 0: no addend; 1: add what `out` holds; 2: add sigma_g(c0) to component 0; 3: add the limb of `add`
+    // times cst2 (cst2 == nullptr: as it is)
+    int u_cstride, out_cstride, add_cstride, nl, mode;
     unsigned g;
     int dst_stride, u_stride, out_stride, add_stride; // limbs between two operations in each buffer
 };
@@ -76,6 +87,7 @@ template <int NSMAX> struct ConvSetup {
     // rescale
     u64 ql, half;
     double qld;
+    const u64 *tp; // ModDown + rescale: the dropped limb of this component
 };
 
 // slot = position of the limb in the destination buffer; mi = its modulus index
@@ -87,6 +99,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
     S.qld = 0.0;
     S.pm_i = 0;
     S.pm_d = 0.0;
+    S.tp = nullptr;
     const int M = cv.L + cv.K, Ma = cv.level + cv.K;
     const unsigned op = slot / (unsigned)cv.dst_stride;
     slot -= op * (unsigned)cv.dst_stride;
@@ -112,7 +125,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
             S.cd[s] = on ? T.up_hat_d[ci] : 0.0;
             S.cdh[s] = on ? T.up_hat_dh[ci] : 0.0;
         }
-    } else if (PRO == PRO_MODDOWN) {
+    } else if (pro_is_moddown(PRO)) {
         const int c = slot / cv.level, i = slot % cv.level;
 #pragma unroll
         for (int s = 0; s < NSMAX; s++) {
@@ -126,6 +139,12 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
         }
         S.pm_i = T.dn_pmod[i];
         S.pm_d = T.dn_pmod_d[i];
+        if (PRO == PRO_MODDOWN_RS) {
+            S.tp = cv.src2 + (((size_t)op * cv.src2_stride + (size_t)c * cv.level + cv.level - 1) << LOGN);
+            S.ql = T.mod[cv.level - 1].q;
+            S.half = (S.ql - 1) / 2;
+            S.qld = T.mod[cv.level - 1].qd;
+        }
     } else if (PRO == PRO_RESCALE) {
         const int c = slot / (cv.level - 1);
         S.sp[0] = src + ((size_t)c << LOGN);
@@ -152,7 +171,7 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
 #pragma unroll
     for (int s = 0; s < NSMAX; s++) {
         const u64 y = S.sp[s][pos];
-        if (PRO == PRO_MODDOWN) neg += y > S.hs[s] ? 1 : 0;
+        if (pro_is_moddown(PRO)) neg += y > S.hs[s] ? 1 : 0;
         if (!SPLIT)
             acc += ar.mulmod(u2d(y), S.cd[s]);
         else {
@@ -161,9 +180,21 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
         }
         if ((s & 3) == 3 && s + 1 < NSMAX) acc = ar.reduce(acc);
     }
-    if (PRO == PRO_MODDOWN) {
+    if (pro_is_moddown(PRO)) {
         if (NSMAX > 4) acc = ar.reduce(acc);
         acc -= (double)neg * S.pm_d; // p_s * (P/p_s) = P for every centred digit
+    }
+    if (PRO == PRO_MODDOWN_RS) { // + P t with t the centred dropped limb
+        const u64 tv = S.tp[pos];
+        double tc;
+        if (S.qld != 0.0)
+            tc = u2d(tv) - (tv > S.half ? S.qld : 0.0);
+        else {
+            const bool tneg = tv > S.half;
+            const double w = u2d(reduce64(tneg ? S.ql - tv : tv, m));
+            tc = tneg ? -w : w;
+        }
+        acc += ar.mulmod(tc, S.pm_d);
     }
     return acc;
 }
@@ -183,10 +214,17 @@ __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithIn
     for (int s = 0; s < NSMAX; s++) {
         const u64 y = S.sp[s][pos];
         mac128(acc, y, S.ci[s]);
-        if (PRO == PRO_MODDOWN) corr = csub(corr + (y > S.hs[s] ? S.pm_i : 0), m.q);
+        if (pro_is_moddown(PRO)) corr = csub(corr + (y > S.hs[s] ? S.pm_i : 0), m.q);
     }
-    const u64 r = reduce128(acc, m);
-    return PRO == PRO_MODDOWN ? csub(r + m.q - corr, m.q) : r;
+    u64 r = reduce128(acc, m);
+    if (pro_is_moddown(PRO)) r = csub(r + m.q - corr, m.q);
+    if (PRO == PRO_MODDOWN_RS) {
+        const u64 tv = S.tp[pos];
+        const bool tneg = tv > S.half;
+        const u64 pw = mul_mod(reduce64(tneg ? S.ql - tv : tv, m), S.pm_i, m);
+        r = tneg ? csub(r + m.q - pw, m.q) : csub(r + pw, m.q);
+    }
+    return r;
 }
 
 // ---- epilogue: what the forward block pass does with a finished (canonical) NTT value ---------------------
@@ -205,9 +243,11 @@ __device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, unsigned slot
     o.uv = fa.u[(((size_t)op * fa.u_stride + (size_t)c * fa.u_cstride + i) << LOGN) + pos];
     o.av = 0;
     if (fa.mode == 1)
-        o.av = fa.out[(((size_t)op * fa.out_stride + slot) << LOGN) + pos];
+        o.av = fa.out[(((size_t)op * fa.out_stride + (size_t)c * fa.out_cstride + i) << LOGN) + pos];
     else if (fa.mode == 2 && c == 0)
         o.av = fa.add[(((size_t)op * fa.add_stride + i) << LOGN) + galois_index(pos, fa.g, LOGN)];
+    else if (fa.mode == 3)
+        o.av = fa.add[(((size_t)op * fa.add_stride + (size_t)c * fa.add_cstride + i) << LOGN) + pos];
     return o;
 }
 
@@ -217,14 +257,18 @@ __device__ __forceinline__ void fin_store(const FinArgs &fa, const DevTables &T,
 {
     const unsigned op = slot / (unsigned)fa.dst_stride;
     slot -= op * (unsigned)fa.dst_stride;
-    const unsigned i = slot % fa.nl;
+    const unsigned c = slot / fa.nl, i = slot % fa.nl;
     const ModConst m = T.mod[i];
-    const size_t o = (((size_t)op * fa.out_stride + slot) << LOGN) + pos;
+    const size_t o = (((size_t)op * fa.out_stride + (size_t)c * fa.out_cstride + i) << LOGN) + pos;
+    const bool scaled = fa.mode == 3 && fa.cst2 != nullptr;
     u64 res;
-    if (m.qd != 0.0)
-        res = fp_canon(fp_mulmod(u2d(fo.uv) - u2d(rv), fa.cst_d[i], m.qd, m.qinvd) + u2d(fo.av), m.qd, m.qinvd);
-    else
-        res = csub(mul_shoup(fo.uv + m.q - rv, fa.cst[i], m.q) + fo.av, m.q);
+    if (m.qd != 0.0) {
+        const double av = scaled ? fp_mulmod(u2d(fo.av), fa.cst2_d[i], m.qd, m.qinvd) : u2d(fo.av);
+        res = fp_canon(fp_mulmod(u2d(fo.uv) - u2d(rv), fa.cst_d[i], m.qd, m.qinvd) + av, m.qd, m.qinvd);
+    } else {
+        const u64 av = scaled ? mul_shoup(fo.av, fa.cst2[i], m.q) : fo.av;
+        res = csub(mul_shoup(fo.uv + m.q - rv, fa.cst[i], m.q) + av, m.q);
+    }
     fa.out[o] = res;
 }
 
@@ -386,7 +430,7 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols16(u64 *__restrict__ data, 
     u64 *limb = data + ((size_t)slot << 16);
     const ModConst m = T.mod[mi];
     const ConvSetup<NSMAX> S = conv_setup<PRO, NSMAX, 16>(cv, T, slot, mi);
-    const bool split = PRO == PRO_MODUP ? T.up_split != 0 : PRO == PRO_MODDOWN ? T.dn_split != 0 : false;
+    const bool split = PRO == PRO_MODUP ? T.up_split != 0 : pro_is_moddown(PRO) ? T.dn_split != 0 : false;
     if (m.qd == 0.0)
         fwd_cols16_body<PRO, false>(limb, tile * 16, make_int(T, mi, 16), lds, S, m);
     else if (split)
@@ -461,7 +505,7 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols12(u64 *__restrict__ data, 
     u64 *limb = data + ((size_t)slot << 12);
     const ModConst m = T.mod[mi];
     const ConvSetup<NSMAX> S = conv_setup<PRO, NSMAX, 12>(cv, T, slot, mi);
-    const bool split = PRO == PRO_MODUP ? T.up_split != 0 : PRO == PRO_MODDOWN ? T.dn_split != 0 : false;
+    const bool split = PRO == PRO_MODUP ? T.up_split != 0 : pro_is_moddown(PRO) ? T.dn_split != 0 : false;
     if (m.qd == 0.0)
         fwd_cols12_body<PRO, false>(limb, make_int(T, mi, 12), S, m);
     else if (split)

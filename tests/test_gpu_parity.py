@@ -125,6 +125,33 @@ def test_hmult_relin_and_rescale(env):
     assert np.array_equal(he.to_host(da), o.hmult_relin(a, b, evk))
 
 
+def test_hmult_relin_rescale_in_one_call(env):
+    """The fused Mult + rescale against the oracle's rescale(hmult_relin(a, b)) on every residue, and the
+    batched form against the single one."""
+    import torch
+
+    he, o, p = env.he, env.o, env.params
+    key, evk = env.synth_key(301, 1)
+    for level in [l for l in _levels(p) if l >= 2]:
+        a, b = wl.uniform_ct(1402 + level, p, level), wl.uniform_ct(1502 + level, p, level)
+        da, db = he.to_device(a), he.to_device(b)
+        got = he.to_host(he.hmult_relin_rescale(key, da, db))
+        want = o.rescale(o.hmult_relin(a, b, evk))
+        assert got.shape == (2, level - 1, p.N)
+        assert np.array_equal(got, want), level
+    level = _levels(p)[0]
+    count = 3
+    a = torch.stack([he.to_device(wl.uniform_ct(1600 + i, p, level)) for i in range(count)])
+    b = torch.stack([he.to_device(wl.uniform_ct(1700 + i, p, level)) for i in range(count)])
+    outb = he.hmult_relin_rescale_batch(key, a, b)
+    for i in range(count):
+        assert torch.equal(outb[i], he.rescale(he.hmult_relin(key, a[i], b[i]))), i
+    with pytest.raises(Exception) as ei:
+        one = he.to_device(wl.uniform_ct(1800, p, 1))
+        he.hmult_relin_rescale(key, one, one, out=he.empty_ct(1))
+    assert "HE_ELEVEL" in str(ei.value)
+
+
 def test_hrot_single_and_hoisted(env):
     he, o, p = env.he, env.o, env.params
     rots = [1, 5, p.N // 4] if p.logN == 12 else [1, 1 << 14]
