@@ -239,9 +239,9 @@ static FinArgs fin_args(const u64 *u, u64 *out, const u64 *add, const ShoupConst
                         int nl, int mode, unsigned g, int dst_stride, int u_stride, int out_stride, int add_stride)
 {
     FinArgs fa;
-    fa.u = u, fa.out = out, fa.add = add;
+    fa.u = u, fa.out = out, fa.add = add, fa.self = nullptr;
     fa.cst = cst, fa.cst_d = cst_d, fa.cst2 = nullptr, fa.cst2_d = nullptr;
-    fa.u_cstride = u_cstride, fa.out_cstride = nl, fa.add_cstride = nl, fa.nl = nl, fa.mode = mode;
+    fa.u_cstride = u_cstride, fa.out_cstride = nl, fa.add_cstride = nl, fa.self_stride = 0, fa.nl = nl, fa.mode = mode;
     fa.g = g;
     fa.dst_stride = dst_stride, fa.u_stride = u_stride, fa.out_stride = out_stride, fa.add_stride = add_stride;
     return fa;
@@ -300,7 +300,7 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
 #undef COLS1
         if (fin) {
             // reads the transform's input, the minuend and the addend, writes the result
-            const double b = (double)nb * N8 * (3.0 + (fin->mode == 1 ? 1.0 : fin->mode == 2 ? 0.5 : 0.0));
+            const double b = (double)nb * N8 * (3.0 + (fin->mode == 1 || fin->mode == 3 ? 1.0 : fin->mode == 2 ? 0.5 : fin->mode == 4 ? 1.5 : 0.0));
             if (c->logN == 16)
                 KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<16, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin);
             else
@@ -617,8 +617,9 @@ static int32_t ks_apply(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
     for (int o = 0; o < count; o++)
         for (int cc = 0; cc < 2; cc++)
             for (int i = 0; i < level; i++) r.add(o * W + cc * level + i, i);
-    const FinArgs fa = fin_args(ws + w.u * N, out, c0, c->dev.dn_pinv, c->dev.dn_pinv_d, Ma, level, mode,
-                                (unsigned)evk->galois, W, W, out_stride, c0_stride);
+    FinArgs fa = fin_args(ws + w.u * N, out, c0, c->dev.dn_pinv, c->dev.dn_pinv_d, Ma, level, mode,
+                          (unsigned)evk->galois, W, W, out_stride, c0_stride);
+    if (mode == 4) fa.self = c0, fa.self_stride = c0_stride; // c0 points at the whole input ciphertext [2][level][N]
     return ntt_forward(c, st, ws + w.r * N, r, PRO_MODDOWN, cv, &fa, 2 * c->K * count);
 }
 
@@ -736,9 +737,10 @@ extern "C" int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t 
     return HE_OK;
 }
 
-// out: operation o at d_out + o*out_stride limbs
-static int32_t hrot_batch_to(he_ctx *ctx, const he_evk *rot, const u64 *d_ct, u64 *d_out, int out_stride, int level,
-                             int count, void *d_ws, size_t ws_bytes, hipStream_t st)
+// in: operation o at d_ct + o*in_stride limbs; out: operation o at d_out + o*out_stride limbs.
+// plus_input: the result is ct + Rotate(ct) instead of Rotate(ct).
+static int32_t hrot_batch_to(he_ctx *ctx, const he_evk *rot, const u64 *d_ct, int in_stride, u64 *d_out, int out_stride,
+                             int level, int count, void *d_ws, size_t ws_bytes, hipStream_t st, bool plus_input = false)
 {
     int32_t rc = ks_guard(ctx, rot, level, count, d_ws, ws_bytes);
     if (rc != HE_OK) return rc;
@@ -747,14 +749,14 @@ static int32_t hrot_batch_to(he_ctx *ctx, const he_evk *rot, const u64 *d_ct, u6
     u64 *ws = (u64 *)d_ws;
     const WsLayout w = ws_layout(ctx, level);
     const u64 *c1 = d_ct + (size_t)level * ctx->N;
-    if ((rc = ks_raise(ctx, c1, 2 * level, ws, w, level, count, st)) != HE_OK) return rc;
-    return ks_apply(ctx, rot, c1, 2 * level, ws, w, level, count, d_out, out_stride, d_ct, 2 * level, 2, st);
+    if ((rc = ks_raise(ctx, c1, in_stride, ws, w, level, count, st)) != HE_OK) return rc;
+    return ks_apply(ctx, rot, c1, in_stride, ws, w, level, count, d_out, out_stride, d_ct, in_stride, plus_input ? 4 : 2, st);
 }
 
 extern "C" int32_t he_hrot_batch(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level,
                                  int32_t count, void *d_ws, size_t ws_bytes, void *stream)
 {
-    return hrot_batch_to(ctx, rot, d_ct, d_out, 2 * level, level, count, d_ws, ws_bytes, (hipStream_t)stream);
+    return hrot_batch_to(ctx, rot, d_ct, 2 * level, d_out, 2 * level, level, count, d_ws, ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int32_t he_hrot(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level,
@@ -773,14 +775,26 @@ extern "C" int32_t he_rotate_sum_batch(he_ctx *ctx, const he_evk *const *rots, i
     const WsLayout w = ws_layout(ctx, level);
     if (!batch_fits(w, count)) return HE_EINVAL;
     if (ws_bytes < w.total * (size_t)count * ctx->N * sizeof(u64)) return HE_EWORKSPACE;
-    u64 *tmp = (u64 *)d_ws + w.tmp * ctx->N; // operation o's rotated ciphertext at tmp + o*w.total limbs
+    // ct + Rotate(ct) is written by the key switch itself, alternately into the workspace (operation o at
+    // tmp + o*w.total limbs) and back into d_ct
+    u64 *tmp = (u64 *)d_ws + w.tmp * ctx->N;
+    const int W = (int)w.total;
+    hipStream_t st = (hipStream_t)stream;
+    bool in_tmp = false;
     for (int k = 0; k < n_rot; k++) {
-        if ((rc = hrot_batch_to(ctx, rots[k], d_ct, tmp, (int)w.total, level, count, d_ws, ws_bytes, (hipStream_t)stream)) !=
-            HE_OK)
-            return rc;
-        if ((rc = limbwise(ctx, d_ct, tmp, d_ct, level, 0, 2 * level, 2 * level, stream, count, 2 * level, (int)w.total,
-                           2 * level)) != HE_OK)
-            return rc;
+        rc = in_tmp ? hrot_batch_to(ctx, rots[k], tmp, W, d_ct, 2 * level, level, count, d_ws, ws_bytes, st, true)
+                    : hrot_batch_to(ctx, rots[k], d_ct, 2 * level, tmp, W, level, count, d_ws, ws_bytes, st, true);
+        if (rc != HE_OK) return rc;
+        in_tmp = !in_tmp;
+    }
+    if (in_tmp) {
+        const size_t row = (size_t)2 * level * ctx->N * sizeof(u64);
+        hipError_t e = hipMemcpy2DAsync(d_ct, row, tmp, (size_t)W * ctx->N * sizeof(u64), row, (size_t)count,
+                                        hipMemcpyDeviceToDevice, st);
+        if (e != hipSuccess) {
+            ctx->hip_err = std::string("hipMemcpy2DAsync: ") + hipGetErrorString(e);
+            return HE_EHIP;
+        }
     }
     return HE_OK;
 }

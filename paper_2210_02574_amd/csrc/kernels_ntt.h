@@ -54,11 +54,12 @@ struct FinArgs {
     u64 *out;       // component stride out_cstride limbs
     const u64 *add; // mode 2: c0 limbs [nl][N], read through the automorphism index map; mode 3: component
                     // stride add_cstride limbs
+    const u64 *self; // mode 4: [2][nl][N] per operation, self_stride limbs apart
     const ShoupConst *cst, *cst2;
     const double *cst_d, *cst2_d;
     // mode 0: no addend; 1: add what `out` holds; 2: add sigma_g(c0) to component 0; 3: add the limb of `add`
-    // times cst2 (cst2 == nullptr: as it is)
-    int u_cstride, out_cstride, add_cstride, nl, mode;
+    // times cst2 (cst2 == nullptr: as it is); 4: as 2, plus the limb of `self` (rotate-and-add)
+    int u_cstride, out_cstride, add_cstride, self_stride, nl, mode;
     unsigned g;
     int dst_stride, u_stride, out_stride, add_stride; // limbs between two operations in each buffer
 };
@@ -234,7 +235,7 @@ struct FinOperands {
     u64 uv, av;
 };
 template <int LOGN>
-__device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, unsigned slot, unsigned pos)
+__device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, const DevTables &T, unsigned slot, unsigned pos)
 {
     const unsigned op = slot / (unsigned)fa.dst_stride;
     slot -= op * (unsigned)fa.dst_stride;
@@ -248,6 +249,11 @@ __device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, unsigned slot
         o.av = fa.add[(((size_t)op * fa.add_stride + i) << LOGN) + galois_index(pos, fa.g, LOGN)];
     else if (fa.mode == 3)
         o.av = fa.add[(((size_t)op * fa.add_stride + (size_t)c * fa.add_cstride + i) << LOGN) + pos];
+    else if (fa.mode == 4) {
+        const u64 sv = fa.self[(((size_t)op * fa.self_stride + (size_t)c * fa.nl + i) << LOGN) + pos];
+        const u64 rv = c == 0 ? fa.add[(((size_t)op * fa.add_stride + i) << LOGN) + galois_index(pos, fa.g, LOGN)] : 0;
+        o.av = csub(sv + rv, T.mod[i].q);
+    }
     return o;
 }
 
@@ -299,7 +305,7 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
     for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[bg * 256 + il + 16 * k]);
     if (EPI == EPI_FIN) {
 #pragma unroll
-        for (int k = 0; k < 16; k++) fo[k] = fin_load<LOGN>(fa, slot, bg * 256 + il + 16 * k);
+        for (int k = 0; k < 16; k++) fo[k] = fin_load<LOGN>(fa, T, slot, bg * 256 + il + 16 * k);
     }
     ar.fwd16(a, LOGN - 8, bg, true);
 #pragma unroll
