@@ -181,6 +181,29 @@ def train_step_ms(he, w: "Workload") -> float:
     return (time.perf_counter() - t0) * 1e3
 
 
+def inference_ms(he, w: "Workload", reps: int = 10) -> float:
+    """Latency of one encrypted inference (32 samples x 768 features -> 4 logits each at level 24: 3 hoisted and
+    8 sequential rotations, 4 plaintext products, one rescale) on uniform residues.  Milliseconds per call."""
+    import torch
+
+    from paper_2210_02574_amd import classifier as cl
+
+    inf = cl.EncryptedInference(he, wl.N16.L)
+    keys = {}
+    for k, r in enumerate(w.offsets):  # 1, 2, 4 .. 512 are among the power-of-two keys
+        keys[r] = w.rot[k]
+    keys[3] = w._key(3000, he.galois_element(3))
+    ct = w._uniform_ct(wl.N16.L)
+    pts = [w._uniform(list(range(wl.N16.L))) for _ in range(4)]
+    inf.run(ct, pts, keys)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        inf.run(ct, pts, keys)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / reps
+
+
 def cpu_baseline(sample_hrot: int = 32, sample_hmult: int = 16, sample_ntt: int = 112):
     """The oracle, as it stands, on a bounded sample of the step: NTT/iNTT pairs, HMult+relin+rescale
     and HRot at level 24; reported in key switches per second."""
@@ -326,6 +349,8 @@ def main():
         "kernels": kernels,
     }
     if not args.no_train_step:
+        out["detail"]["inference_ms"] = inference_ms(he, w)
+        out["detail"]["inference_workload"] = "32 samples x 768 features, 4 classes, 11 HRot, level 24"
         out["detail"]["train_step_ms"] = train_step_ms(he, w)
         out["detail"]["train_step_workload"] = "1024 samples x 768 features, 4 classes, 768 HMult + 2580 HRot"
     if not args.no_cpu_baseline:

@@ -108,6 +108,18 @@ int32_t he_sk_coeffs(const he_sk *sk, int8_t *h_out);
  * context has a device, uploaded to it. */
 int32_t he_keygen_relin(he_ctx *ctx, const he_sk *sk, uint64_t seed, he_evk **out);
 int32_t he_keygen_rot(he_ctx *ctx, const he_sk *sk, int32_t r, uint64_t seed, he_evk **out);
+/* Key of the automorphism X -> X^(2N-1) = X^-1, which conjugates every slot (slot j sits at a root zeta_j
+ * and its conjugate root is zeta_j^-1).  Applied with he_hrot, which applies the automorphism of whatever
+ * Galois key it is given. */
+int32_t he_keygen_conj(he_ctx *ctx, const he_sk *sk, uint64_t seed, he_evk **out);
+/* Public encryption key (b, a), h_pk_out [2][L][N] on the host, NTT domain: a uniform (stream kind 6, one
+ * stream per modulus), b = -a s + e with e Gaussian (kind 7).  Section 2.2 lets the data owner encrypt;
+ * with this key a party without the secret can do so too. */
+int32_t he_keygen_public(const he_ctx *ctx, const he_sk *sk, uint64_t seed, uint64_t *h_pk_out);
+/* Public-key encryption of an integer plaintext: c0 = v b + e0 + m, c1 = v a + e1 on the first `level`
+ * moduli, v ternary (kind 8), e0, e1 Gaussian (kinds 9, 10).  h_ct_out [2][level][N], NTT domain. */
+int32_t he_encrypt_public_coeffs(const he_ctx *ctx, const uint64_t *h_pk, const int64_t *h_coeffs, int32_t level,
+                                 uint64_t seed, uint64_t *h_ct_out);
 /* Wraps a caller-made key-shaped buffer [dnum][2][L+K][N] (host memory, copied) as a key for the
  * Galois element g (1 = relinearisation): used for throughput runs on synthetic residues. */
 int32_t he_evk_from_host(he_ctx *ctx, const uint64_t *h_evk, uint64_t g, he_evk **out);

@@ -232,6 +232,61 @@ class Oracle:
         sp = np.stack([self.small_to_ntt(sg, i) for i in range(self.L)])
         return self._keygen_switch(s, sp, seed)
 
+    def keygen_galois(self, s: np.ndarray, g: int, seed: int) -> np.ndarray:
+        """Switching key from sigma_g(s) to s for any odd g."""
+        s = np.ascontiguousarray(s, dtype=np.int8)
+        sg = np.empty(self.N, dtype=np.int8)
+        self.lib.orc_automorph_small(self.ctx, ctypes.c_uint64(g), _p(s, _i8p), _p(sg, _i8p))
+        sp = np.stack([self.small_to_ntt(sg, i) for i in range(self.L)])
+        return self._keygen_switch(s, sp, seed)
+
+    def keygen_conj(self, s: np.ndarray, seed: int) -> np.ndarray:
+        """Key for complex conjugation of the slots: the automorphism X -> X^(2N-1) = X^-1."""
+        return self.keygen_galois(s, 2 * self.N - 1, seed)
+
+    # ---- public-key encryption (stream kinds 6, 7: key; 8, 9, 10: encryption) -------------------------
+    @staticmethod
+    def _tag(kind: int, digit: int = 0, modidx: int = 0) -> int:
+        return (kind << 32) | (digit << 16) | modidx
+
+    def _mul_limb(self, a, b, i):
+        mi = np.array([i], dtype=np.int32)
+        out = np.empty(self.N, dtype=np.uint64)
+        a = np.ascontiguousarray(a, dtype=np.uint64)
+        b = np.ascontiguousarray(b, dtype=np.uint64)
+        self.lib.orc_limbwise(self.ctx, 2, _p(a, _u64p), _p(b, _u64p), _p(out, _u64p), _p(mi, _i32p), 1)
+        return out
+
+    def keygen_public(self, s: np.ndarray, seed: int) -> np.ndarray:
+        """pk = (b, a) on the L ciphertext moduli, NTT domain: a uniform, b = -a s + e, e Gaussian."""
+        e = self.sample_gauss(seed, self._tag(7), self.N)
+        pk = np.empty((2, self.L, self.N), dtype=np.uint64)
+        for i in range(self.L):
+            qi = self.q[i]
+            a = self.sample_uniform(seed, self._tag(6, 0, i), qi, self.N)
+            as_ = self._mul_limb(a, self.small_to_ntt(s, i), i)
+            eh = self.small_to_ntt(e, i)
+            pk[0, i] = (eh + (np.uint64(qi) - as_)) % np.uint64(qi)
+            pk[1, i] = a
+        return pk
+
+    def encrypt_public_coeffs(self, pk: np.ndarray, coeffs, level: int, seed: int) -> np.ndarray:
+        """c0 = v b + e0 + m, c1 = v a + e1 with v ternary, e0 and e1 Gaussian."""
+        v = self.sample_ternary(seed, self._tag(8), self.N)
+        e0 = self.sample_gauss(seed, self._tag(9), self.N)
+        e1 = self.sample_gauss(seed, self._tag(10), self.N)
+        m = [int(x) for x in np.asarray(coeffs).tolist()]
+        ct = np.empty((2, level, self.N), dtype=np.uint64)
+        for i in range(level):
+            qi = self.q[i]
+            vh = self.small_to_ntt(v, i)
+            me = np.array([(m[k] + int(e0[k])) % qi for k in range(self.N)], dtype=np.uint64)
+            meh = self.ntt(me[None, :], [i])[0]
+            e1h = self.small_to_ntt(e1, i)
+            ct[0, i] = (self._mul_limb(vh, pk[0, i], i) + meh) % np.uint64(qi)
+            ct[1, i] = (self._mul_limb(vh, pk[1, i], i) + e1h) % np.uint64(qi)
+        return ct
+
     # ---- encrypt / decrypt -------------------------------------------------------------
     def encrypt_coeffs(self, s: np.ndarray, coeffs: np.ndarray, level: int, seed: int) -> np.ndarray:
         ct = np.empty((2, level, self.N), dtype=np.uint64)
@@ -402,6 +457,15 @@ class Oracle:
         out = np.empty_like(ct)
         g = self.galois_element(r)
         self.lib.orc_hrot(self.ctx, _p(ct, _u64p), level, _p(evk, _u64p), ctypes.c_uint64(g), _p(out, _u64p))
+        return out
+
+    def hconj(self, ct, evk):
+        """Complex conjugation of every slot (key from keygen_conj)."""
+        ct = np.ascontiguousarray(ct, dtype=np.uint64)
+        evk = np.ascontiguousarray(evk, dtype=np.uint64)
+        out = np.empty_like(ct)
+        self.lib.orc_hrot(self.ctx, _p(ct, _u64p), ct.shape[1], _p(evk, _u64p), ctypes.c_uint64(2 * self.N - 1),
+                          _p(out, _u64p))
         return out
 
     def rotate_sum(self, ct, evks, shift0: int):

@@ -27,6 +27,7 @@ SYMBOLS = [
     "he_ctx_create", "he_ctx_destroy", "he_strerror", "he_last_hip_error", "he_ctx_modulus",
     "he_galois_element", "he_gauss_cdt", "he_workspace_bytes",
     "he_keygen_secret", "he_sk_destroy", "he_sk_coeffs", "he_keygen_relin", "he_keygen_rot",
+    "he_keygen_conj", "he_keygen_public", "he_encrypt_public_coeffs",
     "he_evk_from_host", "he_evk_to_host", "he_evk_destroy",
     "he_encode", "he_decode", "he_plain_to_ntt", "he_encrypt_coeffs", "he_decrypt_coeffs", "he_decrypt",
     "he_ntt", "he_intt", "he_add", "he_sub", "he_pmult", "he_cmult", "he_add_const", "he_moddrop",
@@ -85,6 +86,9 @@ def load_library() -> ctypes.CDLL:
             "he_sk_coeffs": [vp, vp],
             "he_keygen_relin": [vp, vp, u64, ctypes.POINTER(vp)],
             "he_keygen_rot": [vp, vp, i32, u64, ctypes.POINTER(vp)],
+            "he_keygen_conj": [vp, vp, u64, ctypes.POINTER(vp)],
+            "he_keygen_public": [vp, vp, u64, vp],
+            "he_encrypt_public_coeffs": [vp, vp, vp, i32, u64, vp],
             "he_evk_from_host": [vp, vp, u64, ctypes.POINTER(vp)],
             "he_evk_to_host": [vp, vp],
             "he_evk_destroy": [vp],
@@ -243,6 +247,27 @@ class HE:
         h = ctypes.c_void_p()
         self._chk(self.lib.he_keygen_rot(self.ctx, sk.handle, r, seed, ctypes.byref(h)), "he_keygen_rot")
         return EvalKey(self, h)
+
+    def keygen_conj(self, sk: SecretKey, seed: int) -> EvalKey:
+        """Key of slot-wise complex conjugation; apply it with hrot / hconj."""
+        h = ctypes.c_void_p()
+        self._chk(self.lib.he_keygen_conj(self.ctx, sk.handle, seed, ctypes.byref(h)), "he_keygen_conj")
+        return EvalKey(self, h)
+
+    def keygen_public(self, sk: SecretKey, seed: int) -> np.ndarray:
+        pk = np.empty((2, self.L, self.N), dtype=np.uint64)
+        self._chk(self.lib.he_keygen_public(self.ctx, sk.handle, seed, _hp(pk)), "he_keygen_public")
+        return pk
+
+    def encrypt_public_coeffs(self, pk: np.ndarray, coeffs: np.ndarray, level: int, seed: int) -> np.ndarray:
+        pk = np.ascontiguousarray(pk, dtype=np.uint64)
+        assert pk.shape == (2, self.L, self.N)
+        m = np.ascontiguousarray(coeffs, dtype=np.int64)
+        assert m.shape == (self.N,)
+        out = np.empty((2, level, self.N), dtype=np.uint64)
+        self._chk(self.lib.he_encrypt_public_coeffs(self.ctx, _hp(pk), _hp(m), level, seed, _hp(out)),
+                  "he_encrypt_public_coeffs")
+        return out
 
     def evk_from_host(self, evk: np.ndarray, g: int = 1) -> EvalKey:
         evk = np.ascontiguousarray(evk, dtype=np.uint64)
@@ -440,6 +465,10 @@ class HE:
             self.lib.he_rescale(self.ctx, self._dp(ct), self._dp(out), level, ws, wsb, self._stream()), "he_rescale"
         )
         return out
+
+    def hconj(self, conj: EvalKey, ct, out=None):
+        """Complex conjugation of every slot (key from keygen_conj)."""
+        return self.hrot(conj, ct, out=out)
 
     def hrot(self, rot: EvalKey, ct, out=None):
         level = self._level(ct)

@@ -569,13 +569,10 @@ extern "C" int32_t he_keygen_relin(he_ctx *ctx, const he_sk *sk, uint64_t seed, 
     return make_switch_key(ctx, sk, sp, 1, seed, out);
 }
 
-extern "C" int32_t he_keygen_rot(he_ctx *ctx, const he_sk *sk, int32_t r, uint64_t seed, he_evk **out)
+// switching key from sigma_g(s) to s
+static int32_t make_galois_key(he_ctx *ctx, const he_sk *sk, u64 g, u64 seed, he_evk **out)
 {
-    if (!ctx || !sk || !out || sk->ctx != ctx) return HE_EINVAL;
     const u64 N = ctx->N;
-    u64 g;
-    he_galois_element(ctx, r, &g);
-    if (g == 1) return HE_EINVAL; // rotation by a multiple of N/2 needs no key
     // sigma_g(s): coefficient j moves to j*g mod 2N, negated when it wraps past N
     std::vector<int8_t> sg(N);
     for (u64 j = 0; j < N; j++) {
@@ -588,6 +585,21 @@ extern "C" int32_t he_keygen_rot(he_ctx *ctx, const he_sk *sk, int32_t r, uint64
     std::vector<u64> sp((size_t)ctx->L * N);
     parallel_for(ctx->L, [&](int i) { small_to_ntt(ctx, i, sg.data(), sp.data() + (size_t)i * N); });
     return make_switch_key(ctx, sk, sp, g, seed, out);
+}
+
+extern "C" int32_t he_keygen_rot(he_ctx *ctx, const he_sk *sk, int32_t r, uint64_t seed, he_evk **out)
+{
+    if (!ctx || !sk || !out || sk->ctx != ctx) return HE_EINVAL;
+    u64 g;
+    he_galois_element(ctx, r, &g);
+    if (g == 1) return HE_EINVAL; // rotation by a multiple of N/2 needs no key
+    return make_galois_key(ctx, sk, g, seed, out);
+}
+
+extern "C" int32_t he_keygen_conj(he_ctx *ctx, const he_sk *sk, uint64_t seed, he_evk **out)
+{
+    if (!ctx || !sk || !out || sk->ctx != ctx) return HE_EINVAL;
+    return make_galois_key(ctx, sk, 2 * ctx->N - 1, seed, out);
 }
 
 extern "C" int32_t he_evk_from_host(he_ctx *ctx, const uint64_t *h_evk, uint64_t g, he_evk **out)
@@ -722,6 +734,59 @@ extern "C" int32_t he_encrypt_coeffs(const he_ctx *ctx, const he_sk *sk, const i
         for (u64 x = 0; x < N; x++) {
             u64 v = c0[x] + t - mul_mod(c1[x], s[x], t);
             c0[x] = v >= t ? v - t : v;
+        }
+    });
+    return HE_OK;
+}
+
+extern "C" int32_t he_keygen_public(const he_ctx *ctx, const he_sk *sk, uint64_t seed, uint64_t *h_pk_out)
+{
+    if (!ctx || !sk || !h_pk_out || sk->ctx != ctx) return HE_EINVAL;
+    const u64 N = ctx->N;
+    const int L = ctx->L;
+    std::vector<int8_t> e(N);
+    sample_gauss(Stream(seed, 7, 0, 0), e.data(), N);
+    parallel_for(L, [&](int i) {
+        const u64 t = ctx->mod[i];
+        u64 *b = h_pk_out + ((size_t)0 * L + i) * N;
+        u64 *a = h_pk_out + ((size_t)1 * L + i) * N;
+        sample_uniform(Stream(seed, 6, 0, (u64)i), t, a, N);
+        small_to_ntt(ctx, i, e.data(), b);
+        const u64 *s = sk->s_ntt.data() + (size_t)i * N;
+        for (u64 x = 0; x < N; x++) {
+            const u64 v = b[x] + t - mul_mod(a[x], s[x], t);
+            b[x] = v >= t ? v - t : v;
+        }
+    });
+    return HE_OK;
+}
+
+extern "C" int32_t he_encrypt_public_coeffs(const he_ctx *ctx, const uint64_t *h_pk, const int64_t *h_coeffs,
+                                            int32_t level, uint64_t seed, uint64_t *h_ct_out)
+{
+    if (!ctx || !h_pk || !h_coeffs || !h_ct_out) return HE_EINVAL;
+    if (level < 1 || level > ctx->L) return HE_ELEVEL;
+    const u64 N = ctx->N;
+    const int L = ctx->L;
+    std::vector<int8_t> v(N), e0(N), e1(N);
+    sample_ternary(Stream(seed, 8, 0, 0), v.data(), N);
+    sample_gauss(Stream(seed, 9, 0, 0), e0.data(), N);
+    sample_gauss(Stream(seed, 10, 0, 0), e1.data(), N);
+    parallel_for(level, [&](int i) {
+        const u64 t = ctx->mod[i];
+        u64 *c0 = h_ct_out + ((size_t)0 * level + i) * N;
+        u64 *c1 = h_ct_out + ((size_t)1 * level + i) * N;
+        const u64 *b = h_pk + ((size_t)0 * L + i) * N;
+        const u64 *a = h_pk + ((size_t)1 * L + i) * N;
+        std::vector<u64> vh(N);
+        small_to_ntt(ctx, i, v.data(), vh.data());
+        for (u64 x = 0; x < N; x++) c0[x] = signed_residue(h_coeffs[x] + (int64_t)e0[x], t);
+        ntt(ctx, i, c0);
+        small_to_ntt(ctx, i, e1.data(), c1);
+        for (u64 x = 0; x < N; x++) {
+            const u64 w0 = c0[x] + mul_mod(vh[x], b[x], t), w1 = c1[x] + mul_mod(vh[x], a[x], t);
+            c0[x] = w0 >= t ? w0 - t : w0;
+            c1[x] = w1 >= t ? w1 - t : w1;
         }
     });
     return HE_OK;

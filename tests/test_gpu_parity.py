@@ -213,6 +213,35 @@ def test_real_keys_and_decryption(env):
     assert err <= 2.0**-15 * max(1.0, 2.0**40 / scale), err
 
 
+def test_conjugation_and_public_key_encryption(env):
+    """Conjugation is Rotate with the key of X -> X^(2N-1): bit-exact against the oracle on uniform residues,
+    and on a public-key encryption it decrypts to the conjugated slots."""
+    he, o, p = env.he, env.o, env.params
+    g = 2 * p.N - 1
+    key, evk = env.synth_key(950, g)
+    for level in _levels(p)[:3]:
+        ct = wl.uniform_ct(951 + level, p, level)
+        got = he.to_host(he.hconj(key, he.to_device(ct)))
+        assert np.array_equal(got, o.hconj(ct, evk)), level
+    if p.name == "C1":
+        return  # dnum=1 with P << Q: key-switch noise swamps the message
+    level = 3 if p.logN == 12 else 4
+    scale = 2.0**30 if p.logN == 12 else 2.0**40
+    sk, s = he.keygen_secret(960), o.keygen_secret(960)
+    ck = he.keygen_conj(sk, 961)
+    assert np.array_equal(ck.to_host(), o.keygen_conj(s, 961))
+    pk = he.keygen_public(sk, 962)
+    rng = wl.rng(963)
+    z = rng.uniform(-1, 1, he.n) + 1j * rng.uniform(-1, 1, he.n)
+    m = o.encode(z, scale)
+    ct = he.encrypt_public_coeffs(pk, m, level, 964)
+    assert np.array_equal(ct, o.encrypt_public_coeffs(o.keygen_public(s, 962), m, level, 964))
+    out = he.to_host(he.hconj(ck, he.to_device(ct)))
+    err = np.abs(he.decrypt(sk, out, scale) - np.conj(z)).max()
+    tol = 2.0**-15 * max(1.0, 2.0**40 / scale) * 4
+    assert err <= tol, (err, tol)
+
+
 def test_error_codes_on_device_context(env):
     he, p = env.he, env.params
     key, _ = env.synth_key(301, 1)

@@ -68,10 +68,15 @@ def test_tables_keys_and_encryption_bit_exact(lib, oracle_mod, params):
     assert np.array_equal(he.keygen_relin(sk, 12).to_host(), o.keygen_relin(s, 12))
     for r in (1, 64, -1):
         assert np.array_equal(he.keygen_rot(sk, r, 13 + r).to_host(), o.keygen_rot(s, r, 13 + r))
+    assert np.array_equal(he.keygen_conj(sk, 16).to_host(), o.keygen_conj(s, 16))
     m = wl.small_coeffs(14, params.N, 2**35)
     for level in (3, 1):
         a, b = he.encrypt_coeffs(sk, m, level, 15), o.encrypt_coeffs(s, m, level, 15)
         assert np.array_equal(a, b)
+    pk = he.keygen_public(sk, 17)
+    assert np.array_equal(pk, o.keygen_public(s, 17))
+    for level in (3, 2):
+        assert np.array_equal(he.encrypt_public_coeffs(pk, m, level, 18), o.encrypt_public_coeffs(pk, m, level, 18))
     assert np.array_equal(he.plain_to_ntt(m, 2), o.coeffs_to_ntt(m, 2))
 
 

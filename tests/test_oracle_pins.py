@@ -492,6 +492,63 @@ def test_hrot_is_left_cyclic_shift(c1b):
     assert np.median(err) <= 2.0**-18
 
 
+def test_conjugation_key_and_hconj(c1b):
+    """X -> X^(2N-1) on coefficients is a(X^-1): coefficient 0 stays, coefficient j goes to N-j negated; on slots
+    it is complex conjugation (the root of slot j inverts), twice is the identity, and it commutes with Rotate."""
+    o, s = c1b
+    N = o.N
+    t = o.moduli[0]
+    a = wl.rng(61).integers(0, t, size=N, dtype=np.uint64)
+    c = o.automorph_coeff(a, 0, 2 * N - 1).tolist()
+    assert c[0] == int(a[0])
+    assert all(c[N - j] == (t - int(a[j])) % t for j in range(1, N))
+    tol = _ks_bound(o, 2.0**30)
+    g = wl.rng(62)
+    z = g.uniform(-1, 1, o.n) + 1j * g.uniform(-1, 1, o.n)
+    scale = 2.0**30
+    ct = o.encrypt_coeffs(s, o.encode(z, scale), 3, seed=63)
+    ck = o.keygen_conj(s, 64)
+    out = o.hconj(ct, ck)
+    assert np.abs(o.decrypt(s, out, scale) - np.conj(z)).max() <= tol
+    assert np.abs(o.decrypt(s, o.hconj(out, ck), scale) - z).max() <= 2 * tol
+    rk = o.keygen_rot(s, 3, 65)
+    a1 = o.decrypt(s, o.hrot(out, rk, 3), scale)
+    a2 = o.decrypt(s, o.hconj(o.hrot(ct, rk, 3), ck), scale)
+    assert np.abs(a1 - a2).max() <= 4 * tol
+    assert np.abs(a1 - np.conj(np.roll(z, -3))).max() <= 2 * tol
+
+
+def test_public_key_structure_and_encryption(c1b):
+    """b + a s = e is small on every limb (CRT over all limbs, big integers); Dec(Enc_pk(m)) = m + v e + e0 + e1 s
+    with coefficients within the sum of the three noise bounds; and the decoded slots are close to z."""
+    o, s = c1b
+    N = o.N
+    pk = o.keygen_public(s, 71)
+    assert pk.shape == (2, o.L, N)
+    res = np.stack([(pk[0, i].astype(object) + o._mul_limb(pk[1, i], o.small_to_ntt(s, i), i).astype(object)) % o.q[i]
+                    for i in range(o.L)]).astype(np.uint64)
+    e = o.crt_centred(o.intt(res, list(range(o.L))))
+    assert max(abs(v) for v in e) <= 19
+    assert e == [int(v) for v in o.sample_gauss(71, (7 << 32), N)]
+    g = wl.rng(72)
+    z = g.uniform(-1, 1, o.n) + 1j * g.uniform(-1, 1, o.n)
+    scale = 2.0**30
+    m = o.encode(z, scale)
+    for level in (3, 1):
+        ct = o.encrypt_public_coeffs(pk, m, level, 73)
+        assert ct.shape == (2, level, N)
+        d = o.decrypt_coeffs(s, ct)
+        noise = [d[k] - int(m[k]) for k in range(N)]
+        assert max(abs(v) for v in noise) <= 19 * N + 19 + 19 * N  # |v e| + |e0| + |e1 s|, worst case
+        assert max(abs(v) for v in noise) >= 1  # and it is there
+        # typical size: sqrt(2N/3) * sigma * sqrt(2)
+        assert np.std(np.array(noise, dtype=np.float64)) <= 3 * 3.2 * math.sqrt(4 * N / 3)
+        assert np.abs(o.decrypt(s, ct, scale) - z).max() <= 2.0**-12
+    # two encryptions with different seeds differ, same seed repeats
+    assert np.array_equal(o.encrypt_public_coeffs(pk, m, 2, 74), o.encrypt_public_coeffs(pk, m, 2, 74))
+    assert not np.array_equal(o.encrypt_public_coeffs(pk, m, 2, 74), o.encrypt_public_coeffs(pk, m, 2, 75))
+
+
 def test_rotate_sum_adds_blocks(c1b):
     o, s = c1b
     z = wl.slots_uniform(61, o.n)
