@@ -98,6 +98,10 @@ int32_t he_workspace_bytes(const he_ctx *ctx, int32_t level, int32_t count, size
 
 /* Ternary secret key. */
 int32_t he_keygen_secret(he_ctx *ctx, uint64_t seed, he_sk **out);
+/* Secret with exactly h non-zero coefficients (+-1), as bootstrapping wants it: stream kind 11; a position
+ * is the low logN bits of a word, redrawn while that position is taken; the next word's low bit is the sign
+ * (0: +1).  HE_EINVAL unless 1 <= h <= N. */
+int32_t he_keygen_secret_sparse(he_ctx *ctx, uint64_t seed, int32_t h, he_sk **out);
 void he_sk_destroy(he_sk *sk);
 /* Copies the N secret coefficients (-1, 0, +1). */
 int32_t he_sk_coeffs(const he_sk *sk, int8_t *h_out);
@@ -190,6 +194,12 @@ int32_t he_hmult_relin_rescale(he_ctx *ctx, const he_evk *relin, const uint64_t 
  * d_out is [2][level-1][N] and must not alias d_ct. */
 int32_t he_rescale(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level, void *d_ws, size_t ws_bytes,
                    void *stream);
+/* ModRaise, the first step of Bootstrap (Section 2.2 lists the operation; the construction is the published
+ * one): d_ct [2][1][N] modulo q_0 -> d_out [2][level_out][N], the centred coefficients of both components
+ * reduced modulo every q_i.  The result decrypts to m + q_0 I with a small integer polynomial I.
+ * level_out >= 2; d_out must not alias d_ct; workspace as for level_out. */
+int32_t he_modraise(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level_out, void *d_ws, size_t ws_bytes,
+                    void *stream);
 /* Rotate: the digits of c1 are raised un-rotated, the automorphism sigma_g is applied to the
  * raised digits and to c0, then inner product with the key and ModDown:
  * out = (sigma_g(c0) + k0, k1).  d_out must not alias d_ct. */

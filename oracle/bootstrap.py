@@ -1,0 +1,200 @@
+"""Oracle composition of CKKS bootstrapping for sparsely packed ciphertexts (test infrastructure only).
+
+The paper names Bootstrap as the operation that refreshes the level of a ciphertext (Section 2.2) and defers
+the construction to the CKKS literature; this file follows the published construction step by step with the
+oracle's own primitives:
+
+  ModRaise      the level-1 ciphertext is read as a ciphertext modulo Q_L; it decrypts to t = m + q0 I
+  SubSum        trace onto the subring Z[X^(N/2ns)] (log2(n/ns) rotate-and-add steps): t' = (n/ns) t
+  CoeffToSlot   slots <- coefficients: w_k = t_k + i t_(k+ns) = (1/ns) conj(U)^T Z, U[j][k] = xi_j^k,
+                xi_j = exp(2 pi i 5^j / (4 ns)); one baby-step/giant-step matrix product; then the real
+                and imaginary parts with one conjugation
+  EvalMod       t mod q0 ~ (q0 / 2 pi) sin(2 pi t / q0): exp(i theta / 2^r) by its Taylor polynomial
+                (cosine to theta^8, sine to theta^9), r squarings, imaginary part
+  SlotToCoeff   Z'' = U w'' with w'' = eps_lo + i eps_hi
+
+Every constant is folded into the two matrices; "multiply by i" is the monomial X^(N/2), which costs neither
+scale nor level.  The ciphertext values are tracked as (residues, level, scale).
+"""
+import math
+
+import numpy as np
+
+
+def sparse_secret(o, seed: int, h: int) -> np.ndarray:
+    """Ternary secret with exactly h non-zero coefficients: stream kind 11; position = low logN bits of a
+    word (redrawn while the position is taken), then one more word whose low bit gives the sign (0: +1)."""
+    tag = 11 << 32
+    s = np.zeros(o.N, dtype=np.int8)
+    i = placed = 0
+    while placed < h:
+        pos = o.stream_word(seed, tag, i) & (o.N - 1)
+        i += 1
+        if s[pos] != 0:
+            continue
+        s[pos] = 1 if (o.stream_word(seed, tag, i) & 1) == 0 else -1
+        i += 1
+        placed += 1
+    return s
+
+
+def modraise(o, ct: np.ndarray, level_out: int) -> np.ndarray:
+    """[2][1][N] modulo q0 -> [2][level_out][N]: the centred coefficients, reduced modulo every q_i."""
+    q0 = o.q[0]
+    out = np.empty((2, level_out, o.N), dtype=np.uint64)
+    for c in range(2):
+        x = o.intt(ct[c, 0][None, :], [0])[0]
+        xc = [int(v) - q0 if int(v) > (q0 - 1) // 2 else int(v) for v in x.tolist()]
+        for i in range(level_out):
+            limb = np.array([v % o.q[i] for v in xc], dtype=np.uint64)
+            out[c, i] = o.ntt(limb[None, :], [i])[0]
+    return out
+
+
+def special_dft(ns: int) -> np.ndarray:
+    """U[j][k] = xi_j^k, xi_j = exp(2 pi i (5^j mod 4 ns) / (4 ns))."""
+    e = np.array([pow(5, j, 4 * ns) for j in range(ns)], dtype=np.float64)
+    k = np.arange(ns, dtype=np.float64)
+    return np.exp(2j * np.pi * np.outer(e, k) / (4 * ns))
+
+
+class Plan:
+    """Shapes, levels and rotation shifts of one bootstrapping for ns slots."""
+
+    def __init__(self, o, ns: int, r: int = 8, level_in: int = None):
+        self.ns, self.r = ns, r
+        self.L = o.L if level_in is None else level_in
+        self.gap = o.n // ns
+        lg = int(math.log2(ns))
+        self.g1 = 1 << ((lg + 1) // 2)
+        self.g2 = ns // self.g1
+        self.subsum_shifts = [ns << k for k in range(int(math.log2(self.gap)))]
+        self.baby = list(range(1, self.g1))
+        self.giant = [self.g1 * b for b in range(1, self.g2)]
+        self.out_level = self.L - 7 - r
+
+    def rotation_shifts(self):
+        return sorted(set(self.subsum_shifts + self.baby + self.giant))
+
+
+def bsgs_plaintext_slots(M: np.ndarray, plan: Plan, n: int):
+    """Slot vectors of the pre-rotated diagonals: entry [b][a][j] = M[(j - g1 b) % ns][(j + a) % ns], tiled to n."""
+    ns, g1, g2 = plan.ns, plan.g1, plan.g2
+    j = np.arange(ns)
+    out = []
+    for b in range(g2):
+        row = []
+        for a in range(g1):
+            jj = (j - g1 * b) % ns
+            d = M[jj, (jj + g1 * b + a) % ns]
+            row.append(np.tile(d, n // ns))
+        out.append(row)
+    return out
+
+
+def encode_matrix(o, M: np.ndarray, plan: Plan, level: int):
+    """NTT-domain plaintexts of the pre-rotated diagonals at scale q_(level-1), `level` limbs each."""
+    scale = float(o.q[level - 1])
+    return [[o.coeffs_to_ntt(o.encode(v, scale), level) for v in row] for row in bsgs_plaintext_slots(M, plan, o.n)]
+
+
+def linear_transform(o, ct, pts, rot, plan: Plan):
+    """sum_b rot_(g1 b)( sum_a pt[b][a] * rot_a(ct) ), then rescale (level - 1, scale unchanged)."""
+    babies = [ct] + [o.hrot(ct, rot[a], a) for a in plan.baby]
+    acc = None
+    for b in range(plan.g2):
+        inner = None
+        for a in range(plan.g1):
+            term = o.pmult(babies[a], pts[b][a])
+            inner = term if inner is None else o.add(inner, term)
+        if b:
+            inner = o.hrot(inner, rot[plan.g1 * b], plan.g1 * b)
+        acc = inner if acc is None else o.add(acc, inner)
+    return o.rescale(acc)
+
+
+def monomial_i(o, level: int, sign: int = 1) -> np.ndarray:
+    """NTT-domain plaintext of +-X^(N/2): multiplies every slot by +-i."""
+    c = np.zeros(o.N, dtype=np.int64)
+    c[o.N // 2] = sign
+    return o.coeffs_to_ntt(c, level)
+
+
+def _const(o, v: float, s: float, level: int):
+    iv = int(round(v * s))
+    return [iv % o.q[i] for i in range(level)]
+
+
+def _mul(o, a, b, relin):
+    return o.rescale(o.hmult_relin(a, b, relin))
+
+
+def _lin(o, y, level: int, s_in: float, c0: float, c1: float, target: float):
+    """rescale(c1 y) + c0 at scale `target`, one level below y."""
+    q = float(o.q[level - 1])
+    out = o.rescale(o.cmult(y, _const(o, c1, target * q / s_in, level)))
+    return o.add_const(out, _const(o, c0, target, level - 1))
+
+
+def _quartic(o, y, y2, l: int, s_y: float, s_y2: float, r, target: float, relin):
+    """r0 + r1 y + r2 y^2 + r3 y^3 + r4 y^4 at level l-3 and scale `target`; y at level l, y2 = y^2 at l-1."""
+    q = [float(v) for v in o.q]
+    t_in = target * q[l - 3] / s_y2                    # scale of r2 + r3 y + r4 y2 so that y2 * inner lands on target
+    lin23 = o.moddrop(_lin(o, y, l, s_y, r[2], r[3], t_in), l - 2)
+    q4 = o.rescale(o.cmult(y2, _const(o, r[4], t_in * q[l - 2] / s_y2, l - 1)))
+    inner = o.add(lin23, q4)                           # level l-2
+    prod = _mul(o, o.moddrop(y2, l - 2), inner, relin)
+    lin01 = o.moddrop(_lin(o, y, l, s_y, r[0], r[1], target), l - 3)
+    return o.add(prod, lin01)
+
+
+def exp_i(o, theta, level: int, scale: float, relin, r: int):
+    """exp(i 2^r theta) for a ciphertext with real slots theta: (ct, level - 5 - r, scale)."""
+    q = [float(v) for v in o.q]
+    l = level
+    y = _mul(o, theta, theta, relin)                    # level l-1
+    s_y = scale * scale / q[l - 1]
+    y2 = _mul(o, y, y, relin)                           # level l-2
+    s_y2 = s_y * s_y / q[l - 2]
+    cos_c = [(-1) ** k / math.factorial(2 * k) for k in range(5)]
+    sin_c = [(-1) ** k / math.factorial(2 * k + 1) for k in range(5)]
+    t_p = scale                                         # scale of the sine's even factor, level l-4
+    t_s = scale * t_p / q[l - 5]                        # scale of theta * P and of the cosine
+    P = _quartic(o, y, y2, l - 1, s_y, s_y2, sin_c, t_p, relin)
+    C = _quartic(o, y, y2, l - 1, s_y, s_y2, cos_c, t_s, relin)
+    S = _mul(o, o.moddrop(theta, l - 4), P, relin)      # level l-5
+    E = o.add(o.moddrop(C, l - 5), o.pmult(S, monomial_i(o, l - 5)))
+    lvl, s = l - 5, t_s
+    for _ in range(r):
+        E = _mul(o, E, E, relin)
+        s = s * s / q[lvl - 1]
+        lvl -= 1
+    return E, lvl, s
+
+
+def bootstrap(o, ct1, keys, plan: Plan, pts_cts=None, pts_stc=None):
+    """ct1: [2][1][N] at scale delta.  keys: {'relin', 'conj', 'rot': {shift: key}}.
+    Returns (ct, level, factor): the refreshed ciphertext at `level`, encrypting the same slots at scale
+    delta * factor."""
+    L, ns, r = plan.L, plan.ns, plan.r
+    relin, conj, rot = keys["relin"], keys["conj"], keys["rot"]
+    U = special_dft(ns)
+    if pts_cts is None:
+        pts_cts = encode_matrix(o, (math.pi / (plan.gap * 2.0**r * ns)) * U.conj().T, plan, L)
+    ct = modraise(o, ct1, L)
+    for sh in plan.subsum_shifts:
+        ct = o.add(ct, o.hrot(ct, rot[sh], sh))
+    scale = float(o.q[0])                               # the raised ciphertext holds t / q0
+    w = linear_transform(o, ct, pts_cts, rot, plan)     # level L-1: (pi / 2^r) w
+    wc = o.hconj(w, conj)
+    th1 = o.add(w, wc)
+    th2 = o.pmult(o.sub(w, wc), monomial_i(o, L - 1, -1))
+    E1, lvl, s = exp_i(o, th1, L - 1, scale, relin, r)
+    E2, _, _ = exp_i(o, th2, L - 1, scale, relin, r)
+    iE2 = o.pmult(E2, monomial_i(o, lvl))
+    Hp, Hm = o.add(E1, iE2), o.sub(E1, iE2)
+    F = o.pmult(o.sub(Hp, o.hconj(Hm, conj)), monomial_i(o, lvl, -1))
+    if pts_stc is None:
+        pts_stc = encode_matrix(o, U / (4.0 * math.pi), plan, lvl)
+    out = linear_transform(o, F, pts_stc, rot, plan)
+    return out, lvl - 1, s / float(o.q[0])

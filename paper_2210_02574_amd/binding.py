@@ -27,7 +27,7 @@ SYMBOLS = [
     "he_ctx_create", "he_ctx_destroy", "he_strerror", "he_last_hip_error", "he_ctx_modulus",
     "he_galois_element", "he_gauss_cdt", "he_workspace_bytes",
     "he_keygen_secret", "he_sk_destroy", "he_sk_coeffs", "he_keygen_relin", "he_keygen_rot",
-    "he_keygen_conj", "he_keygen_public", "he_encrypt_public_coeffs",
+    "he_keygen_conj", "he_keygen_public", "he_encrypt_public_coeffs", "he_keygen_secret_sparse", "he_modraise",
     "he_evk_from_host", "he_evk_to_host", "he_evk_destroy",
     "he_encode", "he_decode", "he_plain_to_ntt", "he_encrypt_coeffs", "he_decrypt_coeffs", "he_decrypt",
     "he_ntt", "he_intt", "he_add", "he_sub", "he_pmult", "he_cmult", "he_add_const", "he_moddrop",
@@ -70,6 +70,10 @@ def load_library() -> ctypes.CDLL:
                 f"{LIB_PATH} is missing: build it with `python -m paper_2210_02574_amd.build` "
                 "(hipcc --offload-arch=gfx950); there is no fallback path"
             )
+        # torch first: it brings its own HIP runtime, and a process must not end up with the system's runtime
+        # initialised by this library and torch's by torch (the second one then finds no GPU)
+        import torch  # noqa: F401
+
         lib = ctypes.CDLL(LIB_PATH)
         vp, i32, u64, sz, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint64, ctypes.c_size_t, ctypes.c_double
         sig = {
@@ -87,6 +91,8 @@ def load_library() -> ctypes.CDLL:
             "he_keygen_relin": [vp, vp, u64, ctypes.POINTER(vp)],
             "he_keygen_rot": [vp, vp, i32, u64, ctypes.POINTER(vp)],
             "he_keygen_conj": [vp, vp, u64, ctypes.POINTER(vp)],
+            "he_keygen_secret_sparse": [vp, u64, i32, ctypes.POINTER(vp)],
+            "he_modraise": [vp, vp, vp, i32, vp, sz, vp],
             "he_keygen_public": [vp, vp, u64, vp],
             "he_encrypt_public_coeffs": [vp, vp, vp, i32, u64, vp],
             "he_evk_from_host": [vp, vp, u64, ctypes.POINTER(vp)],
@@ -189,6 +195,10 @@ class HE:
         self._pa = (ctypes.c_uint64 * self.K)(*self.p)
         prm = he_params(logN, self.L, self.K, dnum, self._qa, self._pa)
         h = ctypes.c_void_p()
+        if device >= 0:
+            import torch
+
+            torch.cuda.init()  # torch owns device memory and streams: its runtime comes up before the library's
         rc = self.lib.he_ctx_create(ctypes.byref(prm), device, ctypes.byref(h))
         if rc != HE_OK:
             raise HeError(rc, "he_ctx_create")
@@ -237,6 +247,12 @@ class HE:
         h = ctypes.c_void_p()
         self._chk(self.lib.he_keygen_secret(self.ctx, seed, ctypes.byref(h)), "he_keygen_secret")
         return SecretKey(self, h)
+
+    def keygen_secret_sparse(self, seed: int, h: int) -> SecretKey:
+        """Secret with exactly h non-zero coefficients (bootstrapping)."""
+        hd = ctypes.c_void_p()
+        self._chk(self.lib.he_keygen_secret_sparse(self.ctx, seed, h, ctypes.byref(hd)), "he_keygen_secret_sparse")
+        return SecretKey(self, hd)
 
     def keygen_relin(self, sk: SecretKey, seed: int) -> EvalKey:
         h = ctypes.c_void_p()
@@ -464,6 +480,15 @@ class HE:
         self._chk(
             self.lib.he_rescale(self.ctx, self._dp(ct), self._dp(out), level, ws, wsb, self._stream()), "he_rescale"
         )
+        return out
+
+    def modraise(self, ct, level_out: int, out=None):
+        """Level-1 ciphertext -> level_out limbs of the same centred coefficients (first step of bootstrapping)."""
+        assert self._level(ct) == 1
+        out = self.empty_ct(level_out) if out is None else out
+        ws, wsb = self._workspace(level_out)
+        self._chk(self.lib.he_modraise(self.ctx, self._dp(ct), self._dp(out), level_out, ws, wsb, self._stream()),
+                  "he_modraise")
         return out
 
     def hconj(self, conj: EvalKey, ct, out=None):

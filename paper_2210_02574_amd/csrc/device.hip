@@ -232,6 +232,8 @@ static ConvArgs conv_args(const he_ctx *c, const u64 *src, int level, int dst_st
     cv.src_stride = src_stride;
     cv.src2 = nullptr;
     cv.src2_stride = 0;
+    cv.rs_mod = level - 1;
+    cv.rs_nl = level - 1;
     return cv;
 }
 
@@ -834,6 +836,42 @@ extern "C" int32_t he_rescale_batch(he_ctx *ctx, const uint64_t *d_ct, uint64_t 
                                 ctx->dev.rs_inv_d + (size_t)(level - 1) * ctx->L, level, level - 1, 0, 1u, W, 2 * level,
                                 2 * (level - 1), 0);
     return ntt_forward(ctx, st, r, l, PRO_RESCALE, cv, &fa, 2 * count);
+}
+
+// ModRaise, the first step of bootstrapping: the centred coefficients of a level-1 ciphertext reduced modulo
+// every q_i, i < level_out.
+extern "C" int32_t he_modraise(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level_out, void *d_ws,
+                               size_t ws_bytes, void *stream)
+{
+    int32_t rc = level_guard(ctx, level_out);
+    if (rc != HE_OK) return rc;
+    if (level_out < 2) return HE_ELEVEL;
+    if (!d_ct || !d_out || !d_ws || d_ct == d_out) return HE_EINVAL;
+    const WsLayout w = ws_layout(ctx, level_out);
+    if (ws_bytes < w.total * ctx->N * sizeof(u64)) return HE_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    u64 *ws = (u64 *)d_ws;
+    const size_t N = ctx->N;
+    u64 *t = ws + w.x * N; // two limbs: the coefficient-domain components
+    LimbList in;
+    in.add(0, 0, 0);
+    in.add(1, 1, 0);
+    ConvArgs cv = conv_args(ctx, t, level_out, 1 << 30, 0);
+    cv.rs_mod = 0;
+    cv.rs_nl = level_out;
+    if ((rc = ntt_inverse(ctx, st, d_ct, t, in, SCALE_NONE, cv)) != HE_OK) return rc;
+    LimbList l;
+    for (int c = 0; c < 2; c++)
+        for (int i = 1; i < level_out; i++) l.add(c * level_out + i, i);
+    if ((rc = ntt_forward(ctx, st, d_out, l, PRO_RESCALE, cv, nullptr, 2)) != HE_OK) return rc;
+    // limb 0 of both components is the input itself
+    hipError_t e = hipMemcpy2DAsync(d_out, (size_t)level_out * N * sizeof(u64), d_ct, N * sizeof(u64), N * sizeof(u64), 2,
+                                    hipMemcpyDeviceToDevice, st);
+    if (e != hipSuccess) {
+        ctx->hip_err = std::string("hipMemcpy2DAsync: ") + hipGetErrorString(e);
+        return HE_EHIP;
+    }
+    return HE_OK;
 }
 
 extern "C" int32_t he_rescale(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t level, void *d_ws,

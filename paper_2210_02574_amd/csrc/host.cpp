@@ -498,6 +498,26 @@ extern "C" int32_t he_keygen_secret(he_ctx *ctx, uint64_t seed, he_sk **out)
     return HE_OK;
 }
 
+extern "C" int32_t he_keygen_secret_sparse(he_ctx *ctx, uint64_t seed, int32_t h, he_sk **out)
+{
+    if (!ctx || !out || h < 1 || (u64)h > ctx->N) return HE_EINVAL;
+    he_sk *sk = new (std::nothrow) he_sk;
+    if (!sk) return HE_ENOMEM;
+    sk->ctx = ctx;
+    sk->s.assign(ctx->N, 0);
+    sk->s_ntt.resize((size_t)ctx->M * ctx->N);
+    Stream st(seed, 11, 0, 0);
+    for (int placed = 0; placed < h;) {
+        const u64 pos = st.next() & (ctx->N - 1);
+        if (sk->s[pos] != 0) continue;
+        sk->s[pos] = (st.next() & 1) == 0 ? 1 : -1;
+        placed++;
+    }
+    parallel_for(ctx->M, [&](int i) { small_to_ntt(ctx, i, sk->s.data(), sk->s_ntt.data() + (size_t)i * ctx->N); });
+    *out = sk;
+    return HE_OK;
+}
+
 extern "C" void he_sk_destroy(he_sk *sk) { delete sk; }
 
 extern "C" int32_t he_sk_coeffs(const he_sk *sk, int8_t *h_out)

@@ -46,6 +46,8 @@ struct ConvArgs {
     // ModDown + rescale: the dropped limb of component c (coefficient domain) at src2 + (c*level + level-1) limbs
     const u64 *src2;
     int src2_stride;
+    // centred-limb prologue (rescale, ModRaise): modulus index of the source limb, limbs per component in dst
+    int rs_mod, rs_nl;
 };
 
 // A limb's slot within its operation decodes as component c = slot / nl, limb i = slot % nl.
@@ -147,11 +149,11 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
             S.qld = T.mod[cv.level - 1].qd;
         }
     } else if (PRO == PRO_RESCALE) {
-        const int c = slot / (cv.level - 1);
+        const int c = slot / cv.rs_nl;
         S.sp[0] = src + ((size_t)c << LOGN);
-        S.ql = T.mod[cv.level - 1].q;
+        S.ql = T.mod[cv.rs_mod].q;
         S.half = (S.ql - 1) / 2;
-        S.qld = T.mod[cv.level - 1].qd;
+        S.qld = T.mod[cv.rs_mod].qd;
     }
     return S;
 }

@@ -1,0 +1,131 @@
+"""Bootstrapping, CPU side: pins of the oracle's composition (oracle/bootstrap.py) and of its parts, and the
+host-side pieces of the library's driver against them.  Ring N = 2^12 with the 24-prime chain."""
+import math
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+
+@pytest.fixture(scope="module")
+def ctx(oracle_mod):
+    from oracle import bootstrap as ob
+
+    p = wl.B12
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    s = ob.sparse_secret(o, 1, 64)
+    return o, s, ob
+
+
+def test_sparse_secret_has_the_requested_weight(ctx):
+    o, s, ob = ctx
+    assert int(np.abs(s).sum()) == 64 and set(np.unique(s).tolist()) <= {-1, 0, 1}
+    assert abs(int(s.sum())) <= 32  # signs are balanced
+    s2 = ob.sparse_secret(o, 2, 64)
+    assert not np.array_equal(s, s2)
+    import paper_2210_02574_amd as pkg
+
+    he = pkg.HE.from_params(wl.B12)
+    assert np.array_equal(he.keygen_secret_sparse(1, 64).coeffs(), s)
+    assert np.array_equal(he.keygen_secret_sparse(7, 192).coeffs(), ob.sparse_secret(o, 7, 192))
+
+
+def test_special_dft_is_the_decoding_of_the_subring(ctx):
+    """U w equals the first ns slots of the decoding of the polynomial with coefficients Re(w), Im(w) at the
+    multiples of N/(2 ns); and conj(U)^T U = ns I."""
+    o, s, ob = ctx
+    ns = 16
+    U = ob.special_dft(ns)
+    assert np.abs(U.conj().T @ U - ns * np.eye(ns)).max() < 1e-9
+    g = wl.rng(3)
+    w = g.uniform(-1, 1, ns) + 1j * g.uniform(-1, 1, ns)
+    D = o.N // (2 * ns)
+    coeffs = np.zeros(o.N)
+    coeffs[0:ns * D:D] = w.real
+    coeffs[ns * D::D] = w.imag
+    Z = o.decode(coeffs, 1.0)
+    assert np.abs(Z[:ns] - U @ w).max() < 1e-9
+    assert np.abs(Z - np.tile(Z[:ns], o.n // ns)).max() < 1e-9  # period ns
+
+
+def test_modraise_keeps_the_plaintext_modulo_q0(ctx):
+    """The raised ciphertext decrypts (big-integer CRT over all limbs) to m + e + q0 I with |I| small for a
+    sparse secret, and its limb 0 is the input."""
+    o, s, ob = ctx
+    m = wl.small_coeffs(4, o.N, 2**40)
+    ct = o.encrypt_coeffs(s, m, 1, 5)
+    up = ob.modraise(o, ct, 5)
+    assert np.array_equal(up[:, 0], ct[:, 0])
+    d = o.decrypt_coeffs(s, up)
+    low = o.decrypt_coeffs(s, ct)
+    q0 = o.q[0]
+    I = [(d[k] - low[k]) // q0 for k in range(o.N)]
+    assert all((d[k] - low[k]) % q0 == 0 for k in range(o.N))
+    assert 1 <= max(abs(v) for v in I) <= 33  # at most (h + 1) / 2 in absolute value, and not trivially zero
+    assert max(abs(low[k] - int(m[k])) for k in range(o.N)) <= 19
+
+
+def test_linear_transform_multiplies_the_packed_slots(ctx):
+    o, s, ob = ctx
+    ns = 16
+    plan = ob.Plan(o, ns, r=8)
+    g = wl.rng(6)
+    M = g.uniform(-1, 1, (ns, ns)) + 1j * g.uniform(-1, 1, (ns, ns))
+    z = g.uniform(-1, 1, ns) + 1j * g.uniform(-1, 1, ns)
+    level, scale = 4, 2.0**45
+    rot = {sh: o.keygen_rot(s, sh, 20 + sh) for sh in plan.baby + plan.giant}
+    ct = o.encrypt_coeffs(s, o.encode(np.tile(z, o.n // ns), scale), level, 7)
+    out = ob.linear_transform(o, ct, ob.encode_matrix(o, M, plan, level), rot, plan)
+    assert out.shape[1] == level - 1
+    dec = o.decrypt(s, out, scale)
+    assert np.abs(dec[:ns] - M @ z).max() < 1e-6
+    assert np.abs(dec - np.tile(dec[:ns], o.n // ns)).max() < 1e-6
+
+
+def test_bootstrap_refreshes_a_level_one_ciphertext(ctx):
+    """Level 1 -> level 9 of 24 with the same slots: error below 2^-14 at scale 2^40 (the sine's own error is
+    6.6 (m/q0)^3 ~ 6e-9 in units of q0, the Taylor part below 1e-8)."""
+    o, s, ob = ctx
+    ns, r = 16, 8
+    plan = ob.Plan(o, ns, r)
+    assert plan.out_level == 9
+    keys = {"relin": o.keygen_relin(s, 2), "conj": o.keygen_conj(s, 3),
+            "rot": {sh: o.keygen_rot(s, sh, 10 + i) for i, sh in enumerate(plan.rotation_shifts())}}
+    g = wl.rng(5)
+    z = g.uniform(-1, 1, ns) + 1j * g.uniform(-1, 1, ns)
+    delta = 2.0**40
+    ct = o.encrypt_coeffs(s, o.encode(np.tile(z, o.n // ns), delta), 1, 6)
+    out, level, factor = ob.bootstrap(o, ct, keys, plan)
+    assert level == 9 and out.shape == (2, 9, o.N)
+    assert abs(factor - 1.0) < 1e-3
+    dec = o.decrypt(s, out, delta * factor)
+    err = np.abs(dec - np.tile(z, o.n // ns)).max()
+    assert err < 2.0**-14, err
+    # and the refreshed ciphertext multiplies: (z^2) after one Mult + rescale
+    sq = o.rescale(o.hmult_relin(out, out, keys["relin"]))
+    s2 = (delta * factor) ** 2 / o.q[level - 1]
+    assert np.abs(o.decrypt(s, sq, s2)[:ns] - z * z).max() < 2.0**-12
+
+
+def test_driver_plaintexts_agree_with_the_oracle(ctx):
+    """The library driver derives its matrices and diagonals on its own: same slot vectors as the oracle's
+    (1e-12), encodings within one unit."""
+    import paper_2210_02574_amd as pkg
+    from paper_2210_02574_amd.bootstrap import Bootstrapper
+
+    o, s, ob = ctx
+    he = pkg.HE.from_params(wl.B12)
+    ns, r = 16, 8
+    bs = Bootstrapper(he, ns, r)
+    plan = ob.Plan(o, ns, r)
+    assert bs.rotation_shifts() == plan.rotation_shifts() and bs.out_level == plan.out_level
+    U = ob.special_dft(ns)
+    assert np.abs(bs.dft() - U).max() < 1e-12
+    mine = bs.diagonal_slots(bs.cts_matrix())
+    theirs = ob.bsgs_plaintext_slots((math.pi / (plan.gap * 2.0**r * ns)) * U.conj().T, plan, o.n)
+    for b in range(plan.g2):
+        for a in range(plan.g1):
+            assert np.abs(mine[b][a] - theirs[b][a]).max() < 1e-15
+    scale = float(o.q[23])
+    assert np.abs(he.encode(mine[1][2], scale) - o.encode(theirs[1][2], scale)).max() <= 1

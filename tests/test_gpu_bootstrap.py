@@ -1,0 +1,101 @@
+"""Bootstrapping on the device (driver in paper_2210_02574_amd/bootstrap.py) against the oracle's composition:
+bit-exact on every residue of the refreshed ciphertext when both sides use the same plaintext encodings, and
+accurate with the driver's own."""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def test_modraise_matches_oracle(oracle_mod):
+    import paper_2210_02574_amd as pkg
+    from oracle import bootstrap as ob
+
+    for p in (wl.B12, wl.N16):
+        he = pkg.HE.from_params(p, device=0)
+        o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+        ct = wl.uniform_ct(11, p, 1)
+        ct[0, 0, :4] = [0, p.q[0] - 1, (p.q[0] - 1) // 2, (p.q[0] + 1) // 2]
+        for level in (p.L, 2):
+            got = he.to_host(he.modraise(he.to_device(ct), level))
+            if p.logN == 12:
+                assert np.array_equal(got, ob.modraise(o, ct, level)), level
+            else:  # the Python oracle is slow at 2^16: check the definition on sampled limbs
+                for c, i in ((0, 0), (0, 1), (1, level - 1)):
+                    x = o.intt(ct[c, 0][None, :], [0])[0].astype(object)
+                    xc = np.where(x > (p.q[0] - 1) // 2, x - p.q[0], x)
+                    limb = np.array([int(v) % p.q[i] for v in xc], dtype=np.uint64)
+                    assert np.array_equal(got[c, i], o.ntt(limb[None, :], [i])[0]), (level, c, i)
+
+
+def test_bootstrap_bit_exact_and_accurate(oracle_mod):
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from oracle import bootstrap as ob
+    from paper_2210_02574_amd.bootstrap import Bootstrapper
+
+    assert torch.cuda.is_available()
+    p = wl.B12
+    he = pkg.HE.from_params(p, device=0)
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    ns, r = 16, 8
+    bs = Bootstrapper(he, ns, r)
+    plan = ob.Plan(o, ns, r)
+    sk, s = he.keygen_secret_sparse(1, 64), ob.sparse_secret(o, 1, 64)
+    keys = bs.make_keys(sk, 100)
+    okeys = {"relin": o.keygen_relin(s, 100), "conj": o.keygen_conj(s, 101),
+             "rot": {sh: o.keygen_rot(s, sh, 110 + i) for i, sh in enumerate(plan.rotation_shifts())}}
+    rng = wl.rng(5)
+    z = rng.uniform(-1, 1, ns) + 1j * rng.uniform(-1, 1, ns)
+    Z = np.tile(z, he.n // ns)
+    delta = 2.0**40
+    ct = o.encrypt_coeffs(s, o.encode(Z, delta), 1, 6)
+    assert np.array_equal(he.encrypt_coeffs(sk, o.encode(Z, delta), 1, 6), ct)
+    # the oracle's encodings of both matrices, used by both sides
+    U = ob.special_dft(ns)
+    cts_o = ob.encode_matrix(o, (np.pi / (plan.gap * 2.0**r * ns)) * U.conj().T, plan, plan.L)
+    stc_o = ob.encode_matrix(o, U / (4.0 * np.pi), plan, plan.out_level + 1)
+    want, wl_level, wfac = ob.bootstrap(o, ct, okeys, plan, cts_o, stc_o)
+    to_dev = lambda pts: [[he.to_device(x) for x in row] for row in pts]
+    out, level, factor = bs.run(he.to_device(ct), keys, to_dev(cts_o), to_dev(stc_o))
+    got = he.to_host(out)
+    assert level == wl_level == plan.out_level and factor == wfac
+    assert np.array_equal(got, want)
+    err = np.abs(he.decrypt(sk, got, delta * factor) - Z).max()
+    print("bootstrap N=2^12 ns=16: level 1 -> %d, error %.3g" % (level, err))
+    assert err < 2.0**-14
+    # the driver's own plaintexts (its encoder differs from the oracle's by at most one unit per coefficient)
+    out2, _, _ = bs.run(he.to_device(ct), keys)
+    err2 = np.abs(he.decrypt(sk, he.to_host(out2), delta * factor) - Z).max()
+    assert err2 < 2.0**-14
+
+
+def test_bootstrap_at_full_size():
+    """N = 2^16, L = 24, 64 packed slots: level 1 -> 9, accuracy against the encrypted values.  The error is set by
+    the 2^-26 relative rounding of the CoeffToSlot plaintexts (theta is exact to about 7e-10), amplified by
+    2^r (q0 / delta) sqrt(ns) / pi: 4e-4 here, 9e-5 with 16 slots."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from paper_2210_02574_amd.bootstrap import Bootstrapper
+
+    p = wl.N16
+    he = pkg.HE.from_params(p, device=0)
+    ns, r = 64, 8
+    bs = Bootstrapper(he, ns, r)
+    sk = he.keygen_secret_sparse(21, 64)
+    keys = bs.make_keys(sk, 300)
+    rng = wl.rng(22)
+    z = rng.uniform(-1, 1, ns) + 1j * rng.uniform(-1, 1, ns)
+    Z = np.tile(z, he.n // ns)
+    delta = 2.0**40
+    ct = he.encrypt_coeffs(sk, he.encode(Z, delta), 1, 23)
+    out, level, factor = bs.run(he.to_device(ct), keys)
+    torch.cuda.synchronize()
+    assert level == 9
+    err = np.abs(he.decrypt(sk, he.to_host(out), delta * factor) - Z).max()
+    print("bootstrap N=2^16 ns=64: level 1 -> %d, error %.3g" % (level, err))
+    assert err < 2.0**-10

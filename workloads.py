@@ -65,6 +65,9 @@ C1 = Params("C1", 12, _C1_Q, _C1_P, 1)
 C1B = Params("C1B", 12, _C1_Q, _C1_P, 3)
 # N=2^16, 24 ~50-bit primes, 4 ~60-bit special primes, dnum=6: the throughput configuration.
 N16 = Params("N16", 16, _N16_Q, _N16_P, 6)
+# The same prime chain on a small ring (the primes are 1 mod 2^17, hence 1 mod 2^13): 24 levels at N=2^12, deep
+# enough to run a whole bootstrapping where the oracle finishes in seconds.
+B12 = Params("B12", 12, _N16_Q, _N16_P, 6)
 
 
 def active_mod_idx(params: Params, level: int) -> List[int]:
