@@ -162,6 +162,12 @@ int32_t he_sub(he_ctx *ctx, const uint64_t *d_a, const uint64_t *d_b, uint64_t *
 /* Ciphertext times NTT-domain plaintext [level][N]; d_out may alias d_ct. */
 int32_t he_pmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *d_pt, uint64_t *d_out, int32_t level,
                  void *stream);
+/* out = sum over k < count of ct_k * pt_k in one pass: h_d_cts / h_d_pts are host arrays of `count` device
+ * pointers ([2][level][N] ciphertexts, [level][N] NTT-domain plaintexts), 1 <= count <= 64.  The residues
+ * equal those of `count` he_pmult calls summed with he_add.  d_out may alias one of the ciphertexts only
+ * if that ciphertext is not read by another term (each output word depends on the same word of every term). */
+int32_t he_pmult_sum(he_ctx *ctx, const uint64_t *const *h_d_cts, const uint64_t *const *h_d_pts, int32_t count,
+                     uint64_t *d_out, int32_t level, void *stream);
 /* Ciphertext times one residue per limb (h_scalar[i] in [0,q_i), host array read before return). */
 int32_t he_cmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *h_scalar, uint64_t *d_out, int32_t level,
                  void *stream);

@@ -76,6 +76,18 @@ class Plan:
     def rotation_shifts(self):
         return sorted(set(self.subsum_shifts + self.baby + self.giant))
 
+    def natural_factor(self, o) -> float:
+        """Output scale / input scale when the last matrix carries no extra gain: the scale of exp(i theta)
+        after the r squarings, over q0 (follows the rescale rule step by step)."""
+        q = [float(v) for v in o.q]
+        l = self.L - 1
+        s = q[0] * q[0] / q[l - 5]
+        lvl = l - 5
+        for _ in range(self.r):
+            s = s * s / q[lvl - 1]
+            lvl -= 1
+        return s / q[0]
+
 
 def bsgs_plaintext_slots(M: np.ndarray, plan: Plan, n: int):
     """Slot vectors of the pre-rotated diagonals: entry [b][a][j] = M[(j - g1 b) % ns][(j + a) % ns], tiled to n."""
@@ -172,10 +184,11 @@ def exp_i(o, theta, level: int, scale: float, relin, r: int):
     return E, lvl, s
 
 
-def bootstrap(o, ct1, keys, plan: Plan, pts_cts=None, pts_stc=None):
+def bootstrap(o, ct1, keys, plan: Plan, pts_cts=None, pts_stc=None, gain: float = 1.0):
     """ct1: [2][1][N] at scale delta.  keys: {'relin', 'conj', 'rot': {shift: key}}.
     Returns (ct, level, factor): the refreshed ciphertext at `level`, encrypting the same slots at scale
-    delta * factor."""
+    delta * factor.  gain multiplies the last matrix (and the factor): with gain = target / (delta *
+    natural_factor) the result lands exactly on the scale `target`."""
     L, ns, r = plan.L, plan.ns, plan.r
     relin, conj, rot = keys["relin"], keys["conj"], keys["rot"]
     U = special_dft(ns)
@@ -195,6 +208,6 @@ def bootstrap(o, ct1, keys, plan: Plan, pts_cts=None, pts_stc=None):
     Hp, Hm = o.add(E1, iE2), o.sub(E1, iE2)
     F = o.pmult(o.sub(Hp, o.hconj(Hm, conj)), monomial_i(o, lvl, -1))
     if pts_stc is None:
-        pts_stc = encode_matrix(o, U / (4.0 * math.pi), plan, lvl)
+        pts_stc = encode_matrix(o, (gain / (4.0 * math.pi)) * U, plan, lvl)
     out = linear_transform(o, F, pts_stc, rot, plan)
-    return out, lvl - 1, s / float(o.q[0])
+    return out, lvl - 1, gain * s / float(o.q[0])

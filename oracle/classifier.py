@@ -68,14 +68,16 @@ def _const(o, value, scale, level):
     return [v % o.q[i] for i in range(level)]
 
 
-def train_step(o, X, W, Y, relin, rot, level, scale, lr, n_samples, a=None):
+def train_step(o, X, W, Y, relin, rot, level, scale, lr, n_samples, a=None, block=1024):
     """X: list of ciphertexts, W: list (per class), Y[c][i]; rot: dict shift -> key.  Returns new W list.
     Same level/scale schedule as the device driver, derived here from the rescale rule
-    (scale after a rescale = scale before / dropped prime)."""
+    (scale after a rescale = scale before / dropped prime).  block = slots per sample."""
     q = [float(v) for v in o.q]
     a = logistic_poly_coeffs() if a is None else a  # monomial coefficients in x
     mask = np.zeros(o.n)
-    mask[::1024] = 1.0
+    mask[::block] = 1.0
+    lb = block.bit_length() - 1
+    lnb = (o.n // block).bit_length() - 1
     new_w = []
     for c, w in enumerate(W):
         G = None
@@ -83,11 +85,11 @@ def train_step(o, X, W, Y, relin, rot, level, scale, lr, n_samples, a=None):
             # logits: block sums of x*w
             m = o.rescale(o.hmult_relin(x, w, relin))  # level-1
             s1 = scale * scale / q[level - 1]
-            for k in range(10):
+            for k in range(lb):
                 m = o.add(m, o.hrot(m, rot[1 << k], 1 << k))
             pt = o.coeffs_to_ntt(o.encode(mask, q[level - 2]), level - 1)
             z = o.rescale(o.pmult(m, pt))  # level-2, scale s1
-            for k in range(10):
+            for k in range(lb):
                 z = o.add(z, o.hrot(z, rot[-(1 << k)], -(1 << k)))
             # polynomial 0.5 + z (a1 + a3 z^2 + a5 z^4 + a7 z^6) = 0.5 + z ((a1 + a3 z^2) + z^4 (a5 + a7 z^2))
             z2 = o.rescale(o.hmult_relin(z, z, relin))  # level-3
@@ -110,8 +112,8 @@ def train_step(o, X, W, Y, relin, rot, level, scale, lr, n_samples, a=None):
             G = g if G is None else o.add(G, g)
         G = o.rescale(G)  # level-7
         tg = tp * scale / q[level - 7]
-        for k in range(5):
-            G = o.add(G, o.hrot(G, rot[1024 << k], 1024 << k))
+        for k in range(lnb):
+            G = o.add(G, o.hrot(G, rot[block << k], block << k))
         upd = o.rescale(o.cmult(G, _const(o, lr / n_samples, scale * q[level - 8] / tg, level - 7)))
         new_w.append(o.sub(o.moddrop(w, level - 8), upd))
     return new_w

@@ -27,7 +27,7 @@ SYMBOLS = [
     "he_ctx_create", "he_ctx_destroy", "he_strerror", "he_last_hip_error", "he_ctx_modulus",
     "he_galois_element", "he_gauss_cdt", "he_workspace_bytes",
     "he_keygen_secret", "he_sk_destroy", "he_sk_coeffs", "he_keygen_relin", "he_keygen_rot",
-    "he_keygen_conj", "he_keygen_public", "he_encrypt_public_coeffs", "he_keygen_secret_sparse", "he_modraise",
+    "he_keygen_conj", "he_keygen_public", "he_encrypt_public_coeffs", "he_keygen_secret_sparse", "he_modraise", "he_pmult_sum",
     "he_evk_from_host", "he_evk_to_host", "he_evk_destroy",
     "he_encode", "he_decode", "he_plain_to_ntt", "he_encrypt_coeffs", "he_decrypt_coeffs", "he_decrypt",
     "he_ntt", "he_intt", "he_add", "he_sub", "he_pmult", "he_cmult", "he_add_const", "he_moddrop",
@@ -93,6 +93,7 @@ def load_library() -> ctypes.CDLL:
             "he_keygen_conj": [vp, vp, u64, ctypes.POINTER(vp)],
             "he_keygen_secret_sparse": [vp, u64, i32, ctypes.POINTER(vp)],
             "he_modraise": [vp, vp, vp, i32, vp, sz, vp],
+            "he_pmult_sum": [vp, vp, vp, i32, vp, i32, vp],
             "he_keygen_public": [vp, vp, u64, vp],
             "he_encrypt_public_coeffs": [vp, vp, vp, i32, u64, vp],
             "he_evk_from_host": [vp, vp, u64, ctypes.POINTER(vp)],
@@ -480,6 +481,22 @@ class HE:
         self._chk(
             self.lib.he_rescale(self.ctx, self._dp(ct), self._dp(out), level, ws, wsb, self._stream()), "he_rescale"
         )
+        return out
+
+    def pmult_sum(self, cts, pts, out=None):
+        """sum_k cts[k] * pts[k] in one pass (at most 64 terms per call; longer lists are chunked and added)."""
+        assert len(cts) == len(pts) and len(cts) >= 1
+        level = self._level(cts[0])
+        out = self.empty_ct(level) if out is None else out
+        acc = None
+        for lo in range(0, len(cts), 64):
+            c, p = cts[lo:lo + 64], pts[lo:lo + 64]
+            ca = (ctypes.c_void_p * len(c))(*[t.data_ptr() for t in c])
+            pa = (ctypes.c_void_p * len(p))(*[t.data_ptr() for t in p])
+            dst = out if acc is None else self.empty_ct(level)
+            self._chk(self.lib.he_pmult_sum(self.ctx, ca, pa, len(c), self._dp(dst), level, self._stream()),
+                      "he_pmult_sum")
+            acc = dst if acc is None else self.add(acc, dst, out=acc)
         return out
 
     def modraise(self, ct, level_out: int, out=None):

@@ -38,7 +38,7 @@ class Bootstrapper:
         self.out_level = self.L - 7 - r
         assert self.out_level >= 1, "not enough levels for this r"
         self._mono: Dict = {}
-        self._pts = None
+        self._pts: Dict = {}
 
     # ---- keys and plaintexts ----------------------------------------------------------------------------------
 
@@ -66,9 +66,23 @@ class Bootstrapper:
         # (1/ns) conj(U)^T inverts U; 1/gap undoes the trace; pi / 2^r turns (w + conj w) into 2 pi Re(w) / 2^r
         return (math.pi / (self.gap * 2.0**self.r * self.ns)) * self.dft().conj().T
 
-    def stc_matrix(self) -> np.ndarray:
+    def stc_matrix(self, gain: float = 1.0) -> np.ndarray:
         # sin / (2 pi), and the 1/2 of the imaginary-part extraction
-        return self.dft() / (4.0 * math.pi)
+        return (gain / (4.0 * math.pi)) * self.dft()
+
+    def natural_factor(self) -> float:
+        """Output scale over input scale at gain 1: the scale of exp(i theta) after the squarings over q0."""
+        q = [float(v) for v in self.he.q]
+        lvl = self.L - 6
+        s = q[0] * q[0] / q[lvl]
+        for _ in range(self.r):
+            s = s * s / q[lvl - 1]
+            lvl -= 1
+        return s / q[0]
+
+    def gain_for(self, delta_in: float, target_scale: float) -> float:
+        """Gain of the last matrix that makes the refreshed ciphertext land exactly on target_scale."""
+        return target_scale / (delta_in * self.natural_factor())
 
     def diagonal_slots(self, M: np.ndarray):
         """[b][a]: slot vector (length n) of diagonal g1 b + a of M, rotated right by g1 b."""
@@ -94,15 +108,17 @@ class Bootstrapper:
         scale = float(he.q[level - 1])
         return [[self._plain(he.encode(v, scale), level) for v in row] for row in self.diagonal_slots(M)]
 
-    def prepare(self):
-        """Encodes the plaintext diagonals of both matrix products once (they depend only on ns, r and the moduli)."""
-        if self._pts is None:
-            self._pts = (self.encode_matrix(self.cts_matrix(), self.L),
-                         self.encode_matrix(self.stc_matrix(), self.out_level + 1))
+    def prepare(self, gain: float = 1.0):
+        """Encodes the plaintext diagonals of both matrix products once (they depend only on ns, r, the moduli
+        and the gain of the last matrix)."""
+        if "cts" not in self._pts:
+            self._pts["cts"] = self.encode_matrix(self.cts_matrix(), self.L)
             for lvl in (self.L - 1, self.L - 6, self.out_level + 1):
                 for sign in (1, -1):
                     self.monomial(lvl, sign)
-        return self._pts
+        if ("stc", gain) not in self._pts:
+            self._pts[("stc", gain)] = self.encode_matrix(self.stc_matrix(gain), self.out_level + 1)
+        return self._pts["cts"], self._pts[("stc", gain)]
 
     def monomial(self, level: int, sign: int):
         """Plaintext of +-X^(N/2): every slot times +-i, exactly, at no cost in scale or level."""
@@ -121,9 +137,7 @@ class Bootstrapper:
         babies = [ct] + (he.hrot_many([rot[a] for a in range(1, g1)], ct) if g1 > 1 else [])
         acc = None
         for b in range(self.g2):
-            inner = he.pmult(babies[0], pts[b][0])
-            for a in range(1, g1):
-                he.add(inner, he.pmult(babies[a], pts[b][a]), out=inner)
+            inner = he.pmult_sum(babies, pts[b])
             if b:
                 inner = he.hrot(rot[g1 * b], inner)
             acc = inner if acc is None else he.add(acc, inner, out=acc)
@@ -171,15 +185,16 @@ class Bootstrapper:
 
     # ---- the whole operation ------------------------------------------------------------------------------------
 
-    def run(self, ct1, keys, pts_cts=None, pts_stc=None):
+    def run(self, ct1, keys, pts_cts=None, pts_stc=None, gain: float = 1.0):
         """ct1: device ciphertext at level 1 (scale delta, slot vector of period ns).  Returns (ct, level, factor):
-        the same slots at `level` and scale delta * factor."""
+        the same slots at `level` and scale delta * factor.  gain multiplies the last matrix and the factor
+        (see gain_for); explicit plaintexts must have been encoded with the same gain."""
         import torch
 
         he, L = self.he, self.L
         relin, conj, rot = keys["relin"], keys["conj"], keys["rot"]
         if pts_cts is None or pts_stc is None:
-            pts_cts, pts_stc = self.prepare()
+            pts_cts, pts_stc = self.prepare(gain)
         ct = he.modraise(ct1, L)
         he.rotate_sum([rot[sh] for sh in self.trace_shifts], ct)
         scale = float(he.q[0])  # read as a ciphertext of t / q0
@@ -191,4 +206,4 @@ class Bootstrapper:
         plus, minus = he.add(E[0], iE2), he.sub(E[0], iE2)
         F = he.pmult(he.sub(plus, he.hconj(conj, minus)), self.monomial(lvl, -1))
         out = self.linear_transform(F, pts_stc, rot)
-        return out, lvl - 1, s / float(he.q[0])
+        return out, lvl - 1, gain * s / float(he.q[0])

@@ -71,10 +71,7 @@ class EncryptedInference:
         """ct: device ciphertext at self.level, scale s; returns a level-1 lower ciphertext at scale s."""
         he = self.he
         rots = he.hrot_many([keys[r] for r in INFER_HOISTED], ct)
-        acc = he.pmult(ct, pts[0])
-        for r, pt in zip(rots, pts[1:]):
-            he.add(acc, he.pmult(r, pt), out=acc)
-        out = he.rescale(acc)
+        out = he.rescale(he.pmult_sum([ct] + list(rots), pts))
         he.rotate_sum([keys[r] for r in INFER_SUM_SHIFTS], out)
         return out
 
@@ -144,12 +141,19 @@ class EncryptedTrainStep:
     block at the feature offsets (same level and scale); Y[c][i]: labels replicated over each block at
     plan.label_level / plan.label_scale.  Per (class, ciphertext): 6 HMult and 20 HRot; per class 5 more HRot."""
 
-    def __init__(self, he, level: int, scale: float, lr: float, n_samples: int, coeffs=None):
+    def __init__(self, he, level: int, scale: float, lr: float, n_samples: int, coeffs=None, block: int = BLOCK):
+        """block: slots per sample (a power of two; the paper's layout is 1024)."""
         self.he = he
         self.plan = TrainPlan(he.q, level, scale, lr, n_samples, coeffs)
+        assert block & (block - 1) == 0 and block <= he.n
+        self.block = block
+        lb, lnb = block.bit_length() - 1, (he.n // block).bit_length() - 1
+        self.sum_shifts = tuple(1 << k for k in range(lb))           # block sum
+        self.fill_shifts = tuple(-(1 << k) for k in range(lb))       # replicate slot 0 of a block
+        self.block_shifts = tuple(block << k for k in range(lnb))    # sum over the blocks
 
     def rotation_shifts(self):
-        return list(TRAIN_SUM_SHIFTS) + list(TRAIN_FILL_SHIFTS) + list(TRAIN_BLOCK_SHIFTS)
+        return list(self.sum_shifts) + list(self.fill_shifts) + list(self.block_shifts)
 
     def make_keys(self, sk, seed: int):
         rot = {r: self.he.keygen_rot(sk, r, seed + 1 + k) for k, r in enumerate(self.rotation_shifts())}
@@ -157,7 +161,7 @@ class EncryptedTrainStep:
 
     def mask_slots(self) -> np.ndarray:
         m = np.zeros(self.he.n)
-        m[::BLOCK] = 1.0
+        m[::self.block] = 1.0
         return m
 
     def encode_mask(self):
@@ -190,9 +194,9 @@ class EncryptedTrainStep:
         """(p(<x, w>) - y) * x for one ciphertext of samples: level l-6, scale t_p * scale, not rescaled."""
         he = self.he
         m = self._mul(relin, x, w)
-        he.rotate_sum([rot[r] for r in TRAIN_SUM_SHIFTS], m)
+        he.rotate_sum([rot[r] for r in self.sum_shifts], m)
         z = he.rescale(he.pmult(m, mask_pt))
-        he.rotate_sum([rot[r] for r in TRAIN_FILL_SHIFTS], z)
+        he.rotate_sum([rot[r] for r in self.fill_shifts], z)
         e = self.logistic(relin, z)
         he.sub(e, y, out=e)
         return he.hmult_relin(relin, e, x_low)
@@ -207,7 +211,7 @@ class EncryptedTrainStep:
                 g = self.gradient_term(relin, rot, mask_pt, x, X_low[i], w, Y[c][i])
                 G = g if G is None else he.add(G, g, out=G)
             G = he.rescale(G)
-            he.rotate_sum([rot[r] for r in TRAIN_BLOCK_SHIFTS], G)
+            he.rotate_sum([rot[r] for r in self.block_shifts], G)
             level = int(G.shape[1])
             upd = he.rescale(he.cmult(G, _residues(p.step, p.c_w, he.q, level)))
             out.append(he.sub(he.moddrop(w, p.out_level), upd))
@@ -246,9 +250,9 @@ class EncryptedTrainStep:
         for c, w in enumerate(W):
             wb = w.unsqueeze(0).expand(n, -1, -1, -1).contiguous()
             m = self._mul_b(relin, X, wb)
-            he.rotate_sum_batch([rot[r] for r in TRAIN_SUM_SHIFTS], m)
+            he.rotate_sum_batch([rot[r] for r in self.sum_shifts], m)
             z = he.rescale_batch(he.pmult_batch(m, mask_pt))
-            he.rotate_sum_batch([rot[r] for r in TRAIN_FILL_SHIFTS], z)
+            he.rotate_sum_batch([rot[r] for r in self.fill_shifts], z)
             e = self._logistic_b(relin, z)
             he.sub_batch(e, Y[c], out=e)
             g = he.hmult_relin_batch(relin, e, X_low)
@@ -258,7 +262,7 @@ class EncryptedTrainStep:
                 he.add_batch(g[:h], g[k - h:k], out=g[:h])
                 k -= h
             G = he.rescale(g[0])
-            he.rotate_sum([rot[r] for r in TRAIN_BLOCK_SHIFTS], G)
+            he.rotate_sum([rot[r] for r in self.block_shifts], G)
             level = int(G.shape[1])
             upd = he.rescale(he.cmult(G, _residues(p.step, p.c_w, he.q, level)))
             out.append(he.sub(he.moddrop(w, p.out_level), upd))

@@ -445,6 +445,26 @@ extern "C" int32_t he_pmult(he_ctx *ctx, const uint64_t *d_ct, const uint64_t *d
     return he_pmult_batch(ctx, d_ct, d_pt, d_out, level, 1, stream);
 }
 
+extern "C" int32_t he_pmult_sum(he_ctx *ctx, const uint64_t *const *h_d_cts, const uint64_t *const *h_d_pts,
+                                int32_t count, uint64_t *d_out, int32_t level, void *stream)
+{
+    int32_t rc = level_guard(ctx, level);
+    if (rc != HE_OK) return rc;
+    if (!h_d_cts || !h_d_pts || !d_out || count < 1 || count > PMULT_SUM_MAX) return HE_EINVAL;
+    PmultSumArgs a;
+    memset(&a, 0, sizeof(a));
+    for (int k = 0; k < count; k++) {
+        if (!h_d_cts[k] || !h_d_pts[k]) return HE_EINVAL;
+        a.ct[k] = h_d_cts[k];
+        a.pt[k] = h_d_pts[k];
+    }
+    a.count = count;
+    dim3 grid((unsigned)(ctx->N / 256), (unsigned)(2 * level));
+    KLAUNCH(ctx, (hipStream_t)stream, KID_LIMBWISE, (double)(3 * count + 2) * level * ctx->N * 8.0, (k_pmult_sum), grid, a,
+            d_out, ctx->dev, level, ctx->logN);
+    return launch_ok(ctx);
+}
+
 static int32_t scalar_args(he_ctx *ctx, const uint64_t *h_scalar, int level, bool with_companion, ScalarArgs &sc)
 {
     memset(&sc, 0, sizeof(sc));

@@ -50,6 +50,43 @@ __global__ __launch_bounds__(256) void k_addconst(const u64 *__restrict__ a, u64
     out[((size_t)l << logN) + n] = ll < (unsigned)level ? csub(v + sc.s[ll].w, T.mod[ll].q) : v;
 }
 
+// out = sum_k ct_k * pt_k: `count` ciphertexts [2][level][N], each times its own plaintext [level][N]
+// (the inner sums of a baby-step/giant-step matrix product, one pass instead of count products and sums).
+#define PMULT_SUM_MAX 64
+struct PmultSumArgs {
+    const u64 *ct[PMULT_SUM_MAX];
+    const u64 *pt[PMULT_SUM_MAX];
+    int count;
+};
+__global__ __launch_bounds__(256) void k_pmult_sum(PmultSumArgs a, u64 *__restrict__ out, DevTables T, int level, int logN)
+{
+    const unsigned l = blockIdx.y, i = l % level;
+    const size_t n = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t oc = ((size_t)l << logN) + n, op = ((size_t)i << logN) + n;
+    const ModConst m = T.mod[i];
+    u64 r;
+    if (m.qd != 0.0) {
+        double acc = 0.0;
+        for (int k = 0; k < a.count; k++) {
+            acc += fp_mulmod(u2d(a.ct[k][oc]), u2d(a.pt[k][op]), m.qd, m.qinvd);
+            if ((k & 3) == 3) acc = fp_reduce(acc, m.qd, m.qinvd);
+        }
+        r = fp_canon(acc, m.qd, m.qinvd);
+    } else {
+        U128 acc{0, 0};
+        u64 part = 0;
+        for (int k = 0; k < a.count; k++) {
+            mac128(acc, a.ct[k][oc], a.pt[k][op]);
+            if ((k & 7) == 7) { // eight products of two residues below 2^62 fit 128 bits
+                part = csub(part + reduce128(acc, m), m.q);
+                acc = U128{0, 0};
+            }
+        }
+        r = csub(part + reduce128(acc, m), m.q);
+    }
+    out[oc] = r;
+}
+
 // Tensor product: d0 = a0 b0, d1 = a0 b1 + a1 b0 -> out (may alias A or B); d2 = a1 b1 -> d2.
 // blockIdx.z = operation of a batch: input ciphertexts 2*level limbs apart, out buffers out_stride and d2
 // buffers d2_stride limbs apart.

@@ -1,0 +1,64 @@
+"""Encrypted training loop: the paper's recipe (Section 3.1: logistic regression on encrypted embeddings, the
+logistic function as a polynomial, stochastic gradient descent with Nesterov momentum, Bootstrap to keep
+going) as a sequence of library calls.
+
+One iteration, per class, with the weights W at the level Bootstrap returns (l) and scale S:
+  V' = W - (lr / n) sum_samples (p(<x, W>) - y) x        gradient step, eight levels (classifier.EncryptedTrainStep)
+  W' = (1 + gamma) V' - gamma V                           Nesterov's update in its look-ahead form, one level
+  W' <- W' / 2^10                                         one level, down to level 1: Bootstrap wants |m| << q0
+  W  <- Bootstrap(W'), with the gain that lands on S      fifteen levels, back to level l
+The labels and samples stay at level l and scale S, so nothing else changes from one iteration to the next.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .bootstrap import Bootstrapper
+from .classifier import EncryptedTrainStep, _residues
+
+
+class EncryptedTrainer:
+    def __init__(self, he, block: int, lr: float, gamma: float, n_samples: int, scale: float = 2.0**50, r: int = 8,
+                 coeffs=None):
+        self.he, self.block, self.gamma, self.scale = he, block, gamma, scale
+        self.boot = Bootstrapper(he, block, r)
+        self.level = self.boot.out_level
+        assert self.level >= 11, "a gradient step (8), the momentum update (1) and the division (1) need 11 levels"
+        self.step = EncryptedTrainStep(he, self.level, scale, lr, n_samples, coeffs, block)
+        self.shrink = int(round(he.q[1] / 1024.0))                 # divides by ~2^10 when followed by a rescale
+        self.delta_in = scale * self.shrink / float(he.q[1])       # scale of the ciphertext Bootstrap receives
+        self.gain = self.boot.gain_for(self.delta_in, scale)
+
+    def rotation_shifts(self):
+        return sorted(set(self.step.rotation_shifts()) | set(self.boot.rotation_shifts()))
+
+    def make_keys(self, sk, seed: int):
+        he = self.he
+        rot = {sh: he.keygen_rot(sk, sh, seed + 10 + i) for i, sh in enumerate(self.rotation_shifts())}
+        return {"relin": he.keygen_relin(sk, seed), "conj": he.keygen_conj(sk, seed + 1), "rot": rot}
+
+    def momentum(self, v_new, v_old):
+        """(1 + gamma) v_new - gamma v_old, one level down, same scale."""
+        he = self.he
+        level = int(v_new.shape[1])
+        q_drop = float(he.q[level - 1])
+        a = he.cmult(v_new, _residues(1.0 + self.gamma, q_drop, he.q, level))
+        b = he.cmult(he.moddrop(v_old, level) if int(v_old.shape[1]) > level else v_old,
+                     _residues(self.gamma, q_drop, he.q, level))
+        return he.rescale(he.sub(a, b, out=a))
+
+    def refresh(self, keys, w, pts_cts=None, pts_stc=None):
+        """Level >= 2, scale S -> level self.level, scale S."""
+        he = self.he
+        w2 = he.moddrop(w, 2) if int(w.shape[1]) > 2 else w
+        small = he.rescale(he.cmult(w2, [self.shrink % int(he.q[0]), self.shrink % int(he.q[1])]))
+        out, level, _ = self.boot.run(small, keys, pts_cts, pts_stc, gain=self.gain)
+        assert level == self.level
+        return out
+
+    def iterate(self, keys, mask_pt, X, W, V, Y, boot_pts=(None, None)):
+        """X: [n][2][level][N]; W, V: per class (V at level - 8 or above); Y: per class [n][2][label_level][N].
+        Returns (W, V) of the next iteration."""
+        v_new = self.step.run_batched(keys["relin"], keys["rot"], mask_pt, X, W, Y)
+        w_new = [self.refresh(keys, self.momentum(vn, vo), *boot_pts) for vn, vo in zip(v_new, V)]
+        return w_new, v_new

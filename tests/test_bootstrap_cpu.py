@@ -129,3 +129,44 @@ def test_driver_plaintexts_agree_with_the_oracle(ctx):
             assert np.abs(mine[b][a] - theirs[b][a]).max() < 1e-15
     scale = float(o.q[23])
     assert np.abs(he.encode(mine[1][2], scale) - o.encode(theirs[1][2], scale)).max() <= 1
+
+
+def test_training_iteration_with_momentum_and_bootstrap(oracle_mod):
+    """One whole iteration of the paper's training recipe on the small ring (26 levels): gradient step with the
+    degree-7 polynomial, Nesterov look-ahead update, division by 2^10, Bootstrap back to level 11 at exactly the
+    working scale; the decrypted weights follow the fp64 iteration to 1e-4."""
+    from oracle import bootstrap as ob
+    from oracle import classifier as oc
+    from oracle import training as ot
+    from training_common import Problem
+
+    p = wl.T12
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    pr = Problem(o.n)
+    plan = ob.Plan(o, pr.block, 8)
+    level, S, lr, gamma = plan.out_level, 2.0**50, 1.0, 0.5
+    assert level == 11
+    s = ob.sparse_secret(o, 1, 64)
+    step_shifts = [1 << k for k in range(6)] + [-(1 << k) for k in range(6)] + [pr.block << k for k in range(5)]
+    shifts = sorted(set(step_shifts) | set(plan.rotation_shifts()))
+    keys = {"relin": o.keygen_relin(s, 100), "conj": o.keygen_conj(s, 101),
+            "rot": {sh: o.keygen_rot(s, sh, 110 + i) for i, sh in enumerate(shifts)}}
+    a = oc.logistic_poly_coeffs()
+    q = [float(v) for v in o.q]
+    s1 = S * S / q[level - 1]
+    s4 = (s1 * s1 / q[level - 3]) ** 2 / q[level - 4]
+    label_scale = s1 * (s4 * S / q[level - 5]) / q[level - 6]
+    X = [o.encrypt_coeffs(s, o.encode(pr.slots_x(), S), level, 200)]
+    W = [o.encrypt_coeffs(s, o.encode(pr.slots_w(pr.w0), S), level, 201)]
+    V = [o.moddrop(W[0], level - 8)]
+    Y = [[o.encrypt_coeffs(s, o.encode(pr.slots_y(), label_scale), level - 6, 202)]]
+    W1, V1 = ot.iterate(o, X, W, V, Y, keys, plan, pr.block, S, lr, gamma, pr.nb, a)
+    assert W1[0].shape == (2, level, o.N) and V1[0].shape == (2, level - 8, o.N)
+    wp, vp = pr.plain_iteration(pr.w0, pr.w0, a, lr, gamma)
+    dec_w = o.decrypt(s, W1[0], S).real
+    dec_v = o.decrypt(s, V1[0], S).real
+    sl = slice(pr.off, pr.off + pr.dim)
+    assert np.abs(dec_v[sl] - vp).max() < 1e-6
+    assert np.abs(dec_w[sl] - wp).max() < 1e-4
+    assert np.abs(dec_w - np.tile(dec_w[:pr.block], pr.nb)).max() < 1e-4  # still one block repeated
+    assert np.abs(wp - pr.w0).max() > 0.05  # the step moved the weights

@@ -35,7 +35,7 @@ class Env:
         return self._keys[(seed, g)]
 
 
-@pytest.fixture(scope="module", params=["C1", "C1B", "N16"])
+@pytest.fixture(scope="module", params=["C1", "C1B", "N16", "I12", "M12"])
 def env(request, pkg, oracle_mod):
     return Env(pkg, oracle_mod, getattr(wl, request.param))
 
@@ -85,7 +85,7 @@ def test_ntt_edge_values(env):
 
 def _levels(p):
     if p.logN == 12:
-        return [3, 2, 1]
+        return list(range(p.L, 0, -1))
     return [24, 23, 21, 9, 4, 1]
 
 
@@ -103,6 +103,21 @@ def test_elementwise(env):
         # in place
         he.add(da, db, out=da)
         assert np.array_equal(he.to_host(da), o.add(a, b))
+
+
+def test_pmult_sum(env):
+    """sum_k ct_k * pt_k in one pass against the oracle's products and sums (70 terms: more than one call)."""
+    he, o, p = env.he, env.o, env.params
+    level = min(3, p.L) if p.logN == 12 else 9
+    terms = 70 if p.logN == 12 else 5
+    cts = [wl.uniform_ct(2000 + k, p, level) for k in range(terms)]
+    pts = [wl.uniform_limbs(2100 + k, p, list(range(level))) for k in range(terms)]
+    want = None
+    for c, t in zip(cts, pts):
+        term = o.pmult(c, t)
+        want = term if want is None else o.add(want, term)
+    got = he.pmult_sum([he.to_device(c) for c in cts], [he.to_device(t) for t in pts])
+    assert np.array_equal(he.to_host(got), want)
 
 
 def test_hmult_relin_and_rescale(env):
@@ -189,7 +204,7 @@ def test_real_keys_and_decryption(env):
     if p.name == "C1":
         pytest.skip("dnum=1 with P << Q: key-switch noise swamps the message (parity only)")
     level = 3 if p.logN == 12 else 5
-    scale = 2.0**30 if p.logN == 12 else 2.0**45
+    scale = 2.0**30 if p.name == "C1B" else 2.0**45
     sk, s = he.keygen_secret(801), o.keygen_secret(801)
     relin = he.keygen_relin(sk, 802)
     rot = he.keygen_rot(sk, 3, 803)

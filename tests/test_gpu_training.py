@@ -1,0 +1,70 @@
+"""Encrypted training loop on the device (paper_2210_02574_amd/training.py) against the oracle's composition:
+one iteration bit-exact on every residue (shared plaintext encodings), three iterations against the fp64
+iteration of the same polynomial step."""
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def test_training_iterations_match_oracle_and_plaintext(oracle_mod):
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from oracle import bootstrap as ob
+    from oracle import classifier as oc
+    from oracle import training as ot
+    from paper_2210_02574_amd.training import EncryptedTrainer
+    from training_common import Problem
+
+    assert torch.cuda.is_available()
+    p = wl.T12
+    he = pkg.HE.from_params(p, device=0)
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    pr = Problem(o.n)
+    S, lr, gamma = 2.0**50, 1.0, 0.5
+    a = oc.logistic_poly_coeffs()
+    tr = EncryptedTrainer(he, pr.block, lr, gamma, pr.nb, S, coeffs=np.array([a[k] * 8.0**k for k in range(8)]))
+    plan = ob.Plan(o, pr.block, 8)
+    level = tr.level
+    assert level == plan.out_level == 11 and tr.rotation_shifts() == sorted(
+        set([1 << k for k in range(6)] + [-(1 << k) for k in range(6)] + [pr.block << k for k in range(5)])
+        | set(plan.rotation_shifts()))
+    sk, s = he.keygen_secret_sparse(1, 64), ob.sparse_secret(o, 1, 64)
+    keys = tr.make_keys(sk, 100)
+    okeys = {"relin": o.keygen_relin(s, 100), "conj": o.keygen_conj(s, 101),
+             "rot": {sh: o.keygen_rot(s, sh, 110 + i) for i, sh in enumerate(tr.rotation_shifts())}}
+    tp = tr.step.plan
+    x_ct = o.encrypt_coeffs(s, o.encode(pr.slots_x(), S), level, 200)
+    w_ct = o.encrypt_coeffs(s, o.encode(pr.slots_w(pr.w0), S), level, 201)
+    y_ct = o.encrypt_coeffs(s, o.encode(pr.slots_y(), tp.label_scale), tp.label_level, 202)
+    # oracle iteration and its plaintext encodings (mask, both Bootstrap matrices)
+    U = ob.special_dft(pr.block)
+    cts_o = ob.encode_matrix(o, (np.pi / (plan.gap * 2.0**plan.r * pr.block)) * U.conj().T, plan, plan.L)
+    stc_o = ob.encode_matrix(o, (tr.gain / (4.0 * np.pi)) * U, plan, level + 1)
+    W1, V1 = ot.iterate(o, [x_ct], [w_ct], [o.moddrop(w_ct, level - 8)], [[y_ct]], okeys, plan, pr.block, S, lr, gamma,
+                        pr.nb, a, cts_o, stc_o)
+    mask = np.zeros(o.n)
+    mask[::pr.block] = 1.0
+    mask_pt = he.to_device(o.coeffs_to_ntt(o.encode(mask, float(o.q[level - 2])), level - 1))
+    to_dev = lambda pts: [[he.to_device(x) for x in row] for row in pts]
+    X = he.to_device(x_ct).unsqueeze(0).contiguous()
+    Y = [he.to_device(y_ct).unsqueeze(0).contiguous()]
+    W = [he.to_device(w_ct)]
+    V = [he.moddrop(W[0], level - 8)]
+    boot_pts = (to_dev(cts_o), to_dev(stc_o))
+    Wn, Vn = tr.iterate(keys, mask_pt, X, W, V, Y, boot_pts)
+    assert np.array_equal(he.to_host(Vn[0]), V1[0])
+    assert np.array_equal(he.to_host(Wn[0]), W1[0])
+    # two more iterations with the driver's own plaintexts; compare with the fp64 iteration
+    wp, vp = pr.plain_iteration(pr.w0, pr.w0, a, lr, gamma)
+    mask_own = tr.step.encode_mask()
+    for it in range(2):
+        Wn, Vn = tr.iterate(keys, mask_own, X, Wn, Vn, Y)
+        wp, vp = pr.plain_iteration(wp, vp, a, lr, gamma)
+        dec = he.decrypt(sk, he.to_host(Wn[0]), S).real
+        err = np.abs(dec[pr.off:pr.off + pr.dim] - wp).max()
+        print("iteration %d: max weight error %.3g (|w| up to %.3g)" % (it + 2, err, np.abs(wp).max()))
+        assert err < 2e-4

@@ -68,6 +68,19 @@ N16 = Params("N16", 16, _N16_Q, _N16_P, 6)
 # The same prime chain on a small ring (the primes are 1 mod 2^17, hence 1 mod 2^13): 24 levels at N=2^12, deep
 # enough to run a whole bootstrapping where the oracle finishes in seconds.
 B12 = Params("B12", 12, _N16_Q, _N16_P, 6)
+# Small rings that put ciphertext primes on the integer path of the device kernels (2^50 and above): all three
+# of I12; every other one of M12, where 55-bit and 45-bit primes alternate so that floating-point limbs take
+# sources of 2^50 and above in both base conversions.
+_W55 = tuple(2**55 - d for d in (311295, 434175, 696319))
+_W45 = tuple(2**45 - d for d in (204799, 385023))
+_W60 = tuple(2**60 - d for d in (16383, 98303))
+I12 = Params("I12", 12, _W55, _W60[:1], 3)
+M12 = Params("M12", 12, (_W55[0], _W45[0], _W55[1], _W45[1]), _W60, 2)
+# Two more primes of the same rule: 26 levels, enough for one training iteration (9 levels), the division
+# before bootstrapping (1), a bootstrapping (15) and the level it starts from; dnum = 7 keeps 4 primes per digit.
+_T_Q = _N16_Q + (2**50 - 64356351, 2**50 - 64749567)
+T16 = Params("T16", 16, _T_Q, _N16_P, 7)
+T12 = Params("T12", 12, _T_Q, _N16_P, 7)
 
 
 def active_mod_idx(params: Params, level: int) -> List[int]:
