@@ -142,6 +142,31 @@ struct ArithFp {
             }
         }
     }
+    // Stage 0 of a 32-element column step (N = 2^17): pairs (lo[k], hi[k]) are N/2 apart, twiddle index 1.
+    // Forward: inputs within 1q of zero (reduced or canonical).  Inverse: last stage, with the 1/N factors.
+    __device__ __forceinline__ void fwd_stage0(V (&lo)[16], V (&hi)[16], bool reduce_first) const
+    {
+        const double w = twf[1];
+        if (reduce_first) {
+#pragma unroll
+            for (int k = 0; k < 16; k++) lo[k] = reduce(lo[k]), hi[k] = reduce(hi[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const double t = mulmod(hi[k], w), x = lo[k];
+            lo[k] = x + t;
+            hi[k] = x - t;
+        }
+    }
+    __device__ __forceinline__ void inv_stage0_last(V (&lo)[16], V (&hi)[16]) const
+    {
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const double u = lo[k], v = hi[k];
+            lo[k] = mulmod(u + v, n0);
+            hi[k] = mulmod(u - v, n1);
+        }
+    }
 };
 
 // ArithInt ranges: [0, 4q) between forward stages, [0, 2q) between inverse stages.
@@ -196,6 +221,26 @@ struct ArithInt {
                     a[k1] = mul_shoup_lazy(u - v + q2, w, q);
                 }
             }
+        }
+    }
+    __device__ __forceinline__ void fwd_stage0(V (&lo)[16], V (&hi)[16], bool) const
+    {
+        const ShoupConst w = twf[1];
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const u64 u = csub(lo[k], q2);
+            const u64 v = mul_shoup_lazy(hi[k], w, q);
+            lo[k] = u + v;
+            hi[k] = u - v + q2;
+        }
+    }
+    __device__ __forceinline__ void inv_stage0_last(V (&lo)[16], V (&hi)[16]) const
+    {
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const u64 u = lo[k], v = hi[k];
+            lo[k] = mul_shoup_lazy(u + v, n0, q);
+            hi[k] = mul_shoup_lazy(u - v + q2, n1, q);
         }
     }
 };

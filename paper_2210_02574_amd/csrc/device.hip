@@ -44,8 +44,9 @@ template <class Tv> static int32_t upload(he_ctx *c, const std::vector<Tv> &v, c
 
 int32_t dev_upload_tables(he_ctx *c)
 {
-    if (c->logN != 12 && c->logN != 16) return HE_EINVAL;
+    if (c->logN != 12 && c->logN != 16 && c->logN != 17) return HE_EINVAL;
     if (c->alpha > 8 || c->K > 8 || c->M > 64) return HE_EINVAL; // conversion kernels are built for up to 8 sources
+    if (c->logN == 17 && (c->alpha > 4 || c->K > 4)) return HE_EINVAL; // ... and for up to 4 at N = 2^17
     HIP_TRY(c, hipSetDevice(c->device));
     int32_t rc;
 #define UP(field)                                                                                                    \
@@ -293,17 +294,30 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
         break;                                                                                                       \
     default: COLS1(KERN, GRID, PRO_RESCALE, 4); break;                                                               \
     }
-        if (c->logN == 16) {
+#define COLS4(KERN, GRID)                                                                                            \
+    switch (pro) {                                                                                                   \
+    case PRO_LOAD: COLS1(KERN, GRID, PRO_LOAD, 4); break;                                                            \
+    case PRO_MODUP: COLS1(KERN, GRID, PRO_MODUP, 4); break;                                                          \
+    case PRO_MODDOWN: COLS1(KERN, GRID, PRO_MODDOWN, 4); break;                                                      \
+    case PRO_MODDOWN_RS: COLS1(KERN, GRID, PRO_MODDOWN_RS, 4); break;                                                \
+    default: COLS1(KERN, GRID, PRO_RESCALE, 4); break;                                                               \
+    }
+        if (c->logN == 17) {
+            COLS4(k_ntt_fwd_cols17, 16 * nb)
+        } else if (c->logN == 16) {
             COLS(k_ntt_fwd_cols16, 16 * nb)
         } else {
             COLS(k_ntt_fwd_cols12, nb)
         }
+#undef COLS4
 #undef COLS
 #undef COLS1
         if (fin) {
             // reads the transform's input, the minuend and the addend, writes the result
             const double b = (double)nb * N8 * (3.0 + (fin->mode == 1 || fin->mode == 3 ? 1.0 : fin->mode == 2 ? 0.5 : fin->mode == 4 ? 1.5 : 0.0));
-            if (c->logN == 16)
+            if (c->logN == 17)
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<17, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin);
+            else if (c->logN == 16)
                 KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<16, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin);
             else
                 KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<12, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin);
@@ -312,7 +326,9 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
             if (int_blocks_only)
                 for (nbb = 0; nbb < nb && c->modc[lb.mod[nbb]].qd == 0.0;) nbb++;
             if (nbb == 0) return;
-            if (c->logN == 16)
+            if (c->logN == 17)
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<17, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin);
+            else if (c->logN == 16)
                 KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<16, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin);
             else
                 KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<12, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin);
@@ -336,7 +352,11 @@ static int32_t ntt_inverse(he_ctx *c, hipStream_t st, const u64 *src, u64 *dst, 
     case SCALE_MODUP: ICOLS1(KERN, GRID, SCALE_MODUP); break;                                                        \
     default: ICOLS1(KERN, GRID, SCALE_MODDOWN); break;                                                               \
     }
-        if (c->logN == 16) {
+        if (c->logN == 17) {
+            if (!blocks_done)
+                KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<17>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
+            ICOLS(k_ntt_inv_cols17, 16 * nb)
+        } else if (c->logN == 16) {
             if (!blocks_done)
                 KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<16>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
             ICOLS(k_ntt_inv_cols16, 16 * nb)
@@ -610,7 +630,9 @@ static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
     ia.g = g, ia.ws_stride = W, ia.d_stride = d_stride, ia.inv_special = 1;
     // reads beta digits and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
     const double inner_bytes = (double)count * (3 * beta + 2) * Ma * N * 8.0;
-    if (c->logN == 16)
+    if (c->logN == 17)
+        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<17>), grid, ia, c->dev);
+    else if (c->logN == 16)
         KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<16>), grid, ia, c->dev);
     else
         KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<12>), grid, ia, c->dev);

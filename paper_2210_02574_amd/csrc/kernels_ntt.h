@@ -6,6 +6,7 @@
 // between steps the 256-thread work-group exchanges data through LDS.  A limb of N = 2^16 takes
 // two kernels: the column pass (stages 0-7 on 16 columns x 256 rows, row stride 256 elements,
 // 128-byte global segments) and the block pass (stages 8-15 on 16 contiguous blocks of 256).
+// N = 2^17 keeps the two kernels: its column pass runs nine stages on 512 rows (32 elements per thread).
 // N = 2^12 uses a four-stage column pass (one thread per column) and the same block pass.
 // The inverse runs the block pass first and the column pass last.
 //
@@ -283,7 +284,6 @@ __device__ __forceinline__ void fin_store(const FinArgs &fa, const DevTables &T,
 // LDS tile of 16 groups x 256 elements; one pad word per 16 elements and 16 pad words per group
 // keep both the "stride-16" and the "16 consecutive" access patterns free of bank conflicts.
 #define TILE_GROUP 272
-#define TILE_WORDS (16 * TILE_GROUP)
 // threads per work-group of the block pass: 16 threads per 256-element block
 #ifndef BLK_THREADS
 #define BLK_THREADS 256
@@ -386,65 +386,136 @@ __global__ __launch_bounds__(BLK_THREADS) void k_ntt_inv_blocks(const u64 *src, 
         inv_blocks_body<LOGN>(in, limb, make_int(T, mi, LOGN), lds, tile);
 }
 
-// ---- column pass, N = 2^16: 256 rows x 16 columns per work-group (element (r, c) at r*256 + c) ----------------
+// ---- column pass, N = 2^16 and 2^17: all rows x 16 columns per work-group (element (r, c) at r*256 + c) ---------
+//
+// N = 2^16: 256 rows, 16 elements per thread, stages 0-3 then 4-7.  N = 2^17: 512 rows, 32 elements per thread:
+// stage 0 pairs the two halves of the rows, each half then takes stages 1-4 as a 16-element step, and after
+// the exchange every thread runs stages 5-8 on two groups of 16 consecutive rows.
 
+template <int LOGN> struct ColsGeom {
+    static constexpr int ROWS = 1 << (LOGN - 8);
+    static constexpr int HALVES = ROWS / 256;          // 16-element register steps per thread and phase
+    static constexpr int LDS_WORDS = (ROWS / 16) * TILE_GROUP;
+};
+
+// the 16 inputs of one thread in rows rl + 16 k + 256 h (plain load or base conversion)
 template <int PRO, bool SPLIT, int NSMAX, class A>
-__device__ __forceinline__ void fwd_cols16_body(u64 *__restrict__ limb, unsigned col0, const A &ar, u64 *lds,
-                                                const ConvSetup<NSMAX> &S, const ModConst &m)
+__device__ __forceinline__ void cols_inputs(typename A::V (&a)[16], const u64 *__restrict__ limb, unsigned col0, int h,
+                                            const A &ar, const ConvSetup<NSMAX> &S, const ModConst &m)
 {
     const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
-    typename A::V a[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) {
-        const unsigned pos = (rl + 16 * k) * 256 + col0 + c;
+        const unsigned pos = (rl + 16 * k + 256 * h) * 256 + col0 + c;
         a[k] = PRO == PRO_LOAD ? ar.load(limb[pos]) : conv_get<PRO, SPLIT>(S, ar, m, pos);
     }
-    ar.fwd16(a, 0, 0, PRO != PRO_LOAD);
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a[k]);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(16 * rl + k, c)]);
-    ar.fwd16(a, 4, rl, true);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[(16 * rl + k) * 256 + col0 + c] = ar.store_mid(a[k]); // the block pass finishes
 }
-
-template <class A>
-__device__ __forceinline__ void inv_cols16_body(u64 *__restrict__ limb, unsigned col0, const A &ar, u64 *lds)
+// second phase of the forward column pass for rows 16 g .. 16 g + 15
+template <int S_BASE, class A>
+__device__ __forceinline__ void cols_finish_group(typename A::V (&a)[16], u64 *__restrict__ limb, unsigned col0, unsigned g,
+                                                  const A &ar, const u64 *lds)
 {
-    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
-    typename A::V a[16];
+    const unsigned c = threadIdx.x & 15;
 #pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[(16 * rl + k) * 256 + col0 + c]);
-    ar.template inv16<false>(a, 4, rl);
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(16 * g + k, c)]);
+    ar.fwd16(a, S_BASE, g, true);
 #pragma unroll
-    for (int k = 0; k < 16; k++) lds[col_at(16 * rl + k, c)] = ar.store_mid(a[k]);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(rl + 16 * k, c)]);
-    ar.template inv16<true>(a, 0, 0);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[(rl + 16 * k) * 256 + col0 + c] = ar.store_final(a[k]);
+    for (int k = 0; k < 16; k++) limb[(16 * g + k) * 256 + col0 + c] = ar.store_mid(a[k]); // the block pass finishes
 }
 
+template <int LOGN, int PRO, bool SPLIT, int NSMAX, class A>
+__device__ __forceinline__ void fwd_cols_body(u64 *__restrict__ limb, unsigned col0, const A &ar, u64 *lds,
+                                              const ConvSetup<NSMAX> &S, const ModConst &m)
+{
+    constexpr int H = ColsGeom<LOGN>::HALVES;
+    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
+    typename A::V a0[16];
+    cols_inputs<PRO, SPLIT>(a0, limb, col0, 0, ar, S, m);
+    if (H == 1) {
+        ar.fwd16(a0, 0, 0, PRO != PRO_LOAD);
+#pragma unroll
+        for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a0[k]);
+        __syncthreads();
+        cols_finish_group<4>(a0, limb, col0, rl, ar, lds);
+    } else {
+        typename A::V a1[16];
+        // one half's source loads at a time: 32 outputs x up to 8 sources in flight would not fit the registers
+        if (PRO != PRO_LOAD) __builtin_amdgcn_sched_barrier(0);
+        cols_inputs<PRO, SPLIT>(a1, limb, col0, 1, ar, S, m);
+        ar.fwd_stage0(a0, a1, PRO != PRO_LOAD);
+        ar.fwd16(a0, 1, 0, true);
+        ar.fwd16(a1, 1, 1, true);
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            lds[col_at(rl + 16 * k, c)] = ar.store_mid(a0[k]);
+            lds[col_at(rl + 16 * k + 256, c)] = ar.store_mid(a1[k]);
+        }
+        __syncthreads();
+        cols_finish_group<5>(a0, limb, col0, rl, ar, lds);
+        cols_finish_group<5>(a1, limb, col0, rl + 16, ar, lds);
+    }
+}
+
+template <int LOGN, class A>
+__device__ __forceinline__ void inv_cols_body(u64 *__restrict__ limb, unsigned col0, const A &ar, u64 *lds)
+{
+    constexpr int H = ColsGeom<LOGN>::HALVES;
+    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
+    typename A::V a[H][16];
+#pragma unroll
+    for (int h = 0; h < H; h++) {
+        const unsigned g = rl + 16 * h;
+#pragma unroll
+        for (int k = 0; k < 16; k++) a[h][k] = ar.load_mid(limb[(16 * g + k) * 256 + col0 + c]);
+        ar.template inv16<false>(a[h], H + 3, g);
+#pragma unroll
+        for (int k = 0; k < 16; k++) lds[col_at(16 * g + k, c)] = ar.store_mid(a[h][k]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < H; h++) {
+#pragma unroll
+        for (int k = 0; k < 16; k++) a[h][k] = ar.load_mid(lds[col_at(rl + 16 * k + 256 * h, c)]);
+        if (H == 1)
+            ar.template inv16<true>(a[h], 0, 0);
+        else
+            ar.template inv16<false>(a[h], 1, h);
+    }
+    if (H == 2) ar.inv_stage0_last(a[0], a[H - 1]);
+#pragma unroll
+    for (int h = 0; h < H; h++)
+#pragma unroll
+        for (int k = 0; k < 16; k++) limb[(rl + 16 * k + 256 * h) * 256 + col0 + c] = ar.store_final(a[h][k]);
+}
+
+template <int LOGN, int PRO, int NSMAX>
+__device__ __forceinline__ void fwd_cols_kernel(u64 *__restrict__ data, const DevTables &T, const LimbBatch &lb,
+                                                const ConvArgs &cv)
+{
+    __shared__ u64 lds[ColsGeom<LOGN>::LDS_WORDS];
+    const unsigned tile = blockIdx.x & 15, b = blockIdx.x >> 4;
+    const unsigned mi = lb.mod[b], slot = lb.slot[b];
+    u64 *limb = data + ((size_t)slot << LOGN);
+    const ModConst m = T.mod[mi];
+    const ConvSetup<NSMAX> S = conv_setup<PRO, NSMAX, LOGN>(cv, T, slot, mi);
+    const bool split = PRO == PRO_MODUP ? T.up_split != 0 : pro_is_moddown(PRO) ? T.dn_split != 0 : false;
+    if (m.qd == 0.0)
+        fwd_cols_body<LOGN, PRO, false>(limb, tile * 16, make_int(T, mi, LOGN), lds, S, m);
+    else if (split)
+        fwd_cols_body<LOGN, PRO, true>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+    else
+        fwd_cols_body<LOGN, PRO, false>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+}
 // grid.x = 16 * batch
 template <int PRO, int NSMAX>
 __global__ __launch_bounds__(256) void k_ntt_fwd_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
 {
-    __shared__ u64 lds[TILE_WORDS];
-    const unsigned tile = blockIdx.x & 15, b = blockIdx.x >> 4;
-    const unsigned mi = lb.mod[b], slot = lb.slot[b];
-    u64 *limb = data + ((size_t)slot << 16);
-    const ModConst m = T.mod[mi];
-    const ConvSetup<NSMAX> S = conv_setup<PRO, NSMAX, 16>(cv, T, slot, mi);
-    const bool split = PRO == PRO_MODUP ? T.up_split != 0 : pro_is_moddown(PRO) ? T.dn_split != 0 : false;
-    if (m.qd == 0.0)
-        fwd_cols16_body<PRO, false>(limb, tile * 16, make_int(T, mi, 16), lds, S, m);
-    else if (split)
-        fwd_cols16_body<PRO, true>(limb, tile * 16, make_fp(T, mi, 16), lds, S, m);
-    else
-        fwd_cols16_body<PRO, false>(limb, tile * 16, make_fp(T, mi, 16), lds, S, m);
+    fwd_cols_kernel<16, PRO, NSMAX>(data, T, lb, cv);
+}
+template <int PRO, int NSMAX>
+__global__ __launch_bounds__(256) void k_ntt_fwd_cols17(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
+{
+    fwd_cols_kernel<17, PRO, NSMAX>(data, T, lb, cv);
 }
 
 // extra constant of the inverse column pass for modulus index mi
@@ -465,20 +536,31 @@ __device__ __forceinline__ void scale_consts(int scale, const ConvArgs &cv, cons
     }
 }
 
-template <int SCALE>
-__global__ __launch_bounds__(256) void k_ntt_inv_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
+template <int LOGN, int SCALE>
+__device__ __forceinline__ void inv_cols_kernel(u64 *__restrict__ data, const DevTables &T, const LimbBatch &lb,
+                                                const ConvArgs &cv)
 {
-    __shared__ u64 lds[TILE_WORDS];
+    __shared__ u64 lds[ColsGeom<LOGN>::LDS_WORDS];
     const unsigned tile = blockIdx.x & 15, b = blockIdx.x >> 4;
     const unsigned mi = lb.mod[b];
-    u64 *limb = data + ((size_t)lb.slot[b] << 16);
+    u64 *limb = data + ((size_t)lb.slot[b] << LOGN);
     ShoupConst ci;
     double cd;
     scale_consts(SCALE, cv, T, mi, ci, cd);
     if (T.mod[mi].qd != 0.0)
-        inv_cols16_body(limb, tile * 16, make_fp(T, mi, 16, cd), lds);
+        inv_cols_body<LOGN>(limb, tile * 16, make_fp(T, mi, LOGN, cd), lds);
     else
-        inv_cols16_body(limb, tile * 16, make_int(T, mi, 16, ci), lds);
+        inv_cols_body<LOGN>(limb, tile * 16, make_int(T, mi, LOGN, ci), lds);
+}
+template <int SCALE>
+__global__ __launch_bounds__(256) void k_ntt_inv_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
+{
+    inv_cols_kernel<16, SCALE>(data, T, lb, cv);
+}
+template <int SCALE>
+__global__ __launch_bounds__(256) void k_ntt_inv_cols17(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
+{
+    inv_cols_kernel<17, SCALE>(data, T, lb, cv);
 }
 
 // ---- column pass, N = 2^12: 16 rows x 256 columns, one thread per column --------------------------------------

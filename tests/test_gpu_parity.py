@@ -1,7 +1,7 @@
 """GPU parity: every device entry point, called through the C ABI, against the CPU oracle on the
 same seeded inputs -- bit-exact on every residue.  Sizes: the tiny configuration (N=2^12, literal
 dnum=1 and the one-prime-per-digit variant) in full, and N=2^16 / L=24 / dnum=6 at several levels
-including partial last digits."""
+including partial last digits; the paper-scale ring N=2^17 / L=30 / dnum=8 at three levels."""
 import numpy as np
 import pytest
 
@@ -35,7 +35,7 @@ class Env:
         return self._keys[(seed, g)]
 
 
-@pytest.fixture(scope="module", params=["C1", "C1B", "N16", "I12", "M12"])
+@pytest.fixture(scope="module", params=["C1", "C1B", "N16", "I12", "M12", "P17"])
 def env(request, pkg, oracle_mod):
     return Env(pkg, oracle_mod, getattr(wl, request.param))
 
@@ -86,6 +86,8 @@ def test_ntt_edge_values(env):
 def _levels(p):
     if p.logN == 12:
         return list(range(p.L, 0, -1))
+    if p.logN == 17:
+        return [30, 7, 1]
     return [24, 23, 21, 9, 4, 1]
 
 

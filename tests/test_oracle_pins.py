@@ -24,7 +24,7 @@ def tiny(orc, logN=4, L=4, K=2, dnum=2, qbits=20, pbits=24):
 
 # ----------------------------------------------------------------------------- parameters
 
-@pytest.mark.parametrize("params,qbits,pbits", [(wl.C1, 40, 50), (wl.N16, 50, 60), (wl.T16, 50, 60)])
+@pytest.mark.parametrize("params,qbits,pbits", [(wl.C1, 40, 50), (wl.N16, 50, 60), (wl.T16, 50, 60), (wl.P17, 50, 60)])
 def test_prime_tables_follow_the_rule(params, qbits, pbits):
     """The moduli are the largest primes = 1 mod 2N below 2^bits, descending (sympy primality)."""
     assert list(params.q) == ntt_primes(params.logN, qbits, params.L)

@@ -68,6 +68,18 @@ N16 = Params("N16", 16, _N16_Q, _N16_P, 6)
 # The same prime chain on a small ring (the primes are 1 mod 2^17, hence 1 mod 2^13): 24 levels at N=2^12, deep
 # enough to run a whole bootstrapping where the oracle finishes in seconds.
 B12 = Params("B12", 12, _N16_Q, _N16_P, 6)
+# The paper's ring degree (Section 3.1: N = 2^17, a 1540-bit modulus, level 29): 30 primes just below 2^50
+# (1500 bits; 2^50 is the limit of the floating-point kernels), 4 special primes below 2^60, dnum = 8.
+_P17_Q = tuple(
+    2**50 - d
+    for d in (
+        4718591, 20447231, 22806527, 23855103, 36438015, 40894463, 44826623, 45088767, 54263807, 55312383,
+        60817407, 62128127, 63176703, 64749567, 66322431, 72351743, 72613887, 75497471, 75759615, 78118911,
+        84148223, 84410367, 84934655, 88080383, 89915391, 96206847, 99876863, 106954751, 110886911, 114294783,
+    )
+)
+_P17_P = tuple(2**60 - d for d in (262143, 8126463, 14417919, 25427967))
+P17 = Params("P17", 17, _P17_Q, _P17_P, 8)
 # Small rings that put ciphertext primes on the integer path of the device kernels (2^50 and above): all three
 # of I12; every other one of M12, where 55-bit and 45-bit primes alternate so that floating-point limbs take
 # sources of 2^50 and above in both base conversions.
