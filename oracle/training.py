@@ -1,6 +1,6 @@
 """Oracle composition of one iteration of encrypted logistic-regression training with Nesterov momentum and
 Bootstrap (test infrastructure only): gradient step (oracle/classifier.py), look-ahead update
-W' = (1 + gamma) V' - gamma V, division by about 2^10 with one rescale, Bootstrap with the gain that returns
+W' = (1 + gamma) V' - gamma V, division by about 2^shrink_bits with one rescale, Bootstrap with the gain that returns
 to the working scale (oracle/bootstrap.py)."""
 from . import bootstrap as ob
 from . import classifier as oc
@@ -11,13 +11,14 @@ def _const(o, v, s, level):
     return [iv % o.q[i] for i in range(level)]
 
 
-def iterate(o, X, W, V, Y, keys, plan, block, scale, lr, gamma, n_samples, a=None, pts_cts=None, pts_stc=None):
+def iterate(o, X, W, V, Y, keys, plan, block, scale, lr, gamma, n_samples, a=None, pts_cts=None, pts_stc=None,
+            shrink_bits=6):
     """W at level plan.out_level, V at plan.out_level - 8 (or above), X at plan.out_level; all at `scale`.
     Returns (W_next, V_next)."""
     level = plan.out_level
     q = [float(v) for v in o.q]
     v_new = oc.train_step(o, X, W, Y, keys["relin"], keys["rot"], level, scale, lr, n_samples, a, block)
-    shrink = int(round(o.q[1] / 1024.0))
+    shrink = int(round(o.q[1] / 2.0**shrink_bits))
     delta_in = scale * shrink / q[1]
     gain = scale / (delta_in * plan.natural_factor(o))
     w_next = []

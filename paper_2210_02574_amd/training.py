@@ -5,8 +5,11 @@ going) as a sequence of library calls.
 One iteration, per class, with the weights W at the level Bootstrap returns (l) and scale S:
   V' = W - (lr / n) sum_samples (p(<x, W>) - y) x        gradient step, eight levels (classifier.EncryptedTrainStep)
   W' = (1 + gamma) V' - gamma V                           Nesterov's update in its look-ahead form, one level
-  W' <- W' / 2^10                                         one level, down to level 1: Bootstrap wants |m| << q0
-  W  <- Bootstrap(W'), with the gain that lands on S      fifteen levels, back to level l
+  W' <- W' / 2^6                                          one level, down to level 1: Bootstrap wants |m| << q0
+  W  <- Bootstrap(W'), with the gain that lands on S      7 + r levels, back to level l
+The divisor trades the two error sources of Bootstrap against each other: the sine's own error grows with
+(|m| / q0)^3, while the rounding of the CoeffToSlot plaintexts is amplified by q0 / |m|; 2^6 with r = 7 keeps
+both near 1e-4 for weights up to about 3 at 1024 packed slots.
 The labels and samples stay at level l and scale S, so nothing else changes from one iteration to the next.
 """
 from __future__ import annotations
@@ -18,14 +21,14 @@ from .classifier import EncryptedTrainStep, _residues
 
 
 class EncryptedTrainer:
-    def __init__(self, he, block: int, lr: float, gamma: float, n_samples: int, scale: float = 2.0**50, r: int = 8,
-                 coeffs=None):
+    def __init__(self, he, block: int, lr: float, gamma: float, n_samples: int, scale: float = 2.0**50, r: int = 7,
+                 coeffs=None, shrink_bits: int = 6):
         self.he, self.block, self.gamma, self.scale = he, block, gamma, scale
         self.boot = Bootstrapper(he, block, r)
         self.level = self.boot.out_level
         assert self.level >= 11, "a gradient step (8), the momentum update (1) and the division (1) need 11 levels"
         self.step = EncryptedTrainStep(he, self.level, scale, lr, n_samples, coeffs, block)
-        self.shrink = int(round(he.q[1] / 1024.0))                 # divides by ~2^10 when followed by a rescale
+        self.shrink = int(round(he.q[1] / 2.0**shrink_bits))       # divides by ~2^shrink_bits when followed by a rescale
         self.delta_in = scale * self.shrink / float(he.q[1])       # scale of the ciphertext Bootstrap receives
         self.gain = self.boot.gain_for(self.delta_in, scale)
 

@@ -133,7 +133,7 @@ def test_driver_plaintexts_agree_with_the_oracle(ctx):
 
 def test_training_iteration_with_momentum_and_bootstrap(oracle_mod):
     """One whole iteration of the paper's training recipe on the small ring (26 levels): gradient step with the
-    degree-7 polynomial, Nesterov look-ahead update, division by 2^10, Bootstrap back to level 11 at exactly the
+    degree-7 polynomial, Nesterov look-ahead update, division by 2^6, Bootstrap back to level 12 at exactly the
     working scale; the decrypted weights follow the fp64 iteration to 1e-4."""
     from oracle import bootstrap as ob
     from oracle import classifier as oc
@@ -143,9 +143,9 @@ def test_training_iteration_with_momentum_and_bootstrap(oracle_mod):
     p = wl.T12
     o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
     pr = Problem(o.n)
-    plan = ob.Plan(o, pr.block, 8)
+    plan = ob.Plan(o, pr.block, 7)
     level, S, lr, gamma = plan.out_level, 2.0**50, 1.0, 0.5
-    assert level == 11
+    assert level == 12
     s = ob.sparse_secret(o, 1, 64)
     step_shifts = [1 << k for k in range(6)] + [-(1 << k) for k in range(6)] + [pr.block << k for k in range(5)]
     shifts = sorted(set(step_shifts) | set(plan.rotation_shifts()))

@@ -27,9 +27,9 @@ def test_training_iterations_match_oracle_and_plaintext(oracle_mod):
     S, lr, gamma = 2.0**50, 1.0, 0.5
     a = oc.logistic_poly_coeffs()
     tr = EncryptedTrainer(he, pr.block, lr, gamma, pr.nb, S, coeffs=np.array([a[k] * 8.0**k for k in range(8)]))
-    plan = ob.Plan(o, pr.block, 8)
+    plan = ob.Plan(o, pr.block, 7)
     level = tr.level
-    assert level == plan.out_level == 11 and tr.rotation_shifts() == sorted(
+    assert level == plan.out_level == 12 and tr.rotation_shifts() == sorted(
         set([1 << k for k in range(6)] + [-(1 << k) for k in range(6)] + [pr.block << k for k in range(5)])
         | set(plan.rotation_shifts()))
     sk, s = he.keygen_secret_sparse(1, 64), ob.sparse_secret(o, 1, 64)
