@@ -7,7 +7,9 @@ One step = one pass of the whole hot path at N=2^16, L=24, K=4, dnum=6 over synt
   * 15 hoisted rotations of one level-24 ciphertext by 2^0 .. 2^14,
   * 128 single rotations at mixed levels 8..24.
 Every step therefore performs 64 + 15 + 128 = 207 key switches; `value` is key switches per
-second over the whole step with all inputs resident in HBM.  The line also carries the roofline
+second over the whole step with all inputs resident in HBM.  All operations of a step are independent;
+with more than one stream they are issued round-robin to the streams without joins between the four kinds
+(`detail` times the kinds one after the other in a separate pass).  The line also carries the roofline
 of the kernel that takes the most time (measured with HIP events inside the library over a
 repeat of the timed steps) and the CPU oracle timed on a bounded sample of the same workload.
 
@@ -108,7 +110,8 @@ class Workload:
         evk = wl.uniform_evk(seed, self.params)
         return self.he.evk_from_host(evk, g)
 
-    def step(self, marks=None):
+    def step(self, marks=None, serial=False):
+        """serial: every operation on the current stream, one after the other (each kernel alone on the GPU)."""
         he = self.he
 
         def mark(name):
@@ -117,6 +120,8 @@ class Workload:
                 ev.record()
                 marks.append((name, ev))
 
+        if marks is None and self.streams and not serial:
+            return self._step_overlapped()
         mark("start")
         he.ntt(self.ntt_limbs, self.ntt_mods)
         he.intt(self.ntt_limbs, self.ntt_mods)
@@ -127,8 +132,26 @@ class Workload:
         mark("hmult_relin_rescale")
         he.hrot_many(self.rot, self.hoist_in, outs=self.hoist_out)
         mark("hrot_hoisted")
-        self._spread(self.n_single, self._single_one)
+        if serial:
+            for i in range(self.n_single):
+                self._single_one(i)
+        else:
+            self._spread(self.n_single, self._single_one)
         mark("hrot_single")
+
+    def _step_overlapped(self):
+        """The same operations as step(), all of them independent, dealt to the side streams without joins
+        between the four kinds: the NTT pairs and the hoisted rotations first, then the HMult batches and the
+        single rotations round-robin."""
+        he, torch = self.he, self.torch
+        jobs = [lambda: (he.ntt(self.ntt_limbs, self.ntt_mods), he.intt(self.ntt_limbs, self.ntt_mods)),
+                lambda: he.hrot_many(self.rot, self.hoist_in, outs=self.hoist_out)]
+        for lo in range(0, self.n_hmult, self.hm_chunk):
+            hi = min(lo + self.hm_chunk, self.n_hmult)
+            jobs.append(lambda lo=lo, hi=hi: he.hmult_relin_rescale_batch(self.relin, self.hm_a[lo:hi], self.hm_b[lo:hi],
+                                                                          out=self.rs_out[lo:hi]))
+        jobs += [lambda i=i: self._single_one(i) for i in range(self.n_single)]
+        self._spread(len(jobs), lambda k: jobs[k]())
 
     def _single_one(self, i):
         self.he.hrot(self.rot[self.single_keys[i]], self.single_in[i], out=self.single_out[i])
@@ -295,14 +318,18 @@ def main():
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()
-    marks = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        w.step(marks)
+        w.step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
-    # segment times from events on the launch stream
+    # the four kinds of operation one after the other (same steps again, outside the timed region): segment
+    # times from events on the launch stream
+    marks = []
+    for _ in range(args.steps):
+        w.step(marks)
+    torch.cuda.synchronize()
     seg = {}
     for (n0, e0), (n1, e1) in zip(marks[:-1], marks[1:]):
         if n1 != "start":
@@ -320,16 +347,25 @@ def main():
         "segment_ms": {k: round(v * 1e3, 3) for k, v in seg_s.items()},
     }
 
-    # the same steps again with per-kernel HIP events inside the library
+    # the same steps again with per-kernel HIP events inside the library: once as timed (operations overlapping
+    # on the streams, so a kernel's duration includes its share of the contention) and once with every
+    # operation on one stream, where each kernel has the GPU to itself: the roofline is taken from the latter
     he.profile_start()
     for _ in range(args.steps):
         w.step()
+    stats_conc = he.profile_stop()
+    he.profile_start()
+    for _ in range(args.steps):
+        w.step(serial=True)
     stats = he.profile_stop()
     dom = max(stats.items(), key=lambda kv: kv[1][1])
     name, (launches, total_ms, nbytes) = dom
     achieved = nbytes / (total_ms / 1e3) / 1e9
+    conc = stats_conc.get(name)
     roofline = {
         "kernel": name,
+        "pass": "serial (each kernel alone on the GPU; same operations as the timed steps)",
+        "frac_while_overlapped": (conc[2] / (conc[1] / 1e3) / 1e9 / HBM_PEAK_GBS) if conc and conc[1] else None,
         "bound": "hbm",
         "achieved": achieved,
         "peak": HBM_PEAK_GBS,
