@@ -37,16 +37,16 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # `--pmc WRITE_SIZE` runs of this command with --streams 1, scaled by the copy-kernel calibration
 # (2 x FETCH_SIZE + 1 x WRITE_SIZE; summary and calibration under profiles/).
 MEASURED_TRAFFIC_BYTES = {
-    "k_inner_blocks": 366182604,
-    "k_ntt_fwd_blocks_fin": 141350502,
-    "k_ntt_fwd_blocks": 35458969,
-    "k_ntt_fwd_cols_modup": 79118745,
-    "k_ntt_fwd_cols_moddown": 32984268,
-    "k_ntt_fwd_cols_rescale": 135507865,
-    "k_ntt_fwd_cols": 269822361,
-    "k_tensor": 1409366425,
-    "k_ntt_inv_blocks": 40550604,
-    "k_ntt_inv_cols": 20910318,
+    "k_inner_blocks": 366106009,
+    "k_ntt_fwd_blocks_fin": 111549440,
+    "k_ntt_fwd_blocks": 35472076,
+    "k_ntt_fwd_cols_modup": 79191859,
+    "k_ntt_fwd_cols_moddown": 24100044,
+    "k_ntt_fwd_cols_moddown_rescale": 159236198,
+    "k_ntt_fwd_cols": 269811097,
+    "k_tensor": 1409365811,
+    "k_ntt_inv_blocks": 40553881,
+    "k_ntt_inv_cols": 20911308,
 }
 
 
