@@ -61,8 +61,10 @@ def special_dft(ns: int) -> np.ndarray:
 class Plan:
     """Shapes, levels and rotation shifts of one bootstrapping for ns slots."""
 
-    def __init__(self, o, ns: int, r: int = 8, level_in: int = None):
-        self.ns, self.r = ns, r
+    def __init__(self, o, ns: int, r: int = 8, level_in: int = None, groups: int = 1):
+        """groups = 1: each matrix product is one dense ns x ns matrix.  groups >= 2: the matrices are applied
+        as that many sparse factors (products of consecutive butterfly stages), one level each."""
+        self.ns, self.r, self.groups = ns, r, groups
         self.L = o.L if level_in is None else level_in
         self.gap = o.n // ns
         lg = int(math.log2(ns))
@@ -71,22 +73,128 @@ class Plan:
         self.subsum_shifts = [ns << k for k in range(int(math.log2(self.gap)))]
         self.baby = list(range(1, self.g1))
         self.giant = [self.g1 * b for b in range(1, self.g2)]
-        self.out_level = self.L - 7 - r
+        self.out_level = self.L - 5 - r - 2 * groups
+        self.factors = butterfly_groups(ns, groups) if groups > 1 else None
 
     def rotation_shifts(self):
-        return sorted(set(self.subsum_shifts + self.baby + self.giant))
+        if self.groups == 1:
+            return sorted(set(self.subsum_shifts + self.baby + self.giant))
+        sh = set(self.subsum_shifts)
+        for G in self.factors:  # a factor and its inverse have the same diagonals
+            sh |= set(SparseDiagonals(G).shifts())
+        sh.discard(0)
+        return sorted(sh)
 
     def natural_factor(self, o) -> float:
         """Output scale / input scale when the last matrix carries no extra gain: the scale of exp(i theta)
         after the r squarings, over q0 (follows the rescale rule step by step)."""
         q = [float(v) for v in o.q]
-        l = self.L - 1
+        l = self.L - self.groups
         s = q[0] * q[0] / q[l - 5]
         lvl = l - 5
         for _ in range(self.r):
             s = s * s / q[lvl - 1]
             lvl -= 1
         return s / q[0]
+
+
+def butterfly_stage(ns: int, ln: int) -> np.ndarray:
+    """One stage of the special FFT on blocks of `ln` entries: (u, v) -> (u + D v, u - D v) with
+    D_j = exp(2 pi i (5^j mod 4 ln) / (4 ln)).  U = B_ns ... B_4 B_2 R, R the bit-reversal permutation."""
+    M = np.zeros((ns, ns), dtype=np.complex128)
+    lh = ln // 2
+    for i in range(0, ns, ln):
+        for j in range(lh):
+            D = np.exp(2j * np.pi * pow(5, j, 4 * ln) / (4 * ln))
+            M[i + j, i + j] = 1.0
+            M[i + j, i + j + lh] = D
+            M[i + j + lh, i + j] = 1.0
+            M[i + j + lh, i + j + lh] = -D
+    return M
+
+
+def butterfly_groups(ns: int, groups: int):
+    """[G_1 .. G_groups], G_1 = the first stages (applied first), with U = G_groups ... G_1 R."""
+    stages = [butterfly_stage(ns, 2 << s) for s in range(int(math.log2(ns)))]
+    per = -(-len(stages) // groups)
+    out = []
+    for g in range(groups):
+        M = np.eye(ns, dtype=np.complex128)
+        for B in stages[g * per:(g + 1) * per]:
+            M = B @ M
+        out.append(M)
+    return out
+
+
+class SparseDiagonals:
+    """Baby-step/giant-step layout for a matrix whose non-zero diagonals are d_min + stride e, e = 0 .. E
+    (offsets taken in (-ns/2, ns/2]): e = g1 b + a."""
+
+    def __init__(self, M: np.ndarray):
+        ns = M.shape[0]
+        j = np.arange(ns)
+        offs = []
+        for d in range(ns):
+            if np.abs(M[j, (j + d) % ns]).max() > 1e-12:
+                offs.append(d if d <= ns // 2 else d - ns)
+        offs.sort()
+        self.ns, self.offsets = ns, offs
+        self.dmin = offs[0]
+        self.stride = math.gcd(*[d - self.dmin for d in offs[1:]]) if len(offs) > 1 else 1
+        self.E = (offs[-1] - self.dmin) // self.stride
+        self.g1 = int(math.ceil(math.sqrt(self.E + 1)))
+        self.g2 = -(-(self.E + 1) // self.g1)
+
+    def giant_shift(self, b: int) -> int:
+        return self.dmin + self.stride * self.g1 * b
+
+    def shifts(self):
+        return [self.stride * a for a in range(1, self.g1)] + [self.giant_shift(b) for b in range(self.g2)]
+
+    def plaintext_slots(self, M: np.ndarray, n: int):
+        """{(b, a): slot vector of diagonal dmin + stride (g1 b + a), rotated right by the giant shift}."""
+        ns = self.ns
+        j = np.arange(ns)
+        out = {}
+        for b in range(self.g2):
+            G = self.giant_shift(b)
+            for a in range(self.g1):
+                d = G + self.stride * a
+                if d not in self.offsets:
+                    continue
+                jj = (j - G) % ns
+                out[(b, a)] = np.tile(M[jj, (jj + d) % ns], n // ns)
+        return out
+
+
+def encode_sparse(o, M: np.ndarray, level: int):
+    """(layout, NTT-domain plaintexts at scale q_(level-1)) of a sparse-diagonal matrix."""
+    sd = SparseDiagonals(M)
+    scale = float(o.q[level - 1])
+    return sd, {k: o.coeffs_to_ntt(o.encode(v, scale), level) for k, v in sd.plaintext_slots(M, o.n).items()}
+
+
+def sparse_transform(o, ct, sd: SparseDiagonals, pts, rot):
+    """sum_b rot_(giant b)( sum_a pt[b, a] * rot_(stride a)(ct) ), then rescale."""
+    babies = {0: ct}
+    for a in range(1, sd.g1):
+        if any((b, a) in pts for b in range(sd.g2)):
+            babies[a] = o.hrot(ct, rot[sd.stride * a], sd.stride * a)
+    acc = None
+    for b in range(sd.g2):
+        inner = None
+        for a in range(sd.g1):
+            if (b, a) not in pts:
+                continue
+            term = o.pmult(babies[a], pts[(b, a)])
+            inner = term if inner is None else o.add(inner, term)
+        if inner is None:
+            continue
+        G = sd.giant_shift(b)
+        if G % o.n:
+            inner = o.hrot(inner, rot[G], G)
+        acc = inner if acc is None else o.add(acc, inner)
+    return o.rescale(acc)
 
 
 def bsgs_plaintext_slots(M: np.ndarray, plan: Plan, n: int):
@@ -191,23 +299,43 @@ def bootstrap(o, ct1, keys, plan: Plan, pts_cts=None, pts_stc=None, gain: float 
     natural_factor) the result lands exactly on the scale `target`."""
     L, ns, r = plan.L, plan.ns, plan.r
     relin, conj, rot = keys["relin"], keys["conj"], keys["rot"]
-    U = special_dft(ns)
-    if pts_cts is None:
-        pts_cts = encode_matrix(o, (math.pi / (plan.gap * 2.0**r * ns)) * U.conj().T, plan, L)
+    g = plan.groups
     ct = modraise(o, ct1, L)
     for sh in plan.subsum_shifts:
         ct = o.add(ct, o.hrot(ct, rot[sh], sh))
     scale = float(o.q[0])                               # the raised ciphertext holds t / q0
-    w = linear_transform(o, ct, pts_cts, rot, plan)     # level L-1: (pi / 2^r) w
+    if g == 1:
+        U = special_dft(ns)
+        if pts_cts is None:
+            pts_cts = encode_matrix(o, (math.pi / (plan.gap * 2.0**r * ns)) * U.conj().T, plan, L)
+        w = linear_transform(o, ct, pts_cts, rot, plan)     # level L-1: (pi / 2^r) w
+    else:
+        # U^-1 = R^-1 G_1^-1 .. G_g^-1: the slots come out in bit-reversed order, which the slot-wise
+        # middle part does not see and the way back (G_g .. G_1, without R) undoes
+        if pts_cts is None:
+            c = (math.pi / (plan.gap * 2.0**r)) ** (1.0 / g)
+            pts_cts = [encode_sparse(o, c * np.linalg.inv(plan.factors[i]), L - (g - 1 - i)) for i in range(g)]
+        w = ct
+        for i in reversed(range(g)):
+            w = sparse_transform(o, w, pts_cts[i][0], pts_cts[i][1], rot)
+    lt = L - g
     wc = o.hconj(w, conj)
     th1 = o.add(w, wc)
-    th2 = o.pmult(o.sub(w, wc), monomial_i(o, L - 1, -1))
-    E1, lvl, s = exp_i(o, th1, L - 1, scale, relin, r)
-    E2, _, _ = exp_i(o, th2, L - 1, scale, relin, r)
+    th2 = o.pmult(o.sub(w, wc), monomial_i(o, lt, -1))
+    E1, lvl, s = exp_i(o, th1, lt, scale, relin, r)
+    E2, _, _ = exp_i(o, th2, lt, scale, relin, r)
     iE2 = o.pmult(E2, monomial_i(o, lvl))
     Hp, Hm = o.add(E1, iE2), o.sub(E1, iE2)
     F = o.pmult(o.sub(Hp, o.hconj(Hm, conj)), monomial_i(o, lvl, -1))
-    if pts_stc is None:
-        pts_stc = encode_matrix(o, (gain / (4.0 * math.pi)) * U, plan, lvl)
-    out = linear_transform(o, F, pts_stc, rot, plan)
-    return out, lvl - 1, gain * s / float(o.q[0])
+    if g == 1:
+        if pts_stc is None:
+            pts_stc = encode_matrix(o, (gain / (4.0 * math.pi)) * special_dft(ns), plan, lvl)
+        out = linear_transform(o, F, pts_stc, rot, plan)
+    else:
+        if pts_stc is None:
+            c = (gain / (4.0 * math.pi)) ** (1.0 / g)
+            pts_stc = [encode_sparse(o, c * plan.factors[i], lvl - i) for i in range(g)]
+        out = F
+        for i in range(g):
+            out = sparse_transform(o, out, pts_stc[i][0], pts_stc[i][1], rot)
+    return out, lvl - g, gain * s / float(o.q[0])

@@ -25,26 +25,101 @@ def _residues(value: float, scale: float, q, level: int) -> List[int]:
     return [v % int(q[i]) for i in range(level)]
 
 
+class DiagonalLayout:
+    """A matrix on the packed slots whose non-zero diagonals lie on an arithmetic progression
+    first + step * e, e = 0 .. count - 1 (offsets read in (-ns/2, ns/2]), cut into baby steps e mod baby and
+    giant steps e // baby.  diag_d[j] = M[j][(j + d) mod ns]."""
+
+    def __init__(self, M: np.ndarray):
+        ns = M.shape[0]
+        rows = np.arange(ns)
+        present = [d for d in range(ns) if np.abs(M[rows, (rows + d) % ns]).max() > 1e-12]
+        signed = sorted(d if d <= ns // 2 else d - ns for d in present)
+        self.ns, self.present = ns, set(signed)
+        self.first = signed[0]
+        gaps = [d - self.first for d in signed[1:]]
+        self.step = int(np.gcd.reduce(gaps)) if gaps else 1
+        self.count = (signed[-1] - self.first) // self.step + 1
+        self.baby = int(math.ceil(math.sqrt(self.count)))
+        self.giant = -(-self.count // self.baby)
+
+    def giant_shift(self, b: int) -> int:
+        return self.first + self.step * self.baby * b
+
+    def shifts(self) -> List[int]:
+        return [self.step * a for a in range(1, self.baby)] + [self.giant_shift(b) for b in range(self.giant)]
+
+    def slot_vectors(self, M: np.ndarray, n: int):
+        """{(b, a): diagonal first + step (baby b + a) as a length-n slot vector, rotated right by giant_shift(b)}."""
+        ns = self.ns
+        rows = np.arange(ns)
+        out = {}
+        for b in range(self.giant):
+            back = (rows - self.giant_shift(b)) % ns
+            for a in range(self.baby):
+                d = self.giant_shift(b) + self.step * a
+                if d in self.present:
+                    out[(b, a)] = np.tile(M[back, (back + d) % ns], n // ns)
+        return out
+
+
 class Bootstrapper:
-    def __init__(self, he, ns: int, r: int = 8, level: int = None):
+    def __init__(self, he, ns: int, r: int = 8, level: int = None, groups: int = 1):
+        """groups = 1: CoeffToSlot and SlotToCoeff are one dense ns x ns matrix each (one level each).
+        groups >= 2: each is a product of that many sparse factors, groups of consecutive butterfly stages of
+        the special FFT (one level per factor; far fewer rotations and plaintexts, and better precision because
+        every factor's entries are large against the rounding of its encoding)."""
         assert ns >= 2 and ns & (ns - 1) == 0 and ns <= he.n
-        self.he, self.ns, self.r = he, ns, r
+        self.he, self.ns, self.r, self.groups = he, ns, r, groups
         self.L = he.L if level is None else level
         self.gap = he.n // ns
         bits = ns.bit_length() - 1
         self.g1 = 1 << ((bits + 1) // 2)   # baby steps 0 .. g1-1
         self.g2 = ns // self.g1            # giant steps 0, g1, .. (g2-1) g1
         self.trace_shifts = [ns << k for k in range(self.gap.bit_length() - 1)]
-        self.out_level = self.L - 7 - r
+        self.out_level = self.L - 5 - r - 2 * groups
         assert self.out_level >= 1, "not enough levels for this r"
         self._mono: Dict = {}
         self._pts: Dict = {}
+        self._factors = None
 
     # ---- keys and plaintexts ----------------------------------------------------------------------------------
 
     def rotation_shifts(self) -> List[int]:
-        giant = [self.g1 * b for b in range(1, self.g2)]
-        return sorted(set(self.trace_shifts) | set(range(1, self.g1)) | set(giant))
+        if self.groups == 1:
+            giant = [self.g1 * b for b in range(1, self.g2)]
+            return sorted(set(self.trace_shifts) | set(range(1, self.g1)) | set(giant))
+        shifts = set(self.trace_shifts)
+        for G in self.factors():  # the inverse of a factor has the same diagonals
+            shifts |= set(DiagonalLayout(G).shifts())
+        shifts.discard(0)
+        return sorted(shifts)
+
+    def butterflies(self, length: int) -> np.ndarray:
+        """Stage of the special FFT on blocks of `length`: (u, v) -> (u + D v, u - D v), D_j = exp(2 pi i 5^j / (4 length))."""
+        ns, half = self.ns, length // 2
+        B = np.zeros((ns, ns), dtype=np.complex128)
+        tw = np.array([np.exp(0.5j * np.pi * pow(5, j, 4 * length) / length) for j in range(half)])
+        for start in range(0, ns, length):
+            top = np.arange(start, start + half)
+            B[top, top] = 1.0
+            B[top, top + half] = tw
+            B[top + half, top] = 1.0
+            B[top + half, top + half] = -tw
+        return B
+
+    def factors(self):
+        """[G_1 .. G_groups] with U = G_groups .. G_1 R, R the bit-reversal permutation of the packed slots."""
+        if self._factors is None:
+            lengths = [2 << s for s in range(self.ns.bit_length() - 1)]
+            per = -(-len(lengths) // self.groups)
+            self._factors = []
+            for g in range(self.groups):
+                G = np.eye(self.ns, dtype=np.complex128)
+                for ln in lengths[g * per:(g + 1) * per]:
+                    G = self.butterflies(ln) @ G
+                self._factors.append(G)
+        return self._factors
 
     def make_keys(self, sk, seed: int):
         he = self.he
@@ -73,7 +148,7 @@ class Bootstrapper:
     def natural_factor(self) -> float:
         """Output scale over input scale at gain 1: the scale of exp(i theta) after the squarings over q0."""
         q = [float(v) for v in self.he.q]
-        lvl = self.L - 6
+        lvl = self.L - self.groups - 5
         s = q[0] * q[0] / q[lvl]
         for _ in range(self.r):
             s = s * s / q[lvl - 1]
@@ -108,16 +183,34 @@ class Bootstrapper:
         scale = float(he.q[level - 1])
         return [[self._plain(he.encode(v, scale), level) for v in row] for row in self.diagonal_slots(M)]
 
+    def encode_sparse(self, M: np.ndarray, level: int):
+        """(layout, {(b, a): device plaintext}) of a sparse-diagonal matrix at scale q_(level-1)."""
+        he = self.he
+        lay = DiagonalLayout(M)
+        scale = float(he.q[level - 1])
+        return lay, {k: self._plain(he.encode(v, scale), level) for k, v in lay.slot_vectors(M, he.n).items()}
+
     def prepare(self, gain: float = 1.0):
         """Encodes the plaintext diagonals of both matrix products once (they depend only on ns, r, the moduli
         and the gain of the last matrix)."""
+        g, L = self.groups, self.L
+        top = self.out_level + g  # level at which the way back starts
         if "cts" not in self._pts:
-            self._pts["cts"] = self.encode_matrix(self.cts_matrix(), self.L)
-            for lvl in (self.L - 1, self.L - 6, self.out_level + 1):
+            if g == 1:
+                self._pts["cts"] = self.encode_matrix(self.cts_matrix(), L)
+            else:
+                c = (math.pi / (self.gap * 2.0**self.r)) ** (1.0 / g)
+                self._pts["cts"] = [self.encode_sparse(c * np.linalg.inv(G), L - (g - 1 - i))
+                                    for i, G in enumerate(self.factors())]
+            for lvl in (L - g, L - g - 5, top):
                 for sign in (1, -1):
                     self.monomial(lvl, sign)
         if ("stc", gain) not in self._pts:
-            self._pts[("stc", gain)] = self.encode_matrix(self.stc_matrix(gain), self.out_level + 1)
+            if g == 1:
+                self._pts[("stc", gain)] = self.encode_matrix(self.stc_matrix(gain), top)
+            else:
+                c = (gain / (4.0 * math.pi)) ** (1.0 / g)
+                self._pts[("stc", gain)] = [self.encode_sparse(c * G, top - i) for i, G in enumerate(self.factors())]
         return self._pts["cts"], self._pts[("stc", gain)]
 
     def monomial(self, level: int, sign: int):
@@ -140,6 +233,25 @@ class Bootstrapper:
             inner = he.pmult_sum(babies, pts[b])
             if b:
                 inner = he.hrot(rot[g1 * b], inner)
+            acc = inner if acc is None else he.add(acc, inner, out=acc)
+        return he.rescale(acc)
+
+    def sparse_transform(self, ct, lay: DiagonalLayout, pts, rot):
+        """Product with a sparse-diagonal matrix (baby steps hoisted, inner sums in one pass each), then rescale."""
+        he = self.he
+        used = [a for a in range(1, lay.baby) if any((b, a) in pts for b in range(lay.giant))]
+        rotated = he.hrot_many([rot[lay.step * a] for a in used], ct) if used else []
+        babies = {0: ct}
+        babies.update(dict(zip(used, rotated)))
+        acc = None
+        for b in range(lay.giant):
+            terms = [a for a in range(lay.baby) if (b, a) in pts]
+            if not terms:
+                continue
+            inner = he.pmult_sum([babies[a] for a in terms], [pts[(b, a)] for a in terms])
+            shift = lay.giant_shift(b)
+            if shift % he.n:
+                inner = he.hrot(rot[shift], inner)
             acc = inner if acc is None else he.add(acc, inner, out=acc)
         return he.rescale(acc)
 
@@ -195,15 +307,28 @@ class Bootstrapper:
         relin, conj, rot = keys["relin"], keys["conj"], keys["rot"]
         if pts_cts is None or pts_stc is None:
             pts_cts, pts_stc = self.prepare(gain)
+        g = self.groups
         ct = he.modraise(ct1, L)
         he.rotate_sum([rot[sh] for sh in self.trace_shifts], ct)
         scale = float(he.q[0])  # read as a ciphertext of t / q0
-        w = self.linear_transform(ct, pts_cts, rot)
+        if g == 1:
+            w = self.linear_transform(ct, pts_cts, rot)
+        else:
+            # U^-1 = R^-1 G_1^-1 .. G_g^-1 without the permutation: the slots come out bit-reversed, which the
+            # slot-wise middle part does not see and the way back (G_g .. G_1, again without R) undoes
+            w = ct
+            for lay, pts in reversed(pts_cts):
+                w = self.sparse_transform(w, lay, pts, rot)
         wc = he.hconj(conj, w)
-        th = torch.stack([he.add(w, wc), he.pmult(he.sub(w, wc), self.monomial(L - 1, -1))])
-        E, lvl, s = self.exp_i(relin, th, L - 1, scale)
+        th = torch.stack([he.add(w, wc), he.pmult(he.sub(w, wc), self.monomial(L - g, -1))])
+        E, lvl, s = self.exp_i(relin, th, L - g, scale)
         iE2 = he.pmult(E[1], self.monomial(lvl, 1))
         plus, minus = he.add(E[0], iE2), he.sub(E[0], iE2)
         F = he.pmult(he.sub(plus, he.hconj(conj, minus)), self.monomial(lvl, -1))
-        out = self.linear_transform(F, pts_stc, rot)
-        return out, lvl - 1, gain * s / float(he.q[0])
+        if g == 1:
+            out = self.linear_transform(F, pts_stc, rot)
+        else:
+            out = F
+            for lay, pts in pts_stc:
+                out = self.sparse_transform(out, lay, pts, rot)
+        return out, lvl - g, gain * s / float(he.q[0])

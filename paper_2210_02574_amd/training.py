@@ -6,7 +6,7 @@ One iteration, per class, with the weights W at the level Bootstrap returns (l) 
   V' = W - (lr / n) sum_samples (p(<x, W>) - y) x        gradient step, eight levels (classifier.EncryptedTrainStep)
   W' = (1 + gamma) V' - gamma V                           Nesterov's update in its look-ahead form, one level
   W' <- W' / 2^6                                          one level, down to level 1: Bootstrap wants |m| << q0
-  W  <- Bootstrap(W'), with the gain that lands on S      7 + r levels, back to level l
+  W  <- Bootstrap(W'), with the gain that lands on S      5 + r + 2 groups levels, back to level l
 The divisor trades the two error sources of Bootstrap against each other: the sine's own error grows with
 (|m| / q0)^3, while the rounding of the CoeffToSlot plaintexts is amplified by q0 / |m|; 2^6 with r = 7 keeps
 both near 1e-4 for weights up to about 3 at 1024 packed slots.
@@ -22,9 +22,9 @@ from .classifier import EncryptedTrainStep, _residues
 
 class EncryptedTrainer:
     def __init__(self, he, block: int, lr: float, gamma: float, n_samples: int, scale: float = 2.0**50, r: int = 7,
-                 coeffs=None, shrink_bits: int = 6):
+                 coeffs=None, shrink_bits: int = 6, groups: int = 2):
         self.he, self.block, self.gamma, self.scale = he, block, gamma, scale
-        self.boot = Bootstrapper(he, block, r)
+        self.boot = Bootstrapper(he, block, r, groups=groups)
         self.level = self.boot.out_level
         assert self.level >= 11, "a gradient step (8), the momentum update (1) and the division (1) need 11 levels"
         self.step = EncryptedTrainStep(he, self.level, scale, lr, n_samples, coeffs, block)

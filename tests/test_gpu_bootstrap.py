@@ -73,6 +73,54 @@ def test_bootstrap_bit_exact_and_accurate(oracle_mod):
     assert err2 < 2.0**-14
 
 
+def test_factored_bootstrap_bit_exact_and_accurate(oracle_mod):
+    """Two sparse factors per matrix product (grouped butterfly stages): bit-exact against the oracle's composition
+    with shared encodings, and more accurate than the dense form."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from oracle import bootstrap as ob
+    from paper_2210_02574_amd.bootstrap import Bootstrapper, DiagonalLayout
+
+    assert torch.cuda.is_available()
+    p = wl.B12
+    he = pkg.HE.from_params(p, device=0)
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    ns, r, g = 64, 7, 2
+    bs = Bootstrapper(he, ns, r, groups=g)
+    plan = ob.Plan(o, ns, r, groups=g)
+    sk, s = he.keygen_secret_sparse(1, 64), ob.sparse_secret(o, 1, 64)
+    keys = bs.make_keys(sk, 100)
+    okeys = {"relin": o.keygen_relin(s, 100), "conj": o.keygen_conj(s, 101),
+             "rot": {sh: o.keygen_rot(s, sh, 110 + i) for i, sh in enumerate(plan.rotation_shifts())}}
+    rng = wl.rng(5)
+    z = rng.uniform(-1, 1, ns) + 1j * rng.uniform(-1, 1, ns)
+    Z = np.tile(z, he.n // ns)
+    delta = 2.0**40
+    ct = o.encrypt_coeffs(s, o.encode(Z, delta), 1, 6)
+    c_in = (np.pi / (plan.gap * 2.0**r)) ** (1.0 / g)
+    c_out = (1.0 / (4.0 * np.pi)) ** (1.0 / g)
+    top = plan.out_level + g
+    cts_o = [ob.encode_sparse(o, c_in * np.linalg.inv(plan.factors[i]), plan.L - (g - 1 - i)) for i in range(g)]
+    stc_o = [ob.encode_sparse(o, c_out * plan.factors[i], top - i) for i in range(g)]
+    want, w_level, wfac = ob.bootstrap(o, ct, okeys, plan, cts_o, stc_o)
+
+    def to_dev(encoded, mats):
+        return [(DiagonalLayout(M), {k: he.to_device(v) for k, v in pts.items()}) for (_, pts), M in zip(encoded, mats)]
+
+    fac = bs.factors()
+    out, level, factor = bs.run(he.to_device(ct), keys, to_dev(cts_o, [c_in * np.linalg.inv(G) for G in fac]),
+                                to_dev(stc_o, [c_out * G for G in fac]))
+    got = he.to_host(out)
+    assert level == w_level == plan.out_level and factor == wfac
+    assert np.array_equal(got, want)
+    err = np.abs(he.decrypt(sk, got, delta * factor) - Z).max()
+    print("factored bootstrap N=2^12 ns=64: level 1 -> %d, error %.3g" % (level, err))
+    assert err < 2.0**-19
+    out2, _, _ = bs.run(he.to_device(ct), keys)  # the driver's own plaintexts
+    assert np.abs(he.decrypt(sk, he.to_host(out2), delta * factor) - Z).max() < 2.0**-19
+
+
 def test_bootstrap_at_full_size():
     """N = 2^16, L = 24, 64 packed slots: level 1 -> 9, accuracy against the encrypted values.  The error is set by
     the 2^-26 relative rounding of the CoeffToSlot plaintexts (theta is exact to about 7e-10), amplified by
@@ -99,3 +147,16 @@ def test_bootstrap_at_full_size():
     err = np.abs(he.decrypt(sk, he.to_host(out), delta * factor) - Z).max()
     print("bootstrap N=2^16 ns=64: level 1 -> %d, error %.3g" % (level, err))
     assert err < 2.0**-10
+    # the factored form at 1024 packed slots (the block size of the paper's weight vectors)
+    ns = 1024
+    bs = Bootstrapper(he, ns, 7, groups=2)
+    keys = bs.make_keys(sk, 400)
+    z = rng.uniform(-1, 1, ns) + 1j * rng.uniform(-1, 1, ns)
+    Z = np.tile(z, he.n // ns)
+    ct = he.encrypt_coeffs(sk, he.encode(Z, delta), 1, 24)
+    out, level, factor = bs.run(he.to_device(ct), keys)
+    torch.cuda.synchronize()
+    assert level == 24 - 16
+    err = np.abs(he.decrypt(sk, he.to_host(out), delta * factor) - Z).max()
+    print("factored bootstrap N=2^16 ns=1024: level 1 -> %d, error %.3g" % (level, err))
+    assert err < 2.0**-13

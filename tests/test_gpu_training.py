@@ -27,7 +27,7 @@ def test_training_iterations_match_oracle_and_plaintext(oracle_mod):
     S, lr, gamma = 2.0**50, 1.0, 0.5
     a = oc.logistic_poly_coeffs()
     tr = EncryptedTrainer(he, pr.block, lr, gamma, pr.nb, S, coeffs=np.array([a[k] * 8.0**k for k in range(8)]))
-    plan = ob.Plan(o, pr.block, 7)
+    plan = ob.Plan(o, pr.block, 7, groups=2)
     level = tr.level
     assert level == plan.out_level == 12 and tr.rotation_shifts() == sorted(
         set([1 << k for k in range(6)] + [-(1 << k) for k in range(6)] + [pr.block << k for k in range(5)])
@@ -41,20 +41,27 @@ def test_training_iterations_match_oracle_and_plaintext(oracle_mod):
     w_ct = o.encrypt_coeffs(s, o.encode(pr.slots_w(pr.w0), S), level, 201)
     y_ct = o.encrypt_coeffs(s, o.encode(pr.slots_y(), tp.label_scale), tp.label_level, 202)
     # oracle iteration and its plaintext encodings (mask, both Bootstrap matrices)
-    U = ob.special_dft(pr.block)
-    cts_o = ob.encode_matrix(o, (np.pi / (plan.gap * 2.0**plan.r * pr.block)) * U.conj().T, plan, plan.L)
-    stc_o = ob.encode_matrix(o, (tr.gain / (4.0 * np.pi)) * U, plan, level + 1)
+    g = plan.groups
+    c_in = (np.pi / (plan.gap * 2.0**plan.r)) ** (1.0 / g)
+    c_out = (tr.gain / (4.0 * np.pi)) ** (1.0 / g)
+    cts_o = [ob.encode_sparse(o, c_in * np.linalg.inv(plan.factors[i]), plan.L - (g - 1 - i)) for i in range(g)]
+    stc_o = [ob.encode_sparse(o, c_out * plan.factors[i], level + g - i) for i in range(g)]
     W1, V1 = ot.iterate(o, [x_ct], [w_ct], [o.moddrop(w_ct, level - 8)], [[y_ct]], okeys, plan, pr.block, S, lr, gamma,
                         pr.nb, a, cts_o, stc_o)
     mask = np.zeros(o.n)
     mask[::pr.block] = 1.0
     mask_pt = he.to_device(o.coeffs_to_ntt(o.encode(mask, float(o.q[level - 2])), level - 1))
-    to_dev = lambda pts: [[he.to_device(x) for x in row] for row in pts]
+    from paper_2210_02574_amd.bootstrap import DiagonalLayout
+
+    def to_dev(encoded, mats):  # the driver's own layout of the same matrices, the oracle's encodings
+        return [(DiagonalLayout(M), {k: he.to_device(v) for k, v in pts.items()}) for (_, pts), M in zip(encoded, mats)]
+
     X = he.to_device(x_ct).unsqueeze(0).contiguous()
     Y = [he.to_device(y_ct).unsqueeze(0).contiguous()]
     W = [he.to_device(w_ct)]
     V = [he.moddrop(W[0], level - 8)]
-    boot_pts = (to_dev(cts_o), to_dev(stc_o))
+    fac = tr.boot.factors()
+    boot_pts = (to_dev(cts_o, [c_in * np.linalg.inv(G) for G in fac]), to_dev(stc_o, [c_out * G for G in fac]))
     Wn, Vn = tr.iterate(keys, mask_pt, X, W, V, Y, boot_pts)
     assert np.array_equal(he.to_host(Vn[0]), V1[0])
     assert np.array_equal(he.to_host(Wn[0]), W1[0])

@@ -88,9 +88,10 @@ _W45 = tuple(2**45 - d for d in (204799, 385023))
 _W60 = tuple(2**60 - d for d in (16383, 98303))
 I12 = Params("I12", 12, _W55, _W60[:1], 3)
 M12 = Params("M12", 12, (_W55[0], _W45[0], _W55[1], _W45[1]), _W60, 2)
-# Two more primes of the same rule: 26 levels, enough for one training iteration (9 levels), the division
-# before bootstrapping (1), a bootstrapping (15) and the level it starts from; dnum = 7 keeps 4 primes per digit.
-_T_Q = _N16_Q + (2**50 - 64356351, 2**50 - 64749567)
+# Four more primes of the same rule: 28 levels, enough for one training iteration (9 levels), the division
+# before bootstrapping (1), a bootstrapping with two-factor matrix products (16) and the level it starts from;
+# dnum = 7 keeps 4 primes per digit.
+_T_Q = _N16_Q + (2**50 - 64356351, 2**50 - 64749567, 2**50 - 65667071, 2**50 - 66322431)
 T16 = Params("T16", 16, _T_Q, _N16_P, 7)
 T12 = Params("T12", 12, _T_Q, _N16_P, 7)
 
