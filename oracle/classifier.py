@@ -68,14 +68,16 @@ def _const(o, value, scale, level):
     return [v % o.q[i] for i in range(level)]
 
 
-def train_step(o, X, W, Y, relin, rot, level, scale, lr, n_samples, a=None, block=1024):
+def train_step(o, X, W, Y, relin, rot, level, scale, lr, n_samples, a=None, block=1024, c15=None):
     """X: list of ciphertexts, W: list (per class), Y[c][i]; rot: dict shift -> key.  Returns new W list.
     Same level/scale schedule as the device driver, derived here from the rescale rule
-    (scale after a rescale = scale before / dropped prime).  block = slots per sample."""
+    (scale after a rescale = scale before / dropped prime).  block = slots per sample.
+    c15: monomial coefficients (in x/12) of a degree-15 polynomial; if given it replaces the degree-7 one, the
+    mask then also divides by 12, and the step is one level deeper."""
     q = [float(v) for v in o.q]
     a = logistic_poly_coeffs() if a is None else a  # monomial coefficients in x
     mask = np.zeros(o.n)
-    mask[::block] = 1.0
+    mask[::block] = 1.0 if c15 is None else 1.0 / 12.0
     lb = block.bit_length() - 1
     lnb = (o.n // block).bit_length() - 1
     new_w = []
@@ -91,6 +93,12 @@ def train_step(o, X, W, Y, relin, rot, level, scale, lr, n_samples, a=None, bloc
             z = o.rescale(o.pmult(m, pt))  # level-2, scale s1
             for k in range(lb):
                 z = o.add(z, o.hrot(z, rot[-(1 << k)], -(1 << k)))
+            if c15 is not None:
+                p, tp = logistic15(o, z, relin, level - 2, s1, c15)  # level-7
+                e = o.sub(p, Y[c][i])
+                g = o.hmult_relin(e, o.moddrop(x, level - 7), relin)
+                G = g if G is None else o.add(G, g)
+                continue
             # polynomial 0.5 + z (a1 + a3 z^2 + a5 z^4 + a7 z^6) = 0.5 + z ((a1 + a3 z^2) + z^4 (a5 + a7 z^2))
             z2 = o.rescale(o.hmult_relin(z, z, relin))  # level-3
             s2 = s1 * s1 / q[level - 3]
@@ -110,12 +118,13 @@ def train_step(o, X, W, Y, relin, rot, level, scale, lr, n_samples, a=None, bloc
             e = o.sub(p, Y[c][i])
             g = o.hmult_relin(e, o.moddrop(x, level - 6), relin)
             G = g if G is None else o.add(G, g)
-        G = o.rescale(G)  # level-7
-        tg = tp * scale / q[level - 7]
+        lg = G.shape[1]  # level-6, or level-7 with the degree-15 polynomial
+        G = o.rescale(G)
+        tg = tp * scale / q[lg - 1]
         for k in range(lnb):
             G = o.add(G, o.hrot(G, rot[block << k], block << k))
-        upd = o.rescale(o.cmult(G, _const(o, lr / n_samples, scale * q[level - 8] / tg, level - 7)))
-        new_w.append(o.sub(o.moddrop(w, level - 8), upd))
+        upd = o.rescale(o.cmult(G, _const(o, lr / n_samples, scale * q[lg - 2] / tg, lg - 1)))
+        new_w.append(o.sub(o.moddrop(w, lg - 2), upd))
     return new_w
 
 

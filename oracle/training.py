@@ -12,12 +12,12 @@ def _const(o, v, s, level):
 
 
 def iterate(o, X, W, V, Y, keys, plan, block, scale, lr, gamma, n_samples, a=None, pts_cts=None, pts_stc=None,
-            shrink_bits=6):
+            shrink_bits=6, c15=None):
     """W at level plan.out_level, V at plan.out_level - 8 (or above), X at plan.out_level; all at `scale`.
     Returns (W_next, V_next)."""
     level = plan.out_level
     q = [float(v) for v in o.q]
-    v_new = oc.train_step(o, X, W, Y, keys["relin"], keys["rot"], level, scale, lr, n_samples, a, block)
+    v_new = oc.train_step(o, X, W, Y, keys["relin"], keys["rot"], level, scale, lr, n_samples, a, block, c15)
     shrink = int(round(o.q[1] / 2.0**shrink_bits))
     delta_in = scale * shrink / q[1]
     gain = scale / (delta_in * plan.natural_factor(o))

@@ -107,12 +107,34 @@ TRAIN_BLOCK_SHIFTS = tuple(BLOCK << k for k in range(5))     # sum over the 32 b
 class TrainPlan:
     """Levels and scales of every intermediate of one step, fixed by the parameter set."""
 
-    def __init__(self, q: Sequence[int], level: int, scale: float, lr: float, n_samples: int, coeffs=None):
+    def __init__(self, q: Sequence[int], level: int, scale: float, lr: float, n_samples: int, coeffs=None,
+                 degree: int = 7):
+        """degree 7: least-squares polynomial on [-8, 8] (coeffs: monomial coefficients in x/8).  degree 15: the
+        paper's minimax polynomial on [-12, 12] (coeffs: monomial coefficients in x/12), one level deeper."""
         qf = [float(v) for v in q]
-        self.level, self.scale = level, scale
+        self.level, self.scale, self.degree = level, scale, degree
         l = level
         self.s1 = scale * scale / qf[l - 1]                 # x*w, level l-1
         self.mask_scale = qf[l - 2]                         # mask product rescales back to s1, level l-2
+        self.step = lr / n_samples
+        if degree == 15:
+            self.mask_value = 1.0 / 12.0                    # the mask also maps z to t = z / 12
+            self.c15 = minimax_logistic_coeffs()[0] if coeffs is None else np.asarray(coeffs, dtype=np.float64)
+            l0, s = l - 2, self.s1                          # t at level l-2
+            self.s_y = s * s / qf[l0 - 1]                   # y = t^2
+            self.s_y2 = self.s_y * self.s_y / qf[l0 - 2]
+            self.s_y4 = self.s_y2 * self.s_y2 / qf[l0 - 3]
+            self.t_hi = s                                   # c13 + c15 y
+            self.t_b = self.s_y2 * self.t_hi / qf[l0 - 3]   # B
+            self.t_q = self.s_y4 * self.t_b / qf[l0 - 4]    # Q = y^4 B + A
+            self.t_hi_a = self.t_q * qf[l0 - 3] / self.s_y2
+            self.t_p = s * self.t_q / qf[l0 - 5]            # p(t), level l-7
+            self.label_level, self.label_scale = l - 7, self.t_p
+            self.t_g = self.t_p * scale / qf[l - 8]
+            self.c_w = scale * qf[l - 9] / self.t_g
+            self.out_level = l - 9
+            return
+        self.mask_value = 1.0
         self.s2 = self.s1 * self.s1 / qf[l - 3]             # z^2, level l-3
         self.s4 = self.s2 * self.s2 / qf[l - 4]             # z^4, level l-4
         self.t_u = scale                                    # a7 z^2 + a5, level l-4
@@ -124,7 +146,6 @@ class TrainPlan:
         self.t_g = self.t_p * scale / qf[l - 7]             # gradient after rescale, level l-7
         self.c_w = scale * qf[l - 8] / self.t_g             # update constant; result at level l-8, `scale`
         self.out_level = l - 8
-        self.step = lr / n_samples
         c = sigmoid_ls_coeffs() if coeffs is None else coeffs  # monomial coefficients in t = x/8
         self.a1, self.a3, self.a5, self.a7 = c[1] / 8.0, c[3] / 8.0**3, c[5] / 8.0**5, c[7] / 8.0**7
 
@@ -141,10 +162,11 @@ class EncryptedTrainStep:
     block at the feature offsets (same level and scale); Y[c][i]: labels replicated over each block at
     plan.label_level / plan.label_scale.  Per (class, ciphertext): 6 HMult and 20 HRot; per class 5 more HRot."""
 
-    def __init__(self, he, level: int, scale: float, lr: float, n_samples: int, coeffs=None, block: int = BLOCK):
-        """block: slots per sample (a power of two; the paper's layout is 1024)."""
+    def __init__(self, he, level: int, scale: float, lr: float, n_samples: int, coeffs=None, block: int = BLOCK,
+                 degree: int = 7):
+        """block: slots per sample (a power of two; the paper's layout is 1024).  degree: 7 or 15 (see TrainPlan)."""
         self.he = he
-        self.plan = TrainPlan(he.q, level, scale, lr, n_samples, coeffs)
+        self.plan = TrainPlan(he.q, level, scale, lr, n_samples, coeffs, degree)
         assert block & (block - 1) == 0 and block <= he.n
         self.block = block
         lb, lnb = block.bit_length() - 1, (he.n // block).bit_length() - 1
@@ -161,7 +183,7 @@ class EncryptedTrainStep:
 
     def mask_slots(self) -> np.ndarray:
         m = np.zeros(self.he.n)
-        m[::self.block] = 1.0
+        m[::self.block] = self.plan.mask_value
         return m
 
     def encode_mask(self):
@@ -179,8 +201,10 @@ class EncryptedTrainStep:
         return he.add_const(out, _residues(const, t_scale, he.q, level - 1), out=out)
 
     def logistic(self, relin, z):
-        """p(z) for z at level l-2, scale s1 -> level l-6, scale t_p."""
+        """p(z) for z at level l-2, scale s1 -> level l-6, scale t_p (degree 15: z / 12 in, level l-7 out)."""
         he, p = self.he, self.plan
+        if p.degree == 15:
+            return self._logistic15_b(relin, z.unsqueeze(0))[0]
         z2 = self._mul(relin, z, z)
         z4 = self._mul(relin, z2, z2)
         u = self._affine(z2, p.a7, p.c_u, p.a5, p.t_u)
@@ -228,8 +252,37 @@ class EncryptedTrainStep:
         out = he.rescale_batch(he.cmult_batch(cts, _residues(coeff, c_scale, he.q, level)))
         return he.add_const_batch(out, _residues(const, t_scale, he.q, level - 1), out=out)
 
+    def _lin_b(self, y, c0: float, c1: float, target: float, s_in: float):
+        """rescale(c1 y) + c0 at scale `target`, one level below y."""
+        he = self.he
+        level = int(y.shape[2])
+        out = he.rescale_batch(he.cmult_batch(y, _residues(c1, target * float(he.q[level - 1]) / s_in, he.q, level)))
+        return he.add_const_batch(out, _residues(c0, target, he.q, level - 1), out=out)
+
+    def _logistic15_b(self, relin, t):
+        """1/2 + t Q(t^2) with the degree-15 minimax coefficients, t = z / 12 at level l-2 -> level l-7."""
+        he, p, c = self.he, self.plan, self.plan.c15
+        l0 = p.level - 2
+        y = self._mul_b(relin, t, t)
+        y2 = self._mul_b(relin, y, y)
+        y4 = self._mul_b(relin, y2, y2)
+        a_hi = self._lin_b(y, c[5], c[7], p.t_hi_a, p.s_y)
+        b_hi = self._lin_b(y, c[13], c[15], p.t_hi, p.s_y)
+        a_lo = he.moddrop_batch(self._lin_b(y, c[1], c[3], p.t_q, p.s_y), l0 - 3)
+        b_lo = he.moddrop_batch(self._lin_b(y, c[9], c[11], p.t_b, p.s_y), l0 - 3)
+        A = self._mul_b(relin, y2, a_hi)
+        he.add_batch(A, a_lo, out=A)
+        B = self._mul_b(relin, y2, b_hi)
+        he.add_batch(B, b_lo, out=B)
+        Q = self._mul_b(relin, y4, B)
+        he.add_batch(Q, he.moddrop_batch(A, l0 - 4), out=Q)
+        out = self._mul_b(relin, he.moddrop_batch(t, l0 - 4), Q)
+        return he.add_const_batch(out, _residues(0.5, p.t_p, he.q, l0 - 5), out=out)
+
     def _logistic_b(self, relin, z):
         he, p = self.he, self.plan
+        if p.degree == 15:
+            return self._logistic15_b(relin, z)
         z2 = self._mul_b(relin, z, z)
         z4 = self._mul_b(relin, z2, z2)
         u = self._affine_b(z2, p.a7, p.c_u, p.a5, p.t_u)

@@ -22,12 +22,14 @@ from .classifier import EncryptedTrainStep, _residues
 
 class EncryptedTrainer:
     def __init__(self, he, block: int, lr: float, gamma: float, n_samples: int, scale: float = 2.0**50, r: int = 7,
-                 coeffs=None, shrink_bits: int = 6, groups: int = 2):
+                 coeffs=None, shrink_bits: int = 6, groups: int = 2, degree: int = 7):
+        """degree: 7 (least squares on [-8, 8]) or 15 (the paper's minimax polynomial on [-12, 12], one more level)."""
         self.he, self.block, self.gamma, self.scale = he, block, gamma, scale
         self.boot = Bootstrapper(he, block, r, groups=groups)
         self.level = self.boot.out_level
-        assert self.level >= 11, "a gradient step (8), the momentum update (1) and the division (1) need 11 levels"
-        self.step = EncryptedTrainStep(he, self.level, scale, lr, n_samples, coeffs, block)
+        need = (9 if degree == 15 else 8) + 3
+        assert self.level >= need, "the gradient step, the momentum update (1) and the division (1) end at level 1"
+        self.step = EncryptedTrainStep(he, self.level, scale, lr, n_samples, coeffs, block, degree)
         self.shrink = int(round(he.q[1] / 2.0**shrink_bits))       # divides by ~2^shrink_bits when followed by a rescale
         self.delta_in = scale * self.shrink / float(he.q[1])       # scale of the ciphertext Bootstrap receives
         self.gain = self.boot.gain_for(self.delta_in, scale)
@@ -60,7 +62,7 @@ class EncryptedTrainer:
         return out
 
     def iterate(self, keys, mask_pt, X, W, V, Y, boot_pts=(None, None)):
-        """X: [n][2][level][N]; W, V: per class (V at level - 8 or above); Y: per class [n][2][label_level][N].
+        """X: [n][2][level][N]; W, V: per class (V at the step's output level or above); Y: per class [n][2][label_level][N].
         Returns (W, V) of the next iteration."""
         v_new = self.step.run_batched(keys["relin"], keys["rot"], mask_pt, X, W, Y)
         w_new = [self.refresh(keys, self.momentum(vn, vo), *boot_pts) for vn, vo in zip(v_new, V)]

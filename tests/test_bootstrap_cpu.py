@@ -190,7 +190,8 @@ def test_driver_plaintexts_agree_with_the_oracle(ctx):
         assert a.keys() == b.keys() and max(np.abs(a[k] - b[k]).max() for k in a) < 1e-12
 
 
-def test_training_iteration_with_momentum_and_bootstrap(oracle_mod):
+@pytest.mark.parametrize("degree", [7, 15])
+def test_training_iteration_with_momentum_and_bootstrap(oracle_mod, degree):
     """One whole iteration of the paper's training recipe on the small ring (26 levels): gradient step with the
     degree-7 polynomial, Nesterov look-ahead update, division by 2^6, Bootstrap back to level 12 at exactly the
     working scale; the decrypted weights follow the fp64 iteration to 1e-4."""
@@ -211,17 +212,26 @@ def test_training_iteration_with_momentum_and_bootstrap(oracle_mod):
     keys = {"relin": o.keygen_relin(s, 100), "conj": o.keygen_conj(s, 101),
             "rot": {sh: o.keygen_rot(s, sh, 110 + i) for i, sh in enumerate(shifts)}}
     a = oc.logistic_poly_coeffs()
+    c15 = None
     q = [float(v) for v in o.q]
     s1 = S * S / q[level - 1]
-    s4 = (s1 * s1 / q[level - 3]) ** 2 / q[level - 4]
-    label_scale = s1 * (s4 * S / q[level - 5]) / q[level - 6]
+    if degree == 7:
+        s4 = (s1 * s1 / q[level - 3]) ** 2 / q[level - 4]
+        label_scale, label_level = s1 * (s4 * S / q[level - 5]) / q[level - 6], level - 6
+    else:  # the label scale is the scale the degree-15 evaluation returns; take it from a dry run on an encryption of 0
+        from paper_2210_02574_amd import classifier as cl
+
+        c15 = cl.minimax_logistic_coeffs()[0]
+        zero = o.encrypt_coeffs(s, np.zeros(o.N, dtype=np.int64), level - 2, 199)
+        _, label_scale = oc.logistic15(o, zero, keys["relin"], level - 2, s1, c15)
+        label_level = level - 7
     X = [o.encrypt_coeffs(s, o.encode(pr.slots_x(), S), level, 200)]
     W = [o.encrypt_coeffs(s, o.encode(pr.slots_w(pr.w0), S), level, 201)]
-    V = [o.moddrop(W[0], level - 8)]
-    Y = [[o.encrypt_coeffs(s, o.encode(pr.slots_y(), label_scale), level - 6, 202)]]
-    W1, V1 = ot.iterate(o, X, W, V, Y, keys, plan, pr.block, S, lr, gamma, pr.nb, a)
-    assert W1[0].shape == (2, level, o.N) and V1[0].shape == (2, level - 8, o.N)
-    wp, vp = pr.plain_iteration(pr.w0, pr.w0, a, lr, gamma)
+    V = [o.moddrop(W[0], label_level - 2)]
+    Y = [[o.encrypt_coeffs(s, o.encode(pr.slots_y(), label_scale), label_level, 202)]]
+    W1, V1 = ot.iterate(o, X, W, V, Y, keys, plan, pr.block, S, lr, gamma, pr.nb, a, c15=c15)
+    assert W1[0].shape == (2, level, o.N) and V1[0].shape == (2, label_level - 2, o.N)
+    wp, vp = pr.plain_iteration(pr.w0, pr.w0, a, lr, gamma, c15)
     dec_w = o.decrypt(s, W1[0], S).real
     dec_v = o.decrypt(s, V1[0], S).real
     sl = slice(pr.off, pr.off + pr.dim)

@@ -9,7 +9,8 @@ import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-def test_training_iterations_match_oracle_and_plaintext(oracle_mod):
+@pytest.mark.parametrize("degree", [7, 15])
+def test_training_iterations_match_oracle_and_plaintext(oracle_mod, degree):
     import torch
 
     import paper_2210_02574_amd as pkg
@@ -26,7 +27,14 @@ def test_training_iterations_match_oracle_and_plaintext(oracle_mod):
     pr = Problem(o.n)
     S, lr, gamma = 2.0**50, 1.0, 0.5
     a = oc.logistic_poly_coeffs()
-    tr = EncryptedTrainer(he, pr.block, lr, gamma, pr.nb, S, coeffs=np.array([a[k] * 8.0**k for k in range(8)]))
+    c15 = None
+    if degree == 7:
+        tr = EncryptedTrainer(he, pr.block, lr, gamma, pr.nb, S, coeffs=np.array([a[k] * 8.0**k for k in range(8)]))
+    else:  # the paper's activation: degree-15 minimax polynomial on [-12, 12], same coefficients on both sides
+        from paper_2210_02574_amd import classifier as cl
+
+        c15 = cl.minimax_logistic_coeffs()[0]
+        tr = EncryptedTrainer(he, pr.block, lr, gamma, pr.nb, S, coeffs=c15, degree=15)
     plan = ob.Plan(o, pr.block, 7, groups=2)
     level = tr.level
     assert level == plan.out_level == 12 and tr.rotation_shifts() == sorted(
@@ -46,10 +54,11 @@ def test_training_iterations_match_oracle_and_plaintext(oracle_mod):
     c_out = (tr.gain / (4.0 * np.pi)) ** (1.0 / g)
     cts_o = [ob.encode_sparse(o, c_in * np.linalg.inv(plan.factors[i]), plan.L - (g - 1 - i)) for i in range(g)]
     stc_o = [ob.encode_sparse(o, c_out * plan.factors[i], level + g - i) for i in range(g)]
-    W1, V1 = ot.iterate(o, [x_ct], [w_ct], [o.moddrop(w_ct, level - 8)], [[y_ct]], okeys, plan, pr.block, S, lr, gamma,
-                        pr.nb, a, cts_o, stc_o)
+    v_level = tp.out_level
+    W1, V1 = ot.iterate(o, [x_ct], [w_ct], [o.moddrop(w_ct, v_level)], [[y_ct]], okeys, plan, pr.block, S, lr, gamma,
+                        pr.nb, a, cts_o, stc_o, c15=c15)
     mask = np.zeros(o.n)
-    mask[::pr.block] = 1.0
+    mask[::pr.block] = tp.mask_value
     mask_pt = he.to_device(o.coeffs_to_ntt(o.encode(mask, float(o.q[level - 2])), level - 1))
     from paper_2210_02574_amd.bootstrap import DiagonalLayout
 
@@ -59,18 +68,18 @@ def test_training_iterations_match_oracle_and_plaintext(oracle_mod):
     X = he.to_device(x_ct).unsqueeze(0).contiguous()
     Y = [he.to_device(y_ct).unsqueeze(0).contiguous()]
     W = [he.to_device(w_ct)]
-    V = [he.moddrop(W[0], level - 8)]
+    V = [he.moddrop(W[0], v_level)]
     fac = tr.boot.factors()
     boot_pts = (to_dev(cts_o, [c_in * np.linalg.inv(G) for G in fac]), to_dev(stc_o, [c_out * G for G in fac]))
     Wn, Vn = tr.iterate(keys, mask_pt, X, W, V, Y, boot_pts)
     assert np.array_equal(he.to_host(Vn[0]), V1[0])
     assert np.array_equal(he.to_host(Wn[0]), W1[0])
     # two more iterations with the driver's own plaintexts; compare with the fp64 iteration
-    wp, vp = pr.plain_iteration(pr.w0, pr.w0, a, lr, gamma)
+    wp, vp = pr.plain_iteration(pr.w0, pr.w0, a, lr, gamma, c15)
     mask_own = tr.step.encode_mask()
     for it in range(2):
         Wn, Vn = tr.iterate(keys, mask_own, X, Wn, Vn, Y)
-        wp, vp = pr.plain_iteration(wp, vp, a, lr, gamma)
+        wp, vp = pr.plain_iteration(wp, vp, a, lr, gamma, c15)
         dec = he.decrypt(sk, he.to_host(Wn[0]), S).real
         err = np.abs(dec[pr.off:pr.off + pr.dim] - wp).max()
         print("iteration %d: max weight error %.3g (|w| up to %.3g)" % (it + 2, err, np.abs(wp).max()))

@@ -30,9 +30,10 @@ class Problem:
     def slots_y(self):
         return np.repeat(self.y, self.block)
 
-    def plain_iteration(self, w, v, a, lr, gamma):
-        """The same polynomial step in fp64: returns (w_next, v_next)."""
+    def plain_iteration(self, w, v, a, lr, gamma, c15=None):
+        """The same polynomial step in fp64: returns (w_next, v_next).  a: monomial coefficients in x of the
+        degree-7 polynomial; c15: monomial coefficients in x/12 of the degree-15 one (used if given)."""
         z = self.X @ w
-        p = sum(a[k] * z**k for k in range(8))
+        p = sum(a[k] * z**k for k in range(8)) if c15 is None else np.polyval(np.asarray(c15)[::-1], z / 12.0)
         vn = w - lr * ((p - self.y)[:, None] * self.X).sum(0) / self.nb
         return (1 + gamma) * vn - gamma * v, vn
