@@ -212,7 +212,9 @@ int32_t he_modraise(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int32_t 
 int32_t he_hrot(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level, void *d_ws,
                 size_t ws_bytes, void *stream);
 /* `count` rotations of one ciphertext sharing a single decomposition + ModUp (hoisting);
- * h_d_outs is a host array of `count` device pointers.  Bit-identical to `count` he_hrot calls. */
+ * h_d_outs is a host array of `count` device pointers.  Bit-identical to `count` he_hrot calls.
+ * The workspace must hold one operation (he_workspace_bytes with count 1); if it holds m >= 2 operations,
+ * up to min(m, 32) rotations at a time also share their inner-product, inverse and ModDown launches. */
 int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t count, const uint64_t *d_ct,
                      uint64_t *const *h_d_outs, int32_t level, void *d_ws, size_t ws_bytes, void *stream);
 /* for k < count: ct <- ct + Rotate(ct, shift0 * 2^k), in place; rots[k] is the key of that shift. */

@@ -528,7 +528,7 @@ class HE:
         outs = [self.empty_ct(level) for _ in range(n)] if outs is None else outs
         keys = (ctypes.c_void_p * n)(*[k.handle for k in rots])
         ptrs = (ctypes.c_void_p * n)(*[o.data_ptr() for o in outs])
-        ws, wsb = self._workspace(level)
+        ws, wsb = self._workspace(level, min(n, 32))  # room for all rotations: they then share every launch
         self._chk(
             self.lib.he_hrot_many(self.ctx, keys, n, self._dp(ct), ptrs, level, ws, wsb, self._stream()),
             "he_hrot_many",

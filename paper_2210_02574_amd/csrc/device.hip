@@ -246,9 +246,12 @@ static FinArgs fin_args(const u64 *u, u64 *out, const u64 *add, const ShoupConst
     fa.cst = cst, fa.cst_d = cst_d, fa.cst2 = nullptr, fa.cst2_d = nullptr;
     fa.u_cstride = u_cstride, fa.out_cstride = nl, fa.add_cstride = nl, fa.self_stride = 0, fa.nl = nl, fa.mode = mode;
     fa.g = g;
+    fa.hoisted = 0;
     fa.dst_stride = dst_stride, fa.u_stride = u_stride, fa.out_stride = out_stride, fa.add_stride = add_stride;
     return fa;
 }
+static const HoistOuts kNoHoistOuts = {};
+static const HoistKeys kNoHoistKeys = {};
 static const FinArgs kNoFin = fin_args(nullptr, nullptr, nullptr, nullptr, nullptr, 0, 1, 0, 1u, 1 << 30, 0, 0, 0);
 
 // Forward NTT of the listed limbs of `data`.  pro selects what the column pass transforms (the
@@ -258,8 +261,10 @@ static const FinArgs kNoFin = fin_args(nullptr, nullptr, nullptr, nullptr, nullp
 // int_blocks_only: the block pass runs only for limbs on the integer path (the others are finished by the
 // kernel that consumes them).
 static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList &l, int pro, const ConvArgs &cv,
-                           const FinArgs *fin, int src_limbs, bool int_blocks_only = false)
+                           const FinArgs *fin, int src_limbs, bool int_blocks_only = false,
+                           const HoistOuts *hoist = nullptr)
 {
+    const HoistOuts &ho = hoist ? *hoist : kNoHoistOuts;
     const bool wide = std::max(c->alpha, c->K) > 4;
     const double N8 = (double)c->N * 8.0;
     return for_batches(c, l, [&](const LimbBatch &lb, int nb) {
@@ -316,22 +321,22 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
             // reads the transform's input, the minuend and the addend, writes the result
             const double b = (double)nb * N8 * (3.0 + (fin->mode == 1 || fin->mode == 3 ? 1.0 : fin->mode == 2 ? 0.5 : fin->mode == 4 ? 1.5 : 0.0));
             if (c->logN == 17)
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<17, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin);
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<17, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin, ho);
             else if (c->logN == 16)
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<16, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin);
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<16, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin, ho);
             else
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<12, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin);
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<12, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin, ho);
         } else {
             int nbb = nb; // integer-path limbs come first in a batch
             if (int_blocks_only)
                 for (nbb = 0; nbb < nb && c->modc[lb.mod[nbb]].qd == 0.0;) nbb++;
             if (nbb == 0) return;
             if (c->logN == 17)
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<17, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin);
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<17, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin, kNoHoistOuts);
             else if (c->logN == 16)
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<16, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin);
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<16, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin, kNoHoistOuts);
             else
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<12, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin);
+                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<12, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin, kNoHoistOuts);
         }
     });
 }
@@ -617,8 +622,9 @@ static int32_t ks_raise(he_ctx *c, const u64 *d_ntt, int d_stride, u64 *ws, cons
 }
 
 // Step 3 and the inverse transform of step 4: u and, in its special limbs, the scaled coefficient-domain digits.
+// hoist != nullptr: `count` rotations of one raised input (operation 0's workspace), operation o with key hoist->evk[o].
 static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_stride, u64 *ws, const WsLayout &w,
-                        int level, int count, hipStream_t st)
+                        int level, int count, hipStream_t st, const HoistKeys *hoist = nullptr)
 {
     const size_t N = c->N;
     const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha, W = (int)w.total;
@@ -627,15 +633,17 @@ static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
     InnerArgs ia;
     ia.raised = ws + w.raised * N, ia.d = d_ntt, ia.evk = evk->dev, ia.u = ws + w.u * N;
     ia.level = level, ia.L = c->L, ia.K = K, ia.alpha = c->alpha, ia.beta = beta;
-    ia.g = g, ia.ws_stride = W, ia.d_stride = d_stride, ia.inv_special = 1;
+    ia.g = g, ia.raised_stride = hoist ? 0 : W, ia.u_stride = W, ia.d_stride = d_stride, ia.inv_special = 1;
+    ia.hoisted = hoist ? 1 : 0;
+    const HoistKeys &hk = hoist ? *hoist : kNoHoistKeys;
     // reads beta digits and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
     const double inner_bytes = (double)count * (3 * beta + 2) * Ma * N * 8.0;
     if (c->logN == 17)
-        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<17>), grid, ia, c->dev);
+        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<17>), grid, ia, c->dev, hk);
     else if (c->logN == 16)
-        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<16>), grid, ia, c->dev);
+        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<16>), grid, ia, c->dev, hk);
     else
-        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<12>), grid, ia, c->dev);
+        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<12>), grid, ia, c->dev, hk);
     int32_t rc = launch_ok(c);
     if (rc != HE_OK) return rc;
     LimbList sp;
@@ -776,7 +784,34 @@ extern "C" int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t 
     const WsLayout w = ws_layout(ctx, level);
     const u64 *c1 = d_ct + (size_t)level * ctx->N;
     if ((rc = ks_raise(ctx, c1, 0, ws, w, level, 1, st)) != HE_OK) return rc;
-    for (int r = 0; r < count; r++)
+    const size_t N = ctx->N;
+    const int W = (int)w.total, Ma = level + ctx->K;
+    // With workspace for several operations the rotations share every launch: operation o keeps its inner
+    // products and ModDown corrections in workspace o, all read the raised digits of workspace 0.
+    const int fit = (int)std::min<size_t>(ws_bytes / (w.total * N * sizeof(u64)), HOIST_MAX);
+    int r = 0;
+    while (fit >= 2 && count - r >= 2 && batch_fits(w, std::min(fit, count - r))) {
+        const int nb = std::min(fit, count - r);
+        HoistKeys hk = {};
+        HoistOuts ho = {};
+        for (int o = 0; o < nb; o++) {
+            hk.evk[o] = rots[r + o]->dev;
+            hk.g[o] = ho.g[o] = (unsigned)rots[r + o]->galois;
+            ho.out[o] = h_d_outs[r + o];
+        }
+        if ((rc = ks_inner(ctx, rots[r], c1, 0, ws, w, level, nb, st, &hk)) != HE_OK) return rc;
+        const ConvArgs cv = conv_args(ctx, ws + w.u * N, level, W, W);
+        LimbList lr;
+        for (int o = 0; o < nb; o++)
+            for (int cc = 0; cc < 2; cc++)
+                for (int i = 0; i < level; i++) lr.add(o * W + cc * level + i, i);
+        FinArgs fa = fin_args(ws + w.u * N, nullptr, d_ct, ctx->dev.dn_pinv, ctx->dev.dn_pinv_d, Ma, level, 2, 1u, W, W, 0, 0);
+        fa.hoisted = 1;
+        if ((rc = ntt_forward(ctx, st, ws + w.r * N, lr, PRO_MODDOWN, cv, &fa, 2 * ctx->K * nb, false, &ho)) != HE_OK)
+            return rc;
+        r += nb;
+    }
+    for (; r < count; r++)
         if ((rc = ks_apply(ctx, rots[r], c1, 0, ws, w, level, 1, h_d_outs[r], 0, d_ct, 0, 2, st)) != HE_OK) return rc;
     return HE_OK;
 }

@@ -159,21 +159,28 @@ struct InnerArgs {
     u64 *u;
     int level, L, K, alpha, beta;
     unsigned g;
-    int ws_stride, d_stride;
+    int raised_stride, u_stride, d_stride; // limbs between two operations of a batch in each buffer
     int inv_special;
+    int hoisted; // operation z uses key and Galois element z of the HoistKeys argument (one raised input for all)
+};
+#define HOIST_MAX 32
+struct HoistKeys {
+    const u64 *evk[HOIST_MAX];
+    unsigned g[HOIST_MAX];
 };
 
 // grid = (N / 4096, level + K, count)
-template <int LOGN> __global__ __launch_bounds__(256) void k_inner_blocks(InnerArgs ia, DevTables T)
+template <int LOGN> __global__ __launch_bounds__(256) void k_inner_blocks(InnerArgs ia, DevTables T, HoistKeys hk)
 {
     __shared__ u64 lds[16 * TILE_GROUP];
     const int level = ia.level, M = ia.L + ia.K, Ma = level + ia.K;
     const int a = Ma - 1 - (int)blockIdx.y; // special limbs (the slowest) first
     const unsigned tile = blockIdx.x;
-    const u64 *raised = ia.raised + (((size_t)blockIdx.z * ia.ws_stride) << LOGN);
-    u64 *u = ia.u + (((size_t)blockIdx.z * ia.ws_stride) << LOGN);
+    const u64 *raised = ia.raised + (((size_t)blockIdx.z * ia.raised_stride) << LOGN);
+    u64 *u = ia.u + (((size_t)blockIdx.z * ia.u_stride) << LOGN);
     const u64 *d = ia.d + (((size_t)blockIdx.z * ia.d_stride) << LOGN);
-    const unsigned g = ia.g;
+    const unsigned g = ia.hoisted ? hk.g[blockIdx.z] : ia.g;
+    const u64 *evk = ia.hoisted ? hk.evk[blockIdx.z] : ia.evk;
     const int mi = active_mod(a, level, ia.L);
     const int own = a < level ? a / ia.alpha : -1;
     const ModConst m = T.mod[mi];
@@ -220,8 +227,8 @@ template <int LOGN> __global__ __launch_bounds__(256) void k_inner_blocks(InnerA
                 }
                 __syncthreads();
             }
-            const u64 *e0 = ia.evk + ((((size_t)j * 2 + 0) * M + mi) << LOGN) + bg * 256 + il;
-            const u64 *e1 = ia.evk + ((((size_t)j * 2 + 1) * M + mi) << LOGN) + bg * 256 + il;
+            const u64 *e0 = evk + ((((size_t)j * 2 + 0) * M + mi) << LOGN) + bg * 256 + il;
+            const u64 *e1 = evk + ((((size_t)j * 2 + 1) * M + mi) << LOGN) + bg * 256 + il;
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 acc0[k] += ar.mulmod(dv[k], u2d(e0[16 * k]));
@@ -242,8 +249,8 @@ template <int LOGN> __global__ __launch_bounds__(256) void k_inner_blocks(InnerA
             for (int k = 0; k < 8; k++) acc0[k] = acc1[k] = U128{0, 0};
             for (int j = 0; j < ia.beta; j++) {
                 const u64 *dj = j == own ? d + ((size_t)a << LOGN) : raised + (((size_t)j * Ma + a) << LOGN);
-                const u64 *e0 = ia.evk + ((((size_t)j * 2 + 0) * M + mi) << LOGN) + bg * 256 + il;
-                const u64 *e1 = ia.evk + ((((size_t)j * 2 + 1) * M + mi) << LOGN) + bg * 256 + il;
+                const u64 *e0 = evk + ((((size_t)j * 2 + 0) * M + mi) << LOGN) + bg * 256 + il;
+                const u64 *e1 = evk + ((((size_t)j * 2 + 1) * M + mi) << LOGN) + bg * 256 + il;
 #pragma unroll
                 for (int k = 0; k < 8; k++) {
                     const u64 dv = dj[src[8 * h + k]];

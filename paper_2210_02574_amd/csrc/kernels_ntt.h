@@ -64,6 +64,7 @@ struct FinArgs {
     // times cst2 (cst2 == nullptr: as it is); 4: as 2, plus the limb of `self` (rotate-and-add)
     int u_cstride, out_cstride, add_cstride, self_stride, nl, mode;
     unsigned g;
+    int hoisted; // operation o writes to out[o] and uses Galois element g[o] of the HoistOuts argument
     int dst_stride, u_stride, out_stride, add_stride; // limbs between two operations in each buffer
 };
 
@@ -233,12 +234,19 @@ __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithIn
 
 // ---- epilogue: what the forward block pass does with a finished (canonical) NTT value ---------------------
 
+#define HOIST_OUT_MAX 32
+struct HoistOuts {
+    u64 *out[HOIST_OUT_MAX];
+    unsigned g[HOIST_OUT_MAX];
+};
+
 // Operands of the epilogue for one output: issued before the transform so that the loads overlap it.
 struct FinOperands {
     u64 uv, av;
 };
 template <int LOGN>
-__device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, const DevTables &T, unsigned slot, unsigned pos)
+__device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, const HoistOuts &ho, const DevTables &T, unsigned slot,
+                                                unsigned pos)
 {
     const unsigned op = slot / (unsigned)fa.dst_stride;
     slot -= op * (unsigned)fa.dst_stride;
@@ -249,7 +257,7 @@ __device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, const DevTabl
     if (fa.mode == 1)
         o.av = fa.out[(((size_t)op * fa.out_stride + (size_t)c * fa.out_cstride + i) << LOGN) + pos];
     else if (fa.mode == 2 && c == 0)
-        o.av = fa.add[(((size_t)op * fa.add_stride + i) << LOGN) + galois_index(pos, fa.g, LOGN)];
+        o.av = fa.add[(((size_t)op * fa.add_stride + i) << LOGN) + galois_index(pos, fa.hoisted ? ho.g[op] : fa.g, LOGN)];
     else if (fa.mode == 3)
         o.av = fa.add[(((size_t)op * fa.add_stride + (size_t)c * fa.add_cstride + i) << LOGN) + pos];
     else if (fa.mode == 4) {
@@ -261,8 +269,8 @@ __device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, const DevTabl
 }
 
 template <int LOGN>
-__device__ __forceinline__ void fin_store(const FinArgs &fa, const DevTables &T, unsigned slot, unsigned pos, u64 rv,
-                                          const FinOperands &fo)
+__device__ __forceinline__ void fin_store(const FinArgs &fa, const HoistOuts &ho, const DevTables &T, unsigned slot,
+                                          unsigned pos, u64 rv, const FinOperands &fo)
 {
     const unsigned op = slot / (unsigned)fa.dst_stride;
     slot -= op * (unsigned)fa.dst_stride;
@@ -278,7 +286,7 @@ __device__ __forceinline__ void fin_store(const FinArgs &fa, const DevTables &T,
         const u64 av = scaled ? mul_shoup(fo.av, fa.cst2[i], m.q) : fo.av;
         res = csub(mul_shoup(fo.uv + m.q - rv, fa.cst[i], m.q) + av, m.q);
     }
-    fa.out[o] = res;
+    (fa.hoisted ? ho.out[op] : fa.out)[o] = res;
 }
 
 // LDS tile of 16 groups x 256 elements; one pad word per 16 elements and 16 pad words per group
@@ -297,7 +305,7 @@ __device__ __forceinline__ unsigned col_at(unsigned r, unsigned c) { return (r >
 
 template <int LOGN, int EPI, class A>
 __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A &ar, u64 *lds, unsigned tile,
-                                                const FinArgs &fa, const DevTables &T, unsigned slot)
+                                                const FinArgs &fa, const HoistOuts &ho, const DevTables &T, unsigned slot)
 {
     const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
     const unsigned bg = tile * BLK_PER_WG + blk; // block index within the limb
@@ -307,7 +315,7 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
     for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[bg * 256 + il + 16 * k]);
     if (EPI == EPI_FIN) {
 #pragma unroll
-        for (int k = 0; k < 16; k++) fo[k] = fin_load<LOGN>(fa, T, slot, bg * 256 + il + 16 * k);
+        for (int k = 0; k < 16; k++) fo[k] = fin_load<LOGN>(fa, ho, T, slot, bg * 256 + il + 16 * k);
     }
     ar.fwd16(a, LOGN - 8, bg, true);
 #pragma unroll
@@ -325,7 +333,7 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
         const unsigned pos = bg * 256 + il + 16 * k;
         const u64 v = lds[tile_at(blk, il + 16 * k)];
         if (EPI == EPI_FIN)
-            fin_store<LOGN>(fa, T, slot, pos, v, fo[k]);
+            fin_store<LOGN>(fa, ho, T, slot, pos, v, fo[k]);
         else
             limb[pos] = v;
     }
@@ -357,7 +365,8 @@ __device__ __forceinline__ void inv_blocks_body(const u64 *in, u64 *limb, const 
 
 // grid.x = (N/4096) * batch
 template <int LOGN, int EPI>
-__global__ __launch_bounds__(BLK_THREADS) void k_ntt_fwd_blocks(u64 *__restrict__ data, DevTables T, LimbBatch lb, FinArgs fa)
+__global__ __launch_bounds__(BLK_THREADS) void k_ntt_fwd_blocks(u64 *__restrict__ data, DevTables T, LimbBatch lb, FinArgs fa,
+                                                                HoistOuts ho)
 {
     __shared__ u64 lds[BLK_PER_WG * TILE_GROUP];
     constexpr unsigned TILES = (1u << LOGN) / (256 * BLK_PER_WG);
@@ -365,9 +374,9 @@ __global__ __launch_bounds__(BLK_THREADS) void k_ntt_fwd_blocks(u64 *__restrict_
     const unsigned mi = lb.mod[b], slot = lb.slot[b];
     u64 *limb = data + ((size_t)slot << LOGN);
     if (T.mod[mi].qd != 0.0)
-        fwd_blocks_body<LOGN, EPI>(limb, make_fp(T, mi, LOGN), lds, tile, fa, T, slot);
+        fwd_blocks_body<LOGN, EPI>(limb, make_fp(T, mi, LOGN), lds, tile, fa, ho, T, slot);
     else
-        fwd_blocks_body<LOGN, EPI>(limb, make_int(T, mi, LOGN), lds, tile, fa, T, slot);
+        fwd_blocks_body<LOGN, EPI>(limb, make_int(T, mi, LOGN), lds, tile, fa, ho, T, slot);
 }
 
 template <int LOGN>
