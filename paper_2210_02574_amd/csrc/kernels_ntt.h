@@ -289,8 +289,8 @@ __device__ __forceinline__ void fin_store(const FinArgs &fa, const HoistOuts &ho
     (fa.hoisted ? ho.out[op] : fa.out)[o] = res;
 }
 
-// LDS tile of 16 groups x 256 elements; one pad word per 16 elements and 16 pad words per group
-// keep both the "stride-16" and the "16 consecutive" access patterns free of bank conflicts.
+// LDS tile of the block pass: 16 groups x 256 elements; one pad word per 16 elements and 16 pad words per
+// group keep both the "stride-16" and the "16 consecutive" access patterns free of bank conflicts.
 #define TILE_GROUP 272
 // threads per work-group of the block pass: 16 threads per 256-element block
 #ifndef BLK_THREADS
@@ -298,8 +298,10 @@ __device__ __forceinline__ void fin_store(const FinArgs &fa, const HoistOuts &ho
 #endif
 #define BLK_PER_WG (BLK_THREADS / 16)
 __device__ __forceinline__ unsigned tile_at(unsigned grp, unsigned i) { return grp * TILE_GROUP + i + (i >> 4); }
-// column pass: row r (0..255) of column c (0..15); 16 pad words after every 16 rows
-__device__ __forceinline__ unsigned col_at(unsigned r, unsigned c) { return (r >> 4) * TILE_GROUP + (r & 15) * 16 + c; }
+// column pass: row r of column c (0..15).  The 16 lanes of a column group always touch 16 consecutive words,
+// so this tile needs no padding: 32 KiB at N = 2^16, five work-groups per compute unit.
+#define COL_GROUP 256
+__device__ __forceinline__ unsigned col_at(unsigned r, unsigned c) { return (r >> 4) * COL_GROUP + (r & 15) * 16 + c; }
 
 // ---- block pass ---------------------------------------------------------------------------------------------
 
@@ -404,7 +406,7 @@ __global__ __launch_bounds__(BLK_THREADS) void k_ntt_inv_blocks(const u64 *src, 
 template <int LOGN> struct ColsGeom {
     static constexpr int ROWS = 1 << (LOGN - 8);
     static constexpr int HALVES = ROWS / 256;          // 16-element register steps per thread and phase
-    static constexpr int LDS_WORDS = (ROWS / 16) * TILE_GROUP;
+    static constexpr int LDS_WORDS = (ROWS / 16) * COL_GROUP;
 };
 
 // the 16 inputs of one thread in rows rl + 16 k + 256 h (plain load or base conversion)
