@@ -296,7 +296,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-train-step", action="store_true")
-    ap.add_argument("--hmult-batch", type=int, default=16, help="ciphertext pairs per batched HMult call")
+    ap.add_argument("--hmult-batch", type=int, default=8, help="ciphertext pairs per batched HMult call")
     ap.add_argument("--streams", type=int, default=3, help="HIP streams for the independent operations of a step")
     args = ap.parse_args()
     if args.gpus != 1:
