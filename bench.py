@@ -250,6 +250,44 @@ def bootstrap_ms(he, w: "Workload", ns: int = 1024, reps: int = 3) -> float:
     return (time.perf_counter() - t0) * 1e3 / reps
 
 
+def paper_scale_rates(reps: int = 5) -> dict:
+    """The paper's ring degree (N = 2^17, 30 primes below 2^50, 4 special primes, dnum = 8) on uniform residues:
+    rotations in batches of four and Mult + rescale in batches of four at level 30."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+
+    p = wl.P17
+    he = pkg.HE.from_params(p, device=0)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(17)
+
+    def uniform_batch(count):
+        out = torch.empty((count, 2, p.L, p.N), dtype=torch.int64, device=dev)
+        for i in range(p.L):
+            out[:, :, i].random_(0, p.q[i], generator=gen)
+        return out
+
+    rot = he.evk_from_host(wl.uniform_evk(1701, p), he.galois_element(1))
+    relin = he.evk_from_host(wl.uniform_evk(1702, p), 1)
+    a, b = uniform_batch(4), uniform_batch(4)
+    out = he.empty_batch(4, p.L)
+    out2 = he.empty_batch(4, p.L - 1)
+    res = {}
+    for name, fn in (("hrot_per_s", lambda: he.hrot_batch(rot, a, out=out)),
+                     ("hmult_relin_rescale_per_s", lambda: he.hmult_relin_rescale_batch(relin, a, b, out=out2))):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        res[name] = 4 * reps / (time.perf_counter() - t0)
+    res["workload"] = "N=2^17, L=30, K=4, dnum=8, level 30, batches of 4"
+    return res
+
+
 def cpu_baseline(sample_hrot: int = 32, sample_hmult: int = 16, sample_ntt: int = 112):
     """The oracle, as it stands, on a bounded sample of the step: NTT/iNTT pairs, HMult+relin+rescale
     and HRot at level 24; reported in key switches per second."""
@@ -411,6 +449,7 @@ def main():
         out["detail"]["inference_ms"] = inference_ms(he, w)
         out["detail"]["inference_workload"] = "32 samples x 768 features, 4 classes, 11 HRot, level 24"
         out["detail"]["train_step_ms"] = train_step_ms(he, w)
+        out["detail"]["paper_scale"] = paper_scale_rates()
         out["detail"]["bootstrap_ms"] = bootstrap_ms(he, w)
         out["detail"]["bootstrap_workload"] = ("1024 packed slots (the block of the paper's weight vectors), level 1 -> 8, "
                                                "5 + 4 x 14 HRot, 2 conjugations, 24 HMult")

@@ -260,6 +260,8 @@ def test_conjugation_and_public_key_encryption(env):
 
 
 def test_error_codes_on_device_context(env):
+    import ctypes
+
     he, p = env.he, env.params
     key, _ = env.synth_key(301, 1)
     rkey, _ = env.synth_key(901, env.o.galois_element(1))
@@ -273,8 +275,12 @@ def test_error_codes_on_device_context(env):
     with pytest.raises(Exception) as ei:
         he.hmult_relin(rkey, a, a)
     assert "HE_ENOKEY" in str(ei.value)
-    import ctypes
-
+    with pytest.raises(Exception) as ei:
+        he.modraise(a, 1, out=he.empty_ct(1))  # ModRaise goes to at least two limbs
+    assert "HE_ELEVEL" in str(ei.value)
+    ptrs = (ctypes.c_void_p * 65)(*([a.data_ptr()] * 65))
+    rc = he.lib.he_pmult_sum(he.ctx, ptrs, ptrs, 65, ctypes.c_void_p(a.data_ptr()), 1, None)
+    assert rc == -1  # more than 64 terms in one call
     rc = he.lib.he_hrot(he.ctx, rkey.handle, ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(a.data_ptr() + 8),
                         1, ctypes.c_void_p(a.data_ptr()), 16, None)
     assert rc == -4  # workspace too small
