@@ -37,16 +37,16 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # `--pmc WRITE_SIZE` runs of this command with --streams 1, scaled by the copy-kernel calibration
 # (2 x FETCH_SIZE + 1 x WRITE_SIZE; summary and calibration under profiles/).
 MEASURED_TRAFFIC_BYTES = {
-    "k_inner_blocks": 366106009,
-    "k_ntt_fwd_blocks_fin": 111549440,
-    "k_ntt_fwd_blocks": 35472076,
-    "k_ntt_fwd_cols_modup": 79191859,
-    "k_ntt_fwd_cols_moddown": 24100044,
-    "k_ntt_fwd_cols_moddown_rescale": 159236198,
-    "k_ntt_fwd_cols": 269811097,
-    "k_tensor": 1409365811,
-    "k_ntt_inv_blocks": 40553881,
-    "k_ntt_inv_cols": 20911308,
+    "k_inner_blocks": 391477452,
+    "k_ntt_fwd_blocks_fin": 114842009,
+    "k_ntt_inv_blocks": 39403724,
+    "k_tensor": 704721100,
+    "k_ntt_fwd_cols_modup": 77318758,
+    "k_ntt_fwd_blocks": 35470848,
+    "k_ntt_inv_cols": 21338990,
+    "k_ntt_fwd_cols_moddown": 25461452,
+    "k_ntt_fwd_cols_moddown_rescale": 119644979,
+    "k_ntt_fwd_cols": 269782425,
 }
 
 
