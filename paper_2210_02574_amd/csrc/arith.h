@@ -94,7 +94,8 @@ struct ArithFp {
     __device__ __forceinline__ V load_mid(u64 m) const { return __longlong_as_double(m); }
     __device__ __forceinline__ u64 store_mid(V v) const { return (u64)__double_as_longlong(v); }
     __device__ __forceinline__ u64 store_final(V v) const { return fp_canon(v, q, qinv); }
-    __device__ __forceinline__ void fwd16(V (&a)[16], unsigned s_base, unsigned G, bool reduce_first) const
+    // tw(c): twiddle c of the 15 this step uses, stage sp's at c = 2^sp - 1 .. 2^(sp+1) - 2
+    template <class F> __device__ __forceinline__ void fwd16_with(V (&a)[16], bool reduce_first, F tw) const
     {
         if (reduce_first) {
 #pragma unroll
@@ -103,10 +104,9 @@ struct ArithFp {
 #pragma unroll
         for (int sp = 0; sp < 4; sp++) {
             const int dist = 8 >> sp;
-            const unsigned idx0 = (1u << (s_base + sp)) + (G << sp);
 #pragma unroll
             for (int g = 0; g < (1 << sp); g++) {
-                const double w = twf[idx0 + g];
+                const double w = tw((1 << sp) - 1 + g);
 #pragma unroll
                 for (int e = 0; e < dist; e++) {
                     const int k0 = g * 2 * dist + e, k1 = k0 + dist;
@@ -116,6 +116,16 @@ struct ArithFp {
                 }
             }
         }
+    }
+    // index in twf of twiddle c (as above) of the step that starts at stage s_base in group G
+    static __device__ __forceinline__ unsigned fwd16_twiddle(unsigned s_base, unsigned G, unsigned c)
+    {
+        const unsigned sp = 31u - (unsigned)__clz((int)(c + 1));
+        return (1u << (s_base + sp)) + (G << sp) + (c + 1 - (1u << sp));
+    }
+    __device__ __forceinline__ void fwd16(V (&a)[16], unsigned s_base, unsigned G, bool reduce_first) const
+    {
+        fwd16_with(a, reduce_first, [&](int c) { return twf[fwd16_twiddle(s_base, G, (unsigned)c)]; });
     }
     template <bool LAST> __device__ __forceinline__ void inv16(V (&a)[16], unsigned s_base, unsigned G) const
     {

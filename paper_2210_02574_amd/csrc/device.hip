@@ -629,12 +629,18 @@ static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
     const size_t N = c->N;
     const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha, W = (int)w.total;
     const unsigned g = (unsigned)evk->galois;
-    dim3 grid((unsigned)(N / 4096), (unsigned)Ma, (unsigned)count);
+    // the kernel reads keys and its NTT-domain input, and writes u, in 16-byte pairs
+    auto misaligned = [](const void *p) { return ((uintptr_t)p & 15u) != 0; };
+    if (misaligned(ws) || misaligned(d_ntt) || misaligned(evk->dev)) return HE_EINVAL;
+    if (hoist)
+        for (int o = 0; o < count; o++)
+            if (misaligned(hoist->evk[o])) return HE_EINVAL;
+    dim3 grid(inner_grid((unsigned)(N / 4096), (unsigned)Ma, (unsigned)count));
     InnerArgs ia;
     ia.raised = ws + w.raised * N, ia.d = d_ntt, ia.evk = evk->dev, ia.u = ws + w.u * N;
     ia.level = level, ia.L = c->L, ia.K = K, ia.alpha = c->alpha, ia.beta = beta;
     ia.g = g, ia.raised_stride = hoist ? 0 : W, ia.u_stride = W, ia.d_stride = d_stride, ia.inv_special = 1;
-    ia.hoisted = hoist ? 1 : 0;
+    ia.hoisted = hoist ? 1 : 0, ia.count = count;
     const HoistKeys &hk = hoist ? *hoist : kNoHoistKeys;
     // reads beta digits and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
     const double inner_bytes = (double)count * (3 * beta + 2) * Ma * N * 8.0;
