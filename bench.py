@@ -58,7 +58,7 @@ class Workload:
     N_SINGLE = 128
 
     def __init__(self, he, seed: int = 2, n_hmult: int = None, n_single: int = None, n_ntt: int = None,
-                 n_streams: int = 1, hm_chunk: int = 16):
+                 n_streams: int = 1, hm_chunk: int = 16, group_singles: bool = True):
         import torch
 
         self.torch = torch
@@ -93,6 +93,18 @@ class Workload:
         self.single_keys = [self.offsets.index(o) for o in offs]
         self.single_in = [self._uniform_ct(lv) for lv in levels]
         self.single_out = [he.empty_ct(lv) for lv in levels]
+        # The single rotations are independent (own ciphertext, level and key each).  Those at the same level are
+        # stored back to back and issued as one call with one key per ciphertext, so that their kernels are
+        # launched once per level instead of once per rotation.
+        self.single_groups = []
+        if group_singles:
+            for lv in sorted(set(levels), reverse=True):
+                idx = [i for i in range(self.n_single) if levels[i] == lv]
+                cts = torch.stack([self.single_in[i] for i in idx])
+                outs = he.empty_batch(len(idx), lv)
+                for k, i in enumerate(idx):
+                    self.single_in[i], self.single_out[i] = cts[k], outs[k]
+                self.single_groups.append(([self.rot[self.single_keys[i]] for i in idx], cts, outs))
         self.key_switches = self.n_hmult + len(self.offsets) + self.n_single
 
     def _uniform(self, mod_idx):
@@ -132,11 +144,12 @@ class Workload:
         mark("hmult_relin_rescale")
         he.hrot_many(self.rot, self.hoist_in, outs=self.hoist_out)
         mark("hrot_hoisted")
+        n_jobs = len(self.single_groups) or self.n_single
         if serial:
-            for i in range(self.n_single):
+            for i in range(n_jobs):
                 self._single_one(i)
         else:
-            self._spread(self.n_single, self._single_one)
+            self._spread(n_jobs, self._single_one)
         mark("hrot_single")
 
     def _step_overlapped(self):
@@ -150,11 +163,15 @@ class Workload:
             hi = min(lo + self.hm_chunk, self.n_hmult)
             jobs.append(lambda lo=lo, hi=hi: he.hmult_relin_rescale_batch(self.relin, self.hm_a[lo:hi], self.hm_b[lo:hi],
                                                                           out=self.rs_out[lo:hi]))
-        jobs += [lambda i=i: self._single_one(i) for i in range(self.n_single)]
+        jobs += [lambda i=i: self._single_one(i) for i in range(len(self.single_groups) or self.n_single)]
         self._spread(len(jobs), lambda k: jobs[k]())
 
     def _single_one(self, i):
-        self.he.hrot(self.rot[self.single_keys[i]], self.single_in[i], out=self.single_out[i])
+        if self.single_groups:
+            keys, cts, outs = self.single_groups[i]
+            self.he.hrot_batch_keys(keys, cts, out=outs)
+        else:
+            self.he.hrot(self.rot[self.single_keys[i]], self.single_in[i], out=self.single_out[i])
 
     def _spread(self, count, fn):
         """Runs fn(0..count-1); with side streams the independent calls are dealt round-robin to them and
@@ -335,6 +352,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-train-step", action="store_true")
     ap.add_argument("--hmult-batch", type=int, default=8, help="ciphertext pairs per batched HMult call")
+    ap.add_argument("--no-group-singles", action="store_true",
+                    help="issue every single rotation as a call of its own instead of one call per level")
     ap.add_argument("--streams", type=int, default=3, help="HIP streams for the independent operations of a step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -353,7 +372,7 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     he = pkg.HE.from_params(wl.N16, device=0)
-    w = Workload(he, n_streams=args.streams, hm_chunk=args.hmult_batch)
+    w = Workload(he, n_streams=args.streams, hm_chunk=args.hmult_batch, group_singles=not args.no_group_singles)
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()
@@ -440,6 +459,7 @@ def main():
             "key_switches_per_step": w.key_switches,
             "streams": args.streams,
             "hmult_batch": args.hmult_batch,
+            "single_hrot_calls": "one call per level (one key per ciphertext)" if w.single_groups else "one call each",
         },
         "detail": detail,
         "roofline": roofline,

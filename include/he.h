@@ -251,6 +251,12 @@ int32_t he_rescale_batch(he_ctx *ctx, const uint64_t *d_ct, uint64_t *d_out, int
                          size_t ws_bytes, void *stream);
 int32_t he_hrot_batch(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level,
                       int32_t count, void *d_ws, size_t ws_bytes, void *stream);
+/* Rotate (Section 2.2) of `count` independent ciphertexts at one level, operation o with its own key rots[o]
+ * (host array of key handles; any mix of Galois elements other than 1): the launches of he_hrot_batch with one
+ * key per operation.  Bit-identical to he_hrot(rots[o], ct o).  Operations are processed in groups of at most 32;
+ * a workspace for fewer operations than that (at least one) makes the groups smaller. */
+int32_t he_hrot_batch_keys(he_ctx *ctx, const he_evk *const *rots, const uint64_t *d_ct, uint64_t *d_out, int32_t level,
+                           int32_t count, void *d_ws, size_t ws_bytes, void *stream);
 /* n_rot sequential rotate-and-add steps applied to every ciphertext of the batch, in place */
 int32_t he_rotate_sum_batch(he_ctx *ctx, const he_evk *const *rots, int32_t n_rot, uint64_t *d_ct, int32_t level,
                             int32_t count, void *d_ws, size_t ws_bytes, void *stream);

@@ -623,8 +623,9 @@ static int32_t ks_raise(he_ctx *c, const u64 *d_ntt, int d_stride, u64 *ws, cons
 
 // Step 3 and the inverse transform of step 4: u and, in its special limbs, the scaled coefficient-domain digits.
 // hoist != nullptr: `count` rotations of one raised input (operation 0's workspace), operation o with key hoist->evk[o].
+// shared_raised = false: per-operation keys as well, but every operation has its own raised input.
 static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_stride, u64 *ws, const WsLayout &w,
-                        int level, int count, hipStream_t st, const HoistKeys *hoist = nullptr)
+                        int level, int count, hipStream_t st, const HoistKeys *hoist = nullptr, bool shared_raised = true)
 {
     const size_t N = c->N;
     const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha, W = (int)w.total;
@@ -639,7 +640,7 @@ static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
     InnerArgs ia;
     ia.raised = ws + w.raised * N, ia.d = d_ntt, ia.evk = evk->dev, ia.u = ws + w.u * N;
     ia.level = level, ia.L = c->L, ia.K = K, ia.alpha = c->alpha, ia.beta = beta;
-    ia.g = g, ia.raised_stride = hoist ? 0 : W, ia.u_stride = W, ia.d_stride = d_stride, ia.inv_special = 1;
+    ia.g = g, ia.raised_stride = hoist && shared_raised ? 0 : W, ia.u_stride = W, ia.d_stride = d_stride, ia.inv_special = 1;
     ia.hoisted = hoist ? 1 : 0, ia.count = count;
     const HoistKeys &hk = hoist ? *hoist : kNoHoistKeys;
     // reads beta digits and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
@@ -848,6 +849,49 @@ extern "C" int32_t he_hrot(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct,
                            void *d_ws, size_t ws_bytes, void *stream)
 {
     return he_hrot_batch(ctx, rot, d_ct, d_out, level, 1, d_ws, ws_bytes, stream);
+}
+
+extern "C" int32_t he_hrot_batch_keys(he_ctx *ctx, const he_evk *const *rots, const uint64_t *d_ct, uint64_t *d_out,
+                                      int32_t level, int32_t count, void *d_ws, size_t ws_bytes, void *stream)
+{
+    if (!rots || count < 1) return HE_EINVAL;
+    int32_t rc;
+    for (int r = 0; r < count; r++) {
+        if ((rc = ks_guard(ctx, rots[r], level, 1, d_ws, ws_bytes)) != HE_OK) return rc;
+        if (rots[r]->galois == 1) return HE_ENOKEY;
+    }
+    if (!d_ct || !d_out || d_ct == d_out) return HE_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    u64 *ws = (u64 *)d_ws;
+    const WsLayout w = ws_layout(ctx, level);
+    const size_t N = ctx->N;
+    const int W = (int)w.total, Ma = level + ctx->K, ct_limbs = 2 * level;
+    int fit = (int)std::min<size_t>(ws_bytes / (w.total * N * sizeof(u64)), HOIST_MAX);
+    while (fit > 1 && !batch_fits(w, fit)) fit--;
+    for (int r = 0; r < count;) {
+        const int nb = std::min(fit, count - r);
+        const u64 *in = d_ct + (size_t)r * ct_limbs * N, *c1 = in + (size_t)level * N;
+        if ((rc = ks_raise(ctx, c1, ct_limbs, ws, w, level, nb, st)) != HE_OK) return rc;
+        HoistKeys hk = {};
+        HoistOuts ho = {};
+        for (int o = 0; o < nb; o++) {
+            hk.evk[o] = rots[r + o]->dev;
+            hk.g[o] = ho.g[o] = (unsigned)rots[r + o]->galois;
+            ho.out[o] = d_out + (size_t)(r + o) * ct_limbs * N;
+        }
+        if ((rc = ks_inner(ctx, rots[r], c1, ct_limbs, ws, w, level, nb, st, &hk, false)) != HE_OK) return rc;
+        const ConvArgs cv = conv_args(ctx, ws + w.u * N, level, W, W);
+        LimbList lr;
+        for (int o = 0; o < nb; o++)
+            for (int cc = 0; cc < 2; cc++)
+                for (int i = 0; i < level; i++) lr.add(o * W + cc * level + i, i);
+        FinArgs fa = fin_args(ws + w.u * N, nullptr, in, ctx->dev.dn_pinv, ctx->dev.dn_pinv_d, Ma, level, 2, 1u, W, W, 0, ct_limbs);
+        fa.hoisted = 1;
+        if ((rc = ntt_forward(ctx, st, ws + w.r * N, lr, PRO_MODDOWN, cv, &fa, 2 * ctx->K * nb, false, &ho)) != HE_OK)
+            return rc;
+        r += nb;
+    }
+    return HE_OK;
 }
 
 extern "C" int32_t he_rotate_sum_batch(he_ctx *ctx, const he_evk *const *rots, int32_t n_rot, uint64_t *d_ct,

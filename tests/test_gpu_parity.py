@@ -170,6 +170,8 @@ def test_hmult_relin_rescale_in_one_call(env):
 
 
 def test_hrot_single_and_hoisted(env):
+    import torch
+
     he, o, p = env.he, env.o, env.params
     rots = [1, 5, p.N // 4] if p.logN == 12 else [1, 1 << 14]
     keys = [env.synth_key(500 + r, o.galois_element(r)) for r in rots]
@@ -185,6 +187,11 @@ def test_hrot_single_and_hoisted(env):
         for got, want in zip(outs, singles):
             assert np.array_equal(he.to_host(got), want)
         assert np.array_equal(he.to_host(d), ct)  # input untouched
+        # one key per ciphertext of a batch: two different inputs, against the oracle
+        ct2 = wl.uniform_ct(650 + level, p, level)
+        both = he.hrot_batch_keys([k for k, _ in keys[:2]], torch.stack([d, he.to_device(ct2)]))
+        assert np.array_equal(he.to_host(both[0]), singles[0])
+        assert np.array_equal(he.to_host(both[1]), o.hrot(ct2, keys[1][1], rots[1])), level
 
 
 def test_rotate_sum(env):
@@ -316,6 +323,8 @@ def test_batched_calls_equal_single_calls(env):
         same(he.rescale_batch(a), lambda i: he.rescale(a[i]))
     same(he.hmult_relin_batch(relin, a, b), lambda i: he.hmult_relin(relin, a[i], b[i]))
     same(he.hrot_batch(rkeys[0], a), lambda i: he.hrot(rkeys[0], a[i]))
+    mixed = [rkeys[i % 2] for i in range(count)]
+    same(he.hrot_batch_keys(mixed, a), lambda i: he.hrot(mixed[i], a[i]))
     rs = he.rotate_sum_batch(rkeys, a.clone())
     same(rs, lambda i: he.rotate_sum(rkeys, a[i].clone()))
     # in place
