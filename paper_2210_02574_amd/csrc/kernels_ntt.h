@@ -367,7 +367,7 @@ __device__ __forceinline__ void inv_blocks_body(const u64 *in, u64 *limb, const 
 
 // grid.x = (N/4096) * batch
 template <int LOGN, int EPI>
-__global__ __launch_bounds__(BLK_THREADS) void k_ntt_fwd_blocks(u64 *__restrict__ data, DevTables T, LimbBatch lb, FinArgs fa,
+__global__ __launch_bounds__(BLK_THREADS, EPI == EPI_FIN ? 4 : 1) void k_ntt_fwd_blocks(u64 *__restrict__ data, DevTables T, LimbBatch lb, FinArgs fa,
                                                                 HoistOuts ho)
 {
     __shared__ u64 lds[BLK_PER_WG * TILE_GROUP];
