@@ -565,6 +565,9 @@ extern "C" int32_t he_moddrop(he_ctx *ctx, const uint64_t *d_ct, int32_t in_leve
     return he_moddrop_batch(ctx, d_ct, in_level, d_out, out_level, 1, stream);
 }
 
+// the key-switch kernels read and write 16-byte pairs
+static inline bool misaligned16(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
 // ---- workspace layout (in limbs of N words), per operation of a batch
 struct WsLayout {
     size_t x, d, raised, u, r, tmp, total;
@@ -630,12 +633,7 @@ static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
     const size_t N = c->N;
     const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha, W = (int)w.total;
     const unsigned g = (unsigned)evk->galois;
-    // the kernel reads keys and its NTT-domain input, and writes u, in 16-byte pairs
-    auto misaligned = [](const void *p) { return ((uintptr_t)p & 15u) != 0; };
-    if (misaligned(ws) || misaligned(d_ntt) || misaligned(evk->dev)) return HE_EINVAL;
-    if (hoist)
-        for (int o = 0; o < count; o++)
-            if (misaligned(hoist->evk[o])) return HE_EINVAL;
+    if (misaligned16(ws) || misaligned16(d_ntt) || misaligned16(evk->dev)) return HE_EINVAL; // entry points check first
     dim3 grid(inner_grid((unsigned)(N / 4096), (unsigned)Ma, (unsigned)count));
     InnerArgs ia;
     ia.raised = ws + w.raised * N, ia.d = d_ntt, ia.evk = evk->dev, ia.u = ws + w.u * N;
@@ -687,7 +685,7 @@ static int32_t ks_guard(he_ctx *c, const he_evk *evk, int level, int count, void
     int32_t rc = level_guard(c, level);
     if (rc != HE_OK) return rc;
     if (!evk || evk->ctx != c || !evk->dev) return HE_ENOKEY;
-    if (!ws) return HE_EINVAL;
+    if (!ws || misaligned16(ws) || misaligned16(evk->dev)) return HE_EINVAL;
     const WsLayout w = ws_layout(c, level);
     if (!batch_fits(w, count)) return HE_EINVAL;
     if (ws_bytes < w.total * (size_t)count * c->N * sizeof(u64)) return HE_EWORKSPACE;
@@ -701,7 +699,7 @@ extern "C" int32_t he_hmult_relin_batch(he_ctx *ctx, const he_evk *relin, const 
     int32_t rc = ks_guard(ctx, relin, level, count, d_ws, ws_bytes);
     if (rc != HE_OK) return rc;
     if (relin->galois != 1) return HE_ENOKEY;
-    if (!d_a || !d_b || !d_out) return HE_EINVAL;
+    if (!d_a || !d_b || !d_out || misaligned16(d_a) || misaligned16(d_b) || misaligned16(d_out)) return HE_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     u64 *ws = (u64 *)d_ws;
     const WsLayout w = ws_layout(ctx, level);
@@ -732,7 +730,7 @@ extern "C" int32_t he_hmult_relin_rescale_batch(he_ctx *ctx, const he_evk *relin
     if (rc != HE_OK) return rc;
     if (relin->galois != 1) return HE_ENOKEY;
     if (level < 2) return HE_ELEVEL;
-    if (!d_a || !d_b || !d_out) return HE_EINVAL;
+    if (!d_a || !d_b || !d_out || misaligned16(d_a) || misaligned16(d_b) || misaligned16(d_out)) return HE_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     u64 *ws = (u64 *)d_ws;
     const WsLayout w = ws_layout(ctx, level);
@@ -783,9 +781,9 @@ extern "C" int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t 
     for (int r = 0; r < count; r++) {
         if ((rc = ks_guard(ctx, rots[r], level, 1, d_ws, ws_bytes)) != HE_OK) return rc;
         if (rots[r]->galois == 1) return HE_ENOKEY;
-        if (!h_d_outs[r] || h_d_outs[r] == d_ct) return HE_EINVAL;
+        if (!h_d_outs[r] || h_d_outs[r] == d_ct || misaligned16(h_d_outs[r])) return HE_EINVAL;
     }
-    if (!d_ct) return HE_EINVAL;
+    if (!d_ct || misaligned16(d_ct)) return HE_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     u64 *ws = (u64 *)d_ws;
     const WsLayout w = ws_layout(ctx, level);
@@ -831,7 +829,7 @@ static int32_t hrot_batch_to(he_ctx *ctx, const he_evk *rot, const u64 *d_ct, in
     int32_t rc = ks_guard(ctx, rot, level, count, d_ws, ws_bytes);
     if (rc != HE_OK) return rc;
     if (rot->galois == 1) return HE_ENOKEY;
-    if (!d_ct || !d_out || d_ct == d_out) return HE_EINVAL;
+    if (!d_ct || !d_out || d_ct == d_out || misaligned16(d_ct) || misaligned16(d_out)) return HE_EINVAL;
     u64 *ws = (u64 *)d_ws;
     const WsLayout w = ws_layout(ctx, level);
     const u64 *c1 = d_ct + (size_t)level * ctx->N;
@@ -860,7 +858,7 @@ extern "C" int32_t he_hrot_batch_keys(he_ctx *ctx, const he_evk *const *rots, co
         if ((rc = ks_guard(ctx, rots[r], level, 1, d_ws, ws_bytes)) != HE_OK) return rc;
         if (rots[r]->galois == 1) return HE_ENOKEY;
     }
-    if (!d_ct || !d_out || d_ct == d_out) return HE_EINVAL;
+    if (!d_ct || !d_out || d_ct == d_out || misaligned16(d_ct) || misaligned16(d_out)) return HE_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     u64 *ws = (u64 *)d_ws;
     const WsLayout w = ws_layout(ctx, level);
@@ -904,6 +902,11 @@ extern "C" int32_t he_rotate_sum_batch(he_ctx *ctx, const he_evk *const *rots, i
     const WsLayout w = ws_layout(ctx, level);
     if (!batch_fits(w, count)) return HE_EINVAL;
     if (ws_bytes < w.total * (size_t)count * ctx->N * sizeof(u64)) return HE_EWORKSPACE;
+    if (misaligned16(d_ct)) return HE_EINVAL;
+    for (int k = 0; k < n_rot; k++) { // every key is checked before the first launch
+        if ((rc = ks_guard(ctx, rots[k], level, count, d_ws, ws_bytes)) != HE_OK) return rc;
+        if (rots[k]->galois == 1) return HE_ENOKEY;
+    }
     // ct + Rotate(ct) is written by the key switch itself, alternately into the workspace (operation o at
     // tmp + o*w.total limbs) and back into d_ct
     u64 *tmp = (u64 *)d_ws + w.tmp * ctx->N;

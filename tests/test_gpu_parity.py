@@ -291,6 +291,16 @@ def test_error_codes_on_device_context(env):
     rc = he.lib.he_hrot(he.ctx, rkey.handle, ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(a.data_ptr() + 8),
                         1, ctypes.c_void_p(a.data_ptr()), 16, None)
     assert rc == -4  # workspace too small
+    with pytest.raises(Exception) as ei:
+        he.hrot_batch_keys([rkey, key], he.empty_batch(2, 1))  # second key is not a rotation key
+    assert "HE_ENOKEY" in str(ei.value)
+    with pytest.raises(ValueError):
+        he.hrot_batch_keys([rkey], he.empty_batch(2, 1))  # one key per ciphertext
+    ws, wsb = he._workspace(1, 1)
+    keys = (ctypes.c_void_p * 1)(rkey.handle)
+    rc = he.lib.he_hrot_batch_keys(he.ctx, keys, ctypes.c_void_p(a.data_ptr() + 8), ctypes.c_void_p(he.empty_ct(1).data_ptr()),
+                                   1, 1, ws, wsb, None)
+    assert rc == -1  # input not 16-byte aligned: refused before any launch
     _sync()
 
 
