@@ -23,7 +23,7 @@
 #pragma once
 #include "arith.h"
 
-#define HE_MAXB 256
+#define HE_MAXB 512
 // A launch works on up to HE_MAXB limbs: limb b is written at dst + slot[b]*N, read (inverse block
 // pass only) at src + src[b]*N, and uses modulus index mod[b].
 struct LimbBatch {
