@@ -307,6 +307,8 @@ def test_error_codes_on_device_context(env):
 def test_batched_calls_equal_single_calls(env):
     """Every batched entry point on [count][2][level][N] gives, ciphertext by ciphertext, the bits of the
     single-ciphertext call (which the other tests compare with the oracle)."""
+    import ctypes
+
     import torch
 
     he, o, p = env.he, env.o, env.params
@@ -335,6 +337,20 @@ def test_batched_calls_equal_single_calls(env):
     same(he.hrot_batch(rkeys[0], a), lambda i: he.hrot(rkeys[0], a[i]))
     mixed = [rkeys[i % 2] for i in range(count)]
     same(he.hrot_batch_keys(mixed, a), lambda i: he.hrot(mixed[i], a[i]))
+    if p.logN == 12:  # more operations than one group of launches holds (32), and a workspace for fewer still
+        many = torch.stack([he.to_device(wl.uniform_ct(1400 + i, p, level)) for i in range(35)])
+        mkeys = [rkeys[(i // 3) % 2] for i in range(35)]
+        got = he.hrot_batch_keys(mkeys, many)
+        for i in range(35):
+            assert torch.equal(got[i], he.hrot(mkeys[i], many[i])), i
+        ws, wsb = he._workspace(level, 3)
+        small = he.workspace_bytes(level, 3)
+        out = he.empty_batch(35, level)
+        keys = (ctypes.c_void_p * 35)(*[k.handle for k in mkeys])
+        rc = he.lib.he_hrot_batch_keys(he.ctx, keys, ctypes.c_void_p(many.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                       level, 35, ws, small, None)
+        assert rc == 0
+        assert torch.equal(out, got)
     rs = he.rotate_sum_batch(rkeys, a.clone())
     same(rs, lambda i: he.rotate_sum(rkeys, a[i].clone()))
     # in place
