@@ -224,36 +224,46 @@ class Bootstrapper:
 
     # ---- building blocks ----------------------------------------------------------------------------------------
 
+    def _giant_steps(self, items, rot):
+        """sum over items (shift, cts, pts) of Rotate(sum_k cts[k] pts[k], shift).  The rotations are independent,
+        so the inner sums with a non-zero shift are written back to back and go through one call with one key
+        each; modular addition makes the order of the outer sum immaterial."""
+        he = self.he
+        acc = None
+        moving = [it for it in items if it[0] % he.n]
+        for shift, cts, pts in items:
+            if shift % he.n == 0:
+                inner = he.pmult_sum(cts, pts)
+                acc = inner if acc is None else he.add(acc, inner, out=acc)
+        if moving:
+            batch = he.empty_batch(len(moving), he._level(moving[0][1][0]))
+            for k, (_, cts, pts) in enumerate(moving):
+                he.pmult_sum(cts, pts, out=batch[k])
+            rotated = he.hrot_batch_keys([rot[shift] for shift, _, _ in moving], batch)
+            for k in range(len(moving)):
+                acc = rotated[k] if acc is None else he.add(acc, rotated[k], out=acc)
+        return acc
+
     def linear_transform(self, ct, pts, rot):
-        """Matrix product on the packed slots (baby steps hoisted), then rescale."""
+        """Matrix product on the packed slots (baby steps hoisted, giant steps in one call), then rescale."""
         he, g1 = self.he, self.g1
         babies = [ct] + (he.hrot_many([rot[a] for a in range(1, g1)], ct) if g1 > 1 else [])
-        acc = None
-        for b in range(self.g2):
-            inner = he.pmult_sum(babies, pts[b])
-            if b:
-                inner = he.hrot(rot[g1 * b], inner)
-            acc = inner if acc is None else he.add(acc, inner, out=acc)
-        return he.rescale(acc)
+        return he.rescale(self._giant_steps([(g1 * b, babies, pts[b]) for b in range(self.g2)], rot))
 
     def sparse_transform(self, ct, lay: DiagonalLayout, pts, rot):
-        """Product with a sparse-diagonal matrix (baby steps hoisted, inner sums in one pass each), then rescale."""
+        """Product with a sparse-diagonal matrix (baby steps hoisted, inner sums in one pass each, giant steps in
+        one call), then rescale."""
         he = self.he
         used = [a for a in range(1, lay.baby) if any((b, a) in pts for b in range(lay.giant))]
         rotated = he.hrot_many([rot[lay.step * a] for a in used], ct) if used else []
         babies = {0: ct}
         babies.update(dict(zip(used, rotated)))
-        acc = None
+        items = []
         for b in range(lay.giant):
             terms = [a for a in range(lay.baby) if (b, a) in pts]
-            if not terms:
-                continue
-            inner = he.pmult_sum([babies[a] for a in terms], [pts[(b, a)] for a in terms])
-            shift = lay.giant_shift(b)
-            if shift % he.n:
-                inner = he.hrot(rot[shift], inner)
-            acc = inner if acc is None else he.add(acc, inner, out=acc)
-        return he.rescale(acc)
+            if terms:
+                items.append((lay.giant_shift(b), [babies[a] for a in terms], [pts[(b, a)] for a in terms]))
+        return he.rescale(self._giant_steps(items, rot))
 
     def _lin(self, y, level: int, s_in: float, c0: float, c1: float, target: float):
         he = self.he
