@@ -266,6 +266,42 @@ def test_conjugation_and_public_key_encryption(env):
     assert err <= tol, (err, tol)
 
 
+@pytest.mark.parametrize("name", ["W12", "W16"])
+def test_conversions_with_more_than_four_sources(pkg, oracle_mod, name):
+    """alpha = 6 and K = 5: ModUp, ModDown and the fused ModDown + rescale in their forms for up to eight source
+    limbs, at a full and at a partial last digit, against the oracle on every residue."""
+    import torch
+
+    p = getattr(wl, name)
+    assert p.alpha == 6 and p.K == 5
+    env = Env(pkg, oracle_mod, p)
+    he, o = env.he, env.o
+    relin, relin_h = env.synth_key(3301, 1)
+    rkey, rkey_h = env.synth_key(3302, o.galois_element(3))
+    for level in (12, 8, 5):
+        a, b = wl.uniform_ct(3310 + level, p, level), wl.uniform_ct(3330 + level, p, level)
+        da, db = he.to_device(a), he.to_device(b)
+        prod = o.hmult_relin(a, b, relin_h)
+        assert np.array_equal(he.to_host(he.hmult_relin(relin, da, db)), prod), level
+        assert np.array_equal(he.to_host(he.hmult_relin_rescale(relin, da, db)), o.rescale(prod)), level
+        assert np.array_equal(he.to_host(he.hrot(rkey, da)), o.hrot(a, rkey_h, 3)), level
+        both = he.hrot_batch_keys([rkey, rkey], torch.stack([da, db]))
+        assert np.array_equal(he.to_host(both[1]), o.hrot(b, rkey_h, 3)), level
+    _sync()
+
+
+def test_unbuilt_conversion_sizes_are_refused(pkg):
+    """Digits of more than four primes at N = 2^17, and of more than eight anywhere, have no kernel: a device
+    context for them is refused instead of running a smaller one."""
+    with pytest.raises(Exception) as ei:
+        pkg.HE.from_params(wl.Params("X17", 17, wl.P17.q[:12], wl.P17.p, 2), device=0)
+    assert "HE_EINVAL" in str(ei.value)
+    with pytest.raises(Exception) as ei:
+        pkg.HE.from_params(wl.Params("X12", 12, wl.N16.q[:18], wl.N16.p, 2), device=0)
+    assert "HE_EINVAL" in str(ei.value)
+    pkg.HE.from_params(wl.Params("X12h", 12, wl.N16.q[:18], wl.N16.p, 2), device=-1)  # the host functions do not care
+
+
 def test_error_codes_on_device_context(env):
     import ctypes
 

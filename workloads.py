@@ -88,6 +88,11 @@ _W45 = tuple(2**45 - d for d in (204799, 385023))
 _W60 = tuple(2**60 - d for d in (16383, 98303))
 I12 = Params("I12", 12, _W55, _W60[:1], 3)
 M12 = Params("M12", 12, (_W55[0], _W45[0], _W55[1], _W45[1]), _W60, 2)
+# Digits of six primes and five special primes (alpha = 6, K = 5): the base conversions then run in their
+# forms for five to eight source limbs.
+_W_P = _N16_P + (2**60 - 14417919,)
+W12 = Params("W12", 12, _N16_Q[:12], _W_P, 2)
+W16 = Params("W16", 16, _N16_Q[:12], _W_P, 2)
 # Four more primes of the same rule: 28 levels, enough for one training iteration (9 levels), the division
 # before bootstrapping (1), a bootstrapping with two-factor matrix products (16) and the level it starts from;
 # dnum = 7 keeps 4 primes per digit.
