@@ -187,6 +187,19 @@ def test_hrot_single_and_hoisted(env):
         for got, want in zip(outs, singles):
             assert np.array_equal(he.to_host(got), want)
         assert np.array_equal(he.to_host(d), ct)  # input untouched
+        if p.logN == 12:  # the same through a workspace for one and for two operations (three rotations)
+            import ctypes
+
+            handles = (ctypes.c_void_p * len(keys))(*[k.handle for k, _ in keys])
+            for fit in (1, 2):
+                outs2 = [he.empty_ct(level) for _ in keys]
+                ptrs = (ctypes.c_void_p * len(keys))(*[t.data_ptr() for t in outs2])
+                ws, _ = he._workspace(level, 2)
+                rc = he.lib.he_hrot_many(he.ctx, handles, len(keys), ctypes.c_void_p(d.data_ptr()), ptrs, level, ws,
+                                         he.workspace_bytes(level, fit), None)
+                assert rc == 0
+                for got, want in zip(outs2, singles):
+                    assert np.array_equal(he.to_host(got), want), (level, fit)
         # one key per ciphertext of a batch: two different inputs, against the oracle
         ct2 = wl.uniform_ct(650 + level, p, level)
         both = he.hrot_batch_keys([k for k, _ in keys[:2]], torch.stack([d, he.to_device(ct2)]))
