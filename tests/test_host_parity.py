@@ -110,3 +110,14 @@ def test_encode_decode_decrypt_against_oracle(lib, oracle_mod):
     assert np.array_equal(he.decrypt_coeffs(sk, ct), want)
     ct = o.encrypt_coeffs(s, o.encode(z, 2.0**30), 3, 33)
     assert np.abs(he.decrypt(sk, ct, 2.0**30) - z).max() < 2.0**-18
+
+
+def test_missing_library_is_an_import_error(monkeypatch, tmp_path):
+    """No fallback: without the built library the binding raises instead of computing anything."""
+    from paper_2210_02574_amd import binding
+
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libhe_missing.so"))
+    with pytest.raises(ImportError) as ei:
+        binding.load_library()
+    assert "no fallback" in str(ei.value)
