@@ -67,3 +67,12 @@ class EncryptedTrainer:
         v_new = self.step.run_batched(keys["relin"], keys["rot"], mask_pt, X, W, Y)
         w_new = [self.refresh(keys, self.momentum(vn, vo), *boot_pts) for vn, vo in zip(v_new, V)]
         return w_new, v_new
+
+    def fit(self, keys, mask_pt, batches, W, V, epochs: int = 1, boot_pts=(None, None)):
+        """Mini-batch stochastic gradient descent (Section 3.1): `epochs` passes over `batches`, a list of (X, Y)
+        as for iterate(), each of the n_samples this trainer was built for; one Bootstrap per iteration and class.
+        Returns the last (W, V)."""
+        for _ in range(epochs):
+            for X, Y in batches:
+                W, V = self.iterate(keys, mask_pt, X, W, V, Y, boot_pts)
+        return W, V

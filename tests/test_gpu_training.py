@@ -84,3 +84,46 @@ def test_training_iterations_match_oracle_and_plaintext(oracle_mod, degree):
         err = np.abs(dec[pr.off:pr.off + pr.dim] - wp).max()
         print("iteration %d: max weight error %.3g (|w| up to %.3g)" % (it + 2, err, np.abs(wp).max()))
         assert err < 2e-4
+
+
+def test_minibatch_epochs_follow_the_plaintext_recipe():
+    """Two mini-batches, two epochs (four iterations with a Bootstrap each) with the driver's own keys and
+    plaintexts: the decrypted weights follow the fp64 run of the same mini-batch schedule."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from oracle import classifier as oc
+    from paper_2210_02574_amd.training import EncryptedTrainer
+    from training_common import Problem
+
+    assert torch.cuda.is_available()
+    p = wl.T12
+    he = pkg.HE.from_params(p, device=0)
+    probs = [Problem(he.n, seed=7), Problem(he.n, seed=8)]
+    S, lr, gamma = 2.0**50, 2.0, 0.1  # the paper's ciphertext hyperparameters for its multi-class set
+    a = oc.logistic_poly_coeffs()
+    tr = EncryptedTrainer(he, probs[0].block, lr, gamma, probs[0].nb, S, coeffs=np.array([a[k] * 8.0**k for k in range(8)]))
+    sk = he.keygen_secret_sparse(1, 64)
+    keys = tr.make_keys(sk, 100)
+    tp = tr.step.plan
+    batches = []
+    for i, pr in enumerate(probs):
+        X = he.to_device(he.encrypt_coeffs(sk, he.encode(pr.slots_x(), S), tr.level, 500 + i)).unsqueeze(0).contiguous()
+        Y = [he.to_device(he.encrypt_coeffs(sk, he.encode(pr.slots_y(), tp.label_scale), tp.label_level, 510 + i))
+             .unsqueeze(0).contiguous()]
+        batches.append((X, Y))
+    w0 = probs[0].w0
+    W = [he.to_device(he.encrypt_coeffs(sk, he.encode(probs[0].slots_w(w0), S), tr.level, 520))]
+    V = [he.moddrop(W[0], tp.out_level)]
+    W, V = tr.fit(keys, tr.step.encode_mask(), batches, W, V, epochs=2)
+    wp, vp = w0, w0
+    for _ in range(2):
+        for pr in probs:
+            wp, vp = pr.plain_iteration(wp, vp, a, lr, gamma)
+    pr = probs[0]
+    dec = he.decrypt(sk, he.to_host(W[0]), S).real
+    err = np.abs(dec[pr.off:pr.off + pr.dim] - wp).max()
+    print("four iterations: max weight error %.3g (|w| up to %.3g)" % (err, np.abs(wp).max()))
+    assert err < 2e-4
+    # every block of the packed weight vector holds the same weights
+    assert np.abs(dec[pr.block + pr.off:pr.block + pr.off + pr.dim] - wp).max() < 2e-4
