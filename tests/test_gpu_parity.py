@@ -350,6 +350,10 @@ def test_error_codes_on_device_context(env):
     rc = he.lib.he_hrot_batch_keys(he.ctx, keys, ctypes.c_void_p(a.data_ptr() + 8), ctypes.c_void_p(he.empty_ct(1).data_ptr()),
                                    1, 1, ws, wsb, None)
     assert rc == -1  # input not 16-byte aligned: refused before any launch
+    too_many = 65536  # count x workspace limbs no longer fits the 16-bit limb slots of a launch
+    rc = he.lib.he_hrot_batch(he.ctx, rkey.handle, ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(he.empty_ct(1).data_ptr()),
+                              1, too_many, ws, ctypes.c_size_t(1 << 62), None)
+    assert rc == -1
     _sync()
 
 
