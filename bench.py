@@ -99,7 +99,8 @@ class Workload:
         self.single_groups = []
         if group_singles:
             for lv in sorted(set(levels), reverse=True):
-                idx = [i for i in range(self.n_single) if levels[i] == lv]
+                # rotations that share a key sit next to each other: the inner product then reads that key once
+                idx = sorted((i for i in range(self.n_single) if levels[i] == lv), key=lambda i: self.single_keys[i])
                 cts = torch.stack([self.single_in[i] for i in idx])
                 outs = he.empty_batch(len(idx), lv)
                 for k, i in enumerate(idx):
