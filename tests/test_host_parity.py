@@ -53,7 +53,7 @@ def test_context_rejects_bad_parameters(lib):
         he.workspace_bytes(4)
 
 
-@pytest.mark.parametrize("params", [wl.C1, wl.C1B])
+@pytest.mark.parametrize("params", [wl.C1, wl.C1B, wl.M12, wl.W12], ids=lambda p: p.name)
 def test_tables_keys_and_encryption_bit_exact(lib, oracle_mod, params):
     he = lib.HE.from_params(params)
     o = oracle_mod.Oracle(params.logN, params.q, params.p, params.dnum)
