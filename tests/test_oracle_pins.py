@@ -261,8 +261,12 @@ def test_automorphism_coeff_and_ntt_index_rule(orc):
 def test_modup_is_fast_basis_conversion(orc):
     """Raised digit = (sum_i y_i * qhat_i) mod t with y_i = [x_i * qhat_i^-1]_{q_i} in [0,q_i):
     equals [x]_D + k*D with 0 <= k < (digit size)."""
-    o = tiny(orc, logN=3, L=5, K=2, dnum=2, qbits=20, pbits=24)  # alpha=3, digits {0,1,2},{3,4}
-    for level in (5, 4, 2):
+    _modup_pin(tiny(orc, logN=3, L=5, K=2, dnum=2, qbits=20, pbits=24), (5, 4, 2))  # alpha=3, digits {0,1,2},{3,4}
+    _modup_pin(tiny(orc, logN=3, L=11, K=5, dnum=2, qbits=20, pbits=28), (11, 8, 5))  # alpha=6, five special primes
+
+
+def _modup_pin(o, levels):
+    for level in levels:
         x = wl.uniform_limbs(level, wl.Params("t", 3, tuple(o.q), tuple(o.p), 2), list(range(level)))
         out = o.modup(x)
         beta = -(-level // o.alpha)
@@ -368,9 +372,21 @@ def test_encrypt_structure_and_decrypt(orc):
 def test_keyswitch_identity_bigint(orc, level):
     """k0 + k1*s - d*s' is small modulo Q_l: bounded by the key noise term plus the ModDown terms."""
     o = tiny(orc, logN=4, L=4, K=2, dnum=2, qbits=20, pbits=24)  # alpha=2, P ~ 2^48 > digit ~ 2^40
+    _keyswitch_identity(o, level)
+
+
+@pytest.mark.parametrize("level", [11, 8, 5])
+def test_keyswitch_identity_bigint_wide_digits(orc, level):
+    """The same identity with digits of six primes and five special primes (full, partial and single digit)."""
+    o = tiny(orc, logN=4, L=11, K=5, dnum=2, qbits=20, pbits=28)  # alpha=6, P ~ 2^140 > digit ~ 2^120
+    assert o.alpha == 6
+    _keyswitch_identity(o, level)
+
+
+def _keyswitch_identity(o, level):
     s = o.keygen_secret(5)
     evk = o.keygen_relin(s, 6)
-    prm = wl.Params("t", 4, tuple(o.q), tuple(o.p), 2)
+    prm = wl.Params("t", 4, tuple(o.q), tuple(o.p), o.dnum)
     d_coeff = wl.uniform_limbs(9, prm, list(range(level)))
     # make d a consistent RNS image of one integer polynomial
     Q = prod(o.q[:level])
