@@ -296,8 +296,11 @@ def _modup_pin(o, levels):
 def test_moddown_is_exact_division_by_centred_remainder(orc):
     """ModDown(u) = (u - r)/P (mod q_i) with r = sum_k y_k (P/p_k), y_k the centred conversion digits:
     r = [u]_P mod P, |r| < K P / 2, and r/P averages to zero; u is the CRT lift in [0, P*Q_l)."""
-    o = tiny(orc, logN=6, L=3, K=3, dnum=3, qbits=20, pbits=24)
-    level = 3
+    _moddown_pin(tiny(orc, logN=6, L=3, K=3, dnum=3, qbits=20, pbits=24), 3)
+    _moddown_pin(tiny(orc, logN=6, L=4, K=5, dnum=2, qbits=20, pbits=24), 3)  # five special primes, partial last digit
+
+
+def _moddown_pin(o, level):
     act = o.active_moduli(level)
     mods = [o.moduli[mi] for mi in act]
     P = prod(o.p)
