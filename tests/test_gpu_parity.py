@@ -207,6 +207,40 @@ def test_hrot_single_and_hoisted(env):
         assert np.array_equal(he.to_host(both[1]), o.hrot(ct2, keys[1][1], rots[1])), level
 
 
+def test_patterned_inputs_through_the_key_switch(env):
+    """Residues at the ends of their ranges (all q-1, all (q-1)/2, alternating 0 / q-1, within 1000 of q) through
+    Mult, the fused Mult + rescale and Rotate: the lazy ranges of both arithmetic paths at their widest."""
+    he, o, p = env.he, env.o, env.params
+    relin, relin_h = env.synth_key(301, 1)
+    rkey, rkey_h = env.synth_key(500 + 1, o.galois_element(1))
+    g = wl.rng(4242)
+
+    def patterned(kind, level):
+        ct = np.empty((2, level, p.N), dtype=np.uint64)
+        for i in range(level):
+            q = p.q[i]
+            if kind == 0:
+                ct[:, i] = q - 1
+            elif kind == 1:
+                ct[:, i] = (q - 1) // 2
+            elif kind == 2:
+                ct[:, i, ::2], ct[:, i, 1::2] = 0, q - 1
+            else:
+                ct[:, i] = g.integers(q - 1000, q, size=(2, p.N), dtype=np.uint64)
+        return ct
+
+    levels = _levels(p)
+    cases = [(0, 0, levels[0]), (2, 3, levels[0]), (1, 2, levels[1]), (3, 0, levels[-2])]
+    for ka, kb, level in (cases if p.logN == 12 else cases[:2]):
+        a, b = patterned(ka, level), patterned(kb, level)
+        da, db = he.to_device(a), he.to_device(b)
+        want = o.hmult_relin(a, b, relin_h)
+        assert np.array_equal(he.to_host(he.hmult_relin(relin, da, db)), want), (ka, kb, level)
+        if level >= 2:
+            assert np.array_equal(he.to_host(he.hmult_relin_rescale(relin, da, db)), o.rescale(want)), (ka, kb, level)
+        assert np.array_equal(he.to_host(he.hrot(rkey, da)), o.hrot(a, rkey_h, 1)), (ka, level)
+
+
 def test_rotate_sum(env):
     he, o, p = env.he, env.o, env.params
     level = 2 if p.logN == 12 else 6
