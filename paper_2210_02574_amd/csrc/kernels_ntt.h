@@ -160,8 +160,10 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
     return S;
 }
 
-// SPLIT: the sources may be 2^50 or larger, so an FP64 target splits each at bit 31
-template <int PRO, bool SPLIT, int NSMAX>
+// SPLIT: the sources may be 2^50 or larger, so an FP64 target splits each at bit 31.  TINT (ModDown + rescale):
+// the dropped limb is 2^50 or larger and is reduced with integers first; a template parameter rather than a
+// run-time branch, because the integer code would cost every launch 100 registers.
+template <int PRO, bool SPLIT, bool TINT, int NSMAX>
 __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const ArithFp &ar, const ModConst &m, unsigned pos)
 {
     if (PRO == PRO_RESCALE) {
@@ -192,7 +194,7 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
     if (PRO == PRO_MODDOWN_RS) { // + P t with t the centred dropped limb
         const u64 tv = S.tp[pos];
         double tc;
-        if (S.qld != 0.0)
+        if (!TINT)
             tc = u2d(tv) - (tv > S.half ? S.qld : 0.0);
         else {
             const bool tneg = tv > S.half;
@@ -204,7 +206,7 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
     return acc;
 }
 
-template <int PRO, bool SPLIT, int NSMAX>
+template <int PRO, bool SPLIT, bool TINT, int NSMAX>
 __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithInt &, const ModConst &m, unsigned pos)
 {
     if (PRO == PRO_RESCALE) {
@@ -410,7 +412,7 @@ template <int LOGN> struct ColsGeom {
 };
 
 // the 16 inputs of one thread in rows rl + 16 k + 256 h (plain load or base conversion)
-template <int PRO, bool SPLIT, int NSMAX, class A>
+template <int PRO, bool SPLIT, bool TINT, int NSMAX, class A>
 __device__ __forceinline__ void cols_inputs(typename A::V (&a)[16], const u64 *__restrict__ limb, unsigned col0, int h,
                                             const A &ar, const ConvSetup<NSMAX> &S, const ModConst &m)
 {
@@ -418,7 +420,7 @@ __device__ __forceinline__ void cols_inputs(typename A::V (&a)[16], const u64 *_
 #pragma unroll
     for (int k = 0; k < 16; k++) {
         const unsigned pos = (rl + 16 * k + 256 * h) * 256 + col0 + c;
-        a[k] = PRO == PRO_LOAD ? ar.load(limb[pos]) : conv_get<PRO, SPLIT>(S, ar, m, pos);
+        a[k] = PRO == PRO_LOAD ? ar.load(limb[pos]) : conv_get<PRO, SPLIT, TINT>(S, ar, m, pos);
     }
 }
 // second phase of the forward column pass for rows 16 g .. 16 g + 15
@@ -434,14 +436,14 @@ __device__ __forceinline__ void cols_finish_group(typename A::V (&a)[16], u64 *_
     for (int k = 0; k < 16; k++) limb[(16 * g + k) * 256 + col0 + c] = ar.store_mid(a[k]); // the block pass finishes
 }
 
-template <int LOGN, int PRO, bool SPLIT, int NSMAX, class A>
+template <int LOGN, int PRO, bool SPLIT, bool TINT, int NSMAX, class A>
 __device__ __forceinline__ void fwd_cols_body(u64 *__restrict__ limb, unsigned col0, const A &ar, u64 *lds,
                                               const ConvSetup<NSMAX> &S, const ModConst &m)
 {
     constexpr int H = ColsGeom<LOGN>::HALVES;
     const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
     typename A::V a0[16];
-    cols_inputs<PRO, SPLIT>(a0, limb, col0, 0, ar, S, m);
+    cols_inputs<PRO, SPLIT, TINT>(a0, limb, col0, 0, ar, S, m);
     if (H == 1) {
         ar.fwd16(a0, 0, 0, PRO != PRO_LOAD);
 #pragma unroll
@@ -452,7 +454,7 @@ __device__ __forceinline__ void fwd_cols_body(u64 *__restrict__ limb, unsigned c
         typename A::V a1[16];
         // one half's source loads at a time: 32 outputs x up to 8 sources in flight would not fit the registers
         if (PRO != PRO_LOAD) __builtin_amdgcn_sched_barrier(0);
-        cols_inputs<PRO, SPLIT>(a1, limb, col0, 1, ar, S, m);
+        cols_inputs<PRO, SPLIT, TINT>(a1, limb, col0, 1, ar, S, m);
         ar.fwd_stage0(a0, a1, PRO != PRO_LOAD);
         ar.fwd16(a0, 1, 0, true);
         ar.fwd16(a1, 1, 1, true);
@@ -510,12 +512,18 @@ __device__ __forceinline__ void fwd_cols_kernel(u64 *__restrict__ data, const De
     const ModConst m = T.mod[mi];
     const ConvSetup<NSMAX> S = conv_setup<PRO, NSMAX, LOGN>(cv, T, slot, mi);
     const bool split = PRO == PRO_MODUP ? T.up_split != 0 : pro_is_moddown(PRO) ? T.dn_split != 0 : false;
+    const bool tint = PRO == PRO_MODDOWN_RS && S.qld == 0.0; // dropped limb on the integer path
     if (m.qd == 0.0)
-        fwd_cols_body<LOGN, PRO, false>(limb, tile * 16, make_int(T, mi, LOGN), lds, S, m);
-    else if (split)
-        fwd_cols_body<LOGN, PRO, true>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+        fwd_cols_body<LOGN, PRO, false, false>(limb, tile * 16, make_int(T, mi, LOGN), lds, S, m);
+    else if (PRO == PRO_MODDOWN_RS && tint) {
+        if (split)
+            fwd_cols_body<LOGN, PRO, true, PRO == PRO_MODDOWN_RS>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+        else
+            fwd_cols_body<LOGN, PRO, false, PRO == PRO_MODDOWN_RS>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+    } else if (split)
+        fwd_cols_body<LOGN, PRO, true, false>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
     else
-        fwd_cols_body<LOGN, PRO, false>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+        fwd_cols_body<LOGN, PRO, false, false>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
 }
 // grid.x = 16 * batch
 template <int PRO, int NSMAX>
@@ -576,14 +584,14 @@ __global__ __launch_bounds__(256) void k_ntt_inv_cols17(u64 *__restrict__ data, 
 
 // ---- column pass, N = 2^12: 16 rows x 256 columns, one thread per column --------------------------------------
 
-template <int PRO, bool SPLIT, int NSMAX, class A>
+template <int PRO, bool SPLIT, bool TINT, int NSMAX, class A>
 __device__ __forceinline__ void fwd_cols12_body(u64 *__restrict__ limb, const A &ar, const ConvSetup<NSMAX> &S,
                                                 const ModConst &m)
 {
     const unsigned c = threadIdx.x;
     typename A::V a[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = PRO == PRO_LOAD ? ar.load(limb[k * 256 + c]) : conv_get<PRO, SPLIT>(S, ar, m, k * 256 + c);
+    for (int k = 0; k < 16; k++) a[k] = PRO == PRO_LOAD ? ar.load(limb[k * 256 + c]) : conv_get<PRO, SPLIT, TINT>(S, ar, m, k * 256 + c);
     ar.fwd16(a, 0, 0, PRO != PRO_LOAD);
 #pragma unroll
     for (int k = 0; k < 16; k++) limb[k * 256 + c] = ar.store_mid(a[k]);
@@ -607,12 +615,18 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols12(u64 *__restrict__ data, 
     const ModConst m = T.mod[mi];
     const ConvSetup<NSMAX> S = conv_setup<PRO, NSMAX, 12>(cv, T, slot, mi);
     const bool split = PRO == PRO_MODUP ? T.up_split != 0 : pro_is_moddown(PRO) ? T.dn_split != 0 : false;
+    const bool tint = PRO == PRO_MODDOWN_RS && S.qld == 0.0; // dropped limb on the integer path
     if (m.qd == 0.0)
-        fwd_cols12_body<PRO, false>(limb, make_int(T, mi, 12), S, m);
-    else if (split)
-        fwd_cols12_body<PRO, true>(limb, make_fp(T, mi, 12), S, m);
+        fwd_cols12_body<PRO, false, false>(limb, make_int(T, mi, 12), S, m);
+    else if (PRO == PRO_MODDOWN_RS && tint) {
+        if (split)
+            fwd_cols12_body<PRO, true, PRO == PRO_MODDOWN_RS>(limb, make_fp(T, mi, 12), S, m);
+        else
+            fwd_cols12_body<PRO, false, PRO == PRO_MODDOWN_RS>(limb, make_fp(T, mi, 12), S, m);
+    } else if (split)
+        fwd_cols12_body<PRO, true, false>(limb, make_fp(T, mi, 12), S, m);
     else
-        fwd_cols12_body<PRO, false>(limb, make_fp(T, mi, 12), S, m);
+        fwd_cols12_body<PRO, false, false>(limb, make_fp(T, mi, 12), S, m);
 }
 
 template <int SCALE>
