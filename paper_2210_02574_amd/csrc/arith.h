@@ -86,6 +86,7 @@ __device__ __forceinline__ u64 fp_canon(double v, double q, double qinv)
 
 struct ArithFp {
     typedef double V;
+    static constexpr bool IS_FP = true;
     double q, qinv, n0, n1;
     const double *twf, *twi;
     __device__ __forceinline__ V reduce(V v) const { return fp_reduce(v, q, qinv); }
@@ -182,6 +183,7 @@ struct ArithFp {
 // ArithInt ranges: [0, 4q) between forward stages, [0, 2q) between inverse stages.
 struct ArithInt {
     typedef u64 V;
+    static constexpr bool IS_FP = false;
     u64 q, q2;
     ShoupConst n0, n1, post; // post: optional extra constant applied by store_final (post.w == 0: none)
     const ShoupConst *twf, *twi;

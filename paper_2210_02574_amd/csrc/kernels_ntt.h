@@ -270,7 +270,8 @@ __device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, const HoistOu
     return o;
 }
 
-template <int LOGN>
+// FP: the limb's modulus is on the floating-point path (known from the transform's arithmetic at compile time)
+template <int LOGN, bool FP>
 __device__ __forceinline__ void fin_store(const FinArgs &fa, const HoistOuts &ho, const DevTables &T, unsigned slot,
                                           unsigned pos, u64 rv, const FinOperands &fo)
 {
@@ -281,7 +282,7 @@ __device__ __forceinline__ void fin_store(const FinArgs &fa, const HoistOuts &ho
     const size_t o = (((size_t)op * fa.out_stride + (size_t)c * fa.out_cstride + i) << LOGN) + pos;
     const bool scaled = fa.mode == 3 && fa.cst2 != nullptr;
     u64 res;
-    if (m.qd != 0.0) {
+    if (FP) {
         const double av = scaled ? fp_mulmod(u2d(fo.av), fa.cst2_d[i], m.qd, m.qinvd) : u2d(fo.av);
         res = fp_canon(fp_mulmod(u2d(fo.uv) - u2d(rv), fa.cst_d[i], m.qd, m.qinvd) + av, m.qd, m.qinvd);
     } else {
@@ -337,7 +338,7 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
         const unsigned pos = bg * 256 + il + 16 * k;
         const u64 v = lds[tile_at(blk, il + 16 * k)];
         if (EPI == EPI_FIN)
-            fin_store<LOGN>(fa, ho, T, slot, pos, v, fo[k]);
+            fin_store<LOGN, A::IS_FP>(fa, ho, T, slot, pos, v, fo[k]);
         else
             limb[pos] = v;
     }
