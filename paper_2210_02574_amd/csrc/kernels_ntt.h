@@ -409,7 +409,7 @@ __global__ __launch_bounds__(BLK_THREADS) void k_ntt_inv_blocks(const u64 *src, 
 template <int LOGN> struct ColsGeom {
     static constexpr int ROWS = 1 << (LOGN - 8);
     static constexpr int HALVES = ROWS / 256;          // 16-element register steps per thread and phase
-    static constexpr int LDS_WORDS = (ROWS / 16) * COL_GROUP;
+    static constexpr int LDS_WORDS = 16 * COL_GROUP;   // one half of the rows at a time: 32 KiB at either size
 };
 
 // the 16 inputs of one thread in rows rl + 16 k + 256 h (plain load or base conversion)
@@ -424,14 +424,14 @@ __device__ __forceinline__ void cols_inputs(typename A::V (&a)[16], const u64 *_
         a[k] = PRO == PRO_LOAD ? ar.load(limb[pos]) : conv_get<PRO, SPLIT, TINT>(S, ar, m, pos);
     }
 }
-// second phase of the forward column pass for rows 16 g .. 16 g + 15
+// second phase of the forward column pass for rows 16 g .. 16 g + 15, held in LDS as group gl
 template <int S_BASE, class A>
 __device__ __forceinline__ void cols_finish_group(typename A::V (&a)[16], u64 *__restrict__ limb, unsigned col0, unsigned g,
-                                                  const A &ar, const u64 *lds)
+                                                  unsigned gl, const A &ar, const u64 *lds)
 {
     const unsigned c = threadIdx.x & 15;
 #pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(16 * g + k, c)]);
+    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(16 * gl + k, c)]);
     ar.fwd16(a, S_BASE, g, true);
 #pragma unroll
     for (int k = 0; k < 16; k++) limb[(16 * g + k) * 256 + col0 + c] = ar.store_mid(a[k]); // the block pass finishes
@@ -450,7 +450,7 @@ __device__ __forceinline__ void fwd_cols_body(u64 *__restrict__ limb, unsigned c
 #pragma unroll
         for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a0[k]);
         __syncthreads();
-        cols_finish_group<4>(a0, limb, col0, rl, ar, lds);
+        cols_finish_group<4>(a0, limb, col0, rl, rl, ar, lds);
     } else {
         typename A::V a1[16];
         // one half's source loads at a time: 32 outputs x up to 8 sources in flight would not fit the registers
@@ -459,14 +459,16 @@ __device__ __forceinline__ void fwd_cols_body(u64 *__restrict__ limb, unsigned c
         ar.fwd_stage0(a0, a1, PRO != PRO_LOAD);
         ar.fwd16(a0, 1, 0, true);
         ar.fwd16(a1, 1, 1, true);
+        // after stage 0 the two halves of the rows are independent: they go through the same 32 KiB of LDS in turn
 #pragma unroll
-        for (int k = 0; k < 16; k++) {
-            lds[col_at(rl + 16 * k, c)] = ar.store_mid(a0[k]);
-            lds[col_at(rl + 16 * k + 256, c)] = ar.store_mid(a1[k]);
-        }
+        for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a0[k]);
         __syncthreads();
-        cols_finish_group<5>(a0, limb, col0, rl, ar, lds);
-        cols_finish_group<5>(a1, limb, col0, rl + 16, ar, lds);
+        cols_finish_group<5>(a0, limb, col0, rl, rl, ar, lds);
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a1[k]);
+        __syncthreads();
+        cols_finish_group<5>(a1, limb, col0, rl + 16, rl, ar, lds);
     }
 }
 
@@ -476,20 +478,20 @@ __device__ __forceinline__ void inv_cols_body(u64 *__restrict__ limb, unsigned c
     constexpr int H = ColsGeom<LOGN>::HALVES;
     const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
     typename A::V a[H][16];
+    // each half of the rows: stages logN-9 .. logN-12 on 16 consecutive rows, exchange through the same 32 KiB of
+    // LDS, then stages 3 .. 0 (N = 2^16) or 4 .. 1 (N = 2^17: stage 0 pairs the halves afterwards)
 #pragma unroll
     for (int h = 0; h < H; h++) {
         const unsigned g = rl + 16 * h;
 #pragma unroll
         for (int k = 0; k < 16; k++) a[h][k] = ar.load_mid(limb[(16 * g + k) * 256 + col0 + c]);
         ar.template inv16<false>(a[h], H + 3, g);
+        if (h > 0) __syncthreads(); // the previous half has been read back by every thread
 #pragma unroll
-        for (int k = 0; k < 16; k++) lds[col_at(16 * g + k, c)] = ar.store_mid(a[h][k]);
-    }
-    __syncthreads();
+        for (int k = 0; k < 16; k++) lds[col_at(16 * rl + k, c)] = ar.store_mid(a[h][k]);
+        __syncthreads();
 #pragma unroll
-    for (int h = 0; h < H; h++) {
-#pragma unroll
-        for (int k = 0; k < 16; k++) a[h][k] = ar.load_mid(lds[col_at(rl + 16 * k + 256 * h, c)]);
+        for (int k = 0; k < 16; k++) a[h][k] = ar.load_mid(lds[col_at(rl + 16 * k, c)]);
         if (H == 1)
             ar.template inv16<true>(a[h], 0, 0);
         else
@@ -578,7 +580,7 @@ __global__ __launch_bounds__(256) void k_ntt_inv_cols16(u64 *__restrict__ data, 
     inv_cols_kernel<16, SCALE>(data, T, lb, cv);
 }
 template <int SCALE>
-__global__ __launch_bounds__(256) void k_ntt_inv_cols17(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
+__global__ __launch_bounds__(256, 3) void k_ntt_inv_cols17(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
 {
     inv_cols_kernel<17, SCALE>(data, T, lb, cv);
 }
