@@ -157,7 +157,7 @@ __device__ __forceinline__ void inv_blocks_from_pairs(const u64 (&r)[16], u64 *l
     ar.template inv16<false>(a, LOGN - 4, bg * 16 + il);
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_mid(a[k]);
-    __syncthreads();
+    block_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, il + 16 * k)]);
     ar.template inv16<false>(a, LOGN - 8, bg);
@@ -261,7 +261,7 @@ template <int LOGN> __global__ __launch_bounds__(256) void k_inner_blocks(InnerA
                 ar.fwd16_with(dv, true, [&](int c) { return tw_blk[c]; });
 #pragma unroll
                 for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = ar.store_mid(dv[k]);
-                __syncthreads();
+                block_sync();
 #pragma unroll
                 for (int k = 0; k < 16; k++) dv[k] = ar.load_mid(lds[tile_at(blk, 16 * il + k)]);
                 ar.fwd16_with(dv, true, [&](int c) { return tw_thr[c]; });

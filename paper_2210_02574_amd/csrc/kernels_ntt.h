@@ -301,6 +301,16 @@ __device__ __forceinline__ void fin_store(const FinArgs &fa, const HoistOuts &ho
 #endif
 #define BLK_PER_WG (BLK_THREADS / 16)
 __device__ __forceinline__ unsigned tile_at(unsigned grp, unsigned i) { return grp * TILE_GROUP + i + (i >> 4); }
+// Exchange through LDS among the 16 lanes that own one 256-element block.  They belong to one wave, and a wave's
+// LDS operations execute in order, so no work-group barrier is needed: only the compiler has to be kept from
+// moving LDS accesses across this point.
+__device__ __forceinline__ void block_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+static_assert(BLK_THREADS % 64 == 0, "a block's 16 lanes must not straddle two waves");
 // column pass: row r of column c (0..15).  The 16 lanes of a column group always touch 16 consecutive words,
 // so this tile needs no padding: 32 KiB at N = 2^16, five work-groups per compute unit.
 #define COL_GROUP 256
@@ -325,14 +335,14 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
     ar.fwd16(a, LOGN - 8, bg, true);
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = ar.store_mid(a[k]);
-    __syncthreads();
+    block_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, 16 * il + k)]);
     ar.fwd16(a, LOGN - 4, bg * 16 + il, true);
-    __syncthreads();
+    block_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_final(a[k]);
-    __syncthreads();
+    block_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) {
         const unsigned pos = bg * 256 + il + 16 * k;
@@ -353,14 +363,14 @@ __device__ __forceinline__ void inv_blocks_body(const u64 *in, u64 *limb, const 
     typename A::V a[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = in[bg * 256 + il + 16 * k];
-    __syncthreads();
+    block_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) a[k] = ar.load(lds[tile_at(blk, 16 * il + k)]);
     ar.template inv16<false>(a, LOGN - 4, bg * 16 + il);
-    __syncthreads();
+    block_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_mid(a[k]);
-    __syncthreads();
+    block_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, il + 16 * k)]);
     ar.template inv16<false>(a, LOGN - 8, bg);
