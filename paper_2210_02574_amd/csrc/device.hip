@@ -309,6 +309,8 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
     }
         if (c->logN == 17) {
             COLS4(k_ntt_fwd_cols17, 16 * nb)
+        } else if (c->logN == 16 && pro == PRO_MODUP && !wide) {
+            KLAUNCH(c, st, kid_cols, cols_bytes, (k_ntt_fwd_cols16_modup2<4>), 16 * ((nb + 1) / 2), data, c->dev, lb, cv, nb);
         } else if (c->logN == 16) {
             COLS(k_ntt_fwd_cols16, 16 * nb)
         } else {

@@ -514,12 +514,11 @@ __device__ __forceinline__ void inv_cols_body(u64 *__restrict__ limb, unsigned c
         for (int k = 0; k < 16; k++) limb[(rl + 16 * k + 256 * h) * 256 + col0 + c] = ar.store_final(a[h][k]);
 }
 
+// column pass of limb b of the launch (the arithmetic path and the prologue's variant follow from its modulus)
 template <int LOGN, int PRO, int NSMAX>
-__device__ __forceinline__ void fwd_cols_kernel(u64 *__restrict__ data, const DevTables &T, const LimbBatch &lb,
-                                                const ConvArgs &cv)
+__device__ __forceinline__ void fwd_cols_limb(u64 *__restrict__ data, const DevTables &T, const LimbBatch &lb,
+                                              const ConvArgs &cv, unsigned tile, unsigned b, u64 *lds)
 {
-    __shared__ u64 lds[ColsGeom<LOGN>::LDS_WORDS];
-    const unsigned tile = blockIdx.x & 15, b = blockIdx.x >> 4;
     const unsigned mi = lb.mod[b], slot = lb.slot[b];
     u64 *limb = data + ((size_t)slot << LOGN);
     const ModConst m = T.mod[mi];
@@ -537,6 +536,70 @@ __device__ __forceinline__ void fwd_cols_kernel(u64 *__restrict__ data, const De
         fwd_cols_body<LOGN, PRO, true, false>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
     else
         fwd_cols_body<LOGN, PRO, false, false>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+}
+template <int LOGN, int PRO, int NSMAX>
+__device__ __forceinline__ void fwd_cols_kernel(u64 *__restrict__ data, const DevTables &T, const LimbBatch &lb,
+                                                const ConvArgs &cv)
+{
+    __shared__ u64 lds[ColsGeom<LOGN>::LDS_WORDS];
+    fwd_cols_limb<LOGN, PRO, NSMAX>(data, T, lb, cv, blockIdx.x & 15, blockIdx.x >> 4, lds);
+}
+
+// ModUp column pass for two limbs per work-group (N = 2^16; grid.x = 16 * ceil(batch / 2)): limbs 2i and 2i+1 of
+// the launch.  When both are floating-point targets of the same digit of the same operation (the usual case:
+// the targets of a digit follow each other in a launch), the digit's source limbs are read and converted to
+// doubles once and both base conversions are formed from them, term by term as in conv_get; every target
+// otherwise re-reads the same source tile through L2.  Any other pair is processed one limb after the other.
+template <int NSMAX>
+__global__ __launch_bounds__(256) void k_ntt_fwd_cols16_modup2(u64 *__restrict__ data, DevTables T, LimbBatch lb,
+                                                                ConvArgs cv, int nb)
+{
+    __shared__ u64 lds[ColsGeom<16>::LDS_WORDS];
+    const unsigned tile = blockIdx.x & 15, b0 = (blockIdx.x >> 4) * 2, b1 = b0 + 1;
+    if (b1 >= (unsigned)nb) {
+        fwd_cols_limb<16, PRO_MODUP, NSMAX>(data, T, lb, cv, tile, b0, lds);
+        return;
+    }
+    const unsigned mi0 = lb.mod[b0], mi1 = lb.mod[b1], slot0 = lb.slot[b0], slot1 = lb.slot[b1];
+    const ConvSetup<NSMAX> S0 = conv_setup<PRO_MODUP, NSMAX, 16>(cv, T, slot0, mi0);
+    const ConvSetup<NSMAX> S1 = conv_setup<PRO_MODUP, NSMAX, 16>(cv, T, slot1, mi1);
+    bool same = T.up_split == 0 && T.mod[mi0].qd != 0.0 && T.mod[mi1].qd != 0.0;
+#pragma unroll
+    for (int s = 0; s < NSMAX; s++) same = same && S0.sp[s] == S1.sp[s];
+    if (!same) {
+        fwd_cols_limb<16, PRO_MODUP, NSMAX>(data, T, lb, cv, tile, b0, lds);
+        __syncthreads(); // the first limb's second phase has read the tile
+        fwd_cols_limb<16, PRO_MODUP, NSMAX>(data, T, lb, cv, tile, b1, lds);
+        return;
+    }
+    const ArithFp ar0 = make_fp(T, mi0, 16), ar1 = make_fp(T, mi1, 16);
+    const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15, col0 = tile * 16;
+    double a0[16], a1[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+        const unsigned pos = (rl + 16 * k) * 256 + col0 + c;
+        double acc0 = 0.0, acc1 = 0.0;
+#pragma unroll
+        for (int s = 0; s < NSMAX; s++) {
+            const double y = u2d(S0.sp[s][pos]);
+            acc0 += ar0.mulmod(y, S0.cd[s]);
+            acc1 += ar1.mulmod(y, S1.cd[s]);
+            if ((s & 3) == 3 && s + 1 < NSMAX) acc0 = ar0.reduce(acc0), acc1 = ar1.reduce(acc1);
+        }
+        a0[k] = acc0, a1[k] = acc1;
+    }
+    u64 *limb0 = data + ((size_t)slot0 << 16), *limb1 = data + ((size_t)slot1 << 16);
+    ar0.fwd16(a0, 0, 0, true);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar0.store_mid(a0[k]);
+    __syncthreads();
+    cols_finish_group<4>(a0, limb0, col0, rl, rl, ar0, lds);
+    __syncthreads();
+    ar1.fwd16(a1, 0, 0, true);
+#pragma unroll
+    for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar1.store_mid(a1[k]);
+    __syncthreads();
+    cols_finish_group<4>(a1, limb1, col0, rl, rl, ar1, lds);
 }
 // grid.x = 16 * batch
 template <int PRO, int NSMAX>
