@@ -37,16 +37,16 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # `--pmc WRITE_SIZE` runs of this command with --streams 1, scaled by the copy-kernel calibration
 # (2 x FETCH_SIZE + 1 x WRITE_SIZE; summary and calibration under profiles/).
 MEASURED_TRAFFIC_BYTES = {
-    "k_inner_blocks": 1226873856,
-    "k_ntt_fwd_blocks_fin": 510790041,
-    "k_ntt_fwd_blocks": 163063705,
-    "k_ntt_inv_blocks": 143558758,
-    "k_tensor": 704721305,
-    "k_ntt_fwd_cols_modup": 265819955,
-    "k_ntt_fwd_cols_moddown": 128281292,
-    "k_ntt_fwd_cols_moddown_rescale": 235790950,
-    "k_ntt_fwd_cols": 269831987,
-    "k_ntt_inv_cols": 97382025,
+    "k_inner_blocks": 1226694451,
+    "k_ntt_fwd_blocks_fin": 510617190,
+    "k_ntt_fwd_blocks": 163075379,
+    "k_ntt_inv_blocks": 143577804,
+    "k_tensor": 704706764,
+    "k_ntt_fwd_cols_modup": 303587532,
+    "k_ntt_fwd_cols_moddown": 128296857,
+    "k_ntt_fwd_cols_moddown_rescale": 235787673,
+    "k_ntt_fwd_cols": 269812531,
+    "k_ntt_inv_cols": 97379745,
 }
 
 
