@@ -1,6 +1,6 @@
 // Device-side entry points of the RNS-CKKS library: table upload, kernel launch sequences of
 // NTT, Mult (tensor product + relinearisation), Rotate (hybrid key switching), rescale and
-// rotate-and-sum.  The kernels are in kernels_ntt.h and kernels_ks.h.
+// rotate-and-sum.  The kernels are in kernels_ntt.h, kernels_ks.h and kernels_elem.h.
 //
 // Key switch of a polynomial d (NTT domain, `level` limbs) with key evk, Galois element g:
 //   1. inverse NTT of d, its column pass also multiplying limb i by (D/q_i)^-1      -> y  (ws.x)
@@ -20,7 +20,8 @@
 #include <functional>
 #include <vector>
 
-#include "kernels_ks.h"
+#include "kernels_elem.h"
+#include "launch.h"
 
 #define HIP_TRY(ctx, expr)                                                                                           \
     do {                                                                                                             \
@@ -97,17 +98,12 @@ extern "C" int32_t he_evk_to_host(const he_evk *evk, uint64_t *h_out)
 }
 
 // ---- optional per-kernel timing with HIP events on the launch stream (he_profile_start/stop)
-enum KernelId {
-    KID_FWD_COLS, KID_FWD_COLS_MODUP, KID_FWD_COLS_MODDOWN, KID_FWD_COLS_RESCALE, KID_FWD_COLS_MODDOWN_RS, KID_FWD_BLOCKS,
-    KID_FWD_BLOCKS_FIN,
-    KID_INV_BLOCKS, KID_INV_COLS, KID_LIMBWISE, KID_CMULT, KID_TENSOR, KID_INNER, KID_COUNT
-};
 static const char *const kKernelNames[KID_COUNT] = {
     "k_ntt_fwd_cols", "k_ntt_fwd_cols_modup", "k_ntt_fwd_cols_moddown", "k_ntt_fwd_cols_rescale", "k_ntt_fwd_cols_moddown_rescale",
     "k_ntt_fwd_blocks",
     "k_ntt_fwd_blocks_fin", "k_ntt_inv_blocks", "k_ntt_inv_cols", "k_limbwise", "k_cmult", "k_tensor", "k_inner_blocks"};
 
-static bool prof_events(he_ctx *c, int kid, double bytes, ProfRecord &r)
+bool prof_events(he_ctx *c, int kid, double bytes, ProfRecord &r)
 {
     r.kid = kid;
     r.bytes = bytes;
@@ -120,21 +116,27 @@ static bool prof_events(he_ctx *c, int kid, double bytes, ProfRecord &r)
     c->prof.push_back(r);
     return true;
 }
-// Launch wrapper (256 threads per group): `bytes` = bytes the launch has to move by the definition of
-// its step.  While profiling, the launch carries a start and a stop event that take the kernel's own
-// begin and end timestamps.
-#define KLAUNCH_T(c, st, kid, bytes, kernel, grid, threads, ...)                                                    \
-    do {                                                                                                             \
-        ProfRecord pr_;                                                                                              \
-        if ((c)->prof_on && prof_events((c), (kid), (double)(bytes), pr_))                                           \
-            hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, (st), (hipEvent_t)pr_.a, (hipEvent_t)pr_.b,   \
-                                  0, __VA_ARGS__);                                                                   \
-        else                                                                                                         \
-            hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, (st), __VA_ARGS__);                             \
-    } while (0)
-#define KLAUNCH(c, st, kid, bytes, kernel, grid, ...) KLAUNCH_T(c, st, kid, bytes, kernel, grid, 256, __VA_ARGS__)
-// work-groups per limb of the block pass
-#define BLK_TILES(c) ((int)((c)->N / (256 * BLK_PER_WG)))
+
+// launchers of the context's ring size (dev_upload_tables has checked that it is one of the three)
+static const DevLaunch &dev_launch(const he_ctx *c)
+{
+    static const DevLaunch tables[3] = {
+        [] { DevLaunch t{}; dev_launch_n12(t); return t; }(),
+        [] {
+            DevLaunch t{};
+            dev_launch_cols16_0(t), dev_launch_cols16_1(t), dev_launch_cols16_2(t), dev_launch_cols16_3(t);
+            dev_launch_cols16_4(t), dev_launch_cols16_5(t), dev_launch_n16_blocks(t);
+            return t;
+        }(),
+        [] {
+            DevLaunch t{};
+            dev_launch_cols17_0(t), dev_launch_cols17_1(t), dev_launch_cols17_2(t), dev_launch_cols17_3(t);
+            dev_launch_cols17_4(t), dev_launch_cols17_5(t), dev_launch_n17_blocks(t);
+            return t;
+        }(),
+    };
+    return tables[c->logN == 12 ? 0 : c->logN == 16 ? 1 : 2];
+}
 
 extern "C" int32_t he_profile_start(he_ctx *ctx)
 {
@@ -267,6 +269,7 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
     const HoistOuts &ho = hoist ? *hoist : kNoHoistOuts;
     const bool wide = std::max(c->alpha, c->K) > 4;
     const double N8 = (double)c->N * 8.0;
+    const DevLaunch &dl = dev_launch(c);
     return for_batches(c, l, [&](const LimbBatch &lb, int nb) {
         const double cols_bytes = pro == PRO_LOAD ? 2.0 * nb * N8 : (double)(src_limbs + nb) * N8;
         const int kid_cols = pro == PRO_LOAD      ? KID_FWD_COLS
@@ -274,71 +277,17 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
                              : pro == PRO_MODDOWN ? KID_FWD_COLS_MODDOWN
                              : pro == PRO_MODDOWN_RS ? KID_FWD_COLS_MODDOWN_RS
                                                   : KID_FWD_COLS_RESCALE;
-#define COLS1(KERN, GRID, P, NS)                                                                                     \
-    KLAUNCH(c, st, kid_cols, cols_bytes, (KERN<P, NS>), GRID, data, c->dev, lb, cv)
-#define COLS(KERN, GRID)                                                                                             \
-    switch (pro) {                                                                                                   \
-    case PRO_LOAD: COLS1(KERN, GRID, PRO_LOAD, 4); break;                                                            \
-    case PRO_MODUP:                                                                                                  \
-        if (wide)                                                                                                    \
-            COLS1(KERN, GRID, PRO_MODUP, 8);                                                                        \
-        else                                                                                                         \
-            COLS1(KERN, GRID, PRO_MODUP, 4);                                                                         \
-        break;                                                                                                       \
-    case PRO_MODDOWN:                                                                                                \
-        if (wide)                                                                                                    \
-            COLS1(KERN, GRID, PRO_MODDOWN, 8);                                                                      \
-        else                                                                                                         \
-            COLS1(KERN, GRID, PRO_MODDOWN, 4);                                                                       \
-        break;                                                                                                       \
-    case PRO_MODDOWN_RS:                                                                                             \
-        if (wide)                                                                                                    \
-            COLS1(KERN, GRID, PRO_MODDOWN_RS, 8);                                                                   \
-        else                                                                                                         \
-            COLS1(KERN, GRID, PRO_MODDOWN_RS, 4);                                                                    \
-        break;                                                                                                       \
-    default: COLS1(KERN, GRID, PRO_RESCALE, 4); break;                                                               \
-    }
-#define COLS4(KERN, GRID)                                                                                            \
-    switch (pro) {                                                                                                   \
-    case PRO_LOAD: COLS1(KERN, GRID, PRO_LOAD, 4); break;                                                            \
-    case PRO_MODUP: COLS1(KERN, GRID, PRO_MODUP, 4); break;                                                          \
-    case PRO_MODDOWN: COLS1(KERN, GRID, PRO_MODDOWN, 4); break;                                                      \
-    case PRO_MODDOWN_RS: COLS1(KERN, GRID, PRO_MODDOWN_RS, 4); break;                                                \
-    default: COLS1(KERN, GRID, PRO_RESCALE, 4); break;                                                               \
-    }
-        if (c->logN == 17) {
-            COLS4(k_ntt_fwd_cols17, 16 * nb)
-        } else if (c->logN == 16 && pro == PRO_MODUP && !wide) {
-            KLAUNCH(c, st, kid_cols, cols_bytes, (k_ntt_fwd_cols16_modup2<4>), 16 * ((nb + 1) / 2), data, c->dev, lb, cv, nb);
-        } else if (c->logN == 16) {
-            COLS(k_ntt_fwd_cols16, 16 * nb)
-        } else {
-            COLS(k_ntt_fwd_cols12, nb)
-        }
-#undef COLS4
-#undef COLS
-#undef COLS1
+        dl.fwd_cols[pro](c, st, kid_cols, cols_bytes, wide, data, lb, nb, cv);
         if (fin) {
             // reads the transform's input, the minuend and the addend, writes the result
             const double b = (double)nb * N8 * (3.0 + (fin->mode == 1 || fin->mode == 3 ? 1.0 : fin->mode == 2 ? 0.5 : fin->mode == 4 ? 1.5 : 0.0));
-            if (c->logN == 17)
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<17, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin, ho);
-            else if (c->logN == 16)
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<16, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin, ho);
-            else
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS_FIN, b, (k_ntt_fwd_blocks<12, EPI_FIN>), BLK_TILES(c) * nb, BLK_THREADS, data, c->dev, lb, *fin, ho);
+            dl.fwd_blocks(c, st, b, true, data, lb, nb, *fin, ho);
         } else {
             int nbb = nb; // integer-path limbs come first in a batch
             if (int_blocks_only)
                 for (nbb = 0; nbb < nb && c->modc[lb.mod[nbb]].qd == 0.0;) nbb++;
             if (nbb == 0) return;
-            if (c->logN == 17)
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<17, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin, kNoHoistOuts);
-            else if (c->logN == 16)
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<16, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin, kNoHoistOuts);
-            else
-                KLAUNCH_T(c, st, KID_FWD_BLOCKS, 2.0 * nbb * N8, (k_ntt_fwd_blocks<12, EPI_STORE>), BLK_TILES(c) * nbb, BLK_THREADS, data, c->dev, lb, kNoFin, kNoHoistOuts);
+            dl.fwd_blocks(c, st, 2.0 * nbb * N8, false, data, lb, nbb, kNoFin, kNoHoistOuts);
         }
     });
 }
@@ -350,30 +299,11 @@ static int32_t ntt_inverse(he_ctx *c, hipStream_t st, const u64 *src, u64 *dst, 
                            const ConvArgs &cv, bool blocks_done = false)
 {
     const double N8 = (double)c->N * 8.0;
+    const DevLaunch &dl = dev_launch(c);
     return for_batches(c, l, [&](const LimbBatch &lb, int nb) {
         const double bytes = 2.0 * nb * N8;
-#define ICOLS1(KERN, GRID, S) KLAUNCH(c, st, KID_INV_COLS, bytes, (KERN<S>), GRID, dst, c->dev, lb, cv)
-#define ICOLS(KERN, GRID)                                                                                            \
-    switch (scale) {                                                                                                 \
-    case SCALE_NONE: ICOLS1(KERN, GRID, SCALE_NONE); break;                                                          \
-    case SCALE_MODUP: ICOLS1(KERN, GRID, SCALE_MODUP); break;                                                        \
-    default: ICOLS1(KERN, GRID, SCALE_MODDOWN); break;                                                               \
-    }
-        if (c->logN == 17) {
-            if (!blocks_done)
-                KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<17>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
-            ICOLS(k_ntt_inv_cols17, 16 * nb)
-        } else if (c->logN == 16) {
-            if (!blocks_done)
-                KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<16>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
-            ICOLS(k_ntt_inv_cols16, 16 * nb)
-        } else {
-            if (!blocks_done)
-                KLAUNCH_T(c, st, KID_INV_BLOCKS, bytes, (k_ntt_inv_blocks<12>), BLK_TILES(c) * nb, BLK_THREADS, src, dst, c->dev, lb);
-            ICOLS(k_ntt_inv_cols12, nb)
-        }
-#undef ICOLS
-#undef ICOLS1
+        if (!blocks_done) dl.inv_blocks(c, st, bytes, src, dst, lb, nb);
+        dl.inv_cols(c, st, bytes, scale, dst, lb, nb, cv);
     });
 }
 
@@ -645,12 +575,7 @@ static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
     const HoistKeys &hk = hoist ? *hoist : kNoHoistKeys;
     // reads beta digits and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
     const double inner_bytes = (double)count * (3 * beta + 2) * Ma * N * 8.0;
-    if (c->logN == 17)
-        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<17>), grid, ia, c->dev, hk);
-    else if (c->logN == 16)
-        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<16>), grid, ia, c->dev, hk);
-    else
-        KLAUNCH(c, st, KID_INNER, inner_bytes, (k_inner_blocks<12>), grid, ia, c->dev, hk);
+    dev_launch(c).inner(c, st, inner_bytes, grid.x, ia, hk);
     int32_t rc = launch_ok(c);
     if (rc != HE_OK) return rc;
     LimbList sp;
