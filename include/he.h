@@ -53,6 +53,7 @@ extern "C" {
 #define HE_EHIP (-5)       /* a HIP call failed; see he_last_hip_error */
 #define HE_ENODEV (-6)     /* device function called on a host-only context */
 #define HE_ENOMEM (-7)
+#define HE_ESCRATCH (-8)   /* the operation needs more than the library's static scratch array holds */
 
 typedef struct he_ctx he_ctx;
 typedef struct he_sk he_sk;
@@ -220,6 +221,22 @@ int32_t he_hrot_many(he_ctx *ctx, const he_evk *const *rots, int32_t count, cons
 /* for k < count: ct <- ct + Rotate(ct, shift0 * 2^k), in place; rots[k] is the key of that shift. */
 int32_t he_rotate_sum(he_ctx *ctx, const he_evk *const *rots, int32_t count, uint64_t *d_ct, int32_t level,
                       void *d_ws, size_t ws_bytes, void *stream);
+
+/* ---- device: a rotation that allocates nothing and takes no workspace ------------------------- */
+
+/* For callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  he_hrot with the library's own scratch
+ * array in place of the workspace argument: a file-scope device array of HE_STATIC_SCRATCH_BYTES (64 MiB)
+ * that every GPU the library runs on holds until the process ends.  Same result as he_hrot, bit for bit.
+ * The call makes no hipMalloc / hipFree and enqueues only kernels on `stream`.  A level whose workspace
+ * (he_workspace_bytes(level, 1)) exceeds the array is refused with HE_ESCRATCH before anything is launched:
+ * the array holds every level at N = 2^12 and levels up to 9 of the 24-prime, dnum = 6 set at N = 2^16.
+ * All calls on one GPU share that GPU's array (whatever the context), which keeps the last call's contents;
+ * the operation needs no zeroed memory.  Calls that overlap on one GPU (two streams, two threads) race on it:
+ * order them on one stream or with events. */
+#define HE_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int32_t he_hrot_noalloc(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level,
+                        void *stream);
 
 /* ---- device: batches of independent ciphertexts ----------------------------------------------- */
 

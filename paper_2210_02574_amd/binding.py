@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libhe_gfx950.so")
 HE_OK = 0
 ERRORS = {
     -1: "HE_EINVAL", -2: "HE_ELEVEL", -3: "HE_ENOKEY", -4: "HE_EWORKSPACE",
-    -5: "HE_EHIP", -6: "HE_ENODEV", -7: "HE_ENOMEM",
+    -5: "HE_EHIP", -6: "HE_ENODEV", -7: "HE_ENOMEM", -8: "HE_ESCRATCH",
 }
 
 # every symbol include/he.h declares
@@ -34,6 +34,7 @@ SYMBOLS = [
     "he_hmult_relin", "he_hmult_relin_rescale", "he_rescale", "he_hrot", "he_hrot_many", "he_rotate_sum",
     "he_add_batch", "he_sub_batch", "he_pmult_batch", "he_cmult_batch", "he_add_const_batch", "he_moddrop_batch",
     "he_hmult_relin_batch", "he_hmult_relin_rescale_batch", "he_rescale_batch", "he_hrot_batch", "he_hrot_batch_keys", "he_rotate_sum_batch",
+    "he_hrot_noalloc",
     "he_profile_start", "he_profile_stop",
 ]
 
@@ -117,6 +118,7 @@ def load_library() -> ctypes.CDLL:
             "he_hmult_relin_rescale": [vp, vp, vp, vp, vp, i32, vp, sz, vp],
             "he_rescale": [vp, vp, vp, i32, vp, sz, vp],
             "he_hrot": [vp, vp, vp, vp, i32, vp, sz, vp],
+            "he_hrot_noalloc": [vp, vp, vp, vp, i32, vp],
             "he_hrot_many": [vp, vp, i32, vp, vp, i32, vp, sz, vp],
             "he_rotate_sum": [vp, vp, i32, vp, i32, vp, sz, vp],
             "he_add_batch": [vp, vp, vp, vp, i32, i32, vp],
@@ -520,6 +522,16 @@ class HE:
         self._chk(
             self.lib.he_hrot(self.ctx, rot.handle, self._dp(ct), self._dp(out), level, ws, wsb, self._stream()),
             "he_hrot",
+        )
+        return out
+
+    def hrot_noalloc(self, rot: EvalKey, ct, out):
+        """hrot on the library's static scratch array: no workspace, no allocation (the caller passes `out`)."""
+        level = self._level(ct)
+        assert tuple(out.shape) == tuple(ct.shape)
+        self._chk(
+            self.lib.he_hrot_noalloc(self.ctx, rot.handle, self._dp(ct), self._dp(out), level, self._stream()),
+            "he_hrot_noalloc",
         )
         return out
 

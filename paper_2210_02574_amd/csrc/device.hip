@@ -18,6 +18,7 @@
 #include <algorithm>
 #include <cstring>
 #include <functional>
+#include <mutex>
 #include <vector>
 
 #include "kernels_elem.h"
@@ -31,6 +32,32 @@
             return HE_EHIP;                                                                                          \
         }                                                                                                            \
     } while (0)
+
+// Scratch array of he_hrot_noalloc: the workspace of one rotation for callers that cannot allocate and pass
+// none.  Every GPU the library runs on holds its own copy at its own address; in host code the name below is
+// only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned long long scratch[HE_STATIC_SCRATCH_BYTES / sizeof(unsigned long long)];
+
+// Address of `scratch` on the context's device, asked for once per device (the caller has made that device
+// current) and kept: kernels and copies take this pointer, never the array's name.
+static int32_t static_scratch_address(he_ctx *c)
+{
+    static std::mutex mu;
+    static u64 *per_device[64] = {};
+    std::lock_guard<std::mutex> lock(mu);
+    if (c->device < 0 || c->device >= 64) return HE_EINVAL;
+    if (!per_device[c->device]) {
+        void *p = nullptr;
+        HIP_TRY(c, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) {
+            c->hip_err = "hipGetSymbolAddress(scratch) returned a null address";
+            return HE_EHIP;
+        }
+        per_device[c->device] = (u64 *)p;
+    }
+    c->static_scratch = per_device[c->device];
+    return HE_OK;
+}
 
 template <class Tv> static int32_t upload(he_ctx *c, const std::vector<Tv> &v, const Tv **out)
 {
@@ -50,6 +77,7 @@ int32_t dev_upload_tables(he_ctx *c)
     if (c->logN == 17 && (c->alpha > 4 || c->K > 4)) return HE_EINVAL; // ... and for up to 4 at N = 2^17
     HIP_TRY(c, hipSetDevice(c->device));
     int32_t rc;
+    if ((rc = static_scratch_address(c)) != HE_OK) return rc; // once per context, with its device current
 #define UP(field)                                                                                                    \
     if ((rc = upload(c, c->field, &c->dev.field)) != HE_OK) return rc;
     if ((rc = upload(c, c->modc, &c->dev.mod)) != HE_OK) return rc;
@@ -774,6 +802,18 @@ extern "C" int32_t he_hrot(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct,
                            void *d_ws, size_t ws_bytes, void *stream)
 {
     return he_hrot_batch(ctx, rot, d_ct, d_out, level, 1, d_ws, ws_bytes, stream);
+}
+
+// he_hrot on the library's own scratch array: no workspace argument, no allocation.
+extern "C" int32_t he_hrot_noalloc(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint64_t *d_out, int32_t level,
+                                   void *stream)
+{
+    int32_t rc = level_guard(ctx, level);
+    if (rc != HE_OK) return rc;
+    if (!ctx->static_scratch) return HE_EHIP;
+    if (ws_layout(ctx, level).total * ctx->N * sizeof(u64) > HE_STATIC_SCRATCH_BYTES) return HE_ESCRATCH;
+    return hrot_batch_to(ctx, rot, d_ct, 2 * level, d_out, 2 * level, level, 1, ctx->static_scratch, HE_STATIC_SCRATCH_BYTES,
+                         (hipStream_t)stream);
 }
 
 extern "C" int32_t he_hrot_batch_keys(he_ctx *ctx, const he_evk *const *rots, const uint64_t *d_ct, uint64_t *d_out,

@@ -93,6 +93,7 @@ struct he_ctx {
     std::vector<uint32_t> slot_exp;       // 5^j mod 2N
     DevTables dev{};
     std::vector<void *> dev_allocs;
+    u64 *static_scratch = nullptr; // address, on this context's device, of the library's file-scope scratch array
     mutable std::string hip_err;
     bool prof_on = false;
     std::vector<ProfRecord> prof;

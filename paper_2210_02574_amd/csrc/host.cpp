@@ -156,6 +156,7 @@ extern "C" const char *he_strerror(int32_t code)
     case HE_EHIP: return "HIP error";
     case HE_ENODEV: return "context has no device";
     case HE_ENOMEM: return "out of memory";
+    case HE_ESCRATCH: return "operation does not fit the static scratch array";
     }
     return "unknown error";
 }
