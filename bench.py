@@ -268,6 +268,84 @@ def bootstrap_ms(he, w: "Workload", ns: int = 1024, reps: int = 3) -> float:
     return (time.perf_counter() - t0) * 1e3 / reps
 
 
+def train_iteration_ms(reps: int = 2) -> float:
+    """One iteration of the paper's training recipe (Section 3.1) for one class at full size, on uniform residues
+    with the real plaintexts: N = 2^16, 28 primes (dnum = 7), 1024 samples x 768 features in 32 ciphertexts of
+    1024-slot blocks; gradient step with the degree-7 polynomial (batched over the 32 ciphertexts), Nesterov
+    look-ahead, division, Bootstrap of the 1024-slot weight vector (level 1 -> 12).  Milliseconds per iteration."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from paper_2210_02574_amd.training import EncryptedTrainer
+
+    p = wl.T16
+    he = pkg.HE.from_params(p, device=0)
+    tr = EncryptedTrainer(he, 1024, 1.0, 0.5, 1024, 2.0**50)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(16)
+
+    def uniform_batch(count, level):
+        out = torch.empty((count, 2, level, p.N), dtype=torch.int64, device=dev)
+        for i in range(level):
+            out[:, :, i].random_(0, p.q[i], generator=gen)
+        return out
+
+    def key(seed, g):
+        return he.evk_from_host(wl.uniform_evk(seed, p), g)
+
+    keys = {"relin": key(5000, 1), "conj": key(5001, 2 * p.N - 1),
+            "rot": {sh: key(5002 + i, he.galois_element(sh)) for i, sh in enumerate(tr.rotation_shifts())}}
+    tr.boot.prepare(tr.gain)
+    tp = tr.step.plan
+    X = uniform_batch(32, tr.level)
+    Y = [uniform_batch(32, tp.label_level)]
+    W = [uniform_batch(1, tr.level)[0]]
+    V = [uniform_batch(1, tp.out_level)[0]]
+    mask = tr.step.encode_mask()
+    W, V = tr.iterate(keys, mask, X, W, V, Y)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        W, V = tr.iterate(keys, mask, X, W, V, Y)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / reps
+
+
+def probe(args) -> None:
+    """Short fixed targets for hardware counters and traces (`rocprofv3 ... -- python3 bench.py --probe ...`).
+    `hrot-batch [SET LEVEL COUNT]`: three batched rotations with one key on uniform residues (default: eight
+    level-24 ciphertexts of the N = 2^16 set; `P17 30 4` is the paper's ring degree).  `copy`: five plain
+    device-to-device copies of 256 MiB, the launch of known size (262144 KiB read and written) against which the
+    profiler's HBM traffic counters are scaled."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+
+    if args[0] == "copy":
+        a = torch.empty(32 * 1024 * 1024, dtype=torch.int64, device="cuda").random_()
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print("copied 5 x 256 MiB")
+        return
+    if args[0] != "hrot-batch":
+        print("bench.py: unknown probe %r (hrot-batch, copy)" % args[0], file=sys.stderr)
+        sys.exit(2)
+    p = getattr(wl, args[1]) if len(args) > 1 else wl.N16
+    he = pkg.HE.from_params(p, device=0)
+    level = int(args[2]) if len(args) > 2 else p.L
+    count = int(args[3]) if len(args) > 3 else 8
+    key = he.evk_from_host(wl.uniform_evk(1, p), he.galois_element(1))
+    cts = torch.stack([he.to_device(wl.uniform_ct(30 + i, p, level)) for i in range(count)])
+    out = he.empty_batch(count, level)
+    for _ in range(3):
+        he.hrot_batch(key, cts, out=out)
+    torch.cuda.synchronize()
+    print("3 x hrot_batch of %d ciphertexts at level %d" % (count, level))
+
+
 def paper_scale_rates(reps: int = 5) -> dict:
     """The paper's ring degree (N = 2^17, 30 primes below 2^50, 4 special primes, dnum = 8) on uniform residues:
     rotations in batches of four and Mult + rescale in batches of four at level 30."""
@@ -356,6 +434,8 @@ def main():
     ap.add_argument("--no-group-singles", action="store_true",
                     help="issue every single rotation as a call of its own instead of one call per level")
     ap.add_argument("--streams", type=int, default=3, help="HIP streams for the independent operations of a step")
+    ap.add_argument("--probe", nargs="+", metavar="ARG",
+                    help="run a short profiling target instead of the benchmark: hrot-batch [SET LEVEL COUNT] | copy")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
@@ -372,6 +452,9 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.probe:
+        probe(args.probe)
+        return
     he = pkg.HE.from_params(wl.N16, device=0)
     w = Workload(he, n_streams=args.streams, hm_chunk=args.hmult_batch, group_singles=not args.no_group_singles)
     for _ in range(args.warmup):
@@ -475,6 +558,11 @@ def main():
         out["detail"]["bootstrap_workload"] = ("1024 packed slots (the block of the paper's weight vectors), level 1 -> 8, "
                                                "5 + 4 x 14 HRot, 2 conjugations, 24 HMult")
         out["detail"]["train_step_workload"] = "1024 samples x 768 features, 4 classes, 768 HMult + 2580 HRot"
+        del w
+        torch.cuda.empty_cache()
+        out["detail"]["train_iteration_ms"] = train_iteration_ms()
+        out["detail"]["train_iteration_workload"] = ("per class: N=2^16, L=28, dnum=7, 1024 samples x 768 features in 32 "
+                                                     "ciphertexts, gradient step + Nesterov update + Bootstrap of 1024 slots")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

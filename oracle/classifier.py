@@ -148,6 +148,18 @@ def minimax15_by_linear_program(radius=12.0, grid=1201):
     return res.x[:8], float(res.x[8])
 
 
+def minimax15_coeffs(radius=12.0):
+    """Monomial coefficients in t = x/radius (length 16, constant 1/2, even powers zero) of the odd degree-15
+    minimax approximation of the logistic function, from the linear program on a 4801-point grid: the oracle
+    side's own derivation of the polynomial the paper uses (Section 2.2; its sup error is within the printed
+    0.00614)."""
+    c, _ = minimax15_by_linear_program(radius, grid=4801)
+    mono = np.zeros(16)
+    mono[0] = 0.5
+    mono[1::2] = c
+    return mono
+
+
 def logistic15(o, t, relin, level, scale, c):
     """1/2 + t Q(t^2) on a ciphertext of t at (level, scale); c = monomial coefficients (length 16).
     Horner-free split: Q = A + y^4 B with A = (c1 + c3 y) + y^2 (c5 + c7 y), B = (c9 + c11 y) + y^2 (c13 + c15 y)."""

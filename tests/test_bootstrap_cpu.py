@@ -219,9 +219,7 @@ def test_training_iteration_with_momentum_and_bootstrap(oracle_mod, degree):
         s4 = (s1 * s1 / q[level - 3]) ** 2 / q[level - 4]
         label_scale, label_level = s1 * (s4 * S / q[level - 5]) / q[level - 6], level - 6
     else:  # the label scale is the scale the degree-15 evaluation returns; take it from a dry run on an encryption of 0
-        from paper_2210_02574_amd import classifier as cl
-
-        c15 = cl.minimax_logistic_coeffs()[0]
+        c15 = oc.minimax15_coeffs()
         zero = o.encrypt_coeffs(s, np.zeros(o.N, dtype=np.int64), level - 2, 199)
         _, label_scale = oc.logistic15(o, zero, keys["relin"], level - 2, s1, c15)
         label_level = level - 7

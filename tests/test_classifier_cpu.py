@@ -55,6 +55,11 @@ def test_minimax15_matches_the_paper():
     assert abs(err.max() - sup) < 1e-7
     c_lp, e_lp = oc.minimax15_by_linear_program()
     assert abs(e_lp - sup) < 2e-5
+    # the coefficients every oracle leg uses: inside the printed bound, and close to the library's Remez result
+    c_o = oc.minimax15_coeffs()
+    err_o = np.abs(np.polyval(c_o[::-1], t) - 1 / (1 + np.exp(-12 * t))).max()
+    assert err_o <= 0.00614 and abs(err_o - sup) < 2e-6
+    assert np.abs(np.polyval(c_o[::-1], t) - np.polyval(mono[::-1], t)).max() < 1e-5
     err_lp = np.abs(sum(c_lp[k] * t ** (2 * k + 1) for k in range(8)) + 0.5 - 1 / (1 + np.exp(-12 * t))).max()
     assert abs(err_lp - sup) < 1e-4
 
@@ -65,11 +70,10 @@ def test_oracle_logistic15_decrypts_to_the_logistic_function():
     import workloads as wl
     from oracle import classifier as oc
     from oracle.ckks import Oracle
-    from paper_2210_02574_amd import classifier as cl
 
     p = wl.N16
     o = Oracle(p.logN, p.q, p.p, p.dnum)
-    coeffs, _ = cl.minimax_logistic_coeffs()
+    coeffs = oc.minimax15_coeffs()
     s = o.keygen_secret(61)
     relin = o.keygen_relin(s, 62)
     x = 12.0 * wl.slots_uniform(63, o.n).real

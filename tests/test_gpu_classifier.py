@@ -104,6 +104,73 @@ def test_train_step_slice_matches_oracle_and_plaintext(oracle_mod):
     assert np.abs(dec[1024 + 4: 1024 + 772] - ref).max() <= 2.0**-15
 
 
+@pytest.mark.timeout(600)
+def test_full_shape_train_step_of_one_class(oracle_mod):
+    """The training step at the shape that is timed (Section 3.1; 1024 samples x 768 features in 32 ciphertexts,
+    one class, the batched driver, cross-ciphertext gradient sum and cross-block rotate-and-sum, levels 24 -> 16,
+    scale 2^50) with real keys: the decrypted updated weights against the fp64 step over all 1024 samples within
+    2^-15, and the same driver on the first two ciphertexts bit for bit against the oracle's composition (which
+    runs 52 rotations and 12 Mult for them)."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from oracle import classifier as oc
+    from paper_2210_02574_amd import classifier as cl
+
+    assert torch.cuda.is_available()
+    p = wl.N16
+    he = pkg.HE.from_params(p, device=0)
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    level, scale, lr = 24, 2.0**50, 1.0
+    nb, ncts = he.n // 1024, 32
+    n_samples = nb * ncts
+    X = wl.embeddings(71, n_samples)
+    W0 = wl.weights(72)[0]
+    labels = (np.argmax(X @ wl.weights(73).T, axis=1) == 0).astype(np.float64)
+    a_x = oc.logistic_poly_coeffs()  # the oracle's derivation (monomial coefficients in x); an input of the driver
+    coeffs = np.array([a_x[k] * 8.0**k for k in range(8)])
+    step = cl.EncryptedTrainStep(he, level, scale, lr, n_samples, coeffs)
+    plan = step.plan
+    sk, s = he.keygen_secret(74), o.keygen_secret(74)
+    relin, rot = step.make_keys(sk, 300)
+    zw = np.tile(np.concatenate([np.zeros(4), W0, np.zeros(1024 - 772)]), nb)
+
+    def x_slots(i):
+        return cl.pack_samples(X[i * nb:(i + 1) * nb], he.n)
+
+    def y_slots(i):
+        return np.repeat(labels[i * nb:(i + 1) * nb], 1024)
+
+    # (a) all 32 ciphertexts, the library's own encodings and encryptions
+    Xb = torch.stack([he.to_device(he.encrypt_coeffs(sk, he.encode(x_slots(i), scale), level, 400 + i)) for i in range(ncts)])
+    Yb = torch.stack([he.to_device(he.encrypt_coeffs(sk, he.encode(y_slots(i), plan.label_scale), plan.label_level, 500 + i))
+                      for i in range(ncts)])
+    Wd = he.to_device(he.encrypt_coeffs(sk, he.encode(zw, scale), level, 600))
+    out = step.run_batched(relin, rot, step.encode_mask(), Xb, [Wd], [Yb])[0]
+    assert tuple(out.shape) == (2, plan.out_level, p.N)
+    dec = he.decrypt(sk, he.to_host(out), scale).real
+    pz = np.polyval(coeffs[::-1], (X @ W0) / 8.0)
+    ref = W0 - lr / n_samples * ((pz - labels) @ X)
+    err = np.abs(dec[4:772] - ref).max()
+    print("full-shape train step (32 ciphertexts): max abs error of updated weights %.3g (bound %.3g), step size %.3g"
+          % (err, 2.0**-15, np.abs(ref - W0).max()))
+    assert err <= 2.0**-15
+    assert np.abs(dec[31 * 1024 + 4: 31 * 1024 + 772] - ref).max() <= 2.0**-15  # every block carries the update
+    assert np.abs(ref - W0).max() > 2.0**-10  # the step moved the weights by far more than the bound
+    del Xb, Yb, out
+    # (b) the first two ciphertexts through the same batched driver, bit for bit against the oracle
+    orelin = o.keygen_relin(s, 300)
+    orot = {r: o.keygen_rot(s, r, 301 + k) for k, r in enumerate(step.rotation_shifts())}
+    cx = [o.encrypt_coeffs(s, o.encode(x_slots(i), scale), level, 400 + i) for i in range(2)]
+    cy = [o.encrypt_coeffs(s, o.encode(y_slots(i), plan.label_scale), plan.label_level, 500 + i) for i in range(2)]
+    cw = o.encrypt_coeffs(s, o.encode(zw, scale), level, 600)
+    mask_pt = he.to_device(o.coeffs_to_ntt(o.encode(step.mask_slots(), plan.mask_scale), level - 1))
+    got = step.run_batched(relin, rot, mask_pt, torch.stack([he.to_device(c) for c in cx]), [he.to_device(cw)],
+                           [torch.stack([he.to_device(c) for c in cy])])[0]
+    want = oc.train_step(o, cx, [cw], [cy], orelin, orot, level, scale, lr, n_samples, a_x)[0]
+    assert np.array_equal(he.to_host(got), want)
+
+
 def test_batched_train_step_equals_sequential():
     """The batched driver (one library call per step over all ciphertexts of a class) gives the bits of
     the sequential driver, on three ciphertexts of uniform residues (odd count: uneven pairwise sum)."""
@@ -144,7 +211,8 @@ def test_logistic15_matches_oracle_and_the_paper_bound(oracle_mod):
     he = pkg.HE.from_params(p, device=0)
     o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
     level, scale = 8, 2.0**50
-    coeffs, sup = cl.minimax_logistic_coeffs()
+    coeffs = oc.minimax15_coeffs()  # the oracle's own derivation; the device run takes the same numbers as an input
+    sup = np.abs(np.polyval(coeffs[::-1], np.linspace(-1, 1, 48001)) - 1 / (1 + np.exp(-12 * np.linspace(-1, 1, 48001)))).max()
     sk, s = he.keygen_secret(61), o.keygen_secret(61)
     relin, orelin = he.keygen_relin(sk, 62), o.keygen_relin(s, 62)
     x = 12.0 * wl.slots_uniform(63, he.n).real

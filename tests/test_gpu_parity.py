@@ -207,6 +207,19 @@ def test_hrot_single_and_hoisted(env):
         assert np.array_equal(he.to_host(both[1]), o.hrot(ct2, keys[1][1], rots[1])), level
 
 
+def test_hrot_every_digit_count_at_full_size(env):
+    """One rotation per level 20, 16, 12, 8, 4, 1 at N = 2^16 (5, 4, 3, 2, 1 digits and a one-limb digit), beyond
+    the levels of the test above (6, 6, 6 and 3 digits)."""
+    he, o, p = env.he, env.o, env.params
+    if p.name != "N16":
+        pytest.skip("the other parameter sets run every level in test_hrot_single_and_hoisted")
+    for k, level in enumerate((20, 16, 12, 8, 4, 1)):
+        r = 1 << (2 * k + 1)
+        key, evk = env.synth_key(520 + k, o.galois_element(r))
+        ct = wl.uniform_ct(680 + level, p, level)
+        assert np.array_equal(he.to_host(he.hrot(key, he.to_device(ct))), o.hrot(ct, evk, r)), level
+
+
 def test_patterned_inputs_through_the_key_switch(env):
     """Residues at the ends of their ranges (all q-1, all (q-1)/2, alternating 0 / q-1, within 1000 of q) through
     Mult, the fused Mult + rescale and Rotate: the lazy ranges of both arithmetic paths at their widest."""

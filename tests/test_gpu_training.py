@@ -31,9 +31,7 @@ def test_training_iterations_match_oracle_and_plaintext(oracle_mod, degree):
     if degree == 7:
         tr = EncryptedTrainer(he, pr.block, lr, gamma, pr.nb, S, coeffs=np.array([a[k] * 8.0**k for k in range(8)]))
     else:  # the paper's activation: degree-15 minimax polynomial on [-12, 12], same coefficients on both sides
-        from paper_2210_02574_amd import classifier as cl
-
-        c15 = cl.minimax_logistic_coeffs()[0]
+        c15 = oc.minimax15_coeffs()  # the oracle's own derivation, an input of the device driver
         tr = EncryptedTrainer(he, pr.block, lr, gamma, pr.nb, S, coeffs=c15, degree=15)
     plan = ob.Plan(o, pr.block, 7, groups=2)
     level = tr.level
@@ -127,3 +125,62 @@ def test_minibatch_epochs_follow_the_plaintext_recipe():
     assert err < 2e-4
     # every block of the packed weight vector holds the same weights
     assert np.abs(dec[pr.block + pr.off:pr.block + pr.off + pr.dim] - wp).max() < 2e-4
+
+
+@pytest.mark.timeout(600)
+def test_full_size_training_iteration():
+    """The paper's recipe at full size (Section 3.1): N = 2^16, 28 primes, one sample per 1024-slot block, 1024
+    samples x 768 features in 32 ciphertexts, one class; gradient step, Nesterov look-ahead and a Bootstrap of the
+    1024-slot weight vector per iteration, real keys (sparse secret), the driver's own plaintexts.  Two iterations
+    against the fp64 iteration of the same polynomial step: max weight error <= 1e-5."""
+    import torch
+
+    import paper_2210_02574_amd as pkg
+    from oracle import classifier as oc
+    from paper_2210_02574_amd.training import EncryptedTrainer
+
+    assert torch.cuda.is_available()
+    p = wl.T16
+    he = pkg.HE.from_params(p, device=0)
+    block, dim, off, ncts = 1024, 768, 4, 32
+    nb = he.n // block
+    n_samples = nb * ncts
+    S, lr, gamma = 2.0**50, 1.0, 0.5
+    a = oc.logistic_poly_coeffs()
+    tr = EncryptedTrainer(he, block, lr, gamma, n_samples, S, coeffs=np.array([a[k] * 8.0**k for k in range(8)]))
+    level, tp = tr.level, tr.step.plan
+    assert level == 12 and tp.out_level == 4
+    sk = he.keygen_secret_sparse(1, 64)
+    keys = tr.make_keys(sk, 100)
+    tr.boot.prepare(tr.gain)
+    X = wl.embeddings(81, n_samples)
+    w0 = wl.weights(82)[0]
+    y = (X @ wl.weights(83)[0] > 0).astype(np.float64)
+
+    def blocks(rows):
+        z = np.zeros(he.n)
+        for b in range(nb):
+            z[b * block + off: b * block + off + dim] = rows[b]
+        return z
+
+    Xc = torch.stack([he.to_device(he.encrypt_coeffs(sk, he.encode(blocks(X[i * nb:(i + 1) * nb]), S), level, 200 + i))
+                      for i in range(ncts)])
+    Yc = [torch.stack([he.to_device(he.encrypt_coeffs(sk, he.encode(np.repeat(y[i * nb:(i + 1) * nb], block), tp.label_scale),
+                                                      tp.label_level, 300 + i)) for i in range(ncts)])]
+    W = [he.to_device(he.encrypt_coeffs(sk, he.encode(blocks([w0] * nb), S), level, 400))]
+    V = [he.moddrop(W[0], tp.out_level)]
+    mask = tr.step.encode_mask()
+    wp, vp = w0.copy(), w0.copy()
+    for it in range(2):
+        W, V = tr.iterate(keys, mask, Xc, W, V, Yc)
+        z = X @ wp
+        pz = sum(a[k] * z**k for k in range(8))
+        vn = wp - lr * ((pz - y)[:, None] * X).sum(0) / n_samples
+        wp, vp = (1 + gamma) * vn - gamma * vp, vn
+        assert tuple(W[0].shape) == (2, level, p.N)
+        dec = he.decrypt(sk, he.to_host(W[0]), S).real
+        err = np.abs(dec[off:off + dim] - wp).max()
+        print("full-size iteration %d: max weight error %.3g (|w| up to %.3g)" % (it + 1, err, np.abs(wp).max()))
+        assert err <= 1e-5
+        assert np.abs(dec[5 * block + off: 5 * block + off + dim] - wp).max() <= 1e-5  # every block holds the weights
+    assert np.abs(wp - w0).max() > 1e-2
