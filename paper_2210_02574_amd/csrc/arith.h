@@ -118,6 +118,57 @@ struct ArithFp {
             }
         }
     }
+    // Three forward stages on 8 elements (pairs 4, 2, 1 apart); tw(sp, g): twiddle of stage sp, group g < 2^sp.
+    // Entered with |v| <= q/2 (reduce_first) it ends below 2.7q.
+    template <class F> __device__ __forceinline__ void fwd8_with(V (&a)[8], bool reduce_first, F tw) const
+    {
+        if (reduce_first) {
+#pragma unroll
+            for (int k = 0; k < 8; k++) a[k] = reduce(a[k]);
+        }
+#pragma unroll
+        for (int sp = 0; sp < 3; sp++) {
+            const int dist = 4 >> sp;
+#pragma unroll
+            for (int g = 0; g < (1 << sp); g++) {
+                const double w = tw(sp, g);
+#pragma unroll
+                for (int e = 0; e < dist; e++) {
+                    const int k0 = g * 2 * dist + e, k1 = k0 + dist;
+                    const double t = mulmod(a[k1], w), x = a[k0];
+                    a[k0] = x + t;
+                    a[k1] = x - t;
+                }
+            }
+        }
+    }
+    // Two forward stages on each of the two groups a[0..3], a[4..7] (pairs 2, 1 apart); tw(h, sp, g): twiddle
+    // of group h, stage sp, pair group g < 2^sp.
+    template <class F> __device__ __forceinline__ void fwd4x2_with(V (&a)[8], bool reduce_first, F tw) const
+    {
+        if (reduce_first) {
+#pragma unroll
+            for (int k = 0; k < 8; k++) a[k] = reduce(a[k]);
+        }
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+#pragma unroll
+            for (int sp = 0; sp < 2; sp++) {
+                const int dist = 2 >> sp;
+#pragma unroll
+                for (int g = 0; g < (1 << sp); g++) {
+                    const double w = tw(h, sp, g);
+#pragma unroll
+                    for (int e = 0; e < dist; e++) {
+                        const int k0 = 4 * h + g * 2 * dist + e, k1 = k0 + dist;
+                        const double t = mulmod(a[k1], w), x = a[k0];
+                        a[k0] = x + t;
+                        a[k1] = x - t;
+                    }
+                }
+            }
+        }
+    }
     // index in twf of twiddle c (as above) of the step that starts at stage s_base in group G
     static __device__ __forceinline__ unsigned fwd16_twiddle(unsigned s_base, unsigned G, unsigned c)
     {

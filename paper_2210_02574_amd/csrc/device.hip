@@ -16,6 +16,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <functional>
 #include <mutex>
@@ -97,12 +98,46 @@ void dev_free_tables(he_ctx *c)
     c->dev_allocs.clear();
 }
 
+// Device form of a key: limbs of a modulus below 2^50 (the floating-point path) hold balanced residues as
+// doubles (v, or v - q above (q-1)/2), the other limbs the residues themselves.  The inner product then
+// multiplies key words without converting them, and products with |word| <= q/2 are exact for wider inputs.
 int32_t dev_upload_evk(he_evk *k)
 {
     he_ctx *c = const_cast<he_ctx *>(k->ctx);
+    const size_t N = c->N, limbs = (size_t)c->dnum * 2 * c->M;
+    std::vector<u64> img;
+    try {
+        img.resize(limbs * N);
+    } catch (...) {
+        return HE_ENOMEM;
+    }
+    std::atomic<bool> bad(false);
+    hostmath::parallel_for((int)limbs, [&](int l) {
+        const ModConst &m = c->modc[l % c->M];
+        const u64 *src = k->host.data() + (size_t)l * N, half = (m.q - 1) / 2;
+        u64 *dst = img.data() + (size_t)l * N;
+        bool b = false;
+        for (size_t n = 0; n < N; n++) {
+            const u64 v = src[n];
+            b |= v >= m.q;
+            if (m.qd != 0.0) {
+                const double d = v > half ? -(double)(m.q - v) : (double)v;
+                memcpy(&dst[n], &d, sizeof(d));
+            } else
+                dst[n] = v;
+        }
+        if (b) bad = true;
+    });
+    if (bad) return HE_EINVAL; // a residue that is not below its modulus
     HIP_TRY(c, hipSetDevice(c->device));
-    HIP_TRY(c, hipMalloc((void **)&k->dev, k->host.size() * sizeof(u64)));
-    HIP_TRY(c, hipMemcpy(k->dev, k->host.data(), k->host.size() * sizeof(u64), hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMalloc((void **)&k->dev, img.size() * sizeof(u64)));
+    hipError_t e = hipMemcpy(k->dev, img.data(), img.size() * sizeof(u64), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        c->hip_err = std::string("hipMemcpy (key upload): ") + hipGetErrorString(e);
+        (void)hipFree(k->dev);
+        k->dev = nullptr;
+        return HE_EHIP;
+    }
     return HE_OK;
 }
 
@@ -116,12 +151,23 @@ extern "C" int32_t he_evk_to_host(const he_evk *evk, uint64_t *h_out)
 {
     if (!evk || !h_out) return HE_EINVAL;
     const he_ctx *c = evk->ctx;
-    const size_t words = (size_t)c->dnum * 2 * c->M * c->N;
-    if (evk->dev) {
-        he_ctx *cm = const_cast<he_ctx *>(c);
-        HIP_TRY(cm, hipMemcpy(h_out, evk->dev, words * sizeof(u64), hipMemcpyDeviceToHost));
-    } else
+    const size_t N = c->N, limbs = (size_t)c->dnum * 2 * c->M, words = limbs * N;
+    if (!evk->dev) {
         memcpy(h_out, evk->host.data(), words * sizeof(u64));
+        return HE_OK;
+    }
+    he_ctx *cm = const_cast<he_ctx *>(c);
+    HIP_TRY(cm, hipMemcpy(h_out, evk->dev, words * sizeof(u64), hipMemcpyDeviceToHost));
+    hostmath::parallel_for((int)limbs, [&](int l) { // back from the device form to residues
+        const ModConst &m = c->modc[l % c->M];
+        if (m.qd == 0.0) return;
+        u64 *w = h_out + (size_t)l * N;
+        for (size_t n = 0; n < N; n++) {
+            double d;
+            memcpy(&d, &w[n], sizeof(d));
+            w[n] = d < 0.0 ? m.q - (u64)(-d) : (u64)d;
+        }
+    });
     return HE_OK;
 }
 

@@ -4,6 +4,7 @@
 // butterflies, the same formulation as the device kernels.
 #include <algorithm>
 #include <cmath>
+#include <atomic>
 #include <complex>
 #include <cstring>
 #include <functional>
@@ -221,7 +222,7 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
         delete c;
         return HE_ENOMEM;
     }
-    bool bad = false;
+    std::atomic<bool> bad(false); // written by several workers
     parallel_for(M, [&](int i) {
         const u64 t = c->mod[i];
         const u64 g = least_primitive_root(t);

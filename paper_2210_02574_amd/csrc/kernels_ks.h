@@ -16,38 +16,7 @@
 // limbs of u leave this kernel with the block pass of their inverse transform already applied.
 
 typedef u64 u64x2 __attribute__((ext_vector_type(2)));
-
-// Ownership in the product phase: thread t holds the pairs (4096 tile + 512 i + 2 t, + 1), i = 0..7, so that
-// key loads and result stores are 16 bytes per lane and 1 KiB contiguous per wave.  sigma_g maps an aligned
-// pair onto an aligned pair (possibly swapped): the source of k + 1 is the source of k with its lowest bit
-// flipped, because k + 1 adds N to the exponent 2 brv(k) + 1 and g is odd.
-__device__ __forceinline__ unsigned pair_at(unsigned i) { return 512u * i + 2u * threadIdx.x; }
-
-template <int LOGN, class A>
-__device__ __forceinline__ void inv_blocks_from_pairs(const u64 (&r)[16], u64 *limb, const A &ar, u64 *lds, unsigned bg)
-{
-    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
-    typename A::V a[16];
-#pragma unroll
-    for (int i = 0; i < 8; i++) {
-        const unsigned p = pair_at(i);
-        lds[tile_at(p >> 8, p & 255u)] = r[2 * i];
-        lds[tile_at(p >> 8, (p & 255u) + 1)] = r[2 * i + 1];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load(lds[tile_at(blk, 16 * il + k)]);
-    ar.template inv16<false>(a, LOGN - 4, bg * 16 + il);
-#pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_mid(a[k]);
-    block_sync();
-#pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, il + 16 * k)]);
-    ar.template inv16<false>(a, LOGN - 8, bg);
-#pragma unroll
-    for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = ar.store_mid(a[k]);
-    __syncthreads();
-}
+typedef double f64x2 __attribute__((ext_vector_type(2)));
 
 struct InnerArgs {
     const u64 *raised, *d, *evk;
@@ -74,10 +43,61 @@ __host__ __device__ inline unsigned inner_grid(unsigned tiles, unsigned limbs, u
 {
     return (tiles * limbs + XCDS - 1) / XCDS * XCDS * count;
 }
-template <int LOGN> __global__ __launch_bounds__(256) void k_inner_blocks(InnerArgs ia, DevTables T, HoistKeys hk)
+
+// 512 threads per work-group and eight elements per thread (128 registers, four waves per SIMD).  A 256-element
+// block belongs to 32 lanes (half a wave) and its block pass runs as three register steps, stages 0-2, 3-5 and
+// 6-7 of the block, with two exchanges through LDS among those lanes:
+//   step 1: lane t holds e = t + 32 k;   step 2: lane (g = t & 7, r = t >> 3) holds e = 32 g + r + 4 k;
+//   step 3: lane t holds e = 4 t + k' and 128 + 4 t + k' (k' < 4).
+// With one pad word per 16 elements every 16 consecutive lanes of each pattern hit 16 different 8-byte banks.
+// All 255 twiddles of a block's eight stages sit in LDS, the one of local stage m and group i at 2^m - 1 + i.
+// In the product phase thread t owns the pairs (4096 tile + 1024 i + 2 t, + 1), i < 4.
+
+__device__ __forceinline__ unsigned pair8_at(unsigned i) { return 1024u * i + 2u * threadIdx.x; }
+
+// Inverse block pass of the special limbs from the pairs of the product phase: the 4096 results go through LDS
+// to the first 256 threads, which run the 16-element form; the other threads only take part in the barriers.
+template <int LOGN, class A>
+__device__ __forceinline__ void inv_blocks_from_pairs8(const u64 (&r)[8], u64 *limb, const A &ar, u64 *lds, unsigned tile)
+{
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const unsigned p = pair8_at(i);
+        lds[tile_at(p >> 8, p & 255u)] = r[2 * i];
+        lds[tile_at(p >> 8, (p & 255u) + 1)] = r[2 * i + 1];
+    }
+    __syncthreads();
+    if (threadIdx.x < 256) {
+        const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15, bg = tile * 16 + blk;
+        typename A::V a[16];
+#pragma unroll
+        for (int k = 0; k < 16; k++) a[k] = ar.load(lds[tile_at(blk, 16 * il + k)]);
+        ar.template inv16<false>(a, LOGN - 4, bg * 16 + il);
+#pragma unroll
+        for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_mid(a[k]);
+        block_sync();
+#pragma unroll
+        for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, il + 16 * k)]);
+        ar.template inv16<false>(a, LOGN - 8, bg);
+#pragma unroll
+        for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = ar.store_mid(a[k]);
+    }
+    __syncthreads();
+}
+
+// Addresses are formed as a wave-uniform base plus a 32-bit lane offset so that they stay in scalar registers;
+// the three LDS patterns of the block pass are one base each plus compile-time offsets (with the pad word per
+// 16 elements: t + 32 k sits at t + (t >> 4) + 34 k, 32 g + r + 4 k at 34 g + r + 4 k + (k >> 2), and
+// 128 h + 4 t + k' at 4 t + (t >> 2) + 136 h + k').
+template <class Tv> __device__ __forceinline__ Tv ld_at(const void *base, unsigned byte_off)
+{
+    return *(const Tv *)((const char *)base + byte_off);
+}
+
+template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(InnerArgs ia, DevTables T, HoistKeys hk)
 {
     __shared__ u64 lds[16 * TILE_GROUP];
-    __shared__ double tws[16 * 15 + 256 * 15];
+    __shared__ double tws[16 * 256];
     const int level = ia.level, M = ia.L + ia.K, Ma = level + ia.K;
     const unsigned ntile = 1u << (LOGN - 12);
     const unsigned slot = blockIdx.x / XCDS, op = slot % (unsigned)ia.count;
@@ -85,113 +105,129 @@ template <int LOGN> __global__ __launch_bounds__(256) void k_inner_blocks(InnerA
     if (tl >= ntile * (unsigned)Ma) return; // padding of the last group of eight (whole work-group)
     const int a = Ma - 1 - (int)(tl / ntile); // special limbs (the slowest) first
     const unsigned tile = tl % ntile;
-    const u64 *raised = ia.raised + (((size_t)op * ia.raised_stride) << LOGN);
-    u64 *u = ia.u + (((size_t)op * ia.u_stride) << LOGN);
-    const u64 *d = ia.d + (((size_t)op * ia.d_stride) << LOGN);
     const unsigned g = ia.hoisted ? hk.g[op] : ia.g;
-    const u64 *evk = ia.hoisted ? hk.evk[op] : ia.evk;
     const int mi = active_mod(a, level, ia.L);
     const int own = a < level ? a / ia.alpha : -1;
     const ModConst m = T.mod[mi];
-    const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
-    const unsigned bg = tile * 16 + blk;
+    const unsigned blk = threadIdx.x >> 5, t = threadIdx.x & 31;
     const unsigned tile_in = g == 1 ? tile : galois_index(tile << 12, g, LOGN) >> 12;
-    const unsigned bg_in = tile_in * 16 + blk;
-    unsigned src[8]; // source of the even element of pair i
+    // wave-uniform bases (bytes): raised digit 0 and key component 0 of digit 0 for this limb and tile; digit j is
+    // raised_step / key_step further on, key component 1 comp_step after component 0
+    const char *raised0 = (const char *)(ia.raised + ((((size_t)op * ia.raised_stride + a) << LOGN) + ((size_t)tile_in << 12)));
+    const char *key0 = (const char *)((ia.hoisted ? hk.evk[op] : ia.evk) + (((size_t)mi << LOGN) + ((size_t)tile << 12)));
+    const char *d_limb = (const char *)(ia.d + (((size_t)op * ia.d_stride + a) << LOGN));
+    const size_t raised_step = ((size_t)Ma << LOGN) * 8, comp_step = ((size_t)M << LOGN) * 8, key_step = 2 * comp_step;
+    const unsigned lane16 = threadIdx.x * 16u;        // this thread's pair within a 512-pair row of the tile
+    const unsigned lane_mid = (blk * 256u + t) * 8u;  // element t of block blk
+    // pair i of the product phase: LDS words of the sources of its even and odd element (an aligned pair, in
+    // either order), and whether the pair arrives swapped
+    unsigned lsx[4], lsy[4], swm = 0;
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
-        const unsigned pos = (tile << 12) + pair_at(i);
-        src[i] = g == 1 ? pos : galois_index(pos, g, LOGN);
+    for (int i = 0; i < 4; i++) {
+        const unsigned pos = (tile << 12) + pair8_at(i);
+        const unsigned sr = g == 1 ? pos : galois_index(pos, g, LOGN);
+        const unsigned sl = sr & 4094u, sw = sr & 1u;
+        const unsigned w = (sl >> 8) * TILE_GROUP + (sl & 255u) + ((sl & 255u) >> 4);
+        lsx[i] = w + sw, lsy[i] = w + 1 - sw;
+        swm |= sw << i;
     }
-    const size_t key_at = ((size_t)tile << 11) + threadIdx.x; // in pairs, inside one limb
-    u64 r0[16], r1[16];
+    u64 r0[8], r1[8];
     if (m.qd != 0.0) {
         const ArithFp ar = make_fp(T, mi, LOGN);
-        // Every digit's block pass uses the same twiddles (15 per block for its first four stages, 15 per
-        // thread for the last four): fetched once and kept in LDS, so that no global load sits inside the
-        // block pass and the key loads issued before it stay in flight until the products need them.
-        double *tw_blk = tws, *tw_thr = tws + 16 * 15 + threadIdx.x * 15;
-        if (il < 15) tw_blk[blk * 15 + il] = ar.twf[ArithFp::fwd16_twiddle(LOGN - 8, bg_in, il)];
-#pragma unroll
-        for (unsigned c = 0; c < 15; c++) tw_thr[c] = ar.twf[ArithFp::fwd16_twiddle(LOGN - 4, bg_in * 16 + il, c)];
+        double *tw = tws + blk * 256;
+        for (unsigned c = t; c < 255; c += 32) tw[c] = ar.twf[ArithFp::fwd16_twiddle(LOGN - 8, tile_in * 16 + blk, c)];
         __syncthreads();
-        tw_blk += blk * 15;
-        double acc0[16], acc1[16];
+        const unsigned g2 = t & 7, r2 = t >> 3;
+        u64 *l1 = lds + blk * TILE_GROUP + t + (t >> 4);
+        u64 *l2 = lds + blk * TILE_GROUP + 34 * g2 + r2;
+        u64 *l3 = lds + blk * TILE_GROUP + 4 * t + (t >> 2);
+        double acc0[8], acc1[8];
 #pragma unroll
-        for (int k = 0; k < 16; k++) acc0[k] = acc1[k] = 0.0;
+        for (int k = 0; k < 8; k++) acc0[k] = acc1[k] = 0.0;
         for (int j = 0; j < ia.beta; j++) {
-            double dv[16];
-            u64x2 e0[8], e1[8];
-            const u64x2 *k0 = (const u64x2 *)(evk + ((((size_t)j * 2 + 0) * M + mi) << LOGN)) + key_at;
-            const u64x2 *k1 = (const u64x2 *)(evk + ((((size_t)j * 2 + 1) * M + mi) << LOGN)) + key_at;
+            double dv[8];
+            f64x2 e0[4], e1[4]; // key words of a floating-point limb are balanced doubles
+            const char *kj = key0 + (size_t)j * key_step;
             if (j == own) {
-                const u64 *dj = d + ((size_t)a << LOGN);
 #pragma unroll
-                for (int i = 0; i < 8; i++) {
-                    const u64x2 v = *(const u64x2 *)(dj + (src[i] & ~1u));
-                    const bool sw = src[i] & 1u;
+                for (int i = 0; i < 4; i++) {
+                    const unsigned pos = (tile << 12) + pair8_at(i);
+                    const unsigned sr = g == 1 ? pos : galois_index(pos, g, LOGN);
+                    const u64x2 v = ld_at<u64x2>(d_limb, (sr & ~1u) * 8u);
+                    const bool sw = (swm >> i) & 1u;
                     dv[2 * i] = u2d(sw ? v.y : v.x), dv[2 * i + 1] = u2d(sw ? v.x : v.y);
                 }
 #pragma unroll
-                for (int i = 0; i < 8; i++) e0[i] = k0[256 * i], e1[i] = k1[256 * i];
+                for (int i = 0; i < 4; i++)
+                    e0[i] = ld_at<f64x2>(kj + 8192 * i, lane16), e1[i] = ld_at<f64x2>(kj + comp_step + 8192 * i, lane16);
             } else {
-                const u64 *mid = raised + (((size_t)j * Ma + a) << LOGN);
+                const char *mid = raised0 + (size_t)j * raised_step;
 #pragma unroll
-                for (int k = 0; k < 16; k++) dv[k] = ar.load_mid(mid[bg_in * 256 + il + 16 * k]);
+                for (int k = 0; k < 8; k++) dv[k] = ar.load_mid(ld_at<u64>(mid + 256 * k, lane_mid));
                 // the key loads are issued before the block pass and complete behind it
 #pragma unroll
-                for (int i = 0; i < 8; i++) e0[i] = k0[256 * i], e1[i] = k1[256 * i];
-                ar.fwd16_with(dv, true, [&](int c) { return tw_blk[c]; });
+                for (int i = 0; i < 4; i++)
+                    e0[i] = ld_at<f64x2>(kj + 8192 * i, lane16), e1[i] = ld_at<f64x2>(kj + comp_step + 8192 * i, lane16);
+                // ranges (in units of q): the column pass leaves up to 3.7; reduced, step 1 ends below 2.7 and
+                // step 2 below 6.3; reduced again, step 3 ends below 1.9, small enough for exact products
+                ar.fwd8_with(dv, true, [&](int sp, int gg) { return tw[(1 << sp) - 1 + gg]; });
 #pragma unroll
-                for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = ar.store_mid(dv[k]);
+                for (int k = 0; k < 8; k++) l1[34 * k] = ar.store_mid(dv[k]);
                 block_sync();
 #pragma unroll
-                for (int k = 0; k < 16; k++) dv[k] = ar.load_mid(lds[tile_at(blk, 16 * il + k)]);
-                ar.fwd16_with(dv, true, [&](int c) { return tw_thr[c]; });
+                for (int k = 0; k < 8; k++) dv[k] = ar.load_mid(l2[4 * k + (k >> 2)]);
+                ar.fwd8_with(dv, false, [&](int sp, int gg) { return tw[(8 << sp) - 1 + (g2 << sp) + gg]; });
 #pragma unroll
-                for (int k = 0; k < 16; k++) lds[tile_at(blk, 16 * il + k)] = ar.store_mid(ar.reduce(dv[k]));
+                for (int k = 0; k < 8; k++) l2[4 * k + (k >> 2)] = ar.store_mid(dv[k]);
+                block_sync();
+#pragma unroll
+                for (int k = 0; k < 8; k++) dv[k] = ar.load_mid(l3[136 * (k >> 2) + (k & 3)]);
+                ar.fwd4x2_with(dv, true, [&](int h, int sp, int gg) { return tw[(64 << sp) - 1 + ((t + 32 * h) << sp) + gg]; });
+#pragma unroll
+                for (int k = 0; k < 8; k++) l3[136 * (k >> 2) + (k & 3)] = ar.store_mid(dv[k]);
                 __syncthreads();
 #pragma unroll
-                for (int i = 0; i < 8; i++) {
-                    const unsigned s = src[i] & 4094u;
-                    const double x = ar.load_mid(lds[tile_at(s >> 8, s & 255u)]);
-                    const double y = ar.load_mid(lds[tile_at(s >> 8, (s & 255u) + 1)]);
-                    const bool sw = src[i] & 1u;
-                    dv[2 * i] = sw ? y : x, dv[2 * i + 1] = sw ? x : y;
-                }
+                for (int i = 0; i < 4; i++) dv[2 * i] = ar.load_mid(lds[lsx[i]]), dv[2 * i + 1] = ar.load_mid(lds[lsy[i]]);
                 __syncthreads();
             }
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                acc0[2 * i] += ar.mulmod(dv[2 * i], u2d(e0[i].x));
-                acc0[2 * i + 1] += ar.mulmod(dv[2 * i + 1], u2d(e0[i].y));
-                acc1[2 * i] += ar.mulmod(dv[2 * i], u2d(e1[i].x));
-                acc1[2 * i + 1] += ar.mulmod(dv[2 * i + 1], u2d(e1[i].y));
+            for (int i = 0; i < 4; i++) {
+                acc0[2 * i] += ar.mulmod(dv[2 * i], e0[i].x);
+                acc0[2 * i + 1] += ar.mulmod(dv[2 * i + 1], e0[i].y);
+                acc1[2 * i] += ar.mulmod(dv[2 * i], e1[i].x);
+                acc1[2 * i + 1] += ar.mulmod(dv[2 * i + 1], e1[i].y);
             }
             if ((j & 3) == 3) {
 #pragma unroll
-                for (int k = 0; k < 16; k++) acc0[k] = ar.reduce(acc0[k]), acc1[k] = ar.reduce(acc1[k]);
+                for (int k = 0; k < 8; k++) acc0[k] = ar.reduce(acc0[k]), acc1[k] = ar.reduce(acc1[k]);
             }
         }
 #pragma unroll
-        for (int k = 0; k < 16; k++) r0[k] = fp_canon(acc0[k], m.qd, m.qinvd), r1[k] = fp_canon(acc1[k], m.qd, m.qinvd);
+        for (int k = 0; k < 8; k++) r0[k] = fp_canon(acc0[k], m.qd, m.qinvd), r1[k] = fp_canon(acc1[k], m.qd, m.qinvd);
     } else {
+        // integer path: the raised digits arrive finished (NTT domain); read through the index map
+        unsigned so[4];
 #pragma unroll
-        for (int h = 0; h < 2; h++) {
-            U128 acc0[8], acc1[8];
+        for (int i = 0; i < 4; i++) {
+            const unsigned pos = (tile << 12) + pair8_at(i);
+            so[i] = ((g == 1 ? pos : galois_index(pos, g, LOGN)) & ~1u) * 8u;
+        }
+        const char *fin0 = (const char *)(ia.raised + (((size_t)op * ia.raised_stride + a) << LOGN));
 #pragma unroll
-            for (int k = 0; k < 8; k++) acc0[k] = acc1[k] = U128{0, 0};
+        for (int h = 0; h < 2; h++) { // two pairs at a time: the 128-bit accumulators of four would not fit
+            U128 acc0[4], acc1[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++) acc0[k] = acc1[k] = U128{0, 0};
             for (int j = 0; j < ia.beta; j++) {
-                const u64 *dj = j == own ? d + ((size_t)a << LOGN) : raised + (((size_t)j * Ma + a) << LOGN);
-                const u64x2 *k0 = (const u64x2 *)(evk + ((((size_t)j * 2 + 0) * M + mi) << LOGN)) + key_at;
-                const u64x2 *k1 = (const u64x2 *)(evk + ((((size_t)j * 2 + 1) * M + mi) << LOGN)) + key_at;
+                const char *dj = j == own ? d_limb : fin0 + (size_t)j * raised_step;
+                const char *kj = key0 + (size_t)j * key_step;
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    const unsigned s = src[4 * h + i];
-                    const u64x2 v = *(const u64x2 *)(dj + (s & ~1u));
-                    const bool sw = s & 1u;
+                for (int i = 0; i < 2; i++) {
+                    const int ii = 2 * h + i;
+                    const u64x2 v = ld_at<u64x2>(dj, so[ii]);
+                    const bool sw = (swm >> ii) & 1u;
                     const u64 x = sw ? v.y : v.x, y = sw ? v.x : v.y;
-                    const u64x2 ka = k0[256 * (4 * h + i)], kb = k1[256 * (4 * h + i)];
+                    const u64x2 ka = ld_at<u64x2>(kj + 8192 * ii, lane16), kb = ld_at<u64x2>(kj + comp_step + 8192 * ii, lane16);
                     mac128(acc0[2 * i], x, ka.x);
                     mac128(acc0[2 * i + 1], y, ka.y);
                     mac128(acc1[2 * i], x, kb.x);
@@ -199,25 +235,26 @@ template <int LOGN> __global__ __launch_bounds__(256) void k_inner_blocks(InnerA
                 }
             }
 #pragma unroll
-            for (int k = 0; k < 8; k++) r0[8 * h + k] = reduce128(acc0[k], m), r1[8 * h + k] = reduce128(acc1[k], m);
+            for (int k = 0; k < 4; k++) r0[4 * h + k] = reduce128(acc0[k], m), r1[4 * h + k] = reduce128(acc1[k], m);
         }
     }
-    u64 *u0 = u + (((size_t)0 * Ma + a) << LOGN), *u1 = u + (((size_t)1 * Ma + a) << LOGN);
+    u64 *u0 = ia.u + ((((size_t)op * ia.u_stride + a) << LOGN)), *u1 = u0 + ((size_t)Ma << LOGN);
     if (ia.inv_special && a >= level) {
         if (m.qd != 0.0) {
             const ArithFp ar = make_fp(T, mi, LOGN);
-            inv_blocks_from_pairs<LOGN>(r0, u0, ar, lds, bg);
-            inv_blocks_from_pairs<LOGN>(r1, u1, ar, lds, bg);
+            inv_blocks_from_pairs8<LOGN>(r0, u0, ar, lds, tile);
+            inv_blocks_from_pairs8<LOGN>(r1, u1, ar, lds, tile);
         } else {
             const ArithInt ar = make_int(T, mi, LOGN);
-            inv_blocks_from_pairs<LOGN>(r0, u0, ar, lds, bg);
-            inv_blocks_from_pairs<LOGN>(r1, u1, ar, lds, bg);
+            inv_blocks_from_pairs8<LOGN>(r0, u0, ar, lds, tile);
+            inv_blocks_from_pairs8<LOGN>(r1, u1, ar, lds, tile);
         }
     } else {
+        char *o0 = (char *)(u0 + ((size_t)tile << 12)), *o1 = (char *)(u1 + ((size_t)tile << 12));
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            ((u64x2 *)u0)[key_at + 256 * i] = u64x2{r0[2 * i], r0[2 * i + 1]};
-            ((u64x2 *)u1)[key_at + 256 * i] = u64x2{r1[2 * i], r1[2 * i + 1]};
+        for (int i = 0; i < 4; i++) {
+            *(u64x2 *)(o0 + 8192 * i + lane16) = u64x2{r0[2 * i], r0[2 * i + 1]};
+            *(u64x2 *)(o1 + 8192 * i + lane16) = u64x2{r1[2 * i], r1[2 * i + 1]};
         }
     }
 }
