@@ -58,7 +58,7 @@ class Workload:
     N_SINGLE = 128
 
     def __init__(self, he, seed: int = 2, n_hmult: int = None, n_single: int = None, n_ntt: int = None,
-                 n_streams: int = 1, hm_chunk: int = 16, group_singles: bool = True):
+                 n_streams: int = 1, hm_chunk: int = 16, single_mode: str = "levels", single_chunk: int = 32):
         import torch
 
         self.torch = torch
@@ -93,11 +93,28 @@ class Workload:
         self.single_keys = [self.offsets.index(o) for o in offs]
         self.single_in = [self._uniform_ct(lv) for lv in levels]
         self.single_out = [he.empty_ct(lv) for lv in levels]
-        # The single rotations are independent (own ciphertext, level and key each).  Those at the same level are
-        # stored back to back and issued as one call with one key per ciphertext, so that their kernels are
-        # launched once per level instead of once per rotation.
+        # The single rotations are independent (own ciphertext, level and key each).  They are issued as a server
+        # would batch independent requests: sorted by key and packed back to back, 32 per call of the mixed-level
+        # entry point ("levels", the default: every launch is shared by the 32 operations, and neighbours with the
+        # same key share its memory traffic); or one call per level with one key per ciphertext ("per-level"); or
+        # one he_hrot call each ("each").
         self.single_groups = []
-        if group_singles:
+        self.single_mode = single_mode
+        if single_mode == "levels":
+            order = sorted(range(self.n_single), key=lambda i: (self.single_keys[i], -levels[i]))
+            for lo in range(0, self.n_single, single_chunk):
+                idx = order[lo:lo + single_chunk]
+                packed = torch.cat([self.single_in[i].reshape(-1, p.N) for i in idx])
+                outs = torch.empty_like(packed)
+                at = 0
+                for i in idx:
+                    n = 2 * levels[i]
+                    self.single_in[i] = packed[at:at + n].view(2, levels[i], p.N)
+                    self.single_out[i] = outs[at:at + n].view(2, levels[i], p.N)
+                    at += n
+                self.single_groups.append(([self.rot[self.single_keys[i]] for i in idx], [int(levels[i]) for i in idx],
+                                           packed, outs))
+        elif single_mode == "per-level":
             for lv in sorted(set(levels), reverse=True):
                 # rotations that share a key sit next to each other: the inner product then reads that key once
                 idx = sorted((i for i in range(self.n_single) if levels[i] == lv), key=lambda i: self.single_keys[i])
@@ -105,7 +122,7 @@ class Workload:
                 outs = he.empty_batch(len(idx), lv)
                 for k, i in enumerate(idx):
                     self.single_in[i], self.single_out[i] = cts[k], outs[k]
-                self.single_groups.append(([self.rot[self.single_keys[i]] for i in idx], cts, outs))
+                self.single_groups.append(([self.rot[self.single_keys[i]] for i in idx], None, cts, outs))
         self.key_switches = self.n_hmult + len(self.offsets) + self.n_single
 
     def _uniform(self, mod_idx):
@@ -169,8 +186,11 @@ class Workload:
 
     def _single_one(self, i):
         if self.single_groups:
-            keys, cts, outs = self.single_groups[i]
-            self.he.hrot_batch_keys(keys, cts, out=outs)
+            keys, lv, cts, outs = self.single_groups[i]
+            if lv is None:
+                self.he.hrot_batch_keys(keys, cts, out=outs)
+            else:
+                self.he.hrot_batch_levels(keys, lv, cts, out=outs)
         else:
             self.he.hrot(self.rot[self.single_keys[i]], self.single_in[i], out=self.single_out[i])
 
@@ -431,8 +451,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-train-step", action="store_true")
     ap.add_argument("--hmult-batch", type=int, default=8, help="ciphertext pairs per batched HMult call")
-    ap.add_argument("--no-group-singles", action="store_true",
-                    help="issue every single rotation as a call of its own instead of one call per level")
+    ap.add_argument("--single-mode", choices=["levels", "per-level", "each"], default="levels",
+                    help="how the 128 single rotations are issued: 32 per mixed-level call, one call per level, or one call each")
     ap.add_argument("--streams", type=int, default=3, help="HIP streams for the independent operations of a step")
     ap.add_argument("--probe", nargs="+", metavar="ARG",
                     help="run a short profiling target instead of the benchmark: hrot-batch [SET LEVEL COUNT] | copy")
@@ -456,7 +476,7 @@ def main():
         probe(args.probe)
         return
     he = pkg.HE.from_params(wl.N16, device=0)
-    w = Workload(he, n_streams=args.streams, hm_chunk=args.hmult_batch, group_singles=not args.no_group_singles)
+    w = Workload(he, n_streams=args.streams, hm_chunk=args.hmult_batch, single_mode=args.single_mode)
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()
@@ -543,7 +563,9 @@ def main():
             "key_switches_per_step": w.key_switches,
             "streams": args.streams,
             "hmult_batch": args.hmult_batch,
-            "single_hrot_calls": "one call per level (one key per ciphertext)" if w.single_groups else "one call each",
+            "single_hrot_calls": {"levels": "32 rotations of mixed levels per call, sorted by key",
+                                  "per-level": "one call per level (one key per ciphertext)",
+                                  "each": "one call each"}[args.single_mode],
         },
         "detail": detail,
         "roofline": roofline,

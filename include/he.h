@@ -274,6 +274,16 @@ int32_t he_hrot_batch(he_ctx *ctx, const he_evk *rot, const uint64_t *d_ct, uint
  * a workspace for fewer operations than that (at least one) makes the groups smaller. */
 int32_t he_hrot_batch_keys(he_ctx *ctx, const he_evk *const *rots, const uint64_t *d_ct, uint64_t *d_out, int32_t level,
                            int32_t count, void *d_ws, size_t ws_bytes, void *stream);
+/* Rotate (Section 2.2) of `count` independent ciphertexts at mixed levels in shared launches: operation o is a
+ * level-h_levels[o] ciphertext (host array) with its own key rots[o].  The ciphertexts are packed back to back at
+ * d_ct (operation o starts sum_{o' < o} 2 h_levels[o'] limbs in) and the results are packed the same way at
+ * d_out, which must not overlap d_ct.  Bit-identical to he_hrot(rots[o], ct o, level h_levels[o]).  Operations
+ * are processed in groups of at most 32 that share every launch; a group's buffers are laid out for its largest
+ * level, so the workspace must hold at least he_workspace_bytes(largest level, 1) and a workspace of
+ * he_workspace_bytes(largest level, 32) gives full groups.  Neighbouring operations with the same key share its
+ * memory traffic: sort the operations by key. */
+int32_t he_hrot_batch_levels(he_ctx *ctx, const he_evk *const *rots, const int32_t *h_levels, const uint64_t *d_ct,
+                             uint64_t *d_out, int32_t count, void *d_ws, size_t ws_bytes, void *stream);
 /* n_rot sequential rotate-and-add steps applied to every ciphertext of the batch, in place */
 int32_t he_rotate_sum_batch(he_ctx *ctx, const he_evk *const *rots, int32_t n_rot, uint64_t *d_ct, int32_t level,
                             int32_t count, void *d_ws, size_t ws_bytes, void *stream);

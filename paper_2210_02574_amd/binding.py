@@ -33,7 +33,7 @@ SYMBOLS = [
     "he_ntt", "he_intt", "he_add", "he_sub", "he_pmult", "he_cmult", "he_add_const", "he_moddrop",
     "he_hmult_relin", "he_hmult_relin_rescale", "he_rescale", "he_hrot", "he_hrot_many", "he_rotate_sum",
     "he_add_batch", "he_sub_batch", "he_pmult_batch", "he_cmult_batch", "he_add_const_batch", "he_moddrop_batch",
-    "he_hmult_relin_batch", "he_hmult_relin_rescale_batch", "he_rescale_batch", "he_hrot_batch", "he_hrot_batch_keys", "he_rotate_sum_batch",
+    "he_hmult_relin_batch", "he_hmult_relin_rescale_batch", "he_rescale_batch", "he_hrot_batch", "he_hrot_batch_keys", "he_hrot_batch_levels", "he_rotate_sum_batch",
     "he_hrot_noalloc",
     "he_profile_start", "he_profile_stop",
 ]
@@ -132,6 +132,7 @@ def load_library() -> ctypes.CDLL:
             "he_rescale_batch": [vp, vp, vp, i32, i32, vp, sz, vp],
             "he_hrot_batch": [vp, vp, vp, vp, i32, i32, vp, sz, vp],
             "he_hrot_batch_keys": [vp, vp, vp, vp, i32, i32, vp, sz, vp],
+            "he_hrot_batch_levels": [vp, vp, vp, vp, vp, i32, vp, sz, vp],
             "he_rotate_sum_batch": [vp, vp, i32, vp, i32, i32, vp, sz, vp],
             "he_profile_start": [vp],
             "he_profile_stop": [vp, vp, i32, ctypes.POINTER(i32)],
@@ -664,6 +665,23 @@ class HE:
         ws, wsb = self._workspace(level, min(count, 32))
         self._chk(self.lib.he_hrot_batch_keys(self.ctx, keys, self._dp(cts), self._dp(out), level, count, ws, wsb,
                                               self._stream()), "he_hrot_batch_keys")
+        return out
+
+    def hrot_batch_levels(self, rots: Sequence[EvalKey], levels: Sequence[int], packed, out=None):
+        """Rotate ciphertexts of mixed levels packed back to back (`packed`: flat [sum 2 level_o][N] tensor),
+        operation o with key rots[o]; returns the results packed the same way."""
+        import torch
+
+        lv = np.ascontiguousarray(levels, dtype=np.int32)
+        count = lv.shape[0]
+        if len(rots) != count:
+            raise ValueError("one key per ciphertext")
+        assert packed.dim() == 2 and packed.shape[1] == self.N and int(packed.shape[0]) == 2 * int(lv.sum())
+        out = torch.empty_like(packed) if out is None else out
+        keys = (ctypes.c_void_p * count)(*[k.handle for k in rots])
+        ws, wsb = self._workspace(int(lv.max()), min(count, 32))
+        self._chk(self.lib.he_hrot_batch_levels(self.ctx, keys, _hp(lv), self._dp(packed), self._dp(out), count, ws, wsb,
+                                                self._stream()), "he_hrot_batch_levels")
         return out
 
     def rotate_sum_batch(self, rots: Sequence[EvalKey], cts):

@@ -273,19 +273,20 @@ struct LimbList {
     int size() const { return (int)slot.size(); }
 };
 
-// calls launch(batch, count) for chunks of at most HE_MAXB limbs; limbs on the integer path (moduli
-// of 2^50 and above) take about three times longer and are scheduled first
+// calls launch(batch, count) for chunks of at most HE_MAXB limbs; within a chunk the limbs on the integer path
+// (moduli of 2^50 and above) take about three times longer and are scheduled first, so that the others fill in
+// behind them
 template <class F> static int32_t for_batches(he_ctx *c, const LimbList &l, F launch)
 {
     const int total = l.size();
-    std::vector<int> order(total);
-    for (int b = 0; b < total; b++) order[b] = b;
-    std::stable_partition(order.begin(), order.end(), [&](int b) { return c->modc[l.mod[b]].qd == 0.0; });
+    std::vector<int> order(HE_MAXB);
     for (int off = 0; off < total; off += HE_MAXB) {
         const int nb = std::min(HE_MAXB, total - off);
+        for (int b = 0; b < nb; b++) order[b] = off + b;
+        std::stable_partition(order.begin(), order.begin() + nb, [&](int b) { return c->modc[l.mod[b]].qd == 0.0; });
         LimbBatch lb;
         for (int b = 0; b < nb; b++) {
-            const int o = order[off + b];
+            const int o = order[b];
             lb.slot[b] = (uint16_t)l.slot[o];
             lb.src[b] = (uint16_t)l.src[o];
             lb.mod[b] = (uint8_t)l.mod[o];
@@ -311,6 +312,7 @@ static ConvArgs conv_args(const he_ctx *c, const u64 *src, int level, int dst_st
     cv.src2_stride = 0;
     cv.rs_mod = level - 1;
     cv.rs_nl = level - 1;
+    memset(cv.op_level, 0, sizeof(cv.op_level));
     return cv;
 }
 
@@ -344,7 +346,7 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
     const bool wide = std::max(c->alpha, c->K) > 4;
     const double N8 = (double)c->N * 8.0;
     const DevLaunch &dl = dev_launch(c);
-    return for_batches(c, l, [&](const LimbBatch &lb, int nb) {
+    int32_t rc = for_batches(c, l, [&](const LimbBatch &lb, int nb) {
         const double cols_bytes = pro == PRO_LOAD ? 2.0 * nb * N8 : (double)(src_limbs + nb) * N8;
         const int kid_cols = pro == PRO_LOAD      ? KID_FWD_COLS
                              : pro == PRO_MODUP   ? KID_FWD_COLS_MODUP
@@ -356,13 +358,16 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
             // reads the transform's input, the minuend and the addend, writes the result
             const double b = (double)nb * N8 * (3.0 + (fin->mode == 1 || fin->mode == 3 ? 1.0 : fin->mode == 2 ? 0.5 : fin->mode == 4 ? 1.5 : 0.0));
             dl.fwd_blocks(c, st, b, true, data, lb, nb, *fin, ho);
-        } else {
-            int nbb = nb; // integer-path limbs come first in a batch
-            if (int_blocks_only)
-                for (nbb = 0; nbb < nb && c->modc[lb.mod[nbb]].qd == 0.0;) nbb++;
-            if (nbb == 0) return;
-            dl.fwd_blocks(c, st, 2.0 * nbb * N8, false, data, lb, nbb, kNoFin, kNoHoistOuts);
-        }
+        } else if (!int_blocks_only)
+            dl.fwd_blocks(c, st, 2.0 * nb * N8, false, data, lb, nb, kNoFin, kNoHoistOuts);
+    });
+    if (rc != HE_OK || !int_blocks_only) return rc;
+    // block pass of the integer-path limbs alone, after all column passes: few launches, each as large as possible
+    LimbList li;
+    for (int b = 0; b < l.size(); b++)
+        if (c->modc[l.mod[b]].qd == 0.0) li.add(l.slot[b], l.src[b], l.mod[b]);
+    return for_batches(c, li, [&](const LimbBatch &lb, int nb) {
+        dl.fwd_blocks(c, st, 2.0 * nb * N8, false, data, lb, nb, kNoFin, kNoHoistOuts);
     });
 }
 
@@ -900,6 +905,111 @@ extern "C" int32_t he_hrot_batch_keys(he_ctx *ctx, const he_evk *const *rots, co
         fa.hoisted = 1;
         if ((rc = ntt_forward(ctx, st, ws + w.r * N, lr, PRO_MODDOWN, cv, &fa, 2 * ctx->K * nb, false, &ho)) != HE_OK)
             return rc;
+        r += nb;
+    }
+    return HE_OK;
+}
+
+// Rotations at mixed levels in shared launches.  The buffers of every operation are laid out for the largest
+// level of its group (workspace stride, limbs per raised digit and per component), an operation below that
+// level simply has no limbs between its own level and the layout's, and fewer digits.
+extern "C" int32_t he_hrot_batch_levels(he_ctx *ctx, const he_evk *const *rots, const int32_t *h_levels, const uint64_t *d_ct,
+                                        uint64_t *d_out, int32_t count, void *d_ws, size_t ws_bytes, void *stream)
+{
+    if (!rots || !h_levels || count < 1) return HE_EINVAL;
+    int32_t rc;
+    int lmax_all = 0;
+    for (int r = 0; r < count; r++) {
+        if ((rc = level_guard(ctx, h_levels[r])) != HE_OK) return rc;
+        lmax_all = std::max(lmax_all, (int)h_levels[r]);
+    }
+    for (int r = 0; r < count; r++) {
+        if ((rc = ks_guard(ctx, rots[r], lmax_all, 1, d_ws, ws_bytes)) != HE_OK) return rc;
+        if (rots[r]->galois == 1) return HE_ENOKEY;
+    }
+    if (!d_ct || !d_out || d_ct == d_out || misaligned16(d_ct) || misaligned16(d_out)) return HE_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    u64 *ws = (u64 *)d_ws;
+    const size_t N = ctx->N;
+    const int K = ctx->K, alpha = ctx->alpha, L = ctx->L;
+    size_t done_limbs = 0; // limbs of the operations already processed (inputs and outputs are packed alike)
+    for (int r = 0; r < count;) {
+        // group: as many operations as the workspace holds at the layout of their largest level
+        int nb = 0, lmax = 0;
+        while (r + nb < count && nb < HOIST_MAX) {
+            const int lm = std::max(lmax, (int)h_levels[r + nb]);
+            const WsLayout wl = ws_layout(ctx, lm);
+            if (!batch_fits(wl, nb + 1) || wl.total * (size_t)(nb + 1) * N * sizeof(u64) > ws_bytes) break;
+            lmax = lm, nb++;
+        }
+        if (nb == 0) return HE_EWORKSPACE;
+        const WsLayout w = ws_layout(ctx, lmax);
+        const int W = (int)w.total, Ma = lmax + K;
+        const u64 *in0 = d_ct + done_limbs * N;
+        u64 *out0 = d_out + done_limbs * N;
+        std::vector<size_t> off(nb + 1, 0); // limb offset of operation o within the group
+        for (int o = 0; o < nb; o++) off[o + 1] = off[o] + 2 * (size_t)h_levels[r + o];
+        if (off[nb] > 65535) return HE_EINVAL;
+        ConvArgs cv = conv_args(ctx, ws + w.x * N, lmax, W, W);
+        HoistKeys hk = {};
+        HoistOuts ho = {};
+        for (int o = 0; o < nb; o++) {
+            const int lo = h_levels[r + o];
+            cv.op_level[o] = hk.level[o] = ho.cstride[o] = (uint8_t)lo;
+            hk.evk[o] = rots[r + o]->dev;
+            hk.g[o] = ho.g[o] = (unsigned)rots[r + o]->galois;
+            hk.d[o] = in0 + (off[o] + lo) * N; // c1
+            ho.add[o] = in0 + off[o] * N;      // c0
+            ho.out[o] = out0 + off[o] * N;
+        }
+        // 1. inverse transform of every c1 limb, scaled for its digit's conversion
+        LimbList l;
+        for (int o = 0; o < nb; o++)
+            for (int i = 0; i < h_levels[r + o]; i++) l.add(o * W + i, (int)(off[o] + h_levels[r + o] + i), i);
+        if ((rc = ntt_inverse(ctx, st, in0, ws + w.x * N, l, SCALE_MODUP, cv)) != HE_OK) return rc;
+        // 2. raised digits
+        LimbList rl;
+        int src_limbs = 0;
+        for (int o = 0; o < nb; o++) {
+            const int lo = h_levels[r + o], beta = (lo + alpha - 1) / alpha;
+            src_limbs += lo;
+            for (int j = 0; j < beta; j++) {
+                const int dlo = j * alpha, dhi = std::min(dlo + alpha, lo);
+                for (int a = 0; a < Ma; a++) {
+                    if ((a >= dlo && a < dhi) || (a >= lo && a < lmax)) continue;
+                    rl.add(o * W + j * Ma + a, a < lmax ? a : L + (a - lmax));
+                }
+            }
+        }
+        if ((rc = ntt_forward(ctx, st, ws + w.raised * N, rl, PRO_MODUP, cv, nullptr, src_limbs, true)) != HE_OK) return rc;
+        // 3. inner products (block pass of the special limbs' inverse transform included) and 4. its column pass
+        if (misaligned16(ws)) return HE_EINVAL;
+        InnerArgs ia;
+        ia.raised = ws + w.raised * N, ia.d = in0, ia.evk = rots[r]->dev, ia.u = ws + w.u * N;
+        ia.level = lmax, ia.L = L, ia.K = K, ia.alpha = alpha, ia.beta = (lmax + alpha - 1) / alpha;
+        ia.g = 1u, ia.raised_stride = W, ia.u_stride = W, ia.d_stride = 0, ia.inv_special = 1, ia.hoisted = 1, ia.count = nb;
+        double inner_bytes = 0.0;
+        for (int o = 0; o < nb; o++) {
+            const int lo = h_levels[r + o], beta = (lo + alpha - 1) / alpha;
+            inner_bytes += (double)(3 * beta + 2) * (lo + K) * N * 8.0;
+        }
+        dev_launch(ctx).inner(ctx, st, inner_bytes, inner_grid((unsigned)(N / 4096), (unsigned)Ma, (unsigned)nb), ia, hk);
+        if ((rc = launch_ok(ctx)) != HE_OK) return rc;
+        LimbList sp;
+        for (int o = 0; o < nb; o++)
+            for (int cc = 0; cc < 2; cc++)
+                for (int k = 0; k < K; k++) sp.add(o * W + cc * Ma + lmax + k, L + k);
+        const ConvArgs cu = conv_args(ctx, ws + w.u * N, lmax, W, W);
+        if ((rc = ntt_inverse(ctx, st, ws + w.u * N, ws + w.u * N, sp, SCALE_MODDOWN, cu, true)) != HE_OK) return rc;
+        // 5. ModDown: corrections transformed and applied, plus the rotated c0
+        LimbList lr;
+        for (int o = 0; o < nb; o++)
+            for (int cc = 0; cc < 2; cc++)
+                for (int i = 0; i < h_levels[r + o]; i++) lr.add(o * W + cc * lmax + i, i);
+        FinArgs fa = fin_args(ws + w.u * N, nullptr, in0, ctx->dev.dn_pinv, ctx->dev.dn_pinv_d, Ma, lmax, 2, 1u, W, W, 0, 0);
+        fa.hoisted = 1;
+        if ((rc = ntt_forward(ctx, st, ws + w.r * N, lr, PRO_MODDOWN, cu, &fa, 2 * K * nb, false, &ho)) != HE_OK) return rc;
+        done_limbs += off[nb];
         r += nb;
     }
     return HE_OK;

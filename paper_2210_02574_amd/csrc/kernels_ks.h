@@ -28,10 +28,14 @@ struct InnerArgs {
     int hoisted; // operation z uses key and Galois element z of the HoistKeys argument (one raised input for all)
     int count;   // operations in this launch
 };
-#define HOIST_MAX 32
+#define HOIST_MAX HE_OPS_MAX
 struct HoistKeys {
     const u64 *evk[HOIST_MAX];
     unsigned g[HOIST_MAX];
+    // mixed-level rotations: the operation's level (0: InnerArgs.level, which always gives the buffer layout)
+    // and its NTT-domain input polynomial (null: InnerArgs.d + operation * d_stride)
+    const u64 *d[HOIST_MAX];
+    uint8_t level[HOIST_MAX];
 };
 
 // One-dimensional grid of inner_grid() work-groups; every buffer is 16-byte aligned.  Work-groups go to the
@@ -106,6 +110,10 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
     const int a = Ma - 1 - (int)(tl / ntile); // special limbs (the slowest) first
     const unsigned tile = tl % ntile;
     const unsigned g = ia.hoisted ? hk.g[op] : ia.g;
+    // an operation below the layout's level has no limbs a in [its level, level) and fewer digits
+    const int op_level = ia.hoisted && hk.level[op] ? hk.level[op] : level;
+    if (a < level && a >= op_level) return;
+    const int beta = (op_level + ia.alpha - 1) / ia.alpha;
     const int mi = active_mod(a, level, ia.L);
     const int own = a < level ? a / ia.alpha : -1;
     const ModConst m = T.mod[mi];
@@ -115,7 +123,7 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
     // raised_step / key_step further on, key component 1 comp_step after component 0
     const char *raised0 = (const char *)(ia.raised + ((((size_t)op * ia.raised_stride + a) << LOGN) + ((size_t)tile_in << 12)));
     const char *key0 = (const char *)((ia.hoisted ? hk.evk[op] : ia.evk) + (((size_t)mi << LOGN) + ((size_t)tile << 12)));
-    const char *d_limb = (const char *)(ia.d + (((size_t)op * ia.d_stride + a) << LOGN));
+    const char *d_limb = (const char *)((ia.hoisted && hk.d[op] ? hk.d[op] : ia.d + (((size_t)op * ia.d_stride) << LOGN)) + ((size_t)a << LOGN));
     const size_t raised_step = ((size_t)Ma << LOGN) * 8, comp_step = ((size_t)M << LOGN) * 8, key_step = 2 * comp_step;
     const unsigned lane16 = threadIdx.x * 16u;        // this thread's pair within a 512-pair row of the tile
     const unsigned lane_mid = (blk * 256u + t) * 8u;  // element t of block blk
@@ -144,7 +152,7 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
         double acc0[8], acc1[8];
 #pragma unroll
         for (int k = 0; k < 8; k++) acc0[k] = acc1[k] = 0.0;
-        for (int j = 0; j < ia.beta; j++) {
+        for (int j = 0; j < beta; j++) {
             double dv[8];
             f64x2 e0[4], e1[4]; // key words of a floating-point limb are balanced doubles
             const char *kj = key0 + (size_t)j * key_step;
@@ -218,7 +226,7 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
             U128 acc0[4], acc1[4];
 #pragma unroll
             for (int k = 0; k < 4; k++) acc0[k] = acc1[k] = U128{0, 0};
-            for (int j = 0; j < ia.beta; j++) {
+            for (int j = 0; j < beta; j++) {
                 const char *dj = j == own ? d_limb : fin0 + (size_t)j * raised_step;
                 const char *kj = key0 + (size_t)j * key_step;
 #pragma unroll

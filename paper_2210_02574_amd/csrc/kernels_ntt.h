@@ -24,6 +24,8 @@
 #include "arith.h"
 
 #define HE_MAXB 512
+// operations per launch that can carry a key, a Galois element, a level and pointers of their own
+#define HE_OPS_MAX 32
 // A launch works on up to HE_MAXB limbs: limb b is written at dst + slot[b]*N, read (inverse block
 // pass only) at src + src[b]*N, and uses modulus index mod[b].
 struct LimbBatch {
@@ -49,7 +51,17 @@ struct ConvArgs {
     int src2_stride;
     // centred-limb prologue (rescale, ModRaise): modulus index of the source limb, limbs per component in dst
     int rs_mod, rs_nl;
+    // Operations of one launch at different levels (mixed-level rotations): op_level[o] != 0 is the level of
+    // operation o, while `level` stays the level the buffers are laid out for (the largest of the launch).
+    uint8_t op_level[HE_OPS_MAX];
 };
+// level of the operation that owns destination slot `slot`
+__device__ __forceinline__ int conv_op_level(const ConvArgs &cv, unsigned slot)
+{
+    const unsigned op = slot / (unsigned)cv.dst_stride;
+    const int l = op < HE_OPS_MAX ? cv.op_level[op] : 0;
+    return l ? l : cv.level;
+}
 
 // A limb's slot within its operation decodes as component c = slot / nl, limb i = slot % nl.
 struct FinArgs {
@@ -106,6 +118,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
     S.pm_d = 0.0;
     S.tp = nullptr;
     const int M = cv.L + cv.K, Ma = cv.level + cv.K;
+    const int op_level = conv_op_level(cv, slot);
     const unsigned op = slot / (unsigned)cv.dst_stride;
     slot -= op * (unsigned)cv.dst_stride;
     const u64 *src = cv.src + (((size_t)op * cv.src_stride) << LOGN);
@@ -118,7 +131,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
     }
     if (PRO == PRO_MODUP) {
         const int j = slot / Ma;
-        const int lo = j * cv.alpha, hi = min(lo + cv.alpha, cv.level);
+        const int lo = j * cv.alpha, hi = min(lo + cv.alpha, op_level);
         const int ns = hi - lo;
         const size_t cs = ((size_t)j * cv.alpha + (ns - 1)) * cv.alpha;
 #pragma unroll
@@ -236,10 +249,14 @@ __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithIn
 
 // ---- epilogue: what the forward block pass does with a finished (canonical) NTT value ---------------------
 
-#define HOIST_OUT_MAX 32
+#define HOIST_OUT_MAX HE_OPS_MAX
 struct HoistOuts {
     u64 *out[HOIST_OUT_MAX];
     unsigned g[HOIST_OUT_MAX];
+    // mixed-level rotations: the operation's input c0 limbs (mode 2 addend) and the limbs per component of its
+    // output; null / 0: the launch-wide values of FinArgs
+    const u64 *add[HOIST_OUT_MAX];
+    uint8_t cstride[HOIST_OUT_MAX];
 };
 
 // Operands of the epilogue for one output: issued before the transform so that the loads overlap it.
@@ -258,8 +275,10 @@ __device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, const HoistOu
     o.av = 0;
     if (fa.mode == 1)
         o.av = fa.out[(((size_t)op * fa.out_stride + (size_t)c * fa.out_cstride + i) << LOGN) + pos];
-    else if (fa.mode == 2 && c == 0)
-        o.av = fa.add[(((size_t)op * fa.add_stride + i) << LOGN) + galois_index(pos, fa.hoisted ? ho.g[op] : fa.g, LOGN)];
+    else if (fa.mode == 2 && c == 0) {
+        const u64 *add = fa.hoisted && ho.add[op] ? ho.add[op] : fa.add + (((size_t)op * fa.add_stride) << LOGN);
+        o.av = add[((size_t)i << LOGN) + galois_index(pos, fa.hoisted ? ho.g[op] : fa.g, LOGN)];
+    }
     else if (fa.mode == 3)
         o.av = fa.add[(((size_t)op * fa.add_stride + (size_t)c * fa.add_cstride + i) << LOGN) + pos];
     else if (fa.mode == 4) {
@@ -279,7 +298,8 @@ __device__ __forceinline__ void fin_store(const FinArgs &fa, const HoistOuts &ho
     slot -= op * (unsigned)fa.dst_stride;
     const unsigned c = slot / fa.nl, i = slot % fa.nl;
     const ModConst m = T.mod[i];
-    const size_t o = (((size_t)op * fa.out_stride + (size_t)c * fa.out_cstride + i) << LOGN) + pos;
+    const unsigned out_cstride = fa.hoisted && ho.cstride[op] ? ho.cstride[op] : (unsigned)fa.out_cstride;
+    const size_t o = (((size_t)op * fa.out_stride + (size_t)c * out_cstride + i) << LOGN) + pos;
     const bool scaled = fa.mode == 3 && fa.cst2 != nullptr;
     u64 res;
     if (FP) {
@@ -614,14 +634,14 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols17(u64 *__restrict__ data, 
 }
 
 // extra constant of the inverse column pass for modulus index mi
-__device__ __forceinline__ void scale_consts(int scale, const ConvArgs &cv, const DevTables &T, unsigned mi,
+__device__ __forceinline__ void scale_consts(int scale, const ConvArgs &cv, const DevTables &T, unsigned mi, unsigned slot,
                                              ShoupConst &ci, double &cd)
 {
     ci = ShoupConst{0, 0};
     cd = 0.0;
     if (scale == SCALE_MODUP) {
         const int j = mi / cv.alpha, ii = mi - j * cv.alpha;
-        const int na = min(cv.alpha, cv.level - j * cv.alpha);
+        const int na = min(cv.alpha, conv_op_level(cv, slot) - j * cv.alpha);
         const size_t idx = ((size_t)j * cv.alpha + (na - 1)) * cv.alpha + ii;
         ci = T.up_inv[idx];
         cd = T.up_inv_d[idx];
@@ -641,7 +661,7 @@ __device__ __forceinline__ void inv_cols_kernel(u64 *__restrict__ data, const De
     u64 *limb = data + ((size_t)lb.slot[b] << LOGN);
     ShoupConst ci;
     double cd;
-    scale_consts(SCALE, cv, T, mi, ci, cd);
+    scale_consts(SCALE, cv, T, mi, lb.slot[b], ci, cd);
     if (T.mod[mi].qd != 0.0)
         inv_cols_body<LOGN>(limb, tile * 16, make_fp(T, mi, LOGN, cd), lds);
     else
@@ -712,7 +732,7 @@ __global__ __launch_bounds__(256) void k_ntt_inv_cols12(u64 *__restrict__ data, 
     u64 *limb = data + ((size_t)lb.slot[blockIdx.x] << 12);
     ShoupConst ci;
     double cd;
-    scale_consts(SCALE, cv, T, mi, ci, cd);
+    scale_consts(SCALE, cv, T, mi, lb.slot[blockIdx.x], ci, cd);
     if (T.mod[mi].qd != 0.0)
         inv_cols12_body(limb, make_fp(T, mi, 12, cd));
     else

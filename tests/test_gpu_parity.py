@@ -220,6 +220,44 @@ def test_hrot_every_digit_count_at_full_size(env):
         assert np.array_equal(he.to_host(he.hrot(key, he.to_device(ct))), o.hrot(ct, evk, r)), level
 
 
+def test_hrot_mixed_levels_in_one_call(env):
+    """Rotations at different levels through one call (shared launches, buffers laid out for the largest level of
+    a group): every output against the oracle's rotation of that ciphertext at its own level.  Levels span full and
+    partial last digits, a one-limb ciphertext, repeated keys next to each other, and the largest level not first."""
+    import torch
+
+    he, o, p = env.he, env.o, env.params
+    if p.logN == 16:
+        levels, rots = [17, 24, 24, 12, 8, 3, 1, 9, 21], [1, 1, 64, 64, 64, 1 << 14, 2, 2, 1]
+    elif p.logN == 17:
+        levels, rots = [7, 30, 1, 12], [1, 1, 4, 4]
+    else:
+        levels = [min(l, p.L) for l in (2, 3, 1, 3, 2)]
+        rots = [1, 1, 5, 5, p.N // 4]
+    keys = {r: env.synth_key(540 + k, o.galois_element(r)) for k, r in enumerate(sorted(set(rots)))}
+    cts = [wl.uniform_ct(690 + k, p, lv) for k, lv in enumerate(levels)]
+    packed = torch.cat([he.to_device(c).reshape(-1, p.N) for c in cts])
+    out = he.hrot_batch_levels([keys[r][0] for r in rots], levels, packed)
+    got = he.to_host(out)
+    at = 0
+    for k, (lv, r, ct) in enumerate(zip(levels, rots, cts)):
+        want = o.hrot(ct, keys[r][1], r)
+        assert np.array_equal(got[at:at + 2 * lv].reshape(2, lv, p.N), want), (k, lv, r)
+        at += 2 * lv
+    assert np.array_equal(he.to_host(packed), np.concatenate([c.reshape(-1, p.N) for c in cts]))  # inputs untouched
+    # a workspace that holds one operation only: groups of one, same results
+    import ctypes
+
+    lv32 = np.ascontiguousarray(levels, dtype=np.int32)
+    handles = (ctypes.c_void_p * len(levels))(*[keys[r][0].handle for r in rots])
+    out1 = torch.zeros_like(packed)
+    ws, _ = he._workspace(max(levels), 1)
+    rc = he.lib.he_hrot_batch_levels(he.ctx, handles, ctypes.c_void_p(lv32.ctypes.data), ctypes.c_void_p(packed.data_ptr()),
+                                     ctypes.c_void_p(out1.data_ptr()), len(levels), ws, he.workspace_bytes(max(levels), 1), None)
+    assert rc == 0
+    assert torch.equal(out1, out)
+
+
 def test_patterned_inputs_through_the_key_switch(env):
     """Residues at the ends of their ranges (all q-1, all (q-1)/2, alternating 0 / q-1, within 1000 of q) through
     Mult, the fused Mult + rescale and Rotate: the lazy ranges of both arithmetic paths at their widest."""
