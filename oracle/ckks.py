@@ -37,7 +37,7 @@ def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=gnu11", "-o", tmp, _SRC, "-lm"]
+            ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-std=gnu11", "-o", tmp, _SRC, "-lm"]
         )
         os.replace(tmp, _LIB)
     return _LIB
@@ -391,6 +391,11 @@ class Oracle:
         out = np.empty((3, level, self.N), dtype=np.uint64)
         self.lib.orc_tensor(self.ctx, _p(a, _u64p), _p(b, _u64p), level, _p(out, _u64p))
         return out
+
+    def set_exact(self, exact: bool):
+        """Selects the corrected base conversions (ModUp to [x]_D, ModDown to the rounded quotient) for every
+        key switch of this context; off by default."""
+        self.lib.orc_set_exact(self.ctx, 1 if exact else 0)
 
     def modup(self, x_coeff):
         x = np.ascontiguousarray(x_coeff, dtype=np.uint64)

@@ -105,6 +105,7 @@ typedef struct {
     u64 *ipsi_br; /* [M][N]  psi^{-brv(i)} */
     u64 *ninv;    /* [M] N^{-1} */
     u64 cdt[38];  /* discrete-Gaussian cumulative thresholds, set by caller */
+    int exact;    /* 0: fast (uncorrected) base conversions; 1: corrected ones (see orc_set_exact) */
 } orc_ctx;
 
 /* Context: moduli q_0..q_{L-1}, p_0..p_{K-1}; for each modulus t the root is
@@ -166,6 +167,19 @@ u64 orc_modulus(const orc_ctx *c, int i) { return c->mod[i]; }
 u64 orc_psi(const orc_ctx *c, int i) { return c->psi[i]; }
 int orc_alpha(const orc_ctx *c) { return c->alpha; }
 void orc_set_cdt(orc_ctx *c, const u64 *cdt) { memcpy(c->cdt, cdt, sizeof(c->cdt)); }
+/* Selects the corrected form of both base conversions (a separately specified variant, off by default).
+ * The multiple v of the source modulus that the fast conversion leaves in its result is estimated in
+ * double precision and taken out:
+ *   ModUp:   v = floor(s),  s = sum over the digit's limbs, in order, of (double)y_i * (1.0 / (double)q_i);
+ *            out_t = sum_i y_i [qhat_i]_t - v [D]_t  mod t, so the raised value is [x]_D in [0, D)
+ *   ModDown: v = rint(s),   s = sum over k, in order, of (double)y'_k * (1.0 / (double)p_k), y'_k the centred digit;
+ *            r_i = sum_k y'_k [Phat_k]_{q_i} - v [P]_{q_i}  mod q_i, so r is the centred [u]_P and the result
+ *            (u - r)/P is u/P rounded to nearest
+ * Every product and sum of s is one IEEE double operation (no fused multiply-add), rint rounds halves to even.
+ * When the exact sum lies within the rounding error of s (about 2^-50) of an integer (ModUp) or of a half
+ * (ModDown), v can be one off and the result is the exact one plus or minus one source modulus: still a valid
+ * conversion, and the same on every implementation that follows this definition. */
+void orc_set_exact(orc_ctx *c, int exact) { c->exact = exact; }
 
 /* index of the modulus held by active limb a at level lvl:
  * a < lvl -> q_a, otherwise special prime p_{a-lvl}. */
@@ -653,6 +667,19 @@ void orc_modup(const orc_ctx *c, const u64 *x, int lvl, u64 *out)
                 for (u64 n = 0; n < N; n++)
                     o[n] = addmod(o[n], mulmod(y[(u64)ii * N + n] % t, qhat_t, t), t);
             }
+            if (c->exact) { /* take out v D, v = floor(sum_i y_i / q_i) in double precision */
+                u64 D_t = 1;
+                for (int i2 = lo; i2 < hi; i2++) D_t = mulmod(D_t, c->mod[i2] % t, t);
+                for (u64 n = 0; n < N; n++) {
+                    double sum = 0.0; /* built with -ffp-contract=off: one IEEE rounding per operation */
+                    for (int ii = 0; ii < na; ii++) {
+                        double rq = 1.0 / (double)c->mod[lo + ii];
+                        sum = sum + (double)y[(u64)ii * N + n] * rq;
+                    }
+                    u64 v = (u64)floor(sum);
+                    o[n] = submod(o[n], mulmod(v, D_t, t), t);
+                }
+            }
         }
         free(y);
     }
@@ -703,6 +730,22 @@ void orc_moddown(const orc_ctx *c, const u64 *u, int lvl, u64 *out)
                 else
                     term = mulmod(yk % qi, phat_q, qi);
                 r[n] = addmod(r[n], term, qi);
+            }
+        }
+        if (c->exact) { /* take out v P, v = rint(sum_k y'_k / p_k) in double precision, y' the centred digits */
+            for (u64 n = 0; n < N; n++) {
+                double sum = 0.0;
+                for (int k = 0; k < K; k++) {
+                    u64 pk = c->mod[L + k], yk = y[(u64)k * N + n];
+                    double rp = 1.0 / (double)pk;
+                    double yc = yk > (pk - 1) / 2 ? -(double)(pk - yk) : (double)yk;
+                    sum = sum + yc * rp;
+                }
+                double v = rint(sum);
+                if (v >= 0.0)
+                    r[n] = submod(r[n], mulmod((u64)v, Pmod, qi), qi);
+                else
+                    r[n] = addmod(r[n], mulmod((u64)(-v), Pmod, qi), qi);
             }
         }
         orc_ntt(c, i, r);

@@ -325,6 +325,76 @@ def _moddown_pin(o, level):
     assert max(errs) > 0.5 and min(errs) < -0.5 and abs(sum(errs) / len(errs)) < 0.25
 
 
+def test_exact_modup_is_the_residue_of_the_digit_itself(orc):
+    """Corrected ModUp (the selectable variant): raised digit = [x]_D in [0, D), for every target modulus, and it
+    differs from the fast conversion by exactly the k D the latter leaves in (k = floor(sum_i y_i / q_i))."""
+    for o, levels in ((tiny(orc, logN=3, L=5, K=2, dnum=2, qbits=20, pbits=24), (5, 4, 2)),
+                      (tiny(orc, logN=3, L=11, K=5, dnum=2, qbits=20, pbits=28), (11, 8, 5))):
+        for level in levels:
+            x = wl.uniform_limbs(level, wl.Params("t", 3, tuple(o.q), tuple(o.p), 2), list(range(level)))
+            fast = o.modup(x)
+            o.set_exact(True)
+            out = o.modup(x)
+            o.set_exact(False)
+            act = o.active_moduli(level)
+            seen_k = set()
+            for j in range(-(-level // o.alpha)):
+                C = list(range(j * o.alpha, min((j + 1) * o.alpha, level)))
+                qs = [o.q[i] for i in C]
+                D = prod(qs)
+                for n in range(o.N):
+                    xD = crt([x[i][n] for i in C], qs)
+                    big = sum(int(x[i][n]) * pow(D // o.q[i], -1, o.q[i]) % o.q[i] * (D // o.q[i]) for i in C)
+                    k = (big - xD) // D
+                    seen_k.add(k)
+                    for a, mi in enumerate(act):
+                        t = o.moduli[mi]
+                        want = x[mi][n] if mi in C else xD % t
+                        assert out[j][a][n] == want
+                        assert (int(fast[j][a][n]) - int(out[j][a][n])) % t == (0 if mi in C else k * D % t)
+            assert len(seen_k) > 1  # the fast conversion did leave different multiples in
+
+
+def test_exact_moddown_is_the_rounded_quotient(orc):
+    """Corrected ModDown: (u - r)/P with r the centred residue of u modulo P, i.e. u/P rounded to nearest; the fast
+    form is off by the integer v = rint(sum_k y'_k / p_k), |v| <= K/2."""
+    for o, level in ((tiny(orc, logN=6, L=3, K=3, dnum=3, qbits=20, pbits=24), 3),
+                     (tiny(orc, logN=6, L=4, K=5, dnum=2, qbits=20, pbits=24), 3)):
+        act = o.active_moduli(level)
+        mods = [o.moduli[mi] for mi in act]
+        P = prod(o.p)
+        g = wl.rng(8)
+        u_coeff = np.stack([g.integers(0, t, size=o.N, dtype=np.uint64) for t in mods])
+        u_ntt = o.ntt(u_coeff, act)
+        fast = o.intt(o.moddown(u_ntt, level), list(range(level)))
+        o.set_exact(True)
+        out = o.intt(o.moddown(u_ntt, level), list(range(level)))
+        o.set_exact(False)
+        differ = 0
+        for n in range(o.N):
+            u = crt([u_coeff[a][n] for a in range(len(act))], mods)
+            r = centre(u % P, P)
+            assert (u - r) % P == 0 and abs(2 * r) <= P
+            quo = (u - r) // P  # u/P rounded to nearest, since |r| <= P/2
+            for i in range(level):
+                assert out[i][n] == quo % o.q[i]
+            v = (int(out[0][n]) - int(fast[0][n])) % o.q[0]
+            v = v - o.q[0] if v > o.q[0] // 2 else v
+            assert abs(v) <= (o.K + 1) // 2
+            differ += v != 0
+        assert differ > 0
+
+
+def test_keyswitch_identity_with_exact_conversions(orc):
+    """The key-switch identity k0 + k1 s - d s' = small with both corrected conversions: the ModDown terms of the
+    bound shrink to the rounding of u/P, and the raised digits are bounded by D instead of alpha D."""
+    o = tiny(orc, logN=4, L=4, K=2, dnum=2, qbits=20, pbits=24)
+    o.set_exact(True)
+    for level in (4, 3, 1):
+        _keyswitch_identity(o, level, exact=True)
+    o.set_exact(False)
+
+
 def test_rescale_is_exact_rounded_division(orc):
     o = tiny(orc, logN=3, L=4, K=1, dnum=4, qbits=20, pbits=24)
     level = 4
@@ -386,7 +456,7 @@ def test_keyswitch_identity_bigint_wide_digits(orc, level):
     _keyswitch_identity(o, level)
 
 
-def _keyswitch_identity(o, level):
+def _keyswitch_identity(o, level, exact=False):
     s = o.keygen_secret(5)
     evk = o.keygen_relin(s, 6)
     prm = wl.Params("t", 4, tuple(o.q), tuple(o.p), o.dnum)
@@ -410,6 +480,8 @@ def _keyswitch_identity(o, level):
     P = prod(o.p)
     beta = -(-level // o.alpha)
     bound = beta * o.N * o.alpha * D * 19 / P + (o.K + 2) * (1 + o.N)
+    if exact:  # digits below D (not alpha D); ModDown adds at most 1/2 per component
+        bound = beta * o.N * D * 19 / P + 0.5 * (1 + o.N)
     assert max(abs(v) for v in diff) <= bound
     assert bound < Q / 4 or level == 1
 
@@ -578,6 +650,31 @@ def test_rotate_sum_adds_blocks(c1b):
     got = o.decrypt(s, out, scale).real
     want = sum(np.roll(z, -i) for i in range(16))
     assert np.abs(got - want).max() <= 4 * _ks_bound(o, scale)
+
+
+def test_exact_conversions_keep_the_ckks_invariants(orc):
+    """With the corrected conversions selected, Mult is still the slot-wise product and Rotate the left shift
+    (Section 2.2), within the bounds of the fast forms, and the residues differ from theirs (the variant is live).
+    Parameter set with two primes per digit and two special primes, where both corrections are non-trivial."""
+    p = wl.M12
+    o = orc.Oracle(p.logN, p.q, p.p, p.dnum)
+    s = o.keygen_secret(30)
+    rlk, rot = o.keygen_relin(s, 31), o.keygen_rot(s, 3, 36)
+    z1, z2 = wl.slots_uniform(32, o.n), wl.slots_uniform(33, o.n)
+    scale = 2.0**40
+    a = o.encrypt_coeffs(s, o.encode(z1, scale), 4, seed=34)
+    b = o.encrypt_coeffs(s, o.encode(z2, scale), 4, seed=35)
+    fast = o.hmult_relin(a, b, rlk)
+    o.set_exact(True)
+    try:
+        prod_ct = o.hmult_relin(a, b, rlk)
+        r = o.hrot(a, rot, 3)
+    finally:
+        o.set_exact(False)
+    assert not np.array_equal(prod_ct, fast)
+    assert np.abs(o.decrypt(s, prod_ct, scale * scale) - z1 * z2).max() <= 2.0**-25
+    assert np.abs(o.decrypt(s, fast, scale * scale) - z1 * z2).max() <= 2.0**-25
+    assert np.abs(o.decrypt(s, r, scale) - np.roll(z1, -3)).max() <= _ks_bound(o, scale)
 
 
 def test_pmult_and_cmult(c1b):
