@@ -80,6 +80,18 @@ const char *he_strerror(int32_t code);
 const char *he_last_hip_error(const he_ctx *ctx);
 /* Modulus i and its 2N-th root of unity psi_i. */
 int32_t he_ctx_modulus(const he_ctx *ctx, int32_t i, uint64_t *modulus, uint64_t *psi);
+/* Selects the base conversions of every later key switch of this context (Mult, Rotate, their batched and
+ * fused forms): exact = 0, the default: the fast conversions (ModUp leaves k D, 0 <= k < digit size, in the
+ * raised value; ModDown divides by P up to an integer error below K/2).  exact = 1: the corrected variant, a
+ * separately specified form: ModUp takes out v D with v = floor(s), s = sum over the digit's limbs in order of
+ * (double)y_i * (1.0 / (double)q_i), so that the raised value is the digit's residue in [0, D); ModDown takes
+ * out v P with v = rint(s), s = sum over the centred digits in order of (double)y'_k * (1.0 / (double)p_k), so that
+ * the result is u/P rounded to nearest.  Every product and sum of s is one IEEE double operation (no fused
+ * multiply-add), rint rounds halves to even; where the exact sum is within the rounding error of s of an
+ * integer (a half for ModDown) v may be one off, which changes the result by one source modulus and nothing
+ * else.  The paper defers the scheme to the CKKS literature and fixes neither form.  Not thread safe against
+ * calls that are being enqueued. */
+int32_t he_ctx_set_conversion(he_ctx *ctx, int32_t exact);
 /* Galois element 5^r mod 2N of a left rotation by r slots (r may be negative). */
 int32_t he_galois_element(const he_ctx *ctx, int32_t r, uint64_t *g);
 /* The 38 cumulative thresholds of the discrete Gaussian sampler (sigma 3.2, support [-19,19]). */

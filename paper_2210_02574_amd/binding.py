@@ -25,7 +25,7 @@ ERRORS = {
 # every symbol include/he.h declares
 SYMBOLS = [
     "he_ctx_create", "he_ctx_destroy", "he_strerror", "he_last_hip_error", "he_ctx_modulus",
-    "he_galois_element", "he_gauss_cdt", "he_workspace_bytes",
+    "he_galois_element", "he_gauss_cdt", "he_workspace_bytes", "he_ctx_set_conversion",
     "he_keygen_secret", "he_sk_destroy", "he_sk_coeffs", "he_keygen_relin", "he_keygen_rot",
     "he_keygen_conj", "he_keygen_public", "he_encrypt_public_coeffs", "he_keygen_secret_sparse", "he_modraise", "he_pmult_sum",
     "he_evk_from_host", "he_evk_to_host", "he_evk_destroy",
@@ -83,6 +83,7 @@ def load_library() -> ctypes.CDLL:
             "he_strerror": [i32],
             "he_last_hip_error": [vp],
             "he_ctx_modulus": [vp, i32, ctypes.POINTER(u64), ctypes.POINTER(u64)],
+            "he_ctx_set_conversion": [vp, i32],
             "he_galois_element": [vp, i32, ctypes.POINTER(u64)],
             "he_gauss_cdt": [vp],
             "he_workspace_bytes": [vp, i32, i32, ctypes.POINTER(sz)],
@@ -231,6 +232,10 @@ class HE:
         m, psi = ctypes.c_uint64(), ctypes.c_uint64()
         self._chk(self.lib.he_ctx_modulus(self.ctx, i, ctypes.byref(m), ctypes.byref(psi)), "he_ctx_modulus")
         return int(m.value), int(psi.value)
+
+    def set_exact_conversion(self, exact: bool):
+        """Selects the corrected base conversions (True) or the fast ones (False, the default) for later calls."""
+        self._chk(self.lib.he_ctx_set_conversion(self.ctx, 1 if exact else 0), "he_ctx_set_conversion")
 
     def galois_element(self, r: int) -> int:
         g = ctypes.c_uint64()

@@ -43,6 +43,10 @@ struct DevTables {
     const double *up_hat_d;
     const double *up_hat_dh;   // (D/q_i) 2^31 mod t, for sources split at bit 31
     int up_split;              // some ciphertext prime is >= 2^50: FP64 targets split their sources
+    // corrected conversions: 1.0 / (double)modulus for every modulus, and D mod t for the digit slots of up_hat
+    const double *rq;          // [M]
+    const u64 *up_dmod;        // [dnum*alpha][M]
+    const double *up_dmod_d;   // balanced doubles of the same (0 where the modulus is >= 2^50)
     // ModDown constants
     const ShoupConst *dn_inv;  // [K]      (P/p_k)^-1 mod p_k
     const u64 *dn_hat;         // [K][L]   (P/p_k) mod q_i
@@ -83,6 +87,9 @@ struct he_ctx {
     std::vector<u64> up_hat;
     std::vector<double> up_inv_d, up_hat_d, up_hat_dh, dn_inv_d, dn_hat_d, dn_hat_dh, dn_pinv_d, dn_pmod_d, rs_inv_d, rsp_inv_d;
     std::vector<u64> dn_pmod;
+    std::vector<double> rq, up_dmod_d;
+    std::vector<u64> up_dmod;
+    int exact_conv = 0; // corrected base conversions selected (he_ctx_set_conversion)
     bool up_split = false, dn_split = false;
     std::vector<ShoupConst> dn_inv;
     std::vector<u64> dn_hat;

@@ -315,11 +315,22 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
         c->up_inv_d.assign(c->up_inv.size(), 0.0);
         c->up_hat_d.assign(c->up_hat.size(), 0.0);
         c->up_hat_dh.assign(c->up_hat.size(), 0.0);
+        c->rq.assign(M, 0.0);
+        for (int m = 0; m < M; m++) c->rq[m] = 1.0 / (double)c->mod[m];
+        c->up_dmod.assign((size_t)c->dnum * alpha * M, 0);
+        c->up_dmod_d.assign(c->up_dmod.size(), 0.0);
         for (int j = 0; j < c->dnum; j++)
             for (int a = 1; a <= alpha; a++) {
                 const int lo = j * alpha;
                 if (lo + a > L) break;
                 const size_t slot = (size_t)j * alpha + (a - 1);
+                for (int m = 0; m < M; m++) { // D = product of the digit's a active primes, modulo every modulus
+                    const u64 t = c->mod[m];
+                    u64 d = 1;
+                    for (int ii = 0; ii < a; ii++) d = mul_mod(d, c->mod[lo + ii] % t, t);
+                    c->up_dmod[slot * M + m] = d;
+                    if (t < kFp) c->up_dmod_d[slot * M + m] = bal(d, t);
+                }
                 for (int ii = 0; ii < a; ii++) {
                     const u64 qi = c->mod[lo + ii];
                     if (qi < kFp) c->up_inv_d[slot * alpha + ii] = bal(c->up_inv[slot * alpha + ii].w, qi);
@@ -402,6 +413,13 @@ extern "C" int32_t he_ctx_modulus(const he_ctx *ctx, int32_t i, uint64_t *modulu
     if (!ctx || i < 0 || i >= ctx->M) return HE_EINVAL;
     if (modulus) *modulus = ctx->mod[i];
     if (psi) *psi = ctx->psi[i];
+    return HE_OK;
+}
+
+extern "C" int32_t he_ctx_set_conversion(he_ctx *ctx, int32_t exact)
+{
+    if (!ctx || (exact != 0 && exact != 1)) return HE_EINVAL;
+    ctx->exact_conv = exact;
     return HE_OK;
 }
 

@@ -51,6 +51,9 @@ struct ConvArgs {
     int src2_stride;
     // centred-limb prologue (rescale, ModRaise): modulus index of the source limb, limbs per component in dst
     int rs_mod, rs_nl;
+    // Corrected conversions selected: ModUp takes out floor(sum_i y_i / q_i) D, ModDown rint(sum_k y'_k / p_k) P,
+    // the sums in double precision, one rounding per operation, sources in order.
+    int exact;
     // Operations of one launch at different levels (mixed-level rotations): op_level[o] != 0 is the level of
     // operation o, while `level` stays the level the buffers are laid out for (the largest of the launch).
     uint8_t op_level[HE_OPS_MAX];
@@ -105,6 +108,11 @@ template <int NSMAX> struct ConvSetup {
     u64 ql, half;
     double qld;
     const u64 *tp; // ModDown + rescale: the dropped limb of this component
+    // corrected conversions: 1.0 / (double)modulus of source s (0 past the real count), D mod t (ModUp)
+    bool exact;
+    double rq[NSMAX];
+    u64 dm_i;
+    double dm_d;
 };
 
 // slot = position of the limb in the destination buffer; mi = its modulus index
@@ -117,6 +125,9 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
     S.pm_i = 0;
     S.pm_d = 0.0;
     S.tp = nullptr;
+    S.exact = cv.exact != 0;
+    S.dm_i = 0;
+    S.dm_d = 0.0;
     const int M = cv.L + cv.K, Ma = cv.level + cv.K;
     const int op_level = conv_op_level(cv, slot);
     const unsigned op = slot / (unsigned)cv.dst_stride;
@@ -128,6 +139,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
         S.ci[s] = 0;
         S.cd[s] = S.cdh[s] = 0.0;
         S.hs[s] = ~(u64)0;
+        S.rq[s] = 0.0;
     }
     if (PRO == PRO_MODUP) {
         const int j = slot / Ma;
@@ -142,7 +154,10 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
             S.ci[s] = on ? T.up_hat[ci] : 0;
             S.cd[s] = on ? T.up_hat_d[ci] : 0.0;
             S.cdh[s] = on ? T.up_hat_dh[ci] : 0.0;
+            S.rq[s] = on ? T.rq[lo + s] : 0.0;
         }
+        S.dm_i = T.up_dmod[((size_t)j * cv.alpha + (ns - 1)) * M + mi];
+        S.dm_d = T.up_dmod_d[((size_t)j * cv.alpha + (ns - 1)) * M + mi];
     } else if (pro_is_moddown(PRO)) {
         const int c = slot / cv.level, i = slot % cv.level;
 #pragma unroll
@@ -154,6 +169,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
             S.cd[s] = on ? T.dn_hat_d[ci] : 0.0;
             S.cdh[s] = on ? T.dn_hat_dh[ci] : 0.0;
             S.hs[s] = on ? (T.mod[cv.L + s].q - 1) / 2 : ~(u64)0;
+            S.rq[s] = on ? T.rq[cv.L + s] : 0.0;
         }
         S.pm_i = T.dn_pmod[i];
         S.pm_d = T.dn_pmod_d[i];
@@ -186,12 +202,19 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
         const double w = u2d(reduce64(neg ? S.ql - tv : tv, m));
         return neg ? -w : w;
     }
-    double acc = 0.0;
+    double acc = 0.0, sv = 0.0;
     int neg = 0; // ModDown: number of digits that stand for y - p
 #pragma unroll
     for (int s = 0; s < NSMAX; s++) {
         const u64 y = S.sp[s][pos];
-        if (pro_is_moddown(PRO)) neg += y > S.hs[s] ? 1 : 0;
+        const bool ng = pro_is_moddown(PRO) && y > S.hs[s];
+        if (pro_is_moddown(PRO)) neg += ng ? 1 : 0;
+        if (S.exact) { // the source as a fraction of its modulus (ModDown: of the centred digit)
+            const double yd = !pro_is_moddown(PRO) ? (SPLIT ? (double)y : u2d(y))
+                              : ng               ? -(double)(2 * S.hs[s] + 1 - y)
+                                                 : (double)y;
+            sv = sv + yd * S.rq[s];
+        }
         if (!SPLIT)
             acc += ar.mulmod(u2d(y), S.cd[s]);
         else {
@@ -200,9 +223,11 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
         }
         if ((s & 3) == 3 && s + 1 < NSMAX) acc = ar.reduce(acc);
     }
+    if (PRO == PRO_MODUP && S.exact) acc -= __builtin_floor(sv) * S.dm_d; // at most (sources - 1) D
     if (pro_is_moddown(PRO)) {
         if (NSMAX > 4) acc = ar.reduce(acc);
-        acc -= (double)neg * S.pm_d; // p_s * (P/p_s) = P for every centred digit
+        // p_s * (P/p_s) = P for every centred digit; corrected: plus rint(sv) P, together between 0 and K times P
+        acc -= ((double)neg + (S.exact ? __builtin_rint(sv) : 0.0)) * S.pm_d;
     }
     if (PRO == PRO_MODDOWN_RS) { // + P t with t the centred dropped limb
         const u64 tv = S.tp[pos];
@@ -229,15 +254,25 @@ __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithIn
         return neg ? (w ? m.q - w : 0) : w;
     }
     U128 acc{0, 0};
-    u64 corr = 0;
+    double sv = 0.0;
+    int neg = 0;
 #pragma unroll
     for (int s = 0; s < NSMAX; s++) {
         const u64 y = S.sp[s][pos];
         mac128(acc, y, S.ci[s]);
-        if (pro_is_moddown(PRO)) corr = csub(corr + (y > S.hs[s] ? S.pm_i : 0), m.q);
+        const bool ng = pro_is_moddown(PRO) && y > S.hs[s];
+        if (pro_is_moddown(PRO)) neg += ng ? 1 : 0;
+        if (S.exact) {
+            const double yd = ng ? -(double)(2 * S.hs[s] + 1 - y) : (double)y;
+            sv = sv + yd * S.rq[s];
+        }
     }
     u64 r = reduce128(acc, m);
-    if (pro_is_moddown(PRO)) r = csub(r + m.q - corr, m.q);
+    if (PRO == PRO_MODUP && S.exact) r = csub(r + m.q - mul_mod((u64)__builtin_floor(sv), S.dm_i, m), m.q);
+    if (pro_is_moddown(PRO)) { // every centred digit takes out one P, the correction rint(sv) more: 0 .. K in all
+        const long long tot = neg + (S.exact ? (long long)__builtin_rint(sv) : 0);
+        r = csub(r + m.q - mul_mod((u64)tot, S.pm_i, m), m.q);
+    }
     if (PRO == PRO_MODDOWN_RS) {
         const u64 tv = S.tp[pos];
         const bool tneg = tv > S.half;
@@ -598,13 +633,18 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols16_modup2(u64 *__restrict__
 #pragma unroll
     for (int k = 0; k < 16; k++) {
         const unsigned pos = (rl + 16 * k) * 256 + col0 + c;
-        double acc0 = 0.0, acc1 = 0.0;
+        double acc0 = 0.0, acc1 = 0.0, sv = 0.0;
 #pragma unroll
         for (int s = 0; s < NSMAX; s++) {
             const double y = u2d(S0.sp[s][pos]);
+            if (S0.exact) sv = sv + y * S0.rq[s];
             acc0 += ar0.mulmod(y, S0.cd[s]);
             acc1 += ar1.mulmod(y, S1.cd[s]);
             if ((s & 3) == 3 && s + 1 < NSMAX) acc0 = ar0.reduce(acc0), acc1 = ar1.reduce(acc1);
+        }
+        if (S0.exact) { // one estimate of the multiple of D for both targets
+            const double v = __builtin_floor(sv);
+            acc0 -= v * S0.dm_d, acc1 -= v * S1.dm_d;
         }
         a0[k] = acc0, a1[k] = acc1;
     }

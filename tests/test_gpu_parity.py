@@ -388,6 +388,53 @@ def test_conversions_with_more_than_four_sources(pkg, oracle_mod, name):
     _sync()
 
 
+@pytest.mark.parametrize("name", ["C1", "C1B", "N16", "I12", "M12", "W12", "W16", "P17"])
+def test_corrected_conversions_match_the_oracle(pkg, oracle_mod, name):
+    """The selectable variant with corrected base conversions (ModUp to the digit's own residue, ModDown to the
+    rounded quotient, the multiples estimated in double precision as specified): Mult, the fused Mult + rescale,
+    Rotate and a mixed-level call against the oracle with the same variant selected, on every residue -- on the
+    floating-point and the integer path, split sources, and conversions of five to eight sources.  Where the
+    corrections are non-trivial the residues differ from the default form's."""
+    import torch
+
+    p = getattr(wl, name)
+    env = Env(pkg, oracle_mod, p)
+    he, o = env.he, env.o
+    relin, relin_h = env.synth_key(3401, 1)
+    rkey, rkey_h = env.synth_key(3402, o.galois_element(3))
+    levels = {12: [p.L, max(1, p.L - 1), 1], 16: [p.L, p.L - 3, 9, 2], 17: [30, 7]}[p.logN]
+    he.set_exact_conversion(True)
+    o.set_exact(True)
+    try:
+        for level in sorted(set(levels), reverse=True):
+            a, b = wl.uniform_ct(3410 + level, p, level), wl.uniform_ct(3440 + level, p, level)
+            da, db = he.to_device(a), he.to_device(b)
+            prod = o.hmult_relin(a, b, relin_h)
+            assert np.array_equal(he.to_host(he.hmult_relin(relin, da, db)), prod), level
+            if level >= 2:
+                assert np.array_equal(he.to_host(he.hmult_relin_rescale(relin, da, db)), o.rescale(prod)), level
+            rot = o.hrot(a, rkey_h, 3)
+            assert np.array_equal(he.to_host(he.hrot(rkey, da)), rot), level
+            if level == max(levels) and p.alpha > 1 and p.K > 1:
+                o.set_exact(False)
+                assert not np.array_equal(rot, o.hrot(a, rkey_h, 3))
+                o.set_exact(True)
+        cts = [wl.uniform_ct(3470 + k, p, lv) for k, lv in enumerate(levels)]
+        packed = torch.cat([he.to_device(c).reshape(-1, p.N) for c in cts])
+        got = he.to_host(he.hrot_batch_levels([rkey] * len(levels), levels, packed))
+        at = 0
+        for lv, ct in zip(levels, cts):
+            assert np.array_equal(got[at:at + 2 * lv].reshape(2, lv, p.N), o.hrot(ct, rkey_h, 3)), lv
+            at += 2 * lv
+    finally:
+        he.set_exact_conversion(False)
+        o.set_exact(False)
+    # back to the default form
+    a = wl.uniform_ct(3499, p, levels[0])
+    assert np.array_equal(he.to_host(he.hrot(rkey, he.to_device(a))), o.hrot(a, rkey_h, 3))
+    _sync()
+
+
 def test_unbuilt_conversion_sizes_are_refused(pkg):
     """Digits of more than four primes at N = 2^17, and of more than eight anywhere, have no kernel: a device
     context for them is refused instead of running a smaller one."""
