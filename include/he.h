@@ -13,7 +13,7 @@
  *
  * Conventions
  *  - Moduli: q_0..q_{L-1} (ciphertext primes) then p_0..p_{K-1} (special primes),
- *    all < 2^62, all = 1 mod 2N.  "Modulus index" i < L means q_i, L+k means p_k.
+ *    all < 2^60, all = 1 mod 2N.  "Modulus index" i < L means q_i, L+k means p_k.
  *  - level l = number of limbs present (1..L).  A limb is N uint64 residues in
  *    [0, q).  Every buffer that crosses this interface holds canonical residues.
  *  - NTT domain: out[k] = sum_j a[j] psi^((2 brv(k)+1) j) mod q (bit-reversed

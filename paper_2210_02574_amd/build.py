@@ -16,6 +16,8 @@ LIB = os.path.join(HERE, "libhe_gfx950.so")
 SOURCES = (
     # (source, extra defines, object name), the slowest first
     [("dev_cols.hip", ["-DHE_LOGN=%d" % n, "-DHE_PRO=%d" % p], "dev_cols%d_%d" % (n, p)) for n in (17, 16) for p in (4, 2, 1, 5, 3, 0)]
+    # the corrected base conversions: kernels of their own
+    + [("dev_cols.hip", ["-DHE_LOGN=%d" % n, "-DHE_PRO=%d" % p, "-DHE_EX=1"], "dev_cols_ex%d_%d" % (n, p)) for n in (17, 16) for p in (4, 2, 1)]
     + [(s, [], os.path.splitext(s)[0]) for s in ("dev_n12.hip", "dev_n16_blocks.hip", "dev_n17_blocks.hip", "device.hip", "host.cpp")]
 )
 OBJDIR = os.path.join(HERE, "_build")

@@ -1,4 +1,4 @@
-// Device arithmetic on residues of primes below 2^62 (gfx950).
+// Device arithmetic on residues of primes below 2^60 (gfx950).
 //
 // Two forms are used.  Integer: 64-bit values built from 32-bit multiplies -- Shoup products for
 // multiplications by table constants (w, floor(w 2^64 / q)), 128-bit accumulation with one final
@@ -18,6 +18,18 @@ __device__ __forceinline__ u64 csub(u64 x, u64 q) { return x >= q ? x - q : x; }
 // w*x mod q up to one extra q, for any 64-bit x; w < q with wp = floor(w 2^64 / q)
 __device__ __forceinline__ u64 mul_shoup_lazy(u64 x, ShoupConst w, u64 q) { return x * w.w - mulhi64(x, w.wp) * q; }
 __device__ __forceinline__ u64 mul_shoup(u64 x, ShoupConst w, u64 q) { return csub(mul_shoup_lazy(x, w, q), q); }
+// The same product with a cheaper quotient: of the four 32-bit partial products of x * wp only the high one and
+// the high halves of the two middle ones are kept, so the estimate is at most three below floor(x wp / 2^64)
+// and the result lies in [0, 4q) for any 64-bit x (exact arithmetic modulo 2^64, since 4q < 2^64).
+__device__ __forceinline__ u64 mul_shoup_sloppy(u64 x, ShoupConst w, u64 q)
+{
+    const unsigned xl = (unsigned)x, xh = (unsigned)(x >> 32);
+    const unsigned pl = (unsigned)w.wp, ph = (unsigned)(w.wp >> 32);
+    u64 quo = (u64)xh * ph;
+    quo += __umulhi(xh, pl);
+    quo += __umulhi(xl, ph);
+    return x * w.w - quo * q;
+}
 
 struct U128 {
     u64 lo, hi;
@@ -231,11 +243,12 @@ struct ArithFp {
     }
 };
 
-// ArithInt ranges: [0, 4q) between forward stages, [0, 2q) between inverse stages.
+// ArithInt ranges (q < 2^60, so 8q < 2^63): values stay in [0, 8q) between forward stages and in [0, 4q) between
+// inverse stages; every product with a table constant uses the cheaper quotient and lands in [0, 4q).
 struct ArithInt {
     typedef u64 V;
     static constexpr bool IS_FP = false;
-    u64 q, q2;
+    u64 q, q2, q4;
     ShoupConst n0, n1, post; // post: optional extra constant applied by store_final (post.w == 0: none)
     const ShoupConst *twf, *twi;
     __device__ __forceinline__ V load(u64 m) const { return m; }
@@ -243,8 +256,15 @@ struct ArithInt {
     __device__ __forceinline__ u64 store_mid(V v) const { return v; }
     __device__ __forceinline__ u64 store_final(V v) const
     {
-        const u64 r = csub(csub(v, q2), q);
+        const u64 r = csub(csub(csub(v, q4), q2), q);
         return post.w ? mul_shoup(r, post, q) : r;
+    }
+    __device__ __forceinline__ void fwd_bfly(V &lo, V &hi, ShoupConst w) const
+    {
+        const u64 u = csub(lo, q4);
+        const u64 v = mul_shoup_sloppy(hi, w, q);
+        lo = u + v;
+        hi = u - v + q4;
     }
     __device__ __forceinline__ void fwd16(V (&a)[16], unsigned s_base, unsigned G, bool) const
     {
@@ -256,13 +276,7 @@ struct ArithInt {
             for (int g = 0; g < (1 << sp); g++) {
                 const ShoupConst w = twf[idx0 + g];
 #pragma unroll
-                for (int e = 0; e < dist; e++) {
-                    const int k0 = g * 2 * dist + e, k1 = k0 + dist;
-                    const u64 u = csub(a[k0], q2);
-                    const u64 v = mul_shoup_lazy(a[k1], w, q);
-                    a[k0] = u + v;
-                    a[k1] = u - v + q2;
-                }
+                for (int e = 0; e < dist; e++) fwd_bfly(a[g * 2 * dist + e], a[g * 2 * dist + e + dist], w);
             }
         }
     }
@@ -280,8 +294,8 @@ struct ArithInt {
                 for (int e = 0; e < dist; e++) {
                     const int k0 = g * 2 * dist + e, k1 = k0 + dist;
                     const u64 u = a[k0], v = a[k1];
-                    a[k0] = fin ? mul_shoup_lazy(u + v, n0, q) : csub(u + v, q2);
-                    a[k1] = mul_shoup_lazy(u - v + q2, w, q);
+                    a[k0] = fin ? mul_shoup_sloppy(u + v, n0, q) : csub(u + v, q4);
+                    a[k1] = mul_shoup_sloppy(u - v + q4, w, q);
                 }
             }
         }
@@ -290,20 +304,15 @@ struct ArithInt {
     {
         const ShoupConst w = twf[1];
 #pragma unroll
-        for (int k = 0; k < 16; k++) {
-            const u64 u = csub(lo[k], q2);
-            const u64 v = mul_shoup_lazy(hi[k], w, q);
-            lo[k] = u + v;
-            hi[k] = u - v + q2;
-        }
+        for (int k = 0; k < 16; k++) fwd_bfly(lo[k], hi[k], w);
     }
     __device__ __forceinline__ void inv_stage0_last(V (&lo)[16], V (&hi)[16]) const
     {
 #pragma unroll
         for (int k = 0; k < 16; k++) {
             const u64 u = lo[k], v = hi[k];
-            lo[k] = mul_shoup_lazy(u + v, n0, q);
-            hi[k] = mul_shoup_lazy(u - v + q2, n1, q);
+            lo[k] = mul_shoup_sloppy(u + v, n0, q);
+            hi[k] = mul_shoup_sloppy(u - v + q4, n1, q);
         }
     }
 };
@@ -329,6 +338,7 @@ __device__ __forceinline__ ArithInt make_int(const DevTables &T, unsigned mi, in
     ArithInt A;
     A.q = T.mod[mi].q;
     A.q2 = 2 * A.q;
+    A.q4 = 4 * A.q;
     A.twf = T.tw_fwd + ((size_t)mi << logN);
     A.twi = T.tw_inv + ((size_t)mi << logN);
     A.n0 = T.ninv[2 * mi];

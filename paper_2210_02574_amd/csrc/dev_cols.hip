@@ -1,6 +1,7 @@
 // Column-pass kernels of the ring sizes N = 2^16 and 2^17 and their launchers.  Compiled once per
-// (HE_LOGN, HE_PRO): one object per ring size and prologue, HE_PRO = 5 for the inverse column pass, so
-// that the large kernels build in parallel.
+// (HE_LOGN, HE_PRO, HE_EX): one object per ring size and prologue, HE_PRO = 5 for the inverse column pass, and
+// a further one (HE_EX = 1) for each prologue with a base conversion in its corrected form, so that the large
+// kernels build in parallel.
 #include "launch.h"
 
 #if HE_LOGN == 16
@@ -14,6 +15,9 @@
 #endif
 // the preprocessor sees the prologue as a number: tie the numbers used below to the enumeration
 static_assert(PRO_LOAD == 0 && PRO_MODUP == 1 && PRO_MODDOWN == 2 && PRO_RESCALE == 3 && PRO_MODDOWN_RS == 4, "prologue numbering");
+#ifndef HE_EX
+#define HE_EX 0
+#endif
 #define PASTE3_(a, b, c) a##b##_##c
 #define PASTE3(a, b, c) PASTE3_(a, b, c)
 
@@ -23,20 +27,24 @@ static void fwd_cols(he_ctx *c, hipStream_t st, int kid, double bytes, bool wide
 {
 #if HE_LOGN == 16 && HE_PRO == 1 /* PRO_MODUP */
     if (!wide) {
-        KLAUNCH(c, st, kid, bytes, (k_ntt_fwd_cols16_modup2<4>), 16 * ((nb + 1) / 2), data, c->dev, lb, cv, nb);
+        KLAUNCH(c, st, kid, bytes, (k_ntt_fwd_cols16_modup2<4, HE_EX != 0>), 16 * ((nb + 1) / 2), data, c->dev, lb, cv, nb);
         return;
     }
 #endif
 #if HE_PRO == 0 || HE_PRO == 3 /* PRO_LOAD, PRO_RESCALE: no base conversion, one form */
-    KLAUNCH(c, st, kid, bytes, (FWD_KERNEL<HE_PRO, 4>), 16 * nb, data, c->dev, lb, cv);
+    KLAUNCH(c, st, kid, bytes, (FWD_KERNEL<HE_PRO, 4, HE_EX != 0>), 16 * nb, data, c->dev, lb, cv);
 #else
     if (wide)
-        KLAUNCH(c, st, kid, bytes, (FWD_KERNEL<HE_PRO, NS_WIDE>), 16 * nb, data, c->dev, lb, cv);
+        KLAUNCH(c, st, kid, bytes, (FWD_KERNEL<HE_PRO, NS_WIDE, HE_EX != 0>), 16 * nb, data, c->dev, lb, cv);
     else
-        KLAUNCH(c, st, kid, bytes, (FWD_KERNEL<HE_PRO, 4>), 16 * nb, data, c->dev, lb, cv);
+        KLAUNCH(c, st, kid, bytes, (FWD_KERNEL<HE_PRO, 4, HE_EX != 0>), 16 * nb, data, c->dev, lb, cv);
 #endif
 }
+#if HE_EX
+void PASTE3(dev_launch_cols_ex, HE_LOGN, HE_PRO)(DevLaunch &t) { t.fwd_cols_ex[HE_PRO] = fwd_cols; }
+#else
 void PASTE3(dev_launch_cols, HE_LOGN, HE_PRO)(DevLaunch &t) { t.fwd_cols[HE_PRO] = fwd_cols; }
+#endif
 #else
 static void inv_cols(he_ctx *c, hipStream_t st, double bytes, int scale, u64 *dst, const LimbBatch &lb, int nb,
                      const ConvArgs &cv)

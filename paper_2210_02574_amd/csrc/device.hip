@@ -83,7 +83,7 @@ int32_t dev_upload_tables(he_ctx *c)
     if ((rc = upload(c, c->field, &c->dev.field)) != HE_OK) return rc;
     if ((rc = upload(c, c->modc, &c->dev.mod)) != HE_OK) return rc;
     UP(tw_fwd) UP(tw_inv) UP(ninv) UP(twd_fwd) UP(twd_inv) UP(ninvd)
-    UP(up_inv) UP(up_hat) UP(up_inv_d) UP(up_hat_d) UP(up_hat_dh) UP(rq) UP(up_dmod) UP(up_dmod_d)
+    UP(up_inv) UP(up_hat) UP(up_inv_d) UP(up_hat_d) UP(up_hat_dh) UP(rq) UP(up_dmod) UP(up_dmod_d) UP(up_hat_p)
     UP(dn_inv) UP(dn_hat) UP(dn_pinv) UP(dn_inv_d) UP(dn_hat_d) UP(dn_hat_dh) UP(dn_pinv_d) UP(dn_pmod) UP(dn_pmod_d)
     UP(rs_inv) UP(rs_inv_d) UP(rsp_inv) UP(rsp_inv_d)
 #undef UP
@@ -200,12 +200,14 @@ static const DevLaunch &dev_launch(const he_ctx *c)
             DevLaunch t{};
             dev_launch_cols16_0(t), dev_launch_cols16_1(t), dev_launch_cols16_2(t), dev_launch_cols16_3(t);
             dev_launch_cols16_4(t), dev_launch_cols16_5(t), dev_launch_n16_blocks(t);
+            dev_launch_cols_ex16_1(t), dev_launch_cols_ex16_2(t), dev_launch_cols_ex16_4(t);
             return t;
         }(),
         [] {
             DevLaunch t{};
             dev_launch_cols17_0(t), dev_launch_cols17_1(t), dev_launch_cols17_2(t), dev_launch_cols17_3(t);
             dev_launch_cols17_4(t), dev_launch_cols17_5(t), dev_launch_n17_blocks(t);
+            dev_launch_cols_ex17_1(t), dev_launch_cols_ex17_2(t), dev_launch_cols_ex17_4(t);
             return t;
         }(),
     };
@@ -354,7 +356,7 @@ static int32_t ntt_forward(he_ctx *c, hipStream_t st, u64 *data, const LimbList 
                              : pro == PRO_MODDOWN ? KID_FWD_COLS_MODDOWN
                              : pro == PRO_MODDOWN_RS ? KID_FWD_COLS_MODDOWN_RS
                                                   : KID_FWD_COLS_RESCALE;
-        dl.fwd_cols[pro](c, st, kid_cols, cols_bytes, wide, data, lb, nb, cv);
+        (cv.exact && dl.fwd_cols_ex[pro] ? dl.fwd_cols_ex[pro] : dl.fwd_cols[pro])(c, st, kid_cols, cols_bytes, wide, data, lb, nb, cv);
         if (fin) {
             // reads the transform's input, the minuend and the addend, writes the result
             const double b = (double)nb * N8 * (3.0 + (fin->mode == 1 || fin->mode == 3 ? 1.0 : fin->mode == 2 ? 0.5 : fin->mode == 4 ? 1.5 : 0.0));

@@ -39,6 +39,7 @@ struct DevTables {
     // ModUp constants for digit j holding a active limbs (1 <= a <= alpha), slot (j*alpha + a-1):
     const ShoupConst *up_inv;  // [dnum*alpha][alpha]      (D/q_i)^-1 mod q_i
     const u64 *up_hat;         // [dnum*alpha][alpha][M]   (D/q_i) mod t
+    const u64 *up_hat_p;       // the same shape: floor(((D/q_i) mod t) 2^64 / t), for products on the integer path
     const double *up_inv_d;    // balanced doubles of the same (0 where the modulus is >= 2^50)
     const double *up_hat_d;
     const double *up_hat_dh;   // (D/q_i) 2^31 mod t, for sources split at bit 31
@@ -88,7 +89,7 @@ struct he_ctx {
     std::vector<double> up_inv_d, up_hat_d, up_hat_dh, dn_inv_d, dn_hat_d, dn_hat_dh, dn_pinv_d, dn_pmod_d, rs_inv_d, rsp_inv_d;
     std::vector<u64> dn_pmod;
     std::vector<double> rq, up_dmod_d;
-    std::vector<u64> up_dmod;
+    std::vector<u64> up_dmod, up_hat_p;
     int exact_conv = 0; // corrected base conversions selected (he_ctx_set_conversion)
     bool up_split = false, dn_split = false;
     std::vector<ShoupConst> dn_inv;

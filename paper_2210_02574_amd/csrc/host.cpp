@@ -198,7 +198,7 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
     const int M = c->M, L = c->L, K = c->K, alpha = c->alpha;
     for (int i = 0; i < M; i++) {
         u64 t = i < L ? p->q[i] : p->p[i - L];
-        if (t >= ((u64)1 << 62) || t < 2 * N || (t - 1) % (2 * N) != 0) {
+        if (t >= ((u64)1 << 60) || t < 2 * N || (t - 1) % (2 * N) != 0) {
             delete c;
             return HE_EINVAL;
         }
@@ -315,6 +315,8 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
         c->up_inv_d.assign(c->up_inv.size(), 0.0);
         c->up_hat_d.assign(c->up_hat.size(), 0.0);
         c->up_hat_dh.assign(c->up_hat.size(), 0.0);
+        c->up_hat_p.assign(c->up_hat.size(), 0);
+        for (size_t e = 0; e < c->up_hat.size(); e++) c->up_hat_p[e] = shoup(c->up_hat[e], c->mod[e % M]).wp;
         c->rq.assign(M, 0.0);
         for (int m = 0; m < M; m++) c->rq[m] = 1.0 / (double)c->mod[m];
         c->up_dmod.assign((size_t)c->dnum * alpha * M, 0);

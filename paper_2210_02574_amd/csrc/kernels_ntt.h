@@ -99,7 +99,7 @@ __device__ __forceinline__ unsigned galois_index(unsigned k, unsigned g, int log
 template <int NSMAX> struct ConvSetup {
     const u64 *sp[NSMAX];         // source limbs; entries past the real count repeat entry 0 with zero constants
     double cd[NSMAX], cdh[NSMAX]; // constants as balanced doubles (cdh: constant * 2^31)
-    u64 ci[NSMAX];                // constants as residues (integer targets)
+    u64 ci[NSMAX], cp[NSMAX];     // constants as residues and their companions floor(c 2^64 / t) (integer targets)
     // ModDown: source digit s counts as y - p_s when y > hs[s]; each such digit subtracts P mod q_i
     u64 hs[NSMAX];
     u64 pm_i;
@@ -109,7 +109,6 @@ template <int NSMAX> struct ConvSetup {
     double qld;
     const u64 *tp; // ModDown + rescale: the dropped limb of this component
     // corrected conversions: 1.0 / (double)modulus of source s (0 past the real count), D mod t (ModUp)
-    bool exact;
     double rq[NSMAX];
     u64 dm_i;
     double dm_d;
@@ -125,7 +124,6 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
     S.pm_i = 0;
     S.pm_d = 0.0;
     S.tp = nullptr;
-    S.exact = cv.exact != 0;
     S.dm_i = 0;
     S.dm_d = 0.0;
     const int M = cv.L + cv.K, Ma = cv.level + cv.K;
@@ -136,7 +134,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
 #pragma unroll
     for (int s = 0; s < NSMAX; s++) {
         S.sp[s] = src;
-        S.ci[s] = 0;
+        S.ci[s] = S.cp[s] = 0;
         S.cd[s] = S.cdh[s] = 0.0;
         S.hs[s] = ~(u64)0;
         S.rq[s] = 0.0;
@@ -152,6 +150,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
             const size_t ci = (cs + (on ? s : 0)) * M + mi;
             S.sp[s] = src + ((size_t)(lo + (on ? s : 0)) << LOGN);
             S.ci[s] = on ? T.up_hat[ci] : 0;
+            S.cp[s] = on ? T.up_hat_p[ci] : 0;
             S.cd[s] = on ? T.up_hat_d[ci] : 0.0;
             S.cdh[s] = on ? T.up_hat_dh[ci] : 0.0;
             S.rq[s] = on ? T.rq[lo + s] : 0.0;
@@ -192,7 +191,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
 // SPLIT: the sources may be 2^50 or larger, so an FP64 target splits each at bit 31.  TINT (ModDown + rescale):
 // the dropped limb is 2^50 or larger and is reduced with integers first; a template parameter rather than a
 // run-time branch, because the integer code would cost every launch 100 registers.
-template <int PRO, bool SPLIT, bool TINT, int NSMAX>
+template <int PRO, bool SPLIT, bool TINT, bool EX, int NSMAX>
 __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const ArithFp &ar, const ModConst &m, unsigned pos)
 {
     if (PRO == PRO_RESCALE) {
@@ -209,7 +208,7 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
         const u64 y = S.sp[s][pos];
         const bool ng = pro_is_moddown(PRO) && y > S.hs[s];
         if (pro_is_moddown(PRO)) neg += ng ? 1 : 0;
-        if (S.exact) { // the source as a fraction of its modulus (ModDown: of the centred digit)
+        if (EX) { // the source as a fraction of its modulus (ModDown: of the centred digit)
             const double yd = !pro_is_moddown(PRO) ? (SPLIT ? (double)y : u2d(y))
                               : ng               ? -(double)(2 * S.hs[s] + 1 - y)
                                                  : (double)y;
@@ -223,11 +222,11 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
         }
         if ((s & 3) == 3 && s + 1 < NSMAX) acc = ar.reduce(acc);
     }
-    if (PRO == PRO_MODUP && S.exact) acc -= __builtin_floor(sv) * S.dm_d; // at most (sources - 1) D
+    if (PRO == PRO_MODUP && EX) acc -= __builtin_floor(sv) * S.dm_d; // at most (sources - 1) D
     if (pro_is_moddown(PRO)) {
         if (NSMAX > 4) acc = ar.reduce(acc);
         // p_s * (P/p_s) = P for every centred digit; corrected: plus rint(sv) P, together between 0 and K times P
-        acc -= ((double)neg + (S.exact ? __builtin_rint(sv) : 0.0)) * S.pm_d;
+        acc -= ((double)neg + (EX ? __builtin_rint(sv) : 0.0)) * S.pm_d;
     }
     if (PRO == PRO_MODDOWN_RS) { // + P t with t the centred dropped limb
         const u64 tv = S.tp[pos];
@@ -244,7 +243,7 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
     return acc;
 }
 
-template <int PRO, bool SPLIT, bool TINT, int NSMAX>
+template <int PRO, bool SPLIT, bool TINT, bool EX, int NSMAX>
 __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithInt &, const ModConst &m, unsigned pos)
 {
     if (PRO == PRO_RESCALE) {
@@ -253,25 +252,49 @@ __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithIn
         const u64 w = reduce64(neg ? S.ql - tv : tv, m);
         return neg ? (w ? m.q - w : 0) : w;
     }
+    if (PRO == PRO_MODUP && NSMAX <= 4) {
+        // up to four products in [0, 4q) each, summed without reduction: below 16q < 2^64
+        u64 lazy = 0;
+        double sv = 0.0;
+#pragma unroll
+        for (int s = 0; s < NSMAX; s++) {
+            const u64 y = S.sp[s][pos];
+            lazy += mul_shoup_sloppy(y, ShoupConst{S.ci[s], S.cp[s]}, m.q);
+            if (EX) sv = sv + (double)y * S.rq[s];
+        }
+        lazy = csub(lazy, 8 * m.q); // the range the transform takes
+        if (EX) {
+            const u64 r = csub(csub(csub(lazy, 4 * m.q), 2 * m.q), m.q);
+            return csub(r + m.q - mul_mod((u64)__builtin_floor(sv), S.dm_i, m), m.q);
+        }
+        return lazy;
+    }
     U128 acc{0, 0};
     double sv = 0.0;
-    int neg = 0;
+    u64 corr = 0; // ModDown: every digit that stands for y - p takes out one P
 #pragma unroll
     for (int s = 0; s < NSMAX; s++) {
         const u64 y = S.sp[s][pos];
         mac128(acc, y, S.ci[s]);
         const bool ng = pro_is_moddown(PRO) && y > S.hs[s];
-        if (pro_is_moddown(PRO)) neg += ng ? 1 : 0;
-        if (S.exact) {
+        if (pro_is_moddown(PRO)) corr = csub(corr + (ng ? S.pm_i : 0), m.q);
+        if (EX) {
             const double yd = ng ? -(double)(2 * S.hs[s] + 1 - y) : (double)y;
             sv = sv + yd * S.rq[s];
         }
     }
     u64 r = reduce128(acc, m);
-    if (PRO == PRO_MODUP && S.exact) r = csub(r + m.q - mul_mod((u64)__builtin_floor(sv), S.dm_i, m), m.q);
-    if (pro_is_moddown(PRO)) { // every centred digit takes out one P, the correction rint(sv) more: 0 .. K in all
-        const long long tot = neg + (S.exact ? (long long)__builtin_rint(sv) : 0);
-        r = csub(r + m.q - mul_mod((u64)tot, S.pm_i, m), m.q);
+    if (PRO == PRO_MODUP && EX) r = csub(r + m.q - mul_mod((u64)__builtin_floor(sv), S.dm_i, m), m.q);
+    if (pro_is_moddown(PRO)) {
+        if (EX) { // the correction rint(sv), at most NSMAX / 2 in size, times P
+            const int v = (int)__builtin_rint(sv);
+#pragma unroll
+            for (int t = 0; t < NSMAX / 2; t++) {
+                if (t < v) corr = csub(corr + S.pm_i, m.q);
+                if (t < -v) corr = csub(corr + m.q - S.pm_i, m.q);
+            }
+        }
+        r = csub(r + m.q - corr, m.q);
     }
     if (PRO == PRO_MODDOWN_RS) {
         const u64 tv = S.tp[pos];
@@ -478,7 +501,7 @@ template <int LOGN> struct ColsGeom {
 };
 
 // the 16 inputs of one thread in rows rl + 16 k + 256 h (plain load or base conversion)
-template <int PRO, bool SPLIT, bool TINT, int NSMAX, class A>
+template <int PRO, bool SPLIT, bool TINT, bool EX, int NSMAX, class A>
 __device__ __forceinline__ void cols_inputs(typename A::V (&a)[16], const u64 *__restrict__ limb, unsigned col0, int h,
                                             const A &ar, const ConvSetup<NSMAX> &S, const ModConst &m)
 {
@@ -486,7 +509,7 @@ __device__ __forceinline__ void cols_inputs(typename A::V (&a)[16], const u64 *_
 #pragma unroll
     for (int k = 0; k < 16; k++) {
         const unsigned pos = (rl + 16 * k + 256 * h) * 256 + col0 + c;
-        a[k] = PRO == PRO_LOAD ? ar.load(limb[pos]) : conv_get<PRO, SPLIT, TINT>(S, ar, m, pos);
+        a[k] = PRO == PRO_LOAD ? ar.load(limb[pos]) : conv_get<PRO, SPLIT, TINT, EX>(S, ar, m, pos);
     }
 }
 // second phase of the forward column pass for rows 16 g .. 16 g + 15, held in LDS as group gl
@@ -502,14 +525,14 @@ __device__ __forceinline__ void cols_finish_group(typename A::V (&a)[16], u64 *_
     for (int k = 0; k < 16; k++) limb[(16 * g + k) * 256 + col0 + c] = ar.store_mid(a[k]); // the block pass finishes
 }
 
-template <int LOGN, int PRO, bool SPLIT, bool TINT, int NSMAX, class A>
+template <int LOGN, int PRO, bool SPLIT, bool TINT, bool EX, int NSMAX, class A>
 __device__ __forceinline__ void fwd_cols_body(u64 *__restrict__ limb, unsigned col0, const A &ar, u64 *lds,
                                               const ConvSetup<NSMAX> &S, const ModConst &m)
 {
     constexpr int H = ColsGeom<LOGN>::HALVES;
     const unsigned rl = threadIdx.x >> 4, c = threadIdx.x & 15;
     typename A::V a0[16];
-    cols_inputs<PRO, SPLIT, TINT>(a0, limb, col0, 0, ar, S, m);
+    cols_inputs<PRO, SPLIT, TINT, EX>(a0, limb, col0, 0, ar, S, m);
     if (H == 1) {
         ar.fwd16(a0, 0, 0, PRO != PRO_LOAD);
 #pragma unroll
@@ -520,7 +543,7 @@ __device__ __forceinline__ void fwd_cols_body(u64 *__restrict__ limb, unsigned c
         typename A::V a1[16];
         // one half's source loads at a time: 32 outputs x up to 8 sources in flight would not fit the registers
         if (PRO != PRO_LOAD) __builtin_amdgcn_sched_barrier(0);
-        cols_inputs<PRO, SPLIT, TINT>(a1, limb, col0, 1, ar, S, m);
+        cols_inputs<PRO, SPLIT, TINT, EX>(a1, limb, col0, 1, ar, S, m);
         ar.fwd_stage0(a0, a1, PRO != PRO_LOAD);
         ar.fwd16(a0, 1, 0, true);
         ar.fwd16(a1, 1, 1, true);
@@ -570,7 +593,7 @@ __device__ __forceinline__ void inv_cols_body(u64 *__restrict__ limb, unsigned c
 }
 
 // column pass of limb b of the launch (the arithmetic path and the prologue's variant follow from its modulus)
-template <int LOGN, int PRO, int NSMAX>
+template <int LOGN, int PRO, int NSMAX, bool EX>
 __device__ __forceinline__ void fwd_cols_limb(u64 *__restrict__ data, const DevTables &T, const LimbBatch &lb,
                                               const ConvArgs &cv, unsigned tile, unsigned b, u64 *lds)
 {
@@ -581,23 +604,23 @@ __device__ __forceinline__ void fwd_cols_limb(u64 *__restrict__ data, const DevT
     const bool split = PRO == PRO_MODUP ? T.up_split != 0 : pro_is_moddown(PRO) ? T.dn_split != 0 : false;
     const bool tint = PRO == PRO_MODDOWN_RS && S.qld == 0.0; // dropped limb on the integer path
     if (m.qd == 0.0)
-        fwd_cols_body<LOGN, PRO, false, false>(limb, tile * 16, make_int(T, mi, LOGN), lds, S, m);
+        fwd_cols_body<LOGN, PRO, false, false, EX>(limb, tile * 16, make_int(T, mi, LOGN), lds, S, m);
     else if (PRO == PRO_MODDOWN_RS && tint) {
         if (split)
-            fwd_cols_body<LOGN, PRO, true, PRO == PRO_MODDOWN_RS>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+            fwd_cols_body<LOGN, PRO, true, PRO == PRO_MODDOWN_RS, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
         else
-            fwd_cols_body<LOGN, PRO, false, PRO == PRO_MODDOWN_RS>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+            fwd_cols_body<LOGN, PRO, false, PRO == PRO_MODDOWN_RS, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
     } else if (split)
-        fwd_cols_body<LOGN, PRO, true, false>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+        fwd_cols_body<LOGN, PRO, true, false, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
     else
-        fwd_cols_body<LOGN, PRO, false, false>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+        fwd_cols_body<LOGN, PRO, false, false, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
 }
-template <int LOGN, int PRO, int NSMAX>
+template <int LOGN, int PRO, int NSMAX, bool EX>
 __device__ __forceinline__ void fwd_cols_kernel(u64 *__restrict__ data, const DevTables &T, const LimbBatch &lb,
                                                 const ConvArgs &cv)
 {
     __shared__ u64 lds[ColsGeom<LOGN>::LDS_WORDS];
-    fwd_cols_limb<LOGN, PRO, NSMAX>(data, T, lb, cv, blockIdx.x & 15, blockIdx.x >> 4, lds);
+    fwd_cols_limb<LOGN, PRO, NSMAX, EX>(data, T, lb, cv, blockIdx.x & 15, blockIdx.x >> 4, lds);
 }
 
 // ModUp column pass for two limbs per work-group (N = 2^16; grid.x = 16 * ceil(batch / 2)): limbs 2i and 2i+1 of
@@ -605,14 +628,14 @@ __device__ __forceinline__ void fwd_cols_kernel(u64 *__restrict__ data, const De
 // the targets of a digit follow each other in a launch), the digit's source limbs are read and converted to
 // doubles once and both base conversions are formed from them, term by term as in conv_get; every target
 // otherwise re-reads the same source tile through L2.  Any other pair is processed one limb after the other.
-template <int NSMAX>
+template <int NSMAX, bool EX>
 __global__ __launch_bounds__(256) void k_ntt_fwd_cols16_modup2(u64 *__restrict__ data, DevTables T, LimbBatch lb,
                                                                 ConvArgs cv, int nb)
 {
     __shared__ u64 lds[ColsGeom<16>::LDS_WORDS];
     const unsigned tile = blockIdx.x & 15, b0 = (blockIdx.x >> 4) * 2, b1 = b0 + 1;
     if (b1 >= (unsigned)nb) {
-        fwd_cols_limb<16, PRO_MODUP, NSMAX>(data, T, lb, cv, tile, b0, lds);
+        fwd_cols_limb<16, PRO_MODUP, NSMAX, EX>(data, T, lb, cv, tile, b0, lds);
         return;
     }
     const unsigned mi0 = lb.mod[b0], mi1 = lb.mod[b1], slot0 = lb.slot[b0], slot1 = lb.slot[b1];
@@ -622,9 +645,9 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols16_modup2(u64 *__restrict__
 #pragma unroll
     for (int s = 0; s < NSMAX; s++) same = same && S0.sp[s] == S1.sp[s];
     if (!same) {
-        fwd_cols_limb<16, PRO_MODUP, NSMAX>(data, T, lb, cv, tile, b0, lds);
+        fwd_cols_limb<16, PRO_MODUP, NSMAX, EX>(data, T, lb, cv, tile, b0, lds);
         __syncthreads(); // the first limb's second phase has read the tile
-        fwd_cols_limb<16, PRO_MODUP, NSMAX>(data, T, lb, cv, tile, b1, lds);
+        fwd_cols_limb<16, PRO_MODUP, NSMAX, EX>(data, T, lb, cv, tile, b1, lds);
         return;
     }
     const ArithFp ar0 = make_fp(T, mi0, 16), ar1 = make_fp(T, mi1, 16);
@@ -637,12 +660,12 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols16_modup2(u64 *__restrict__
 #pragma unroll
         for (int s = 0; s < NSMAX; s++) {
             const double y = u2d(S0.sp[s][pos]);
-            if (S0.exact) sv = sv + y * S0.rq[s];
+            if (EX) sv = sv + y * S0.rq[s];
             acc0 += ar0.mulmod(y, S0.cd[s]);
             acc1 += ar1.mulmod(y, S1.cd[s]);
             if ((s & 3) == 3 && s + 1 < NSMAX) acc0 = ar0.reduce(acc0), acc1 = ar1.reduce(acc1);
         }
-        if (S0.exact) { // one estimate of the multiple of D for both targets
+        if (EX) { // one estimate of the multiple of D for both targets
             const double v = __builtin_floor(sv);
             acc0 -= v * S0.dm_d, acc1 -= v * S1.dm_d;
         }
@@ -662,15 +685,16 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols16_modup2(u64 *__restrict__
     cols_finish_group<4>(a1, limb1, col0, rl, rl, ar1, lds);
 }
 // grid.x = 16 * batch
-template <int PRO, int NSMAX>
+// EX: the corrected conversions (a kernel of its own: their extra registers would cost the default form waves)
+template <int PRO, int NSMAX, bool EX>
 __global__ __launch_bounds__(256) void k_ntt_fwd_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
 {
-    fwd_cols_kernel<16, PRO, NSMAX>(data, T, lb, cv);
+    fwd_cols_kernel<16, PRO, NSMAX, EX>(data, T, lb, cv);
 }
-template <int PRO, int NSMAX>
+template <int PRO, int NSMAX, bool EX>
 __global__ __launch_bounds__(256) void k_ntt_fwd_cols17(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
 {
-    fwd_cols_kernel<17, PRO, NSMAX>(data, T, lb, cv);
+    fwd_cols_kernel<17, PRO, NSMAX, EX>(data, T, lb, cv);
 }
 
 // extra constant of the inverse column pass for modulus index mi
@@ -720,14 +744,14 @@ __global__ __launch_bounds__(256, 3) void k_ntt_inv_cols17(u64 *__restrict__ dat
 
 // ---- column pass, N = 2^12: 16 rows x 256 columns, one thread per column --------------------------------------
 
-template <int PRO, bool SPLIT, bool TINT, int NSMAX, class A>
+template <int PRO, bool SPLIT, bool TINT, bool EX, int NSMAX, class A>
 __device__ __forceinline__ void fwd_cols12_body(u64 *__restrict__ limb, const A &ar, const ConvSetup<NSMAX> &S,
                                                 const ModConst &m)
 {
     const unsigned c = threadIdx.x;
     typename A::V a[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = PRO == PRO_LOAD ? ar.load(limb[k * 256 + c]) : conv_get<PRO, SPLIT, TINT>(S, ar, m, k * 256 + c);
+    for (int k = 0; k < 16; k++) a[k] = PRO == PRO_LOAD ? ar.load(limb[k * 256 + c]) : conv_get<PRO, SPLIT, TINT, EX>(S, ar, m, k * 256 + c);
     ar.fwd16(a, 0, 0, PRO != PRO_LOAD);
 #pragma unroll
     for (int k = 0; k < 16; k++) limb[k * 256 + c] = ar.store_mid(a[k]);
@@ -743,7 +767,7 @@ template <class A> __device__ __forceinline__ void inv_cols12_body(u64 *__restri
     for (int k = 0; k < 16; k++) limb[k * 256 + c] = ar.store_final(a[k]);
 }
 
-template <int PRO, int NSMAX>
+template <int PRO, int NSMAX, bool EX>
 __global__ __launch_bounds__(256) void k_ntt_fwd_cols12(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
 {
     const unsigned mi = lb.mod[blockIdx.x], slot = lb.slot[blockIdx.x];
@@ -753,16 +777,16 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols12(u64 *__restrict__ data, 
     const bool split = PRO == PRO_MODUP ? T.up_split != 0 : pro_is_moddown(PRO) ? T.dn_split != 0 : false;
     const bool tint = PRO == PRO_MODDOWN_RS && S.qld == 0.0; // dropped limb on the integer path
     if (m.qd == 0.0)
-        fwd_cols12_body<PRO, false, false>(limb, make_int(T, mi, 12), S, m);
+        fwd_cols12_body<PRO, false, false, EX>(limb, make_int(T, mi, 12), S, m);
     else if (PRO == PRO_MODDOWN_RS && tint) {
         if (split)
-            fwd_cols12_body<PRO, true, PRO == PRO_MODDOWN_RS>(limb, make_fp(T, mi, 12), S, m);
+            fwd_cols12_body<PRO, true, PRO == PRO_MODDOWN_RS, EX>(limb, make_fp(T, mi, 12), S, m);
         else
-            fwd_cols12_body<PRO, false, PRO == PRO_MODDOWN_RS>(limb, make_fp(T, mi, 12), S, m);
+            fwd_cols12_body<PRO, false, PRO == PRO_MODDOWN_RS, EX>(limb, make_fp(T, mi, 12), S, m);
     } else if (split)
-        fwd_cols12_body<PRO, true, false>(limb, make_fp(T, mi, 12), S, m);
+        fwd_cols12_body<PRO, true, false, EX>(limb, make_fp(T, mi, 12), S, m);
     else
-        fwd_cols12_body<PRO, false, false>(limb, make_fp(T, mi, 12), S, m);
+        fwd_cols12_body<PRO, false, false, EX>(limb, make_fp(T, mi, 12), S, m);
 }
 
 template <int SCALE>

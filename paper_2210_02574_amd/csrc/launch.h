@@ -39,6 +39,9 @@ struct DevLaunch {
     // forward column pass of the nb limbs of lb, one launcher per prologue (PRO_*)
     void (*fwd_cols[5])(he_ctx *c, hipStream_t st, int kid, double bytes, bool wide, u64 *data, const LimbBatch &lb, int nb,
                         const ConvArgs &cv);
+    // the same with the corrected base conversions (entries of prologues without a conversion stay null)
+    void (*fwd_cols_ex[5])(he_ctx *c, hipStream_t st, int kid, double bytes, bool wide, u64 *data, const LimbBatch &lb, int nb,
+                           const ConvArgs &cv);
     // forward block pass of the first nb limbs of lb; fin: with the ModDown / rescale epilogue
     void (*fwd_blocks)(he_ctx *c, hipStream_t st, double bytes, bool fin, u64 *data, const LimbBatch &lb, int nb,
                        const FinArgs &fa, const HoistOuts &ho);
@@ -58,7 +61,10 @@ void dev_launch_n17_blocks(DevLaunch &t);
     void dev_launch_cols##n##_2(DevLaunch &t);                                                                       \
     void dev_launch_cols##n##_3(DevLaunch &t);                                                                       \
     void dev_launch_cols##n##_4(DevLaunch &t);                                                                       \
-    void dev_launch_cols##n##_5(DevLaunch &t);
+    void dev_launch_cols##n##_5(DevLaunch &t);                                                                       \
+    void dev_launch_cols_ex##n##_1(DevLaunch &t);                                                                    \
+    void dev_launch_cols_ex##n##_2(DevLaunch &t);                                                                    \
+    void dev_launch_cols_ex##n##_4(DevLaunch &t);
 HE_DECL_COLS(16)
 HE_DECL_COLS(17)
 #undef HE_DECL_COLS
