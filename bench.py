@@ -33,21 +33,36 @@ import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 
-# HBM traffic per launch (bytes, averaged over the launches of one step) from `rocprofv3 --pmc FETCH_SIZE` and
-# `--pmc WRITE_SIZE` runs of this command with --streams 1, scaled by the copy-kernel calibration
-# (2 x FETCH_SIZE + 1 x WRITE_SIZE; summary and calibration under profiles/).
-MEASURED_TRAFFIC_BYTES = {
-    "k_inner_blocks": 1226694451,
-    "k_ntt_fwd_blocks_fin": 510617190,
-    "k_ntt_fwd_blocks": 163075379,
-    "k_ntt_inv_blocks": 143577804,
-    "k_tensor": 704706764,
-    "k_ntt_fwd_cols_modup": 303587532,
-    "k_ntt_fwd_cols_moddown": 128296857,
-    "k_ntt_fwd_cols_moddown_rescale": 235787673,
-    "k_ntt_fwd_cols": 269812531,
-    "k_ntt_inv_cols": 97379745,
-}
+# Published peaks of one MI355X: HBM3E bandwidth, and the vector ALU rate that bounds the instruction-bound kernels:
+# 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (one FP64 multiply-add or one
+# 32-bit integer multiply-add per lane and cycle: 78.6 TFLOP/s of FP64).
+ALU_PEAK_TLIPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+# Hardware-counter figures per launch of each kernel come from the committed rocprofv3 summary below (its header
+# names the commit and the commands): scaled HBM traffic (2 x FETCH_SIZE + WRITE_SIZE, see the calibration there)
+# and vector instructions issued (64 x SQ_INSTS_VALU lane-instructions), both averaged over the launches of this
+# benchmark's step.  They are re-measured whenever a kernel changes; a missing file gives null fields.
+COUNTER_SUMMARY = os.path.join("profiles", "bench_step_N16_L24_counters.md")
+
+
+def load_counter_summary():
+    """{library kernel name: (traffic bytes per launch, lane-instructions per launch)} and the summary's source line."""
+    path = os.path.join(ROOT, COUNTER_SUMMARY)
+    table, source = {}, None
+    if not os.path.exists(path):
+        return table, source
+    source = COUNTER_SUMMARY
+    with open(path) as fh:
+        for line in fh:
+            if line.startswith("Measured at commit"):
+                source = COUNTER_SUMMARY + " (" + line.strip().rstrip(".") + ")"
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) >= 6 and cells[0].startswith("k_") and cells[0] != "kernel":
+                try:
+                    table[cells[0]] = (float(cells[4]), float(cells[5]))
+                except ValueError:
+                    pass
+    return table, source
 
 
 class Workload:
@@ -450,7 +465,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-train-step", action="store_true")
-    ap.add_argument("--hmult-batch", type=int, default=8, help="ciphertext pairs per batched HMult call")
+    ap.add_argument("--hmult-batch", type=int, default=16, help="ciphertext pairs per batched HMult call")
     ap.add_argument("--single-mode", choices=["levels", "per-level", "each"], default="levels",
                     help="how the 128 single rotations are issued: 32 per mixed-level call, one call per level, or one call each")
     ap.add_argument("--streams", type=int, default=3, help="HIP streams for the independent operations of a step")
@@ -520,28 +535,56 @@ def main():
     for _ in range(args.steps):
         w.step(serial=True)
     stats = he.profile_stop()
-    dom = max(stats.items(), key=lambda kv: kv[1][1])
-    name, (launches, total_ms, nbytes) = dom
-    achieved = nbytes / (total_ms / 1e3) / 1e9
+    counters, counter_source = load_counter_summary()
+
+    def kernel_entry(k, v, conc=None):
+        launches, total_ms, nbytes = v
+        avg_s = total_ms / 1e3 / launches if launches else 0.0
+        gbps = nbytes / (total_ms / 1e3) / 1e9 if total_ms else None
+        traffic, lane_insts = counters.get(k, (None, None))
+        e = {
+            "launches": launches, "total_ms": round(total_ms, 3), "avg_launch_us": round(avg_s * 1e6, 2),
+            "GBps": round(gbps, 1) if gbps else None,
+            "frac": round(gbps / HBM_PEAK_GBS, 4) if gbps else None,              # algorithmic bytes / own time / 8 TB/s
+            "traffic": traffic,                                                     # counter bytes per launch
+            "frac_counter": round(traffic / avg_s / 1e9 / HBM_PEAK_GBS, 4) if traffic and avg_s else None,
+            "alu_frac": round(lane_insts / avg_s / 1e12 / ALU_PEAK_TLIPS, 4) if lane_insts and avg_s else None,
+        }
+        fc, fa = e["frac_counter"] or e["frac"] or 0.0, e["alu_frac"] or 0.0
+        e["bound"] = "alu" if fa > fc else "hbm"
+        return e
+
+    kernels = {k: kernel_entry(k, v) for k, v in sorted(stats.items(), key=lambda kv: -kv[1][1])}
+    name = next(iter(kernels))
+    dom = kernels[name]
+    launches, total_ms, nbytes = stats[name]
     conc = stats_conc.get(name)
     roofline = {
         "kernel": name,
         "pass": "serial (each kernel alone on the GPU; same operations as the timed steps)",
         "frac_while_overlapped": (conc[2] / (conc[1] / 1e3) / 1e9 / HBM_PEAK_GBS) if conc and conc[1] else None,
         "bound": "hbm",
-        "achieved": achieved,
+        "achieved": dom["GBps"],
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
-        "frac": achieved / HBM_PEAK_GBS,
-        "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+        "frac": dom["frac"],                  # algorithmic bytes (each operand once per launch) / kernel time / peak
+        "frac_counter": dom["frac_counter"],  # counter-measured HBM traffic / kernel time / peak
+        "traffic": dom["traffic"],
+        "traffic_source": counter_source,
         "launches": launches,
         "avg_launch_us": total_ms * 1e3 / launches,
         "bytes_per_launch": nbytes / launches,
     }
-    kernels = {
-        k: {"launches": v[0], "total_ms": round(v[1], 3), "GBps": round(v[2] / (v[1] / 1e3) / 1e9, 1) if v[1] else None}
-        for k, v in sorted(stats.items(), key=lambda kv: -kv[1][1])
-    }
+    # the kernel with the most time among those bound by instruction issue rather than by memory
+    alu_name = next((k for k, e in kernels.items() if e["bound"] == "alu"), None)
+    roofline_alu = None
+    if alu_name:
+        e = kernels[alu_name]
+        roofline_alu = {
+            "kernel": alu_name, "bound": "alu", "achieved": round(e["alu_frac"] * ALU_PEAK_TLIPS, 2), "peak": round(ALU_PEAK_TLIPS, 2),
+            "unit": "T lane-instructions/s", "frac": e["alu_frac"], "frac_hbm": e["frac"], "frac_hbm_counter": e["frac_counter"],
+            "source": counter_source,
+        }
 
     out = {
         "metric": "HRot key-switches/sec at N=2^16 L=24 (whole step: NTT pairs + HMult+relin+rescale + hoisted and "
@@ -569,6 +612,7 @@ def main():
         },
         "detail": detail,
         "roofline": roofline,
+        "roofline_alu": roofline_alu,
         "kernels": kernels,
     }
     if not args.no_train_step:

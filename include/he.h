@@ -60,7 +60,7 @@ typedef struct he_sk he_sk;
 typedef struct he_evk he_evk;
 
 typedef struct {
-    int32_t logN;      /* ring degree N = 2^logN; device kernels support logN = 12 and 16 */
+    int32_t logN;      /* ring degree N = 2^logN; the device kernels are built for logN = 12, 16 and 17 */
     int32_t L;         /* number of ciphertext primes */
     int32_t K;         /* number of special primes */
     int32_t dnum;      /* number of key-switching digits; alpha = ceil(L/dnum) primes per digit */
@@ -72,7 +72,11 @@ typedef struct {
 
 /* Builds all tables (roots of unity, twiddles, base-conversion constants) on the host and,
  * when device >= 0, uploads them to that HIP device.  device = -1 gives a host-only context on
- * which the host functions work and every device function returns HE_ENODEV. */
+ * which the host functions work and every device function returns HE_ENODEV.
+ * HE_EINVAL: a modulus that is not below 2^60, not = 1 mod 2N or without a 2N-th root of unity, a repeated
+ * modulus, dnum < 1; and, for a device context, a size the kernels are not built for: logN other than 12, 16,
+ * 17; more than 8 primes per digit (alpha = ceil(L/dnum)) or more than 8 special primes (more than 4 of either
+ * at logN = 17); L + K above 64. */
 int32_t he_ctx_create(const he_params *params, int32_t device, he_ctx **out);
 void he_ctx_destroy(he_ctx *ctx);
 const char *he_strerror(int32_t code);
@@ -314,6 +318,8 @@ typedef struct {
     double bytes;
 } he_kernel_stat;
 int32_t he_profile_start(he_ctx *ctx);
+/* *n_out receives the number of kernels that ran; at most max_out entries are written, and HE_EINVAL is returned
+ * (with the first max_out entries filled and *n_out set to the number needed) when max_out is too small. */
 int32_t he_profile_stop(he_ctx *ctx, he_kernel_stat *out, int32_t max_out, int32_t *n_out);
 
 #ifdef __cplusplus

@@ -243,16 +243,19 @@ extern "C" int32_t he_profile_stop(he_ctx *ctx, he_kernel_stat *out, int32_t max
     }
     ctx->prof.clear();
     int32_t n = 0;
-    for (int k = 0; k < KID_COUNT && n < max_out; k++) {
+    for (int k = 0; k < KID_COUNT; k++) {
         if (!cnt[k]) continue;
-        memset(&out[n], 0, sizeof(out[n]));
-        strncpy(out[n].name, kKernelNames[k], sizeof(out[n].name) - 1);
-        out[n].launches = cnt[k];
-        out[n].total_ms = ms[k];
-        out[n].bytes = bytes[k];
+        if (n < max_out) {
+            memset(&out[n], 0, sizeof(out[n]));
+            strncpy(out[n].name, kKernelNames[k], sizeof(out[n].name) - 1);
+            out[n].launches = cnt[k];
+            out[n].total_ms = ms[k];
+            out[n].bytes = bytes[k];
+        }
         n++;
     }
     *n_out = n;
+    if (n > max_out && rc == HE_OK) rc = HE_EINVAL; // the caller's array is too small: n_out says how many are needed
     return rc;
 }
 
@@ -655,8 +658,17 @@ static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
     ia.g = g, ia.raised_stride = hoist && shared_raised ? 0 : W, ia.u_stride = W, ia.d_stride = d_stride, ia.inv_special = 1;
     ia.hoisted = hoist ? 1 : 0, ia.count = count;
     const HoistKeys &hk = hoist ? *hoist : kNoHoistKeys;
-    // reads beta digits and 2*beta key limbs per active modulus, writes 2 limbs per active modulus
-    const double inner_bytes = (double)count * (3 * beta + 2) * Ma * N * 8.0;
+    // Bytes by the definition of the step, each operand once per launch: every operation writes 2 limbs per active
+    // modulus; beta digits per active modulus are read once per raised input (one for hoisted rotations, else one
+    // per operation); 2 beta key limbs per active modulus are read once per distinct key of the launch.
+    int keys = 1;
+    if (hoist) {
+        std::vector<const u64 *> seen(hoist->evk, hoist->evk + count);
+        std::sort(seen.begin(), seen.end());
+        keys = (int)(std::unique(seen.begin(), seen.end()) - seen.begin());
+    }
+    const int inputs = hoist && shared_raised ? 1 : count;
+    const double inner_bytes = ((double)inputs * beta + 2.0 * count + 2.0 * beta * keys) * Ma * N * 8.0;
     dev_launch(c).inner(c, st, inner_bytes, grid.x, ia, hk);
     int32_t rc = launch_ok(c);
     if (rc != HE_OK) return rc;
@@ -991,11 +1003,18 @@ extern "C" int32_t he_hrot_batch_levels(he_ctx *ctx, const he_evk *const *rots, 
         ia.raised = ws + w.raised * N, ia.d = in0, ia.evk = rots[r]->dev, ia.u = ws + w.u * N;
         ia.level = lmax, ia.L = L, ia.K = K, ia.alpha = alpha, ia.beta = (lmax + alpha - 1) / alpha;
         ia.g = 1u, ia.raised_stride = W, ia.u_stride = W, ia.d_stride = 0, ia.inv_special = 1, ia.hoisted = 1, ia.count = nb;
+        // bytes by definition: digits and results per operation, each distinct key once at the largest level it serves
         double inner_bytes = 0.0;
+        std::vector<std::pair<const u64 *, int>> key_level;
         for (int o = 0; o < nb; o++) {
             const int lo = h_levels[r + o], beta = (lo + alpha - 1) / alpha;
-            inner_bytes += (double)(3 * beta + 2) * (lo + K) * N * 8.0;
+            inner_bytes += (double)(beta + 2) * (lo + K) * N * 8.0;
+            bool found = false;
+            for (auto &kl : key_level)
+                if (kl.first == hk.evk[o]) kl.second = std::max(kl.second, lo), found = true;
+            if (!found) key_level.push_back({hk.evk[o], lo});
         }
+        for (const auto &kl : key_level) inner_bytes += 2.0 * ((kl.second + alpha - 1) / alpha) * (kl.second + K) * N * 8.0;
         dev_launch(ctx).inner(ctx, st, inner_bytes, inner_grid((unsigned)(N / 4096), (unsigned)Ma, (unsigned)nb), ia, hk);
         if ((rc = launch_ok(ctx)) != HE_OK) return rc;
         LimbList sp;
