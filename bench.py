@@ -46,7 +46,8 @@ COUNTER_SUMMARY = os.path.join("profiles", "bench_step_N16_L24_counters.md")
 
 
 def load_counter_summary():
-    """{library kernel name: (traffic bytes per launch, lane-instructions per launch)} and the summary's source line."""
+    """{library kernel name: (traffic bytes, lane-instructions, algorithmic bytes), each per launch of the profiled
+    run} and the summary's source line."""
     path = os.path.join(ROOT, COUNTER_SUMMARY)
     table, source = {}, None
     if not os.path.exists(path):
@@ -57,9 +58,9 @@ def load_counter_summary():
             if line.startswith("Measured at commit"):
                 source = COUNTER_SUMMARY + " (" + line.strip().rstrip(".") + ")"
             cells = [c.strip() for c in line.strip().strip("|").split("|")]
-            if len(cells) >= 6 and cells[0].startswith("k_") and cells[0] != "kernel":
+            if len(cells) >= 7 and cells[0].startswith("k_") and cells[0] != "kernel":
                 try:
-                    table[cells[0]] = (float(cells[4]), float(cells[5]))
+                    table[cells[0]] = (float(cells[4]), float(cells[5]), float(cells[6]))
                 except ValueError:
                     pass
     return table, source
@@ -541,7 +542,11 @@ def main():
         launches, total_ms, nbytes = v
         avg_s = total_ms / 1e3 / launches if launches else 0.0
         gbps = nbytes / (total_ms / 1e3) / 1e9 if total_ms else None
-        traffic, lane_insts = counters.get(k, (None, None))
+        # counter figures of the profiled run, carried over in proportion to the algorithmic bytes per launch
+        traffic, lane_insts = None, None
+        if k in counters and counters[k][2] > 0 and launches:
+            scale = nbytes / launches / counters[k][2]
+            traffic, lane_insts = counters[k][0] * scale, counters[k][1] * scale
         e = {
             "launches": launches, "total_ms": round(total_ms, 3), "avg_launch_us": round(avg_s * 1e6, 2),
             "GBps": round(gbps, 1) if gbps else None,

@@ -31,11 +31,16 @@ def hipcc() -> str:
     return "hipcc"
 
 
+CODEGEN_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-ffp-contract=off",
+]
+
+
 def _flags():
-    return [
-        "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
-        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-        "-ffp-contract=off",
+    # HE_EXTRA_HIPCC_FLAGS: diagnostics such as -Rpass-analysis=kernel-resource-usage (not part of the source hash)
+    return CODEGEN_FLAGS + [
         "-Wall", "-Wno-unused-function",
         "-I", os.path.join(ROOT, "include"), "-I", CSRC,
     ] + os.environ.get("HE_EXTRA_HIPCC_FLAGS", "").split()
@@ -52,7 +57,7 @@ def source_hash() -> str:
         h.update(os.path.basename(f).encode() + b"\0")
         with open(f, "rb") as fh:
             h.update(fh.read())
-    h.update(" ".join(_flags()[:-4]).encode())  # flags without the include paths
+    h.update(" ".join(CODEGEN_FLAGS).encode())
     return h.hexdigest()
 
 

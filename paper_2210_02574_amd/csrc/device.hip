@@ -83,12 +83,13 @@ int32_t dev_upload_tables(he_ctx *c)
     if ((rc = upload(c, c->field, &c->dev.field)) != HE_OK) return rc;
     if ((rc = upload(c, c->modc, &c->dev.mod)) != HE_OK) return rc;
     UP(tw_fwd) UP(tw_inv) UP(ninv) UP(twd_fwd) UP(twd_inv) UP(ninvd)
-    UP(up_inv) UP(up_hat) UP(up_inv_d) UP(up_hat_d) UP(up_hat_dh) UP(rq) UP(up_dmod) UP(up_dmod_d) UP(up_hat_p)
+    UP(up_inv) UP(up_hat) UP(up_inv_d) UP(up_hat_d) UP(up_hat_dh) UP(rq) UP(up_dmod) UP(up_dmod_d) UP(up_hat_p) UP(dn_r50_d)
     UP(dn_inv) UP(dn_hat) UP(dn_pinv) UP(dn_inv_d) UP(dn_hat_d) UP(dn_hat_dh) UP(dn_pinv_d) UP(dn_pmod) UP(dn_pmod_d)
     UP(rs_inv) UP(rs_inv_d) UP(rsp_inv) UP(rsp_inv_d)
 #undef UP
     c->dev.up_split = c->up_split ? 1 : 0;
     c->dev.dn_split = c->dn_split ? 1 : 0;
+    c->dev.dn_fold = c->dn_fold ? 1 : 0;
     return HE_OK;
 }
 

@@ -59,6 +59,10 @@ struct DevTables {
     const u64 *dn_pmod;        // [L]      P mod q_i
     const double *dn_pmod_d;   // [L]
     int dn_split;              // some special prime is >= 2^50
+    // ModDown from such primes onto a modulus q below 2^50 with 2^50 mod q small (|.| < 2^40, as for primes just
+    // below a power of two): a source y = yh 2^50 + yl is first folded to yh (2^50 mod q) + yl, exact in a double
+    const double *dn_r50_d;    // [L]  2^50 mod q_i, balanced
+    int dn_fold;               // every floating-point ciphertext modulus qualifies
     // Rescale: q_l^-1 mod q_i
     const ShoupConst *rs_inv;  // [L][L]
     const double *rs_inv_d;    // [L][L]
@@ -88,7 +92,8 @@ struct he_ctx {
     std::vector<u64> up_hat;
     std::vector<double> up_inv_d, up_hat_d, up_hat_dh, dn_inv_d, dn_hat_d, dn_hat_dh, dn_pinv_d, dn_pmod_d, rs_inv_d, rsp_inv_d;
     std::vector<u64> dn_pmod;
-    std::vector<double> rq, up_dmod_d;
+    std::vector<double> rq, up_dmod_d, dn_r50_d;
+    bool dn_fold = false;
     std::vector<u64> up_dmod, up_hat_p;
     int exact_conv = 0; // corrected base conversions selected (he_ctx_set_conversion)
     bool up_split = false, dn_split = false;

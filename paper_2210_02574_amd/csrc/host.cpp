@@ -352,6 +352,14 @@ extern "C" int32_t he_ctx_create(const he_params *p, int32_t device, he_ctx **ou
         c->dn_pmod.assign(L, 0);
         c->dn_pmod_d.assign(L, 0.0);
         for (int i = 0; i < L; i++) c->dn_pmod[i] = prod_mod_excluding(c->mod, L, M, -1, c->mod[i]);
+        c->dn_r50_d.assign(L, 0.0);
+        c->dn_fold = c->dn_split;
+        for (int i = 0; i < L; i++) {
+            const u64 t = c->mod[i];
+            if (t >= kFp) continue;
+            c->dn_r50_d[i] = bal(kFp % t, t);
+            if (std::fabs(c->dn_r50_d[i]) >= 1099511627776.0) c->dn_fold = false; // 2^40
+        }
         c->rs_inv_d.assign((size_t)L * L, 0.0);
         c->rsp_inv_d.assign((size_t)L * L, 0.0);
         for (int k = 0; k < K; k++) {

@@ -104,6 +104,7 @@ template <int NSMAX> struct ConvSetup {
     u64 hs[NSMAX];
     u64 pm_i;
     double pm_d;
+    double r50;  // ModDown, SPLIT 2: 2^50 mod q
     // rescale
     u64 ql, half;
     double qld;
@@ -123,6 +124,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
     S.qld = 0.0;
     S.pm_i = 0;
     S.pm_d = 0.0;
+    S.r50 = 0.0;
     S.tp = nullptr;
     S.dm_i = 0;
     S.dm_d = 0.0;
@@ -172,6 +174,7 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
         }
         S.pm_i = T.dn_pmod[i];
         S.pm_d = T.dn_pmod_d[i];
+        S.r50 = T.dn_r50_d[i];
         if (PRO == PRO_MODDOWN_RS) {
             S.tp = cv.src2 + (((size_t)op * cv.src2_stride + (size_t)c * cv.level + cv.level - 1) << LOGN);
             S.ql = T.mod[cv.level - 1].q;
@@ -188,10 +191,11 @@ __device__ __forceinline__ ConvSetup<NSMAX> conv_setup(const ConvArgs &cv, const
     return S;
 }
 
-// SPLIT: the sources may be 2^50 or larger, so an FP64 target splits each at bit 31.  TINT (ModDown + rescale):
+// SPLIT 1: the sources may be 2^50 or larger, so an FP64 target splits each at bit 31; SPLIT 2 (ModDown): it folds
+// each at bit 50 instead, y = yh 2^50 + yl = yh r50 + yl modulo q with r50 = 2^50 mod q small (one product, not two).  TINT (ModDown + rescale):
 // the dropped limb is 2^50 or larger and is reduced with integers first; a template parameter rather than a
 // run-time branch, because the integer code would cost every launch 100 registers.
-template <int PRO, bool SPLIT, bool TINT, bool EX, int NSMAX>
+template <int PRO, int SPLIT, bool TINT, bool EX, int NSMAX>
 __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const ArithFp &ar, const ModConst &m, unsigned pos)
 {
     if (PRO == PRO_RESCALE) {
@@ -216,7 +220,11 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
         }
         if (!SPLIT)
             acc += ar.mulmod(u2d(y), S.cd[s]);
-        else {
+        else if (SPLIT == 2) {
+            // y = yh 2^50 + yl = yh r50 + yl modulo q: below 2^50 + 2^10 2^40, exact, and one product instead of two
+            const double yh = (double)(unsigned)(y >> 50), yl = u2d(y & 0x3FFFFFFFFFFFFull);
+            acc += ar.mulmod(__builtin_fma(yh, S.r50, yl), S.cd[s]);
+        } else {
             const double yh = (double)(unsigned)(y >> 31), yl = (double)(unsigned)(y & 0x7FFFFFFFu);
             acc += ar.mulmod(yh, S.cdh[s]) + ar.mulmod(yl, S.cd[s]);
         }
@@ -243,7 +251,7 @@ __device__ __forceinline__ double conv_get(const ConvSetup<NSMAX> &S, const Arit
     return acc;
 }
 
-template <int PRO, bool SPLIT, bool TINT, bool EX, int NSMAX>
+template <int PRO, int SPLIT, bool TINT, bool EX, int NSMAX>
 __device__ __forceinline__ u64 conv_get(const ConvSetup<NSMAX> &S, const ArithInt &, const ModConst &m, unsigned pos)
 {
     if (PRO == PRO_RESCALE) {
@@ -501,7 +509,7 @@ template <int LOGN> struct ColsGeom {
 };
 
 // the 16 inputs of one thread in rows rl + 16 k + 256 h (plain load or base conversion)
-template <int PRO, bool SPLIT, bool TINT, bool EX, int NSMAX, class A>
+template <int PRO, int SPLIT, bool TINT, bool EX, int NSMAX, class A>
 __device__ __forceinline__ void cols_inputs(typename A::V (&a)[16], const u64 *__restrict__ limb, unsigned col0, int h,
                                             const A &ar, const ConvSetup<NSMAX> &S, const ModConst &m)
 {
@@ -525,7 +533,7 @@ __device__ __forceinline__ void cols_finish_group(typename A::V (&a)[16], u64 *_
     for (int k = 0; k < 16; k++) limb[(16 * g + k) * 256 + col0 + c] = ar.store_mid(a[k]); // the block pass finishes
 }
 
-template <int LOGN, int PRO, bool SPLIT, bool TINT, bool EX, int NSMAX, class A>
+template <int LOGN, int PRO, int SPLIT, bool TINT, bool EX, int NSMAX, class A>
 __device__ __forceinline__ void fwd_cols_body(u64 *__restrict__ limb, unsigned col0, const A &ar, u64 *lds,
                                               const ConvSetup<NSMAX> &S, const ModConst &m)
 {
@@ -602,18 +610,21 @@ __device__ __forceinline__ void fwd_cols_limb(u64 *__restrict__ data, const DevT
     const ModConst m = T.mod[mi];
     const ConvSetup<NSMAX> S = conv_setup<PRO, NSMAX, LOGN>(cv, T, slot, mi);
     const bool split = PRO == PRO_MODUP ? T.up_split != 0 : pro_is_moddown(PRO) ? T.dn_split != 0 : false;
+    const bool fold = pro_is_moddown(PRO) && !EX && NSMAX <= 4 && T.dn_fold != 0; // the common case only: each variant costs code
     const bool tint = PRO == PRO_MODDOWN_RS && S.qld == 0.0; // dropped limb on the integer path
     if (m.qd == 0.0)
-        fwd_cols_body<LOGN, PRO, false, false, EX>(limb, tile * 16, make_int(T, mi, LOGN), lds, S, m);
+        fwd_cols_body<LOGN, PRO, 0, false, EX>(limb, tile * 16, make_int(T, mi, LOGN), lds, S, m);
     else if (PRO == PRO_MODDOWN_RS && tint) {
         if (split)
-            fwd_cols_body<LOGN, PRO, true, PRO == PRO_MODDOWN_RS, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+            fwd_cols_body<LOGN, PRO, 1, PRO == PRO_MODDOWN_RS, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
         else
-            fwd_cols_body<LOGN, PRO, false, PRO == PRO_MODDOWN_RS, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
-    } else if (split)
-        fwd_cols_body<LOGN, PRO, true, false, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+            fwd_cols_body<LOGN, PRO, 0, PRO == PRO_MODDOWN_RS, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+    } else if (fold)
+        fwd_cols_body<LOGN, PRO, pro_is_moddown(PRO) && !EX && NSMAX <= 4 ? 2 : 0, false, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+    else if (split)
+        fwd_cols_body<LOGN, PRO, 1, false, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
     else
-        fwd_cols_body<LOGN, PRO, false, false, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
+        fwd_cols_body<LOGN, PRO, 0, false, EX>(limb, tile * 16, make_fp(T, mi, LOGN), lds, S, m);
 }
 template <int LOGN, int PRO, int NSMAX, bool EX>
 __device__ __forceinline__ void fwd_cols_kernel(u64 *__restrict__ data, const DevTables &T, const LimbBatch &lb,
@@ -744,7 +755,7 @@ __global__ __launch_bounds__(256, 3) void k_ntt_inv_cols17(u64 *__restrict__ dat
 
 // ---- column pass, N = 2^12: 16 rows x 256 columns, one thread per column --------------------------------------
 
-template <int PRO, bool SPLIT, bool TINT, bool EX, int NSMAX, class A>
+template <int PRO, int SPLIT, bool TINT, bool EX, int NSMAX, class A>
 __device__ __forceinline__ void fwd_cols12_body(u64 *__restrict__ limb, const A &ar, const ConvSetup<NSMAX> &S,
                                                 const ModConst &m)
 {
@@ -776,17 +787,20 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols12(u64 *__restrict__ data, 
     const ConvSetup<NSMAX> S = conv_setup<PRO, NSMAX, 12>(cv, T, slot, mi);
     const bool split = PRO == PRO_MODUP ? T.up_split != 0 : pro_is_moddown(PRO) ? T.dn_split != 0 : false;
     const bool tint = PRO == PRO_MODDOWN_RS && S.qld == 0.0; // dropped limb on the integer path
+    const bool fold = pro_is_moddown(PRO) && !EX && NSMAX <= 4 && T.dn_fold != 0; // the common case only: each variant costs code
     if (m.qd == 0.0)
-        fwd_cols12_body<PRO, false, false, EX>(limb, make_int(T, mi, 12), S, m);
+        fwd_cols12_body<PRO, 0, false, EX>(limb, make_int(T, mi, 12), S, m);
     else if (PRO == PRO_MODDOWN_RS && tint) {
         if (split)
-            fwd_cols12_body<PRO, true, PRO == PRO_MODDOWN_RS, EX>(limb, make_fp(T, mi, 12), S, m);
+            fwd_cols12_body<PRO, 1, PRO == PRO_MODDOWN_RS, EX>(limb, make_fp(T, mi, 12), S, m);
         else
-            fwd_cols12_body<PRO, false, PRO == PRO_MODDOWN_RS, EX>(limb, make_fp(T, mi, 12), S, m);
-    } else if (split)
-        fwd_cols12_body<PRO, true, false, EX>(limb, make_fp(T, mi, 12), S, m);
+            fwd_cols12_body<PRO, 0, PRO == PRO_MODDOWN_RS, EX>(limb, make_fp(T, mi, 12), S, m);
+    } else if (fold)
+        fwd_cols12_body<PRO, pro_is_moddown(PRO) && !EX && NSMAX <= 4 ? 2 : 0, false, EX>(limb, make_fp(T, mi, 12), S, m);
+    else if (split)
+        fwd_cols12_body<PRO, 1, false, EX>(limb, make_fp(T, mi, 12), S, m);
     else
-        fwd_cols12_body<PRO, false, false, EX>(limb, make_fp(T, mi, 12), S, m);
+        fwd_cols12_body<PRO, 0, false, EX>(limb, make_fp(T, mi, 12), S, m);
 }
 
 template <int SCALE>
