@@ -71,6 +71,13 @@ def load_library() -> ctypes.CDLL:
                 f"{LIB_PATH} is missing: build it with `python -m paper_2210_02574_amd.build` "
                 "(hipcc --offload-arch=gfx950); there is no fallback path"
             )
+        from .build import is_stale
+
+        if is_stale() and not os.environ.get("HE_ALLOW_STALE_LIB"):
+            raise ImportError(
+                f"{LIB_PATH} was built from other sources than the present ones: rebuild it with "
+                "`python -m paper_2210_02574_amd.build` (or set HE_ALLOW_STALE_LIB=1 to load it anyway)"
+            )
         # torch first: it brings its own HIP runtime, and a process must not end up with the system's runtime
         # initialised by this library and torch's by torch (the second one then finds no GPU)
         import torch  # noqa: F401

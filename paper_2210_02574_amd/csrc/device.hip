@@ -652,7 +652,7 @@ static int32_t ks_inner(he_ctx *c, const he_evk *evk, const u64 *d_ntt, int d_st
     const int K = c->K, Ma = level + K, beta = (level + c->alpha - 1) / c->alpha, W = (int)w.total;
     const unsigned g = (unsigned)evk->galois;
     if (misaligned16(ws) || misaligned16(d_ntt) || misaligned16(evk->dev)) return HE_EINVAL; // entry points check first
-    dim3 grid(inner_grid((unsigned)(N / 4096), (unsigned)Ma, (unsigned)count));
+    dim3 grid(inner_grid((unsigned)(N / INNER_TILE), (unsigned)Ma, (unsigned)count));
     InnerArgs ia;
     ia.raised = ws + w.raised * N, ia.d = d_ntt, ia.evk = evk->dev, ia.u = ws + w.u * N;
     ia.level = level, ia.L = c->L, ia.K = K, ia.alpha = c->alpha, ia.beta = beta;
@@ -1016,7 +1016,7 @@ extern "C" int32_t he_hrot_batch_levels(he_ctx *ctx, const he_evk *const *rots, 
             if (!found) key_level.push_back({hk.evk[o], lo});
         }
         for (const auto &kl : key_level) inner_bytes += 2.0 * ((kl.second + alpha - 1) / alpha) * (kl.second + K) * N * 8.0;
-        dev_launch(ctx).inner(ctx, st, inner_bytes, inner_grid((unsigned)(N / 4096), (unsigned)Ma, (unsigned)nb), ia, hk);
+        dev_launch(ctx).inner(ctx, st, inner_bytes, inner_grid((unsigned)(N / INNER_TILE), (unsigned)Ma, (unsigned)nb), ia, hk);
         if ((rc = launch_ok(ctx)) != HE_OK) return rc;
         LimbList sp;
         for (int o = 0; o < nb; o++)

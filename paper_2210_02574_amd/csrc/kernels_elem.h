@@ -101,7 +101,9 @@ __global__ __launch_bounds__(256) void k_tensor(const u64 *A, const u64 *B, u64 
     out += ((size_t)blockIdx.z * out_stride) << logN;
     d2 += ((size_t)blockIdx.z * d2_stride) << logN;
     const size_t o0 = ((size_t)i << logN) + n, o1 = ((size_t)(level + i) << logN) + n;
-    const u64 a0 = A[o0], a1 = A[o1], b0 = B[o0], b1 = B[o1];
+    // every operand is read once and every result is for a later launch: streamed past the caches
+    const u64 a0 = __builtin_nontemporal_load(A + o0), a1 = __builtin_nontemporal_load(A + o1);
+    const u64 b0 = __builtin_nontemporal_load(B + o0), b1 = __builtin_nontemporal_load(B + o1);
     u64 r0, r1, r2;
     if (m.qd != 0.0) {
         const double x0 = u2d(a0), x1 = u2d(a1), y0 = u2d(b0), y1 = u2d(b1);
@@ -114,7 +116,7 @@ __global__ __launch_bounds__(256) void k_tensor(const u64 *A, const u64 *B, u64 
         mac128(acc, a1, b0);
         r0 = mul_mod(a0, b0, m), r1 = reduce128(acc, m), r2 = mul_mod(a1, b1, m);
     }
-    out[o0] = r0;
-    out[o1] = r1;
-    d2[o0] = r2;
+    __builtin_nontemporal_store(r0, out + o0);
+    __builtin_nontemporal_store(r1, out + o1);
+    __builtin_nontemporal_store(r2, d2 + o0);
 }

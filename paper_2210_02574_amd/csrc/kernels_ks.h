@@ -6,10 +6,10 @@
 //
 // u[c][a][n] = sum_j D_j[a][pi_g(n)] * evk[j][c][mod(a)][n] on every active limb a, where D_j[a] is the
 // raised digit outside digit j and the NTT-domain input d[a] inside it.
-// One work-group produces 4096 consecutive outputs (16 blocks of 256) of one active limb.  The index map of
+// One work-group produces INNER_TILE consecutive outputs (a few blocks of 256) of one active limb.  The index map of
 // sigma_g sends aligned groups of 2^m consecutive NTT-domain indices to aligned groups (the low bits of
 // (2 brv(k) + 1) g depend only on the low bits of brv(k), i.e. on the high bits of k), so the sources of
-// these outputs are the 4096 indices of one input tile.  For a limb on the floating-point path the raised
+// these outputs are the indices of one input tile of that size.  For a limb on the floating-point path the raised
 // digits arrive as the column pass left them; each is finished here (stages logN-8 .. logN-1) into LDS
 // and read back through the index map, so the transformed digits never travel to memory.  Limbs on
 // the integer path read digits that the block-pass kernel has finished.  With inv_special the special
@@ -48,19 +48,28 @@ __host__ __device__ inline unsigned inner_grid(unsigned tiles, unsigned limbs, u
     return (tiles * limbs + XCDS - 1) / XCDS * XCDS * count;
 }
 
-// 512 threads per work-group and eight elements per thread (128 registers, four waves per SIMD).  A 256-element
+// Eight elements per thread (128 registers, four waves per SIMD) and 128 threads per work-group: measured at 512,
+// 256, 128 and 64 threads, the small work-groups win by 3 to 8 % because the barriers between the phases of a
+// digit then stall two waves instead of eight while the other work-groups of the compute unit run.  A 256-element
 // block belongs to 32 lanes (half a wave) and its block pass runs as three register steps, stages 0-2, 3-5 and
 // 6-7 of the block, with two exchanges through LDS among those lanes:
 //   step 1: lane t holds e = t + 32 k;   step 2: lane (g = t & 7, r = t >> 3) holds e = 32 g + r + 4 k;
 //   step 3: lane t holds e = 4 t + k' and 128 + 4 t + k' (k' < 4).
 // With one pad word per 16 elements every 16 consecutive lanes of each pattern hit 16 different 8-byte banks.
 // All 255 twiddles of a block's eight stages sit in LDS, the one of local stage m and group i at 2^m - 1 + i.
-// In the product phase thread t owns the pairs (4096 tile + 1024 i + 2 t, + 1), i < 4.
+// In the product phase thread t owns the pairs (INNER_TILE tile + 2 INNER_THREADS i + 2 t, + 1), i < 4.
 
-__device__ __forceinline__ unsigned pair8_at(unsigned i) { return 1024u * i + 2u * threadIdx.x; }
+#ifndef INNER_THREADS
+#define INNER_THREADS 128
+#endif
+#define INNER_TILE (INNER_THREADS * 8)      // outputs per work-group
+#define INNER_BLOCKS (INNER_THREADS / 32)   // 256-element blocks per work-group
+#define INNER_TLOG (INNER_THREADS == 512 ? 12 : INNER_THREADS == 256 ? 11 : INNER_THREADS == 128 ? 10 : 9)
+static_assert(INNER_THREADS == 512 || INNER_THREADS == 256 || INNER_THREADS == 128 || INNER_THREADS == 64, "tile of 4096, 2048, 1024 or 512 outputs");
+__device__ __forceinline__ unsigned pair8_at(unsigned i) { return 2u * INNER_THREADS * i + 2u * threadIdx.x; }
 
-// Inverse block pass of the special limbs from the pairs of the product phase: the 4096 results go through LDS
-// to the first 256 threads, which run the 16-element form; the other threads only take part in the barriers.
+// Inverse block pass of the special limbs from the pairs of the product phase: the results go through LDS to the
+// first half of the threads, which run the 16-element form; the other threads only take part in the barriers.
 template <int LOGN, class A>
 __device__ __forceinline__ void inv_blocks_from_pairs8(const u64 (&r)[8], u64 *limb, const A &ar, u64 *lds, unsigned tile)
 {
@@ -71,8 +80,8 @@ __device__ __forceinline__ void inv_blocks_from_pairs8(const u64 (&r)[8], u64 *l
         lds[tile_at(p >> 8, (p & 255u) + 1)] = r[2 * i + 1];
     }
     __syncthreads();
-    if (threadIdx.x < 256) {
-        const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15, bg = tile * 16 + blk;
+    if (threadIdx.x < INNER_THREADS / 2) {
+        const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15, bg = tile * INNER_BLOCKS + blk;
         typename A::V a[16];
 #pragma unroll
         for (int k = 0; k < 16; k++) a[k] = ar.load(lds[tile_at(blk, 16 * il + k)]);
@@ -98,12 +107,12 @@ template <class Tv> __device__ __forceinline__ Tv ld_at(const void *base, unsign
     return *(const Tv *)((const char *)base + byte_off);
 }
 
-template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(InnerArgs ia, DevTables T, HoistKeys hk)
+template <int LOGN> __global__ __launch_bounds__(INNER_THREADS, 4) void k_inner_blocks8(InnerArgs ia, DevTables T, HoistKeys hk)
 {
-    __shared__ u64 lds[16 * TILE_GROUP];
-    __shared__ double tws[16 * 256];
+    __shared__ u64 lds[INNER_BLOCKS * TILE_GROUP];
+    __shared__ double tws[INNER_BLOCKS * 256];
     const int level = ia.level, M = ia.L + ia.K, Ma = level + ia.K;
-    const unsigned ntile = 1u << (LOGN - 12);
+    const unsigned ntile = 1u << (LOGN - INNER_TLOG);
     const unsigned slot = blockIdx.x / XCDS, op = slot % (unsigned)ia.count;
     const unsigned tl = slot / (unsigned)ia.count * XCDS + blockIdx.x % XCDS;
     if (tl >= ntile * (unsigned)Ma) return; // padding of the last group of eight (whole work-group)
@@ -118,11 +127,11 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
     const int own = a < level ? a / ia.alpha : -1;
     const ModConst m = T.mod[mi];
     const unsigned blk = threadIdx.x >> 5, t = threadIdx.x & 31;
-    const unsigned tile_in = g == 1 ? tile : galois_index(tile << 12, g, LOGN) >> 12;
+    const unsigned tile_in = g == 1 ? tile : galois_index(tile << INNER_TLOG, g, LOGN) >> INNER_TLOG;
     // wave-uniform bases (bytes): raised digit 0 and key component 0 of digit 0 for this limb and tile; digit j is
     // raised_step / key_step further on, key component 1 comp_step after component 0
-    const char *raised0 = (const char *)(ia.raised + ((((size_t)op * ia.raised_stride + a) << LOGN) + ((size_t)tile_in << 12)));
-    const char *key0 = (const char *)((ia.hoisted ? hk.evk[op] : ia.evk) + (((size_t)mi << LOGN) + ((size_t)tile << 12)));
+    const char *raised0 = (const char *)(ia.raised + ((((size_t)op * ia.raised_stride + a) << LOGN) + ((size_t)tile_in << INNER_TLOG)));
+    const char *key0 = (const char *)((ia.hoisted ? hk.evk[op] : ia.evk) + (((size_t)mi << LOGN) + ((size_t)tile << INNER_TLOG)));
     const char *d_limb = (const char *)((ia.hoisted && hk.d[op] ? hk.d[op] : ia.d + (((size_t)op * ia.d_stride) << LOGN)) + ((size_t)a << LOGN));
     const size_t raised_step = ((size_t)Ma << LOGN) * 8, comp_step = ((size_t)M << LOGN) * 8, key_step = 2 * comp_step;
     const unsigned lane16 = threadIdx.x * 16u;        // this thread's pair within a 512-pair row of the tile
@@ -132,9 +141,9 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
     unsigned lsx[4], lsy[4], swm = 0;
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-        const unsigned pos = (tile << 12) + pair8_at(i);
+        const unsigned pos = (tile << INNER_TLOG) + pair8_at(i);
         const unsigned sr = g == 1 ? pos : galois_index(pos, g, LOGN);
-        const unsigned sl = sr & 4094u, sw = sr & 1u;
+        const unsigned sl = sr & (INNER_TILE - 2u), sw = sr & 1u;
         const unsigned w = (sl >> 8) * TILE_GROUP + (sl & 255u) + ((sl & 255u) >> 4);
         lsx[i] = w + sw, lsy[i] = w + 1 - sw;
         swm |= sw << i;
@@ -143,7 +152,7 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
     if (m.qd != 0.0) {
         const ArithFp ar = make_fp(T, mi, LOGN);
         double *tw = tws + blk * 256;
-        for (unsigned c = t; c < 255; c += 32) tw[c] = ar.twf[ArithFp::fwd16_twiddle(LOGN - 8, tile_in * 16 + blk, c)];
+        for (unsigned c = t; c < 255; c += 32) tw[c] = ar.twf[ArithFp::fwd16_twiddle(LOGN - 8, tile_in * INNER_BLOCKS + blk, c)];
         __syncthreads();
         const unsigned g2 = t & 7, r2 = t >> 3;
         u64 *l1 = lds + blk * TILE_GROUP + t + (t >> 4);
@@ -159,7 +168,7 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
             if (j == own) {
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
-                    const unsigned pos = (tile << 12) + pair8_at(i);
+                    const unsigned pos = (tile << INNER_TLOG) + pair8_at(i);
                     const unsigned sr = g == 1 ? pos : galois_index(pos, g, LOGN);
                     const u64x2 v = ld_at<u64x2>(d_limb, (sr & ~1u) * 8u);
                     const bool sw = (swm >> i) & 1u;
@@ -167,15 +176,19 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
                 }
 #pragma unroll
                 for (int i = 0; i < 4; i++)
-                    e0[i] = ld_at<f64x2>(kj + 8192 * i, lane16), e1[i] = ld_at<f64x2>(kj + comp_step + 8192 * i, lane16);
+                    e0[i] = ld_at<f64x2>(kj + INNER_THREADS * 16 * i, lane16), e1[i] = ld_at<f64x2>(kj + comp_step + INNER_THREADS * 16 * i, lane16);
             } else {
                 const char *mid = raised0 + (size_t)j * raised_step;
 #pragma unroll
-                for (int k = 0; k < 8; k++) dv[k] = ar.load_mid(ld_at<u64>(mid + 256 * k, lane_mid));
+                for (int k = 0; k < 8; k++) {
+                    // a digit that only this operation reads is streamed past the key slices that the batch shares in L2
+                    const u64 *src = (const u64 *)(mid + 256 * k + lane_mid);
+                    dv[k] = ar.load_mid(ia.raised_stride != 0 ? __builtin_nontemporal_load(src) : *src);
+                }
                 // the key loads are issued before the block pass and complete behind it
 #pragma unroll
                 for (int i = 0; i < 4; i++)
-                    e0[i] = ld_at<f64x2>(kj + 8192 * i, lane16), e1[i] = ld_at<f64x2>(kj + comp_step + 8192 * i, lane16);
+                    e0[i] = ld_at<f64x2>(kj + INNER_THREADS * 16 * i, lane16), e1[i] = ld_at<f64x2>(kj + comp_step + INNER_THREADS * 16 * i, lane16);
                 // ranges (in units of q): the column pass leaves up to 3.7; reduced, step 1 ends below 2.7 and
                 // step 2 below 6.3; reduced again, step 3 ends below 1.9, small enough for exact products
                 ar.fwd8_with(dv, true, [&](int sp, int gg) { return tw[(1 << sp) - 1 + gg]; });
@@ -217,7 +230,7 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
         unsigned so[4];
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            const unsigned pos = (tile << 12) + pair8_at(i);
+            const unsigned pos = (tile << INNER_TLOG) + pair8_at(i);
             so[i] = ((g == 1 ? pos : galois_index(pos, g, LOGN)) & ~1u) * 8u;
         }
         const char *fin0 = (const char *)(ia.raised + (((size_t)op * ia.raised_stride + a) << LOGN));
@@ -235,7 +248,7 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
                     const u64x2 v = ld_at<u64x2>(dj, so[ii]);
                     const bool sw = (swm >> ii) & 1u;
                     const u64 x = sw ? v.y : v.x, y = sw ? v.x : v.y;
-                    const u64x2 ka = ld_at<u64x2>(kj + 8192 * ii, lane16), kb = ld_at<u64x2>(kj + comp_step + 8192 * ii, lane16);
+                    const u64x2 ka = ld_at<u64x2>(kj + INNER_THREADS * 16 * ii, lane16), kb = ld_at<u64x2>(kj + comp_step + INNER_THREADS * 16 * ii, lane16);
                     mac128(acc0[2 * i], x, ka.x);
                     mac128(acc0[2 * i + 1], y, ka.y);
                     mac128(acc1[2 * i], x, kb.x);
@@ -258,11 +271,11 @@ template <int LOGN> __global__ __launch_bounds__(512, 4) void k_inner_blocks8(In
             inv_blocks_from_pairs8<LOGN>(r1, u1, ar, lds, tile);
         }
     } else {
-        char *o0 = (char *)(u0 + ((size_t)tile << 12)), *o1 = (char *)(u1 + ((size_t)tile << 12));
+        char *o0 = (char *)(u0 + ((size_t)tile << INNER_TLOG)), *o1 = (char *)(u1 + ((size_t)tile << INNER_TLOG));
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            *(u64x2 *)(o0 + 8192 * i + lane16) = u64x2{r0[2 * i], r0[2 * i + 1]};
-            *(u64x2 *)(o1 + 8192 * i + lane16) = u64x2{r1[2 * i], r1[2 * i + 1]};
+            __builtin_nontemporal_store(u64x2{r0[2 * i], r0[2 * i + 1]}, (u64x2 *)(o0 + INNER_THREADS * 16 * i + lane16));
+            __builtin_nontemporal_store(u64x2{r1[2 * i], r1[2 * i + 1]}, (u64x2 *)(o1 + INNER_THREADS * 16 * i + lane16));
         }
     }
 }

@@ -337,7 +337,7 @@ __device__ __forceinline__ FinOperands fin_load(const FinArgs &fa, const HoistOu
     slot -= op * (unsigned)fa.dst_stride;
     const unsigned c = slot / fa.nl, i = slot % fa.nl;
     FinOperands o;
-    o.uv = fa.u[(((size_t)op * fa.u_stride + (size_t)c * fa.u_cstride + i) << LOGN) + pos];
+    o.uv = __builtin_nontemporal_load(fa.u + ((((size_t)op * fa.u_stride + (size_t)c * fa.u_cstride + i) << LOGN) + pos));
     o.av = 0;
     if (fa.mode == 1)
         o.av = fa.out[(((size_t)op * fa.out_stride + (size_t)c * fa.out_cstride + i) << LOGN) + pos];
@@ -375,7 +375,7 @@ __device__ __forceinline__ void fin_store(const FinArgs &fa, const HoistOuts &ho
         const u64 av = scaled ? mul_shoup(fo.av, fa.cst2[i], m.q) : fo.av;
         res = csub(mul_shoup(fo.uv + m.q - rv, fa.cst[i], m.q) + av, m.q);
     }
-    (fa.hoisted ? ho.out[op] : fa.out)[o] = res;
+    __builtin_nontemporal_store(res, (fa.hoisted ? ho.out[op] : fa.out) + o); // a result: nothing in this launch reads it
 }
 
 // LDS tile of the block pass: 16 groups x 256 elements; one pad word per 16 elements and 16 pad words per
@@ -413,7 +413,8 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
     typename A::V a[16];
     FinOperands fo[EPI == EPI_FIN ? 16 : 1];
 #pragma unroll
-    for (int k = 0; k < 16; k++) a[k] = ar.load_mid(limb[bg * 256 + il + 16 * k]);
+    for (int k = 0; k < 16; k++)
+        a[k] = ar.load_mid(EPI == EPI_FIN ? __builtin_nontemporal_load(limb + bg * 256 + il + 16 * k) : limb[bg * 256 + il + 16 * k]);
     if (EPI == EPI_FIN) {
 #pragma unroll
         for (int k = 0; k < 16; k++) fo[k] = fin_load<LOGN>(fa, ho, T, slot, bg * 256 + il + 16 * k);
@@ -444,11 +445,15 @@ template <int LOGN, class A>
 __device__ __forceinline__ void inv_blocks_body(const u64 *in, u64 *limb, const A &ar,
                                                 u64 *lds, unsigned tile)
 {
+    const bool stream = in != limb; // out of place: part of a conversion, whose batch is far larger than the caches
     const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
     const unsigned bg = tile * BLK_PER_WG + blk;
     typename A::V a[16];
 #pragma unroll
-    for (int k = 0; k < 16; k++) lds[tile_at(blk, il + 16 * k)] = in[bg * 256 + il + 16 * k];
+    for (int k = 0; k < 16; k++) {
+        const u64 *src = in + bg * 256 + il + 16 * k;
+        lds[tile_at(blk, il + 16 * k)] = stream ? __builtin_nontemporal_load(src) : *src;
+    }
     block_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) a[k] = ar.load(lds[tile_at(blk, 16 * il + k)]);
@@ -461,7 +466,13 @@ __device__ __forceinline__ void inv_blocks_body(const u64 *in, u64 *limb, const 
     for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[tile_at(blk, il + 16 * k)]);
     ar.template inv16<false>(a, LOGN - 8, bg);
 #pragma unroll
-    for (int k = 0; k < 16; k++) limb[bg * 256 + il + 16 * k] = ar.store_mid(a[k]); // the column pass finishes
+    for (int k = 0; k < 16; k++) { // the column pass finishes
+        u64 *dst = limb + bg * 256 + il + 16 * k;
+        if (stream)
+            __builtin_nontemporal_store(ar.store_mid(a[k]), dst);
+        else
+            *dst = ar.store_mid(a[k]);
+    }
 }
 
 // grid.x = (N/4096) * batch
@@ -520,8 +531,9 @@ __device__ __forceinline__ void cols_inputs(typename A::V (&a)[16], const u64 *_
         a[k] = PRO == PRO_LOAD ? ar.load(limb[pos]) : conv_get<PRO, SPLIT, TINT, EX>(S, ar, m, pos);
     }
 }
-// second phase of the forward column pass for rows 16 g .. 16 g + 15, held in LDS as group gl
-template <int S_BASE, class A>
+// second phase of the forward column pass for rows 16 g .. 16 g + 15, held in LDS as group gl.  STREAM: the
+// output is a new buffer that a later kernel reads, so it is stored past the sources that stay in L2
+template <int S_BASE, bool STREAM, class A>
 __device__ __forceinline__ void cols_finish_group(typename A::V (&a)[16], u64 *__restrict__ limb, unsigned col0, unsigned g,
                                                   unsigned gl, const A &ar, const u64 *lds)
 {
@@ -530,7 +542,13 @@ __device__ __forceinline__ void cols_finish_group(typename A::V (&a)[16], u64 *_
     for (int k = 0; k < 16; k++) a[k] = ar.load_mid(lds[col_at(16 * gl + k, c)]);
     ar.fwd16(a, S_BASE, g, true);
 #pragma unroll
-    for (int k = 0; k < 16; k++) limb[(16 * g + k) * 256 + col0 + c] = ar.store_mid(a[k]); // the block pass finishes
+    for (int k = 0; k < 16; k++) { // the block pass finishes
+        u64 *dst = limb + (16 * g + k) * 256 + col0 + c;
+        if (STREAM)
+            __builtin_nontemporal_store(ar.store_mid(a[k]), dst);
+        else
+            *dst = ar.store_mid(a[k]);
+    }
 }
 
 template <int LOGN, int PRO, int SPLIT, bool TINT, bool EX, int NSMAX, class A>
@@ -546,7 +564,7 @@ __device__ __forceinline__ void fwd_cols_body(u64 *__restrict__ limb, unsigned c
 #pragma unroll
         for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a0[k]);
         __syncthreads();
-        cols_finish_group<4>(a0, limb, col0, rl, rl, ar, lds);
+        cols_finish_group<4, PRO != PRO_LOAD>(a0, limb, col0, rl, rl, ar, lds);
     } else {
         typename A::V a1[16];
         // one half's source loads at a time: 32 outputs x up to 8 sources in flight would not fit the registers
@@ -559,16 +577,17 @@ __device__ __forceinline__ void fwd_cols_body(u64 *__restrict__ limb, unsigned c
 #pragma unroll
         for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a0[k]);
         __syncthreads();
-        cols_finish_group<5>(a0, limb, col0, rl, rl, ar, lds);
+        cols_finish_group<5, PRO != PRO_LOAD>(a0, limb, col0, rl, rl, ar, lds);
         __syncthreads();
 #pragma unroll
         for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar.store_mid(a1[k]);
         __syncthreads();
-        cols_finish_group<5>(a1, limb, col0, rl + 16, rl, ar, lds);
+        cols_finish_group<5, PRO != PRO_LOAD>(a1, limb, col0, rl + 16, rl, ar, lds);
     }
 }
 
-template <int LOGN, class A>
+// STREAM: the input is the first half of a conversion's inverse transform, read this once only
+template <int LOGN, bool STREAM, class A>
 __device__ __forceinline__ void inv_cols_body(u64 *__restrict__ limb, unsigned col0, const A &ar, u64 *lds)
 {
     constexpr int H = ColsGeom<LOGN>::HALVES;
@@ -580,7 +599,10 @@ __device__ __forceinline__ void inv_cols_body(u64 *__restrict__ limb, unsigned c
     for (int h = 0; h < H; h++) {
         const unsigned g = rl + 16 * h;
 #pragma unroll
-        for (int k = 0; k < 16; k++) a[h][k] = ar.load_mid(limb[(16 * g + k) * 256 + col0 + c]);
+        for (int k = 0; k < 16; k++) {
+            const u64 *src = limb + (16 * g + k) * 256 + col0 + c;
+            a[h][k] = ar.load_mid(STREAM ? __builtin_nontemporal_load(src) : *src);
+        }
         ar.template inv16<false>(a[h], H + 3, g);
         if (h > 0) __syncthreads(); // the previous half has been read back by every thread
 #pragma unroll
@@ -687,13 +709,13 @@ __global__ __launch_bounds__(256) void k_ntt_fwd_cols16_modup2(u64 *__restrict__
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar0.store_mid(a0[k]);
     __syncthreads();
-    cols_finish_group<4>(a0, limb0, col0, rl, rl, ar0, lds);
+    cols_finish_group<4, true>(a0, limb0, col0, rl, rl, ar0, lds);
     __syncthreads();
     ar1.fwd16(a1, 0, 0, true);
 #pragma unroll
     for (int k = 0; k < 16; k++) lds[col_at(rl + 16 * k, c)] = ar1.store_mid(a1[k]);
     __syncthreads();
-    cols_finish_group<4>(a1, limb1, col0, rl, rl, ar1, lds);
+    cols_finish_group<4, true>(a1, limb1, col0, rl, rl, ar1, lds);
 }
 // grid.x = 16 * batch
 // EX: the corrected conversions (a kernel of its own: their extra registers would cost the default form waves)
@@ -738,9 +760,9 @@ __device__ __forceinline__ void inv_cols_kernel(u64 *__restrict__ data, const De
     double cd;
     scale_consts(SCALE, cv, T, mi, lb.slot[b], ci, cd);
     if (T.mod[mi].qd != 0.0)
-        inv_cols_body<LOGN>(limb, tile * 16, make_fp(T, mi, LOGN, cd), lds);
+        inv_cols_body<LOGN, SCALE != 0>(limb, tile * 16, make_fp(T, mi, LOGN, cd), lds);
     else
-        inv_cols_body<LOGN>(limb, tile * 16, make_int(T, mi, LOGN, ci), lds);
+        inv_cols_body<LOGN, SCALE != 0>(limb, tile * 16, make_int(T, mi, LOGN, ci), lds);
 }
 template <int SCALE>
 __global__ __launch_bounds__(256) void k_ntt_inv_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)

@@ -90,5 +90,5 @@ static void launch_inv_blocks(he_ctx *c, hipStream_t st, double bytes, const u64
 template <int LOGN>
 static void launch_inner(he_ctx *c, hipStream_t st, double bytes, unsigned grid, const InnerArgs &ia, const HoistKeys &hk)
 {
-    KLAUNCH_T(c, st, KID_INNER, bytes, (k_inner_blocks8<LOGN>), grid, 512, ia, c->dev, hk);
+    KLAUNCH_T(c, st, KID_INNER, bytes, (k_inner_blocks8<LOGN>), grid, INNER_THREADS, ia, c->dev, hk);
 }
