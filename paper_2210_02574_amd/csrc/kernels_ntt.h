@@ -414,7 +414,7 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
     FinOperands fo[EPI == EPI_FIN ? 16 : 1];
 #pragma unroll
     for (int k = 0; k < 16; k++)
-        a[k] = ar.load_mid(EPI == EPI_FIN ? __builtin_nontemporal_load(limb + bg * 256 + il + 16 * k) : limb[bg * 256 + il + 16 * k]);
+        a[k] = ar.load_mid(__builtin_nontemporal_load(limb + bg * 256 + il + 16 * k)); // read once: the column pass wrote it
     if (EPI == EPI_FIN) {
 #pragma unroll
         for (int k = 0; k < 16; k++) fo[k] = fin_load<LOGN>(fa, ho, T, slot, bg * 256 + il + 16 * k);
@@ -437,7 +437,7 @@ __device__ __forceinline__ void fwd_blocks_body(u64 *__restrict__ limb, const A 
         if (EPI == EPI_FIN)
             fin_store<LOGN, A::IS_FP>(fa, ho, T, slot, pos, v, fo[k]);
         else
-            limb[pos] = v;
+            __builtin_nontemporal_store(v, limb + pos);
     }
 }
 
@@ -445,14 +445,16 @@ template <int LOGN, class A>
 __device__ __forceinline__ void inv_blocks_body(const u64 *in, u64 *limb, const A &ar,
                                                 u64 *lds, unsigned tile)
 {
-    const bool stream = in != limb; // out of place: part of a conversion, whose batch is far larger than the caches
+    // out of place: part of a conversion, whose batch is far larger than the caches; in place (a plain inverse
+    // transform) the column pass that follows finds the stores in the last-level cache
+    const bool stream = in != limb;
     const unsigned blk = threadIdx.x >> 4, il = threadIdx.x & 15;
     const unsigned bg = tile * BLK_PER_WG + blk;
     typename A::V a[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) {
         const u64 *src = in + bg * 256 + il + 16 * k;
-        lds[tile_at(blk, il + 16 * k)] = stream ? __builtin_nontemporal_load(src) : *src;
+        lds[tile_at(blk, il + 16 * k)] = __builtin_nontemporal_load(src); // read once
     }
     block_sync();
 #pragma unroll
@@ -528,7 +530,7 @@ __device__ __forceinline__ void cols_inputs(typename A::V (&a)[16], const u64 *_
 #pragma unroll
     for (int k = 0; k < 16; k++) {
         const unsigned pos = (rl + 16 * k + 256 * h) * 256 + col0 + c;
-        a[k] = PRO == PRO_LOAD ? ar.load(limb[pos]) : conv_get<PRO, SPLIT, TINT, EX>(S, ar, m, pos);
+        a[k] = PRO == PRO_LOAD ? ar.load(__builtin_nontemporal_load(limb + pos)) : conv_get<PRO, SPLIT, TINT, EX>(S, ar, m, pos);
     }
 }
 // second phase of the forward column pass for rows 16 g .. 16 g + 15, held in LDS as group gl.  STREAM: the
@@ -760,9 +762,9 @@ __device__ __forceinline__ void inv_cols_kernel(u64 *__restrict__ data, const De
     double cd;
     scale_consts(SCALE, cv, T, mi, lb.slot[b], ci, cd);
     if (T.mod[mi].qd != 0.0)
-        inv_cols_body<LOGN, SCALE != 0>(limb, tile * 16, make_fp(T, mi, LOGN, cd), lds);
+        inv_cols_body<LOGN, true>(limb, tile * 16, make_fp(T, mi, LOGN, cd), lds);
     else
-        inv_cols_body<LOGN, SCALE != 0>(limb, tile * 16, make_int(T, mi, LOGN, ci), lds);
+        inv_cols_body<LOGN, true>(limb, tile * 16, make_int(T, mi, LOGN, ci), lds);
 }
 template <int SCALE>
 __global__ __launch_bounds__(256) void k_ntt_inv_cols16(u64 *__restrict__ data, DevTables T, LimbBatch lb, ConvArgs cv)
