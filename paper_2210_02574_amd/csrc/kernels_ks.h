@@ -48,9 +48,10 @@ __host__ __device__ inline unsigned inner_grid(unsigned tiles, unsigned limbs, u
     return (tiles * limbs + XCDS - 1) / XCDS * XCDS * count;
 }
 
-// Eight elements per thread (128 registers, four waves per SIMD) and 128 threads per work-group: measured at 512,
-// 256, 128 and 64 threads, the small work-groups win by 3 to 8 % because the barriers between the phases of a
-// digit then stall two waves instead of eight while the other work-groups of the compute unit run.  A 256-element
+// Eight elements per thread and 128 threads per work-group: measured at 512, 256, 128 and 64 threads, work-groups of
+// 128 win by 3 to 8 % because the barriers between the phases of a digit then stall two waves instead of eight while
+// the other work-groups of the compute unit run.  25 KiB of LDS (exchange tile, twiddles, the next digit) allow six
+// work-groups per compute unit, three waves per SIMD, at up to 170 registers.  A 256-element
 // block belongs to 32 lanes (half a wave) and its block pass runs as three register steps, stages 0-2, 3-5 and
 // 6-7 of the block, with two exchanges through LDS among those lanes:
 //   step 1: lane t holds e = t + 32 k;   step 2: lane (g = t & 7, r = t >> 3) holds e = 32 g + r + 4 k;
@@ -111,6 +112,7 @@ template <int LOGN> __global__ __launch_bounds__(INNER_THREADS, 4) void k_inner_
 {
     __shared__ u64 lds[INNER_BLOCKS * TILE_GROUP];
     __shared__ double tws[INNER_BLOCKS * 256];
+    __shared__ u64 pre[INNER_BLOCKS * 256]; // the next raised digit of this tile, as it lies in memory
     const int level = ia.level, M = ia.L + ia.K, Ma = level + ia.K;
     const unsigned ntile = 1u << (LOGN - INNER_TLOG);
     const unsigned slot = blockIdx.x / XCDS, op = slot % (unsigned)ia.count;
@@ -151,6 +153,30 @@ template <int LOGN> __global__ __launch_bounds__(INNER_THREADS, 4) void k_inner_
     u64 r0[8], r1[8];
     if (m.qd != 0.0) {
         const ArithFp ar = make_fp(T, mi, LOGN);
+        // The raised digit after the one being worked on is already on its way into LDS: each wave copies the two
+        // blocks its lanes own, 4 x 1 KiB, with loads that write to LDS directly (lane i's 16 bytes land at
+        // base + 16 i) and need no registers while they are in flight.
+        const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        auto prefetch = [&](int j) {
+            const char *src = raised0 + (size_t)j * raised_step + wave * 4096u + lane * 16u;
+            // a digit that only this operation reads is streamed past the key slices that the batch shares in L2
+            // (cache policy 2: nontemporal)
+            if (ia.raised_stride != 0) {
+#pragma unroll
+                for (int c = 0; c < 4; c++)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + 1024 * c),
+                                                     (__attribute__((address_space(3))) void *)(pre + wave * 512 + c * 128), 16, 0, 2);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; c++)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + 1024 * c),
+                                                     (__attribute__((address_space(3))) void *)(pre + wave * 512 + c * 128), 16, 0, 0);
+            }
+        };
+        {
+            const int j0 = own == 0 ? 1 : 0;
+            if (j0 < beta) prefetch(j0);
+        }
         double *tw = tws + blk * 256;
         for (unsigned c = t; c < 255; c += 32) tw[c] = ar.twf[ArithFp::fwd16_twiddle(LOGN - 8, tile_in * INNER_BLOCKS + blk, c)];
         __syncthreads();
@@ -178,12 +204,16 @@ template <int LOGN> __global__ __launch_bounds__(INNER_THREADS, 4) void k_inner_
                 for (int i = 0; i < 4; i++)
                     e0[i] = ld_at<f64x2>(kj + INNER_THREADS * 16 * i, lane16), e1[i] = ld_at<f64x2>(kj + comp_step + INNER_THREADS * 16 * i, lane16);
             } else {
-                const char *mid = raised0 + (size_t)j * raised_step;
+                // this digit has arrived (nothing else of this wave is in flight here); once it is in registers the
+                // buffer is free for the next one
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                const u64 *pw = pre + blk * 256 + t;
 #pragma unroll
-                for (int k = 0; k < 8; k++) {
-                    // a digit that only this operation reads is streamed past the key slices that the batch shares in L2
-                    const u64 *src = (const u64 *)(mid + 256 * k + lane_mid);
-                    dv[k] = ar.load_mid(ia.raised_stride != 0 ? __builtin_nontemporal_load(src) : *src);
+                for (int k = 0; k < 8; k++) dv[k] = ar.load_mid(pw[32 * k]);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                {
+                    const int jn = j + 1 == own ? j + 2 : j + 1;
+                    if (jn < beta) prefetch(jn);
                 }
                 // the key loads are issued before the block pass and complete behind it
 #pragma unroll
