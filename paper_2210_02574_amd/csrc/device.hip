@@ -286,8 +286,11 @@ template <class F> static int32_t for_batches(he_ctx *c, const LimbList &l, F la
 {
     const int total = l.size();
     std::vector<int> order(HE_MAXB);
-    for (int off = 0; off < total; off += HE_MAXB) {
-        const int nb = std::min(HE_MAXB, total - off);
+    // chunks of equal size (even, so that pairs of limbs stay together) rather than full ones and a small rest
+    const int nchunks = (total + HE_MAXB - 1) / HE_MAXB;
+    const int per = nchunks ? std::min(HE_MAXB, ((total + nchunks - 1) / nchunks + 1) & ~1) : 0;
+    for (int off = 0; off < total; off += per) {
+        const int nb = std::min(per, total - off);
         for (int b = 0; b < nb; b++) order[b] = off + b;
         std::stable_partition(order.begin(), order.begin() + nb, [&](int b) { return c->modc[l.mod[b]].qd == 0.0; });
         LimbBatch lb;

@@ -23,7 +23,11 @@
 #pragma once
 #include "arith.h"
 
-#define HE_MAXB 512
+// limbs per launch: the table below travels as a kernel argument (10 KiB); large launches matter, halving this
+// costs the conversion passes 11-14 %
+#ifndef HE_MAXB
+#define HE_MAXB 2048
+#endif
 // operations per launch that can carry a key, a Galois element, a level and pointers of their own
 #define HE_OPS_MAX 32
 // A launch works on up to HE_MAXB limbs: limb b is written at dst + slot[b]*N, read (inverse block
