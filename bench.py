@@ -469,7 +469,7 @@ def main():
     ap.add_argument("--hmult-batch", type=int, default=16, help="ciphertext pairs per batched HMult call")
     ap.add_argument("--single-mode", choices=["levels", "per-level", "each"], default="levels",
                     help="how the 128 single rotations are issued: 32 per mixed-level call, one call per level, or one call each")
-    ap.add_argument("--streams", type=int, default=3, help="HIP streams for the independent operations of a step")
+    ap.add_argument("--streams", type=int, default=1, help="HIP streams for the independent operations of a step")
     ap.add_argument("--probe", nargs="+", metavar="ARG",
                     help="run a short profiling target instead of the benchmark: hrot-batch [SET LEVEL COUNT] | copy")
     args = ap.parse_args()
