@@ -469,6 +469,7 @@ def main():
     ap.add_argument("--hmult-batch", type=int, default=16, help="ciphertext pairs per batched HMult call")
     ap.add_argument("--single-mode", choices=["levels", "per-level", "each"], default="levels",
                     help="how the 128 single rotations are issued: 32 per mixed-level call, one call per level, or one call each")
+    ap.add_argument("--single-chunk", type=int, default=32, help="single rotations per call in --single-mode levels")
     ap.add_argument("--streams", type=int, default=1, help="HIP streams for the independent operations of a step")
     ap.add_argument("--probe", nargs="+", metavar="ARG",
                     help="run a short profiling target instead of the benchmark: hrot-batch [SET LEVEL COUNT] | copy")
@@ -492,7 +493,8 @@ def main():
         probe(args.probe)
         return
     he = pkg.HE.from_params(wl.N16, device=0)
-    w = Workload(he, n_streams=args.streams, hm_chunk=args.hmult_batch, single_mode=args.single_mode)
+    w = Workload(he, n_streams=args.streams, hm_chunk=args.hmult_batch, single_mode=args.single_mode,
+                 single_chunk=args.single_chunk)
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()
@@ -611,7 +613,7 @@ def main():
             "key_switches_per_step": w.key_switches,
             "streams": args.streams,
             "hmult_batch": args.hmult_batch,
-            "single_hrot_calls": {"levels": "32 rotations of mixed levels per call, sorted by key",
+            "single_hrot_calls": {"levels": "%d rotations of mixed levels per call, sorted by key" % args.single_chunk,
                                   "per-level": "one call per level (one key per ciphertext)",
                                   "each": "one call each"}[args.single_mode],
         },

@@ -29,7 +29,9 @@
 #define HE_MAXB 2048
 #endif
 // operations per launch that can carry a key, a Galois element, a level and pointers of their own
+#ifndef HE_OPS_MAX
 #define HE_OPS_MAX 32
+#endif
 // A launch works on up to HE_MAXB limbs: limb b is written at dst + slot[b]*N, read (inverse block
 // pass only) at src + src[b]*N, and uses modulus index mod[b].
 struct LimbBatch {
