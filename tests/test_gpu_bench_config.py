@@ -45,3 +45,34 @@ def test_bench_step_outputs_match_oracle(oracle_mod, n_streams):
         got = he.to_host(w.single_out[i])
         assert got.shape[1] == w.single_levels[i]
         assert np.array_equal(got, o.hrot(he.to_host(w.single_in[i]), evk, w.offsets[k])), i
+
+
+def test_full_batches_span_several_launches(oracle_mod):
+    """The batch sizes that bench.py times: 16 products per call (2304 raised limbs, more than one launch of the
+    conversion passes can carry, so the list is split) and 32 mixed-level rotations per call.  Operations on both sides
+    of every split, the first and the last are compared with the oracle bit for bit."""
+    import torch
+
+    import bench
+    import paper_2210_02574_amd as pkg
+
+    p = wl.N16
+    he = pkg.HE.from_params(p, device=0)
+    o = oracle_mod.Oracle(p.logN, p.q, p.p, p.dnum)
+    w = bench.Workload(he, seed=2, n_hmult=16, n_single=32, n_ntt=1, n_streams=1, hm_chunk=16, single_chunk=32)
+    assert len(w.single_groups) == 1
+    w.step()
+    torch.cuda.synchronize()
+    relin = wl.uniform_evk(1000, p)
+    for i in (0, 7, 8, 15):
+        a, b = he.to_host(w.hm_a[i]), he.to_host(w.hm_b[i])
+        assert np.array_equal(he.to_host(w.rs_out[i]), o.rescale(o.hmult_relin(a, b, relin))), i
+    # the call's order is by key, then by level: take its first and last operation and four in between
+    order = sorted(range(w.n_single), key=lambda i: (w.single_keys[i], -w.single_levels[i]))
+    for pos in (0, 9, 15, 16, 22, 31):
+        i = order[pos]
+        k = w.single_keys[i]
+        evk = wl.uniform_evk(1001 + k, p)
+        got = he.to_host(w.single_out[i])
+        assert got.shape[1] == w.single_levels[i]
+        assert np.array_equal(got, o.hrot(he.to_host(w.single_in[i]), evk, w.offsets[k])), (pos, i)
